@@ -1,0 +1,238 @@
+"""Pins for the oracle's next-use computation and Belady changesets (CPU only).
+
+Section 3.3 (cache policy, update lists) and Section 3.4 (recurrence, tracking).
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle.tracker import NextAccessTracker
+from workload import make_workload
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+NEVER = oracle.NEVER
+
+
+def flat(ids_list):
+    off = np.cumsum([0] + [len(x) for x in ids_list]).astype(np.int64)
+    ids = np.array([v for x in ids_list for v in x], dtype=np.int32)
+    return ids, off
+
+
+def random_trace(rng, n, S, max_len):
+    return [list(rng.choice(n, size=rng.integers(0, min(max_len, n) + 1), replace=False))
+            for _ in range(S)]
+
+
+def naive_next_use(ids_list):
+    """The O(S^2) forward scan the paper rejects (Section 3.4), as a cross-check."""
+    out = []
+    for i, ids in enumerate(ids_list):
+        for v in ids:
+            nxt = NEVER
+            for j in range(i + 1, len(ids_list)):
+                if v in ids_list[j]:
+                    nxt = j
+                    break
+            out.append(nxt)
+    return out
+
+
+def test_next_use_against_forward_scan_and_tracker():
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        n, S = int(rng.integers(1, 12)), int(rng.integers(1, 9))
+        tr = random_trace(rng, n, S, 6)
+        ids, off = flat(tr)
+        nxt, first = oracle.next_use(n, ids, off)
+        assert list(nxt) == naive_next_use(tr)
+        t = NextAccessTracker(n, tr)
+        for v in range(n):
+            if t.count[v]:
+                assert t.next_access(v) == first[v]
+            else:
+                assert first[v] == NEVER
+        p = 0
+        for i, cur in enumerate(tr):
+            t.advance(cur)
+            for v in cur:
+                assert t.next_access(v) == nxt[p]
+                p += 1
+
+
+def test_tracker_reproduces_the_values_the_paper_states():
+    kv, trace = {}, []
+    for line in open(os.path.join(GOLDEN, "next_access_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, *v = line.split()
+        if k == "ids":
+            trace.append([int(x) for x in v])
+        else:
+            kv[k] = [int(x) for x in v]
+    n = kv["num_nodes"][0]
+    t = NextAccessTracker(n, trace)
+    assert t.ptr[3] == kv["ptr3"][0] and t.ptr[4] == kv["ptr4"][0]
+    assert [x & 0x7FFFFFFF for x in t.iters[t.ptr[3]:t.ptr[3] + 3]] == kv["node3_iters"]
+    assert t.dummy_index == kv["dummy_index"][0]
+    assert t.iters[t.ptr[3]] >> 31 == 1            # head of node 3's run is marked
+    t.advance(trace[0])
+    assert t.ptr[3] == 5 and t.ptr[4] == 8         # both advanced by one
+    t.advance(trace[1])
+    assert t.ptr[2] == kv["ptr2_after_iteration1"][0]
+    ids, off = flat(trace)
+    nxt, first = oracle.next_use(n, ids, off)
+    assert list(first) == [1, 2, 1, 0, 0]
+    assert list(nxt) == [2, 3, NEVER, 3, 4, NEVER, 4, NEVER, NEVER, NEVER]
+
+
+def replay(n, cap, tr, cs):
+    """Replays the changesets, checking every structural invariant; returns the states."""
+    cache = {int(v): s for s, v in enumerate(cs["init_ids"])}
+    assert len(cache) == len(cs["init_ids"]) <= cap
+    states, total_miss = [set(cache)], 0
+    for i, cur in enumerate(tr):
+        lo, hi = cs["cs_offsets"][i], cs["cs_offsets"][i + 1]
+        ins, outs, pos = cs["in_ids"][lo:hi], cs["out_ids"][lo:hi], cs["in_positions"][lo:hi]
+        misses = [v for v in cur if v not in cache]
+        assert cs["miss_count"][i] == len(misses)
+        total_miss += len(misses)
+        assert set(ins) <= set(misses) and len(set(ins)) == len(ins)
+        assert set(outs) <= set(cache) and len(set(outs)) == len(outs)
+        assert not set(ins) & set(outs)
+        assert all(cur[p] == v for p, v in zip(pos, ins))
+        assert list(pos) == sorted(pos)
+        slots = [cache[int(o)] for o in outs]
+        assert slots == sorted(slots)
+        for v, o in zip(ins, outs):
+            cache[int(v)] = cache.pop(int(o))
+        assert len(cache) <= cap and len(set(cache.values())) == len(cache)
+        states.append(set(cache))
+    return states, total_miss
+
+
+def optimal_misses(tr, cap, c0=None):
+    """Exhaustive search: every C_{i+1} that is a subset of C_i union ids_i with at most
+    `cap` rows is tried.  With c0=None every initial state is tried as well."""
+    S = len(tr)
+    memo = {}
+
+    def go(i, cache):
+        if i == S:
+            return 0
+        key = (i, cache)
+        if key not in memo:
+            cur = frozenset(tr[i])
+            miss = len(cur - cache)
+            pool = sorted(cache | cur)
+            best = None
+            for r in range(min(cap, len(pool)) + 1):
+                for nxt in itertools.combinations(pool, r):
+                    c = go(i + 1, frozenset(nxt))
+                    best = c if best is None else min(best, c)
+            memo[key] = miss + best
+        return memo[key]
+
+    if c0 is not None:
+        return go(0, frozenset(c0))
+    nodes = sorted({v for x in tr for v in x})
+    return min(go(0, frozenset(c)) for r in range(min(cap, len(nodes)) + 1)
+               for c in itertools.combinations(nodes, r))
+
+
+def test_belady_is_optimal_by_exhaustive_search():
+    rng = np.random.default_rng(3)
+    checked_pressure = 0
+    for _ in range(300):
+        n, S, cap = int(rng.integers(2, 7)), int(rng.integers(1, 6)), int(rng.integers(0, 4))
+        tr = [[int(v) for v in x] for x in random_trace(rng, n, S, 3)]
+        ids, off = flat(tr)
+        cs = oracle.changeset(n, ids, off, cap)
+        _, total = replay(n, cap, tr, cs)
+        assert total == int(cs["miss_count"].sum())
+        assert total == optimal_misses(tr, cap, [int(v) for v in cs["init_ids"]])
+        assert total == optimal_misses(tr, cap)           # C_0 is an optimal start too
+        checked_pressure += total > 0
+    assert checked_pressure > 100
+
+
+def test_heap_variant_equals_the_definition_and_the_recurrence():
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        n, S, cap = int(rng.integers(1, 40)), int(rng.integers(1, 12)), int(rng.integers(0, 12))
+        tr = [[int(v) for v in x] for x in random_trace(rng, n, S, 15)]
+        ids, off = flat(tr)
+        a = oracle.changeset(n, ids, off, cap)
+        b = oracle.changeset_by_sorting(n, ids, off, cap)
+        for k in a:
+            assert np.array_equal(a[k], b[k]), k
+        states, _ = replay(n, cap, tr, a)
+        nxt, first = oracle.next_use(n, ids, off)
+        # C_0: the cap smallest (first access, id); line r = rank
+        order = sorted((first[v], v) for v in range(n) if first[v] != NEVER)[:cap]
+        assert [v for _, v in order] == list(a["init_ids"])
+        # C_{i+1} = the cap smallest of union(C_i, ids_i) by (next access, incoming, id)
+        key = {v: first[v] for v in range(n)}
+        p = 0
+        for i, cur in enumerate(tr):
+            for v in cur:
+                key[v] = nxt[p]
+                p += 1
+            cand = sorted((key[v], v not in states[i], v) for v in states[i] | set(cur))
+            assert {v for _, _, v in cand[:cap]} == states[i + 1]
+            assert states[i + 1] <= states[i] | set(cur)
+
+
+def test_last_record_is_empty_and_full_fit_never_changes():
+    rng = np.random.default_rng(7)
+    for _ in range(50):
+        n, S = 20, 6
+        tr = [[int(v) for v in x] for x in random_trace(rng, n, S, 8)]
+        ids, off = flat(tr)
+        cs = oracle.changeset(n, ids, off, 5)
+        assert cs["cs_offsets"][S] == cs["cs_offsets"][S - 1]   # S records, the last is empty
+        distinct = len(set(ids.tolist()))
+        full = oracle.changeset(n, ids, off, distinct)
+        assert len(full["init_ids"]) == distinct and full["cs_offsets"][S] == 0
+        assert full["miss_count"].sum() == 0
+        # init_count + misses >= distinct, with equality iff everything fits
+        assert len(cs["init_ids"]) + cs["miss_count"].sum() >= distinct
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    w = make_workload(1, features=False)
+    r = oracle.sample_superbatch(w.offsets.numpy(), w.indices.numpy(), w.seeds.numpy(),
+                                 w.seed_offsets.numpy(), w.cfg.fanout)
+    return w, r
+
+
+def test_invariants_and_policy_bounds_on_tiny_config(tiny):
+    w, r = tiny
+    n, cap = w.cfg.num_nodes, w.cfg.cap
+    cs = oracle.changeset(n, r["ids"], r["ids_offsets"], cap)
+    tr = [r["ids"][r["ids_offsets"][i]:r["ids_offsets"][i + 1]].tolist()
+          for i in range(w.cfg.S)]
+    _, total = replay(n, cap, tr, cs)
+    # the cache (2048 rows) is smaller than one iteration's ids: rows must bypass it
+    assert cap < min(len(x) for x in tr)
+    assert total <= oracle.lru_misses(n, r["ids"], r["ids_offsets"], cap, cs["init_ids"])
+    deg = (w.offsets[1:] - w.offsets[:-1]).numpy()
+    out_deg = np.bincount(w.indices.numpy(), minlength=n)
+    for score in (deg, out_deg):
+        top = np.argsort(-score, kind="stable")[:cap]
+        assert total <= oracle.static_misses(n, r["ids"], top)
+    b = oracle.changeset_by_sorting(n, r["ids"], r["ids_offsets"], cap)
+    for k in cs:
+        assert np.array_equal(cs[k], b[k]), k
+
+
+def test_lru_helper_counts_misses_of_a_plain_lru():
+    # 3 lines, one id per iteration: textbook LRU
+    tr = [[1], [2], [3], [1], [4], [2], [1]]
+    ids, off = flat(tr)
+    # start empty: 1,2,3 miss; 1 hit; 4 miss (evicts 2); 2 miss (evicts 3); 1 hit
+    assert oracle.lru_misses(5, ids, off, 3, np.array([], dtype=np.int32)) == 5
