@@ -1,0 +1,162 @@
+/*
+ * ginex.h - C ABI of the MI355X (gfx950) hot path of the Ginex inspector-executor
+ * pipeline (arXiv 2208.09151): superbatch sample -> changeset precomputation ->
+ * feature cache initialization -> per-iteration gather + cache update.
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".  The structs
+ *    themselves live in host memory; the pointers inside them follow the same rule.
+ *  - The caller owns every buffer, including the workspace `ws`; the library allocates
+ *    nothing.  Workspace sizes come from the matching *_workspace_bytes query called
+ *    with the same shape arguments.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All kernels
+ *    of a call are enqueued on it.  ginex_cache_init and ginex_gather only enqueue;
+ *    ginex_sample_superbatch and ginex_changeset also wait for the stream before they
+ *    return, because they hand counts back to the host.
+ *  - Every function returns 0 (GINEX_OK) or a negative GINEX_ERR_* code; the message of
+ *    the last failure on the calling thread is returned by ginex_last_error().
+ *    Arguments are validated on the host before anything is launched.  On
+ *    GINEX_ERR_CAPACITY the required element counts are written to the host size
+ *    outputs and the contents of the output arrays are unspecified.
+ *  - Node ids are int32 in [0, num_nodes); CSR offsets are int32 or int64.
+ */
+#ifndef GINEX_H
+#define GINEX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GINEX_OK 0
+#define GINEX_ERR_ARG (-1)        /* null pointer, negative size, unsupported shape   */
+#define GINEX_ERR_CAPACITY (-2)   /* an output array is too small                     */
+#define GINEX_ERR_WORKSPACE (-3)  /* ws_bytes below the *_workspace_bytes figure      */
+#define GINEX_ERR_INPUT (-4)      /* the data violates a documented precondition      */
+#define GINEX_ERR_HIP (-5)        /* a HIP runtime call failed                        */
+
+#define GINEX_MAX_FANOUT 64
+#define GINEX_MAX_HOPS 8
+
+/* Message of the last error on this thread ("" if none). Owned by the library. */
+const char* ginex_last_error(void);
+/* Library version: major*10000 + minor*100 + patch. */
+int32_t ginex_version(void);
+
+/* Graph in CSR form.  Row v lists the nodes that may be sampled for v (the paper stores
+ * in-neighbours, Section 2.2); multi-edges are allowed. */
+typedef struct ginex_csr {
+  int64_t num_nodes;
+  int64_t num_edges;
+  const void* offsets;     /* [num_nodes+1], int32 if offsets_64 == 0, else int64 */
+  int32_t offsets_64;
+  const int32_t* indices;  /* [num_edges] */
+} ginex_csr_t;
+
+/* ---------------------------------------------------------------------------------
+ * Superbatch sample (Section 3.1 "Superbatch Sample"; sampling rule of Section 2.1
+ * "Neighborhood Sampling"): samples S batches at once and returns, per batch, `ids`
+ * (the 1-D list of all sampled node ids) and `adj` (the connectivity among them).
+ *
+ * Batch b (global index first_batch_index+b) starts from seeds[seed_offsets[b] ..
+ * seed_offsets[b+1]).  At hop h every node in the batch's list at the start of the hop
+ * draws min(degree, fanout[h]) distinct positions of its CSR row, uniformly, from a
+ * Philox4x32-10 stream keyed by rng_seed with counter (node, global batch, hop, draw);
+ * unseen neighbours are appended to the list in the order frontier node by frontier
+ * node, pick by ascending row position.  The result for a batch depends only on its
+ * seeds, its global index and rng_seed.
+ *
+ * Outputs
+ *   ids[ids_offsets[b] .. ids_offsets[b+1])   the list of batch b (seeds first, a seed
+ *                                              repeated within a batch is kept once)
+ *   hop_sizes[b*(H+1)+h]                       list length after the seeds (h=0) and
+ *                                              after hop h-1 (h>=1)
+ *   adj: segment g = h*S + b (hop-major) describes hop h of batch b as a CSR over the
+ *   frontier: adj_rowptr[adj_row_offsets[g] + r], r = 0..frontier, starts at 0, and
+ *   adj_col[adj_col_offsets[g] + e] is the position inside the batch's ids of pick e;
+ *   row r belongs to ids[r].  adj_row_offsets/adj_col_offsets have S*H+1 entries.
+ *   Pass adj_rowptr = adj_col = NULL to skip adj (offset arrays are still filled).
+ *   totals (host, [3]): number of ids, of rowptr entries and of col entries (= sampled
+ *   edges) produced, or required on GINEX_ERR_CAPACITY.
+ * Limits: 1 <= H <= GINEX_MAX_HOPS, 1 <= fanout[h] <= GINEX_MAX_FANOUT, and a batch's
+ * list must stay below 2^30 entries.
+ * ------------------------------------------------------------------------------- */
+size_t ginex_sample_workspace_bytes(int64_t num_nodes, int32_t S, int64_t max_batch,
+                                    const int32_t* fanout /*host [H]*/, int32_t H);
+
+int32_t ginex_sample_superbatch(
+    const ginex_csr_t* g /*host struct*/,
+    const int32_t* seeds, const int64_t* seed_offsets /*host [S+1]*/, int32_t S,
+    const int32_t* fanout /*host [H]*/, int32_t H,
+    uint64_t rng_seed, uint32_t first_batch_index,
+    int32_t* ids, int64_t ids_capacity, int64_t* ids_offsets /*[S+1]*/,
+    int64_t* hop_sizes /*[S*(H+1)]*/,
+    int64_t* adj_rowptr, int64_t rowptr_capacity, int32_t* adj_col, int64_t col_capacity,
+    int64_t* adj_row_offsets /*[S*H+1]*/, int64_t* adj_col_offsets /*[S*H+1]*/,
+    int64_t* totals /*host [3]*/,
+    void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------
+ * Changeset precomputation (Section 3.4; lists of Section 3.3 "Feature Cache Update").
+ * Given the access trace ids_0 .. ids_{S-1} of a superbatch (ids within one iteration
+ * distinct) and a cache of `cap` rows, computes
+ *   C_0       the cap rows accessed earliest (ties: smaller id), row of rank r in line r;
+ *   C_{i+1}   the cap elements of union(C_i, ids_i) whose next accessed iteration is
+ *             smallest (ties: a resident row before an incoming one, then smaller id);
+ *   per iteration i: in_ids = C_{i+1}\C_i ordered by position in ids_i, in_positions =
+ *   those positions, out_ids = C_i\C_{i+1} ordered by cache line; in_ids[j] takes the
+ *   line of out_ids[j].  Records of iteration i occupy [cs_offsets[i], cs_offsets[i+1]).
+ *   miss_count[i] = |ids_i \ C_i|.
+ * init_count and total_changes are host outputs.  cs_capacity >= total_changes is
+ * required (ids_offsets[S] always suffices).
+ * Limits: 1 <= S <= 8191, total ids < 2^31.
+ * ------------------------------------------------------------------------------- */
+size_t ginex_changeset_workspace_bytes(int64_t num_nodes, int64_t total_ids, int32_t S,
+                                       int64_t cap);
+
+int32_t ginex_changeset(
+    int64_t num_nodes, const int32_t* ids, const int64_t* ids_offsets /*host [S+1]*/,
+    int32_t S, int64_t cap,
+    int32_t* init_ids /*[cap]*/, int64_t* init_count /*host*/,
+    int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
+    int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
+    int64_t* total_changes /*host*/,
+    void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------
+ * Feature cache (Section 3.3 "Feature Cache Structure"): a 2-D array of `cap` rows in
+ * HBM plus an address table with one entry per node (cache line, or -1).  `slow` is the
+ * full feature table [num_nodes x row_bytes] in memory the GPU can read: host-pinned
+ * memory standing in for the SSD tier, or device memory.  row_bytes % 16 == 0 and every
+ * base pointer 16-byte aligned.
+ * ------------------------------------------------------------------------------- */
+typedef struct ginex_cache {
+  void* rows;
+  int64_t cap;
+  int64_t row_bytes;
+  int32_t* addr;
+  int64_t num_nodes;
+  const void* slow;
+} ginex_cache_t;
+
+/* Feature cache initialization (Section 3.1): addr[*] = -1, then row init_ids[r] is
+ * loaded into line r and addr[init_ids[r]] = r.  init_count <= cap. */
+int32_t ginex_cache_init(const ginex_cache_t* c /*host struct*/, const int32_t* init_ids,
+                         int64_t init_count, void* stream);
+
+/* One executor iteration (Section 3.1 "Main Loop", Section 3.3 worked example):
+ * gather   out[p,:] = addr[ids[p]] >= 0 ? rows[addr[ids[p]],:] : slow[ids[p],:]
+ * then the cache update  line = addr[out_ids[j]]; rows[line,:] = out[in_positions[j],:];
+ *                        addr[out_ids[j]] = -1; addr[in_ids[j]] = line.
+ * `out` is [n x row_bytes] in HBM.  n_change may be 0 (then the three lists may be
+ * NULL). */
+int32_t ginex_gather(const ginex_cache_t* c /*host struct*/, const int32_t* ids, int64_t n,
+                     void* out, const int32_t* in_ids, const int32_t* out_ids,
+                     const int32_t* in_positions, int64_t n_change, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GINEX_H */

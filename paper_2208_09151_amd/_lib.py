@@ -1,0 +1,52 @@
+"""ctypes loader for libginex.so; declares every entry point of include/ginex.h."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libginex.so")
+
+i32, i64, u32, u64, vp, sz = C.c_int32, C.c_int64, C.c_uint32, C.c_uint64, C.c_void_p, C.c_size_t
+
+
+class CsrDesc(C.Structure):
+    _fields_ = [("num_nodes", i64), ("num_edges", i64), ("offsets", vp), ("offsets_64", i32),
+                ("indices", vp)]
+
+
+class CacheDesc(C.Structure):
+    _fields_ = [("rows", vp), ("cap", i64), ("row_bytes", i64), ("addr", vp),
+                ("num_nodes", i64), ("slow", vp)]
+
+
+SIGNATURES = {
+    "ginex_last_error": (C.c_char_p, []),
+    "ginex_version": (i32, []),
+    "ginex_sample_workspace_bytes": (sz, [i64, i32, i64, vp, i32]),
+    "ginex_sample_superbatch": (i32, [C.POINTER(CsrDesc), vp, vp, i32, vp, i32, u64, u32,
+                                      vp, i64, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, sz, vp]),
+    "ginex_changeset_workspace_bytes": (sz, [i64, i64, i32, i64]),
+    "ginex_changeset": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp,
+                              sz, vp]),
+    "ginex_cache_init": (i32, [C.POINTER(CacheDesc), vp, i64, vp]),
+    "ginex_gather": (i32, [C.POINTER(CacheDesc), vp, i64, vp, vp, vp, vp, i64, vp]),
+}
+
+_lib = None
+
+
+def load():
+    """Loads the built library; builds it first only if it has never been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from .build import build
+            build()
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)     # AttributeError if the library lacks a declared symbol
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib

@@ -1,0 +1,812 @@
+// Changeset precomputation on gfx950 (Ginex Section 3.4, lists of Section 3.3).
+//
+// Part 1, next accessed iteration of every access, fully parallel:
+//   (node, flat position) pairs are radix-sorted by node (stable, so each node's accesses
+//   stay in iteration order); an access's successor in the sorted array tells its next
+//   accessed iteration, the head of each node's run tells the node's first access.
+// Part 2, C_0: run heads (first iteration, node) sorted by first iteration; the first
+//   `cap` of them fill cache lines 0..cap-1.
+// Part 3, the recurrence C_{i+1} = f_Belady(union(C_i, ids_i)), serial over iterations and
+//   parallel inside one.  The cache is full from C_0 on (otherwise everything fitted and
+//   nothing ever changes), so iteration i must drop exactly as many candidates as it had
+//   misses.  Keys are (next iteration, incoming?, node id); next iterations take only
+//   S-i distinct values, so a histogram per next iteration (kept incrementally for the
+//   residents, rebuilt for the incoming rows) finds the threshold bucket j*; only inside
+//   j* does the id order matter, and there the k-th smallest id is found by setting the
+//   members' bits in a bitmap over node ids and locating the k-th set bit.
+//   Evicted lines and inserted positions are then compacted in line / position order.
+#include <vector>
+
+#include "common.hpp"
+#include "primitives.hpp"
+
+namespace ginex {
+namespace {
+
+constexpr int TB = 256;
+constexpr int BIG = 1024;          // threads of the single-block kernels
+constexpr int TOUCH_ITEMS = 8;     // accesses per thread in the touch kernel
+constexpr int BITS_WORDS = 8;      // bitmap words per thread in the select kernels
+
+enum { MODE_NONE = 0, MODE_ALL = 1, MODE_SELECT = 2 };
+
+struct Ctrl {        // decisions of the running iteration (device memory)
+  int32_t jstar;     // threshold bucket (S+1: nothing is dropped)
+  int32_t mode_in;   // incoming rows of bucket j*: none / all / ids <= T are inserted
+  int32_t mode_res;  // resident rows of bucket j*: all / ids <= T are kept
+  int32_t keep;      // how many members of the selected class stay
+  int32_t T;         // id threshold of the select
+  int32_t n_change;  // evictions (= insertions) of the iteration
+  int32_t pad[2];
+};
+
+struct State {
+  int32_t* res_id;      // [cap] node held by each cache line
+  int32_t* res_next;    // [cap] its next accessed iteration (S = never)
+  int32_t* addr;        // [N] line of a node or -1
+  uint32_t* rhist;      // [S+1] residents per next iteration
+  uint32_t* ihist;      // [S+1] incoming rows of the running iteration per next iteration
+  uint32_t* bitmap;     // [ceil(N/32)] select scratch, all zero between iterations
+  uint32_t* bit_part;   // popcount of each block of bitmap words
+  Ctrl* ctrl;
+  uint32_t* evict_tiles;  // tile counts / scanned bases, by cache line
+  uint32_t* in_tiles;     // the same by position in ids_i
+  int32_t* out_slot;      // line of the t-th eviction
+  int32_t* in_id;         // node of the t-th insertion
+  int32_t* in_next;       // its next accessed iteration
+  int64_t cap, num_nodes;
+  int32_t S;
+  int32_t tile_items;     // cache lines per thread in the compaction kernels
+  int64_t max_change;     // entries of out_slot / in_id / in_next
+};
+
+__device__ __forceinline__ int32_t iter_of(const int64_t* __restrict__ off, int32_t S, int64_t p) {
+  int32_t lo = 0, hi = S;  // largest i with off[i] <= p
+  while (hi - lo > 1) {
+    const int32_t mid = (lo + hi) >> 1;
+    if (off[mid] <= p) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// ---- part 1 -----------------------------------------------------------------------
+
+__global__ __launch_bounds__(TB) void k_make_pairs(const int32_t* __restrict__ ids, int64_t n,
+                                                   uint64_t* __restrict__ pairs) {
+  const int64_t p = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (p < n) pairs[p] = ((uint64_t)(uint32_t)ids[p] << 32) | (uint64_t)p;
+}
+
+constexpr int LOOK_ITEMS = 8;
+constexpr int LOOK_TILE = TB * LOOK_ITEMS;
+
+// next_iter of every access + number of run heads per tile
+__global__ __launch_bounds__(TB) void k_look_right(const uint64_t* __restrict__ sorted, int64_t n,
+                                                   const int64_t* __restrict__ off, int32_t S,
+                                                   int32_t* __restrict__ next_iter,
+                                                   uint32_t* __restrict__ head_tiles) {
+  __shared__ uint32_t red[TB / WAVE];
+  uint32_t heads = 0;
+  const int64_t base = (int64_t)blockIdx.x * LOOK_TILE;
+#pragma unroll
+  for (int i = 0; i < LOOK_ITEMS; ++i) {
+    const int64_t j = base + i * TB + threadIdx.x;
+    if (j < n) {
+      const uint64_t cur = sorted[j];
+      const uint32_t v = (uint32_t)(cur >> 32);
+      int32_t nxt = S;
+      if (j + 1 < n) {
+        const uint64_t r = sorted[j + 1];
+        if ((uint32_t)(r >> 32) == v) nxt = iter_of(off, S, (int64_t)(r & 0xFFFFFFFFu));
+      }
+      next_iter[cur & 0xFFFFFFFFu] = nxt;
+      heads += (j == 0) || ((uint32_t)(sorted[j - 1] >> 32) != v);
+    }
+  }
+  heads = wave_reduce_sum(heads);
+  if (lane_id() == 0) red[threadIdx.x / WAVE] = heads;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t s = 0;
+    for (int w = 0; w < TB / WAVE; ++w) s += red[w];
+    head_tiles[blockIdx.x] = s;
+  }
+}
+
+// heads[r] = (first iteration << 32 | node) for the r-th distinct node (ascending id)
+__global__ __launch_bounds__(TB) void k_heads_write(const uint64_t* __restrict__ sorted, int64_t n,
+                                                    const int64_t* __restrict__ off, int32_t S,
+                                                    const uint32_t* __restrict__ head_bases,
+                                                    uint64_t* __restrict__ heads) {
+  __shared__ uint32_t smem[TB / WAVE + 1];
+  const int64_t base = (int64_t)blockIdx.x * LOOK_TILE + (int64_t)threadIdx.x * LOOK_ITEMS;
+  uint32_t flags = 0, cnt = 0;
+#pragma unroll
+  for (int i = 0; i < LOOK_ITEMS; ++i) {
+    const int64_t j = base + i;
+    if (j < n) {
+      const uint32_t v = (uint32_t)(sorted[j] >> 32);
+      if (j == 0 || (uint32_t)(sorted[j - 1] >> 32) != v) {
+        flags |= 1u << i;
+        ++cnt;
+      }
+    }
+  }
+  uint32_t total;
+  uint32_t at = head_bases[blockIdx.x] + block_exclusive_scan<uint32_t, TB>(cnt, smem, total);
+#pragma unroll
+  for (int i = 0; i < LOOK_ITEMS; ++i)
+    if (flags >> i & 1) {
+      const uint64_t cur = sorted[base + i];
+      const uint32_t first = (uint32_t)iter_of(off, S, (int64_t)(cur & 0xFFFFFFFFu));
+      heads[at++] = ((uint64_t)first << 32) | (cur >> 32);
+    }
+}
+
+// ---- part 2 -----------------------------------------------------------------------
+
+__global__ __launch_bounds__(TB) void k_init_state(const uint64_t* __restrict__ heads,
+                                                   int64_t count, int32_t* __restrict__ init_ids,
+                                                   State st) {
+  extern __shared__ uint32_t lds_hist[];  // S+1 bins
+  for (int j = threadIdx.x; j <= st.S; j += TB) lds_hist[j] = 0;
+  __syncthreads();
+  const int64_t span = (int64_t)gridDim.x * TB;
+  for (int64_t s = (int64_t)blockIdx.x * TB + threadIdx.x; s < count; s += span) {
+    const uint64_t h = heads[s];
+    const int32_t v = (int32_t)(h & 0xFFFFFFFFu);
+    const int32_t first = (int32_t)(h >> 32);
+    init_ids[s] = v;
+    st.res_id[s] = v;
+    st.res_next[s] = first;
+    st.addr[v] = (int32_t)s;
+    atomicAdd(&lds_hist[first], 1u);
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j <= st.S; j += TB)
+    if (lds_hist[j]) atomicAdd(&st.rhist[j], lds_hist[j]);
+}
+
+__global__ __launch_bounds__(TB) void k_copy_init(const uint64_t* __restrict__ heads, int64_t count,
+                                                  int32_t* __restrict__ init_ids) {
+  const int64_t s = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (s < count) init_ids[s] = (int32_t)(heads[s] & 0xFFFFFFFFu);
+}
+
+// ---- part 3 -----------------------------------------------------------------------
+
+// Refresh the keys of the hits, histogram hits and misses by next iteration.
+__global__ __launch_bounds__(TB) void k_touch(const int32_t* __restrict__ ids,
+                                              const int32_t* __restrict__ next_iter, int64_t n,
+                                              State st, unsigned long long* __restrict__ miss_out) {
+  extern __shared__ uint32_t lds[];  // [S+1] hits, [S+1] misses
+  __shared__ uint32_t red[TB / WAVE];
+  uint32_t* hr = lds;
+  uint32_t* hi = lds + st.S + 1;
+  for (int j = threadIdx.x; j < 2 * (st.S + 1); j += TB) lds[j] = 0;
+  __syncthreads();
+  uint32_t misses = 0;
+  const int64_t base = (int64_t)blockIdx.x * (TB * TOUCH_ITEMS);
+#pragma unroll
+  for (int i = 0; i < TOUCH_ITEMS; ++i) {
+    const int64_t p = base + i * TB + threadIdx.x;
+    if (p < n) {
+      const int32_t nx = next_iter[p];
+      const int32_t line = st.addr[ids[p]];
+      if (line >= 0) {
+        st.res_next[line] = nx;
+        atomicAdd(&hr[nx], 1u);
+      } else {
+        atomicAdd(&hi[nx], 1u);
+        ++misses;
+      }
+    }
+  }
+  misses = wave_reduce_sum(misses);
+  if (lane_id() == 0) red[threadIdx.x / WAVE] = misses;
+  __syncthreads();
+  for (int j = threadIdx.x; j <= st.S; j += TB) {
+    if (hr[j]) atomicAdd(&st.rhist[j], hr[j]);
+    if (hi[j]) atomicAdd(&st.ihist[j], hi[j]);
+  }
+  if (threadIdx.x == 0) {
+    uint32_t s = 0;
+    for (int w = 0; w < TB / WAVE; ++w) s += red[w];
+    if (s) atomicAdd(miss_out, (unsigned long long)s);
+  }
+}
+
+// Single block.  Walks the buckets from "never" downwards until as many candidates as
+// there were misses are dropped; fixes the threshold bucket, what happens inside it, the
+// size of the changeset, and rolls the resident histogram forward to C_{i+1}.
+__global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i,
+                                                   const int64_t* __restrict__ miss_count,
+                                                   int64_t* __restrict__ cs_offsets) {
+  __shared__ int64_t smem[BIG / WAVE + 1];
+  __shared__ int32_t s_jstar;
+  __shared__ uint32_t s_kept;
+  const int32_t S = st.S;
+  const int64_t n_drop = miss_count[i];
+  const int32_t bins = S - i;                     // buckets i+1 .. S, walked as r = S - j
+  const int32_t per = (bins + BIG - 1) / BIG;
+  const int32_t r0 = threadIdx.x * per;
+  int64_t mine = 0;
+  for (int32_t r = r0; r < r0 + per && r < bins; ++r)
+    mine += (int64_t)st.rhist[S - r] + st.ihist[S - r];
+  int64_t total;
+  int64_t before = block_exclusive_scan<int64_t, BIG>(mine, smem, total);
+  if (threadIdx.x == 0) {
+    // default: nothing is dropped (no misses); overwritten below by the thread that
+    // finds the threshold bucket
+    s_jstar = S + 1;
+    s_kept = 0;
+    Ctrl c{};
+    c.jstar = S + 1;
+    c.mode_in = MODE_ALL;
+    c.mode_res = MODE_ALL;
+    c.T = -1;
+    *st.ctrl = c;
+    cs_offsets[i + 1] = cs_offsets[i];
+  }
+  __syncthreads();
+  if (n_drop > 0) {
+    for (int32_t r = r0; r < r0 + per && r < bins; ++r) {
+      const int32_t j = S - r;
+      const int64_t R = st.rhist[j], I = st.ihist[j];
+      if (before <= n_drop && before + R + I > n_drop) {
+        const int64_t rem = n_drop - before;  // still to drop, all from bucket j
+        Ctrl c{};
+        c.jstar = j;
+        int64_t from_res = 0;
+        if (rem == 0) {
+          c.mode_in = MODE_ALL; c.mode_res = MODE_ALL;
+        } else if (rem < I) {
+          c.mode_in = MODE_SELECT; c.mode_res = MODE_ALL; c.keep = (int32_t)(I - rem);
+        } else if (rem == I) {
+          c.mode_in = MODE_NONE; c.mode_res = MODE_ALL;
+        } else {
+          c.mode_in = MODE_NONE; c.mode_res = MODE_SELECT;
+          from_res = rem - I;
+          c.keep = (int32_t)(R - from_res);
+        }
+        c.T = -1;
+        // evictions inside j*; those of the buckets above j* are added after the barrier
+        s_jstar = j;
+        s_kept = (uint32_t)(R + I - rem);
+        c.n_change = (int32_t)from_res;  // completed after the barrier
+        *st.ctrl = c;
+      }
+      before += R + I;
+    }
+  }
+  __syncthreads();
+  const int32_t jstar = s_jstar;
+  // residents evicted from the buckets above j*, and the histogram of C_{i+1}
+  int64_t above = 0;
+  for (int32_t r = r0; r < r0 + per && r < bins; ++r) {
+    const int32_t j = S - r;
+    if (j > jstar) {
+      above += st.rhist[j];
+      st.rhist[j] = 0;
+    } else if (j == jstar) {
+      st.rhist[j] = s_kept;
+    } else {
+      st.rhist[j] += st.ihist[j];
+    }
+    st.ihist[j] = 0;
+  }
+  int64_t above_total;
+  block_exclusive_scan<int64_t, BIG>(above, smem, above_total);
+  if (threadIdx.x == 0 && n_drop > 0) {
+    st.ctrl->n_change += (int32_t)above_total;
+    cs_offsets[i + 1] = cs_offsets[i] + st.ctrl->n_change;
+  }
+}
+
+// Set the bit of every member of the selected class in bucket j*.
+__global__ __launch_bounds__(TB) void k_mark_residents(State st) {
+  const Ctrl c = *st.ctrl;
+  if (c.mode_res != MODE_SELECT) return;
+  const int64_t span = (int64_t)gridDim.x * TB;
+  for (int64_t s = (int64_t)blockIdx.x * TB + threadIdx.x; s < st.cap; s += span)
+    if (st.res_next[s] == c.jstar) {
+      const uint32_t v = (uint32_t)st.res_id[s];
+      atomicOr(&st.bitmap[v >> 5], 1u << (v & 31));
+    }
+}
+
+__global__ __launch_bounds__(TB) void k_mark_incoming(State st, const int32_t* __restrict__ ids,
+                                                      const int32_t* __restrict__ next_iter,
+                                                      int64_t n) {
+  const Ctrl c = *st.ctrl;
+  if (c.mode_in != MODE_SELECT) return;
+  const int64_t p = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (p < n && next_iter[p] == c.jstar) {
+    const uint32_t v = (uint32_t)ids[p];
+    if (st.addr[v] < 0) atomicOr(&st.bitmap[v >> 5], 1u << (v & 31));
+  }
+}
+
+__global__ __launch_bounds__(TB) void k_bits_count(State st, int64_t words) {
+  const Ctrl c = *st.ctrl;
+  if (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT) return;
+  __shared__ uint32_t red[TB / WAVE];
+  const int64_t base = ((int64_t)blockIdx.x * TB + threadIdx.x) * BITS_WORDS;
+  uint32_t cnt = 0;
+#pragma unroll
+  for (int i = 0; i < BITS_WORDS; ++i)
+    if (base + i < words) cnt += __popc(st.bitmap[base + i]);
+  cnt = wave_reduce_sum(cnt);
+  if (lane_id() == 0) red[threadIdx.x / WAVE] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t s = 0;
+    for (int w = 0; w < TB / WAVE; ++w) s += red[w];
+    st.bit_part[blockIdx.x] = s;
+  }
+}
+
+// Single block: T = the id whose bit is the keep-th set bit of the bitmap.
+__global__ __launch_bounds__(BIG) void k_bits_find(State st, int64_t words, int64_t parts) {
+  Ctrl* c = st.ctrl;
+  if (c->mode_res != MODE_SELECT && c->mode_in != MODE_SELECT) return;
+  __shared__ int64_t smem[BIG / WAVE + 1];
+  __shared__ int64_t s_part, s_before;
+  const int64_t keep = c->keep;
+  // 1. the block of words that holds the keep-th set bit
+  const int64_t per = (parts + BIG - 1) / BIG;
+  const int64_t q0 = threadIdx.x * per;
+  int64_t mine = 0;
+  for (int64_t q = q0; q < q0 + per && q < parts; ++q) mine += st.bit_part[q];
+  int64_t total;
+  int64_t before = block_exclusive_scan<int64_t, BIG>(mine, smem, total);
+  if (threadIdx.x == 0) s_part = -1;
+  __syncthreads();
+  for (int64_t q = q0; q < q0 + per && q < parts; ++q) {
+    const int64_t cnt = st.bit_part[q];
+    if (before < keep && before + cnt >= keep) {
+      s_part = q;
+      s_before = before;
+    }
+    before += cnt;
+  }
+  __syncthreads();
+  if (s_part < 0) return;  // fewer set bits than asked for: cannot happen, keep T = -1
+  // 2. the word inside that block (TB*BITS_WORDS words, two per thread of this block)
+  const int64_t wbase = s_part * (TB * BITS_WORDS);
+  constexpr int WPT = TB * BITS_WORDS / BIG;
+  const int64_t w0 = wbase + (int64_t)threadIdx.x * WPT;
+  int64_t cntw = 0;
+  for (int i = 0; i < WPT; ++i)
+    if (w0 + i < words) cntw += __popc(st.bitmap[w0 + i]);
+  int64_t tot2;
+  int64_t bw = s_before + block_exclusive_scan<int64_t, BIG>(cntw, smem, tot2);
+  for (int i = 0; i < WPT; ++i)
+    if (w0 + i < words) {
+      uint32_t word = st.bitmap[w0 + i];
+      const int pc = __popc(word);
+      if (bw < keep && bw + pc >= keep) {
+        int need = (int)(keep - bw);  // the need-th set bit of this word, 1-based
+        int bit = 0;
+        while (true) {
+          bit = __ffs(word) - 1;
+          if (--need == 0) break;
+          word &= word - 1;
+        }
+        c->T = (int32_t)((w0 + i) * 32 + bit);
+      }
+      bw += pc;
+    }
+}
+
+__global__ __launch_bounds__(TB) void k_bits_clear(State st, int64_t words) {
+  const Ctrl c = *st.ctrl;
+  if (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT) return;
+  const int64_t span = (int64_t)gridDim.x * TB;
+  for (int64_t w = (int64_t)blockIdx.x * TB + threadIdx.x; w < words; w += span) st.bitmap[w] = 0;
+}
+
+__device__ __forceinline__ bool evicts(const Ctrl& c, int32_t next, int32_t id) {
+  return next > c.jstar || (next == c.jstar && c.mode_res == MODE_SELECT && id > c.T);
+}
+
+__device__ __forceinline__ bool inserts(const Ctrl& c, int32_t next, int32_t id) {
+  return next < c.jstar ||
+         (next == c.jstar && (c.mode_in == MODE_ALL || (c.mode_in == MODE_SELECT && id <= c.T)));
+}
+
+// Evictions per tile of cache lines.
+__global__ __launch_bounds__(TB) void k_evict_count(State st) {
+  const Ctrl c = *st.ctrl;
+  __shared__ uint32_t red[TB / WAVE];
+  const int64_t base = (int64_t)blockIdx.x * TB * st.tile_items + (int64_t)threadIdx.x * st.tile_items;
+  uint32_t cnt = 0;
+  if (c.n_change > 0)
+    for (int t = 0; t < st.tile_items; ++t) {
+      const int64_t s = base + t;
+      if (s < st.cap) cnt += evicts(c, st.res_next[s], st.res_id[s]);
+    }
+  cnt = wave_reduce_sum(cnt);
+  if (lane_id() == 0) red[threadIdx.x / WAVE] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t s = 0;
+    for (int w = 0; w < TB / WAVE; ++w) s += red[w];
+    st.evict_tiles[blockIdx.x] = s;
+  }
+}
+
+constexpr int IN_ITEMS = 8;
+
+__global__ __launch_bounds__(TB) void k_in_count(State st, const int32_t* __restrict__ ids,
+                                                 const int32_t* __restrict__ next_iter, int64_t n) {
+  const Ctrl c = *st.ctrl;
+  __shared__ uint32_t red[TB / WAVE];
+  const int64_t base = ((int64_t)blockIdx.x * TB + threadIdx.x) * IN_ITEMS;
+  uint32_t cnt = 0;
+  if (c.n_change > 0)
+    for (int t = 0; t < IN_ITEMS; ++t) {
+      const int64_t p = base + t;
+      if (p < n) {
+        const int32_t v = ids[p];
+        cnt += st.addr[v] < 0 && inserts(c, next_iter[p], v);
+      }
+    }
+  cnt = wave_reduce_sum(cnt);
+  if (lane_id() == 0) red[threadIdx.x / WAVE] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t s = 0;
+    for (int w = 0; w < TB / WAVE; ++w) s += red[w];
+    st.in_tiles[blockIdx.x] = s;
+  }
+}
+
+// Two blocks: block 0 scans the eviction tile counts, block 1 the insertion tile counts.
+__global__ __launch_bounds__(BIG) void k_scan_two(uint32_t* a, int64_t na, uint32_t* b, int64_t nb) {
+  __shared__ uint32_t smem[BIG / WAVE + 1];
+  uint32_t* data = blockIdx.x == 0 ? a : b;
+  const int64_t n = blockIdx.x == 0 ? na : nb;
+  uint32_t carry = 0;
+  for (int64_t base = 0; base < n; base += BIG) {
+    const int64_t i = base + threadIdx.x;
+    const uint32_t v = i < n ? data[i] : 0;
+    uint32_t total;
+    const uint32_t ex = block_exclusive_scan<uint32_t, BIG>(v, smem, total);
+    if (i < n) data[i] = carry + ex;
+    carry += total;
+  }
+}
+
+__global__ __launch_bounds__(TB) void k_evict_emit(State st, int32_t i,
+                                                   const int64_t* __restrict__ cs_offsets,
+                                                   int32_t* __restrict__ out_ids,
+                                                   int64_t cs_capacity) {
+  const Ctrl c = *st.ctrl;
+  if (c.n_change <= 0) return;
+  __shared__ uint32_t smem[TB / WAVE + 1];
+  const int64_t base = (int64_t)blockIdx.x * TB * st.tile_items + (int64_t)threadIdx.x * st.tile_items;
+  uint32_t cnt = 0;
+  for (int t = 0; t < st.tile_items; ++t) {
+    const int64_t s = base + t;
+    if (s < st.cap) cnt += evicts(c, st.res_next[s], st.res_id[s]);
+  }
+  uint32_t total;
+  uint32_t at = st.evict_tiles[blockIdx.x] + block_exclusive_scan<uint32_t, TB>(cnt, smem, total);
+  if (!cnt) return;
+  const int64_t dst = cs_offsets[i];
+  for (int t = 0; t < st.tile_items; ++t) {
+    const int64_t s = base + t;
+    if (s < st.cap && evicts(c, st.res_next[s], st.res_id[s])) {
+      if (at < st.max_change) st.out_slot[at] = (int32_t)s;
+      if (dst + at < cs_capacity) out_ids[dst + at] = st.res_id[s];
+      ++at;
+    }
+  }
+}
+
+__global__ __launch_bounds__(TB) void k_in_emit(State st, int32_t i,
+                                                const int32_t* __restrict__ ids,
+                                                const int32_t* __restrict__ next_iter, int64_t n,
+                                                const int64_t* __restrict__ cs_offsets,
+                                                int32_t* __restrict__ in_ids,
+                                                int32_t* __restrict__ in_positions,
+                                                int64_t cs_capacity) {
+  const Ctrl c = *st.ctrl;
+  if (c.n_change <= 0) return;
+  __shared__ uint32_t smem[TB / WAVE + 1];
+  const int64_t base = ((int64_t)blockIdx.x * TB + threadIdx.x) * IN_ITEMS;
+  uint32_t flags = 0, cnt = 0;
+  for (int t = 0; t < IN_ITEMS; ++t) {
+    const int64_t p = base + t;
+    if (p < n) {
+      const int32_t v = ids[p];
+      if (st.addr[v] < 0 && inserts(c, next_iter[p], v)) {
+        flags |= 1u << t;
+        ++cnt;
+      }
+    }
+  }
+  uint32_t total;
+  uint32_t at = st.in_tiles[blockIdx.x] + block_exclusive_scan<uint32_t, TB>(cnt, smem, total);
+  if (!cnt) return;
+  const int64_t dst = cs_offsets[i];
+  for (int t = 0; t < IN_ITEMS; ++t)
+    if (flags >> t & 1) {
+      const int64_t p = base + t;
+      if (at < st.max_change) {
+        st.in_id[at] = ids[p];
+        st.in_next[at] = next_iter[p];
+      }
+      if (dst + at < cs_capacity) {
+        in_ids[dst + at] = ids[p];
+        in_positions[dst + at] = (int32_t)p;
+      }
+      ++at;
+    }
+}
+
+// The t-th inserted row takes the line of the t-th evicted one.
+__global__ __launch_bounds__(TB) void k_apply(State st) {
+  const int32_t n = st.ctrl->n_change;
+  const int64_t t = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (t >= n || t >= st.max_change) return;
+  const int32_t line = st.out_slot[t];
+  const int32_t gone = st.res_id[line];
+  const int32_t v = st.in_id[t];
+  st.res_id[line] = v;
+  st.res_next[line] = st.in_next[t];
+  st.addr[gone] = -1;
+  st.addr[v] = line;
+}
+
+struct Workspace {
+  uint64_t *pairs_a, *pairs_b, *heads_a, *heads_b;
+  uint32_t* hist;
+  uint32_t* head_tiles;
+  int32_t* next_iter;
+  int64_t* d_offsets;
+  int64_t* d_cs_offsets;
+  State st;
+  int64_t look_tiles, evict_tiles, in_tiles, bit_words, bit_parts, max_heads, max_change;
+  size_t bytes;
+};
+
+int bits_for(int64_t values) {  // bits needed to hold 0 .. values-1
+  int b = 1;
+  while (b < 63 && (int64_t(1) << b) < values) ++b;
+  return b;
+}
+
+Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t cap,
+                int64_t max_n) {
+  Arena a(base);
+  Workspace w{};
+  const int64_t t = total > 0 ? total : 1;
+  w.max_heads = t < num_nodes ? t : num_nodes;
+  w.pairs_a = a.take<uint64_t>(t);
+  w.pairs_b = a.take<uint64_t>(t);
+  w.heads_a = a.take<uint64_t>(w.max_heads);
+  w.heads_b = a.take<uint64_t>(w.max_heads);
+  w.hist = a.take<uint32_t>(radix_plan(t).hist_elems);
+  w.look_tiles = ceil_div(t, LOOK_TILE);
+  w.head_tiles = a.take<uint32_t>(w.look_tiles + 1 + scan_scratch_elems(w.look_tiles + 1));
+  w.next_iter = a.take<int32_t>(t);
+  w.d_offsets = a.take<int64_t>(S + 1);
+  w.d_cs_offsets = a.take<int64_t>(S + 1);
+  State& st = w.st;
+  const int64_t c = cap > 0 ? cap : 1;
+  st.cap = cap;
+  st.num_nodes = num_nodes;
+  st.S = S;
+  st.res_id = a.take<int32_t>(c);
+  st.res_next = a.take<int32_t>(c);
+  st.addr = a.take<int32_t>(num_nodes);
+  st.rhist = a.take<uint32_t>(S + 2);
+  st.ihist = a.take<uint32_t>(S + 2);
+  w.bit_words = ceil_div(num_nodes, 32);
+  w.bit_parts = ceil_div(w.bit_words, TB * BITS_WORDS);
+  st.bitmap = a.take<uint32_t>(w.bit_words);
+  st.bit_part = a.take<uint32_t>(w.bit_parts);
+  st.ctrl = a.take<Ctrl>(1);
+  int64_t items = ceil_div(c, (int64_t)TB * 65536);
+  if (items < 8) items = 8;
+  st.tile_items = (int32_t)items;
+  w.evict_tiles = ceil_div(c, (int64_t)TB * items);
+  w.in_tiles = ceil_div(max_n > 0 ? max_n : 1, (int64_t)TB * IN_ITEMS);
+  st.evict_tiles = a.take<uint32_t>(w.evict_tiles);
+  st.in_tiles = a.take<uint32_t>(w.in_tiles);
+  w.max_change = max_n < c ? max_n : c;
+  if (w.max_change < 1) w.max_change = 1;
+  st.out_slot = a.take<int32_t>(w.max_change);
+  st.in_id = a.take<int32_t>(w.max_change);
+  st.in_next = a.take<int32_t>(w.max_change);
+  st.max_change = w.max_change;
+  w.bytes = (a.used + 255) & ~size_t(255);
+  return w;
+}
+
+int32_t check_shape(int64_t num_nodes, int64_t total, int32_t S, int64_t cap, const char* who) {
+  if (num_nodes <= 0 || num_nodes > INT32_MAX)
+    return fail(GINEX_ERR_ARG, "%s: num_nodes=%lld out of range", who, (long long)num_nodes);
+  if (S < 1 || S > 8191) return fail(GINEX_ERR_ARG, "%s: S=%d outside [1, 8191]", who, S);
+  if (total < 0 || total > INT32_MAX)
+    return fail(GINEX_ERR_ARG, "%s: total ids=%lld outside [0, 2^31)", who, (long long)total);
+  if (cap < 0 || cap > INT32_MAX)
+    return fail(GINEX_ERR_ARG, "%s: cap=%lld out of range", who, (long long)cap);
+  return GINEX_OK;
+}
+
+}  // namespace
+}  // namespace ginex
+
+using namespace ginex;
+
+extern "C" size_t ginex_changeset_workspace_bytes(int64_t num_nodes, int64_t total_ids, int32_t S,
+                                                  int64_t cap) {
+  if (check_shape(num_nodes, total_ids, S, cap, "ginex_changeset_workspace_bytes")) return 0;
+  // the longest iteration is not known here: bound it by the total (and by num_nodes,
+  // since the ids of one iteration are distinct)
+  const int64_t max_n = total_ids < num_nodes ? total_ids : num_nodes;
+  return carve(nullptr, num_nodes, total_ids, S, cap, max_n).bytes;
+}
+
+extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
+                                   const int64_t* ids_offsets, int32_t S, int64_t cap,
+                                   int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
+                                   int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
+                                   int64_t* cs_offsets, int64_t* miss_count,
+                                   int64_t* total_changes, void* ws, size_t ws_bytes,
+                                   void* stream) {
+  const char* who = "ginex_changeset";
+  if (!ids_offsets || !init_count || !cs_offsets || !miss_count || !total_changes || !ws)
+    return fail(GINEX_ERR_ARG, "%s: a required pointer is null", who);
+  if (S >= 1 && ids_offsets[0] != 0)
+    return fail(GINEX_ERR_INPUT, "%s: ids_offsets[0] must be 0", who);
+  int64_t max_n = 0;
+  for (int32_t i = 0; S >= 1 && i < S; ++i) {
+    const int64_t n = ids_offsets[i + 1] - ids_offsets[i];
+    if (n < 0) return fail(GINEX_ERR_INPUT, "%s: ids_offsets not monotone at %d", who, i);
+    if (n > num_nodes)
+      return fail(GINEX_ERR_INPUT, "%s: iteration %d has more ids than nodes", who, i);
+    if (n > max_n) max_n = n;
+  }
+  const int64_t total = S >= 1 ? ids_offsets[S] : 0;
+  if (int32_t rc = check_shape(num_nodes, total, S, cap, who)) return rc;
+  if (total > 0 && !ids) return fail(GINEX_ERR_ARG, "%s: ids is null", who);
+  if (cap > 0 && !init_ids) return fail(GINEX_ERR_ARG, "%s: init_ids is null", who);
+  if (cs_capacity < 0 || (cs_capacity > 0 && (!in_ids || !out_ids || !in_positions)))
+    return fail(GINEX_ERR_ARG, "%s: bad changeset output arrays", who);
+  const int64_t bound = total < num_nodes ? total : num_nodes;
+  Workspace w = carve(ws, num_nodes, total, S, cap, bound);
+  if (ws_bytes < w.bytes)
+    return fail(GINEX_ERR_WORKSPACE, "%s: workspace of %zu bytes given, %zu needed", who, ws_bytes,
+                w.bytes);
+  if ((uintptr_t)ws & 255) return fail(GINEX_ERR_ARG, "%s: workspace must be 256-byte aligned", who);
+  hipStream_t st = (hipStream_t)stream;
+  State& state = w.st;
+
+  GINEX_HIP(hipMemcpyAsync(w.d_offsets, ids_offsets, sizeof(int64_t) * (S + 1),
+                           hipMemcpyHostToDevice, st));
+  GINEX_HIP(fill_async<int64_t>(miss_count, S, 0, st));
+  GINEX_HIP(fill_async<int64_t>(cs_offsets, S + 1, 0, st));
+  *init_count = 0;
+  *total_changes = 0;
+  if (total == 0) {
+    GINEX_HIP(hipStreamSynchronize(st));
+    return GINEX_OK;
+  }
+
+  // part 1: sort (node, position) by node, then look right
+  hipLaunchKernelGGL(k_make_pairs, dim3((unsigned)ceil_div(total, TB)), dim3(TB), 0, st, ids, total,
+                     w.pairs_a);
+  GINEX_LAUNCH_CHECK();
+  uint64_t* sorted = nullptr;
+  GINEX_HIP(radix_sort_u64(w.pairs_a, w.pairs_b, total, 32, 32 + bits_for(num_nodes), w.hist, st,
+                           &sorted));
+  hipLaunchKernelGGL(k_look_right, dim3((unsigned)w.look_tiles), dim3(TB), 0, st, sorted, total,
+                     w.d_offsets, S, w.next_iter, w.head_tiles);
+  GINEX_LAUNCH_CHECK();
+  GINEX_HIP(fill_async<uint32_t>(w.head_tiles + w.look_tiles, 1, 0u, st));
+  GINEX_HIP(exclusive_scan_inplace<uint32_t>(w.head_tiles, w.look_tiles + 1,
+                                             w.head_tiles + w.look_tiles + 1, st));
+  uint32_t distinct32 = 0;
+  GINEX_HIP(hipMemcpyAsync(&distinct32, w.head_tiles + w.look_tiles, sizeof(uint32_t),
+                           hipMemcpyDeviceToHost, st));
+  GINEX_HIP(hipStreamSynchronize(st));
+  const int64_t distinct = distinct32;
+  if (distinct > w.max_heads)
+    return fail(GINEX_ERR_INPUT, "%s: %lld distinct ids among %lld nodes: ids out of range?", who,
+                (long long)distinct, (long long)num_nodes);
+
+  // part 2: C_0
+  hipLaunchKernelGGL(k_heads_write, dim3((unsigned)w.look_tiles), dim3(TB), 0, st, sorted, total,
+                     w.d_offsets, S, w.head_tiles, w.heads_a);
+  GINEX_LAUNCH_CHECK();
+  uint64_t* heads = nullptr;
+  GINEX_HIP(radix_sort_u64(w.heads_a, w.heads_b, distinct, 32, 32 + bits_for(S), w.hist, st,
+                           &heads));
+  const int64_t n_init = distinct < cap ? distinct : cap;
+  *init_count = n_init;
+  if (distinct <= cap || cap == 0) {
+    // everything fits (no row ever misses), or there is no cache (every row misses and
+    // nothing is inserted): all changesets are empty
+    if (n_init > 0) {
+      hipLaunchKernelGGL(k_copy_init, dim3((unsigned)ceil_div(n_init, TB)), dim3(TB), 0, st, heads,
+                         n_init, init_ids);
+      GINEX_LAUNCH_CHECK();
+    }
+    if (cap == 0) {
+      // miss_count[i] = |ids_i|
+      std::vector<int64_t> tmp(S);
+      for (int32_t i = 0; i < S; ++i) tmp[i] = ids_offsets[i + 1] - ids_offsets[i];
+      GINEX_HIP(hipMemcpyAsync(miss_count, tmp.data(), sizeof(int64_t) * S, hipMemcpyHostToDevice,
+                               st));
+      GINEX_HIP(hipStreamSynchronize(st));
+      return GINEX_OK;
+    }
+    GINEX_HIP(hipStreamSynchronize(st));
+    return GINEX_OK;
+  }
+  GINEX_HIP(fill_async<int32_t>(state.addr, num_nodes, -1, st));
+  GINEX_HIP(fill_async<uint32_t>(state.rhist, S + 2, 0u, st));
+  GINEX_HIP(fill_async<uint32_t>(state.ihist, S + 2, 0u, st));
+  GINEX_HIP(fill_async<uint32_t>(state.bitmap, w.bit_words, 0u, st));
+  {
+    int64_t blocks = ceil_div(cap, TB * 8);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_init_state, dim3((unsigned)blocks), dim3(TB), sizeof(uint32_t) * (S + 1),
+                       st, heads, cap, init_ids, state);
+    GINEX_LAUNCH_CHECK();
+  }
+
+  // part 3: one round of kernels per iteration, no host round trip in between
+  const size_t touch_lds = sizeof(uint32_t) * 2 * (S + 1);
+  int64_t slot_blocks = ceil_div(cap, TB * 8);
+  if (slot_blocks > 8192) slot_blocks = 8192;
+  int64_t word_blocks = ceil_div(w.bit_words, TB * 8);
+  if (word_blocks > 8192) word_blocks = 8192;
+  for (int32_t i = 0; i < S; ++i) {
+    const int64_t lo = ids_offsets[i];
+    const int64_t n = ids_offsets[i + 1] - lo;
+    const int32_t* ids_i = ids + lo;
+    const int32_t* next_i = w.next_iter + lo;
+    if (n > 0) {
+      hipLaunchKernelGGL(k_touch, dim3((unsigned)ceil_div(n, TB * TOUCH_ITEMS)), dim3(TB), touch_lds,
+                         st, ids_i, next_i, n, state, (unsigned long long*)(miss_count + i));
+      GINEX_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(k_threshold, dim3(1), dim3(BIG), 0, st, state, i, miss_count, cs_offsets);
+    GINEX_LAUNCH_CHECK();
+    if (n == 0) continue;  // nothing missed, nothing changes
+    hipLaunchKernelGGL(k_mark_residents, dim3((unsigned)slot_blocks), dim3(TB), 0, st, state);
+    hipLaunchKernelGGL(k_mark_incoming, dim3((unsigned)ceil_div(n, TB)), dim3(TB), 0, st, state,
+                       ids_i, next_i, n);
+    hipLaunchKernelGGL(k_bits_count, dim3((unsigned)w.bit_parts), dim3(TB), 0, st, state,
+                       w.bit_words);
+    hipLaunchKernelGGL(k_bits_find, dim3(1), dim3(BIG), 0, st, state, w.bit_words, w.bit_parts);
+    hipLaunchKernelGGL(k_bits_clear, dim3((unsigned)word_blocks), dim3(TB), 0, st, state,
+                       w.bit_words);
+    GINEX_LAUNCH_CHECK();
+    const int64_t in_tiles = ceil_div(n, (int64_t)TB * IN_ITEMS);
+    hipLaunchKernelGGL(k_evict_count, dim3((unsigned)w.evict_tiles), dim3(TB), 0, st, state);
+    hipLaunchKernelGGL(k_in_count, dim3((unsigned)in_tiles), dim3(TB), 0, st, state, ids_i, next_i,
+                       n);
+    hipLaunchKernelGGL(k_scan_two, dim3(2), dim3(BIG), 0, st, state.evict_tiles, w.evict_tiles,
+                       state.in_tiles, in_tiles);
+    hipLaunchKernelGGL(k_evict_emit, dim3((unsigned)w.evict_tiles), dim3(TB), 0, st, state, i,
+                       cs_offsets, out_ids, cs_capacity);
+    hipLaunchKernelGGL(k_in_emit, dim3((unsigned)in_tiles), dim3(TB), 0, st, state, i, ids_i, next_i,
+                       n, cs_offsets, in_ids, in_positions, cs_capacity);
+    const int64_t most = n < cap ? n : cap;
+    hipLaunchKernelGGL(k_apply, dim3((unsigned)ceil_div(most, TB)), dim3(TB), 0, st, state);
+    GINEX_LAUNCH_CHECK();
+  }
+  GINEX_HIP(hipMemcpyAsync(total_changes, cs_offsets + S, sizeof(int64_t), hipMemcpyDeviceToHost,
+                           st));
+  GINEX_HIP(hipStreamSynchronize(st));
+  if (*total_changes > cs_capacity)
+    return fail(GINEX_ERR_CAPACITY, "%s: %lld changeset records, capacity %lld", who,
+                (long long)*total_changes, (long long)cs_capacity);
+  return GINEX_OK;
+}

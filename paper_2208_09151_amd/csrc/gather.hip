@@ -1,0 +1,180 @@
+// Executor kernels: feature cache initialization, gather, cache update
+// (Ginex Section 3.1 "Feature Cache Initialization" / "Main Loop", Section 3.3).
+//
+// All three are row copies.  A row of R bytes is moved as R/16 16-byte chunks; one thread
+// moves one chunk, so 16..64 consecutive lanes cover a row and consecutive rows of the
+// output are written back to back (fully coalesced stores).  A thread handles UNROLL
+// chunks that lie far apart to keep several independent loads in flight; the source of a
+// chunk is either a cache line in HBM or a row of the slow tier.
+#include "common.hpp"
+
+namespace ginex {
+namespace {
+
+typedef unsigned int chunk_t __attribute__((ext_vector_type(4)));  // 16 bytes
+constexpr int THREADS = 256;
+constexpr int UNROLL = 4;
+
+// out[p,:] = addr[ids[p]] >= 0 ? rows[addr[ids[p]],:] : slow[ids[p],:]
+__global__ __launch_bounds__(THREADS) void k_gather(
+    const chunk_t* __restrict__ rows, const int32_t* __restrict__ addr,
+    const chunk_t* __restrict__ slow, const int32_t* __restrict__ ids, int64_t n,
+    int32_t cpr /*chunks per row*/, chunk_t* __restrict__ out) {
+  const int64_t total = n * cpr;
+  const int64_t span = (int64_t)gridDim.x * THREADS;
+  int64_t c0 = (int64_t)blockIdx.x * THREADS + threadIdx.x;
+  for (; c0 < total; c0 += span * UNROLL) {
+    chunk_t v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int64_t c = c0 + u * span;
+      if (c < total) {
+        const int64_t p = c / cpr;
+        const int32_t col = (int32_t)(c - p * cpr);
+        const int32_t id = ids[p];
+        const int32_t line = addr[id];
+        const chunk_t* src = line >= 0 ? rows + (int64_t)line * cpr : slow + (int64_t)id * cpr;
+        v[u] = src[col];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int64_t c = c0 + u * span;
+      if (c < total) __builtin_nontemporal_store(v[u], out + c);
+    }
+  }
+}
+
+// line = addr[out_ids[j]]; rows[line,:] = out[in_positions[j],:].  The address table is
+// patched by a second kernel so that every line is resolved before any entry changes
+// (in_ids and out_ids are disjoint, but keeping the phases apart costs nothing).
+__global__ __launch_bounds__(THREADS) void k_update_rows(
+    chunk_t* __restrict__ rows, const int32_t* __restrict__ addr,
+    const chunk_t* __restrict__ out, const int32_t* __restrict__ out_ids,
+    const int32_t* __restrict__ in_positions, int64_t n_change, int32_t cpr) {
+  const int64_t total = n_change * cpr;
+  const int64_t span = (int64_t)gridDim.x * THREADS;
+  for (int64_t c = (int64_t)blockIdx.x * THREADS + threadIdx.x; c < total; c += span) {
+    const int64_t j = c / cpr;
+    const int32_t col = (int32_t)(c - j * cpr);
+    const int32_t line = addr[out_ids[j]];
+    rows[(int64_t)line * cpr + col] = out[(int64_t)in_positions[j] * cpr + col];
+  }
+}
+
+__global__ __launch_bounds__(THREADS) void k_update_addr(
+    int32_t* __restrict__ addr, const int32_t* __restrict__ in_ids,
+    const int32_t* __restrict__ out_ids, int64_t n_change) {
+  const int64_t j = (int64_t)blockIdx.x * THREADS + threadIdx.x;
+  if (j < n_change) {
+    const int32_t o = out_ids[j];
+    const int32_t line = addr[o];
+    addr[o] = -1;
+    addr[in_ids[j]] = line;
+  }
+}
+
+// rows[r,:] = slow[init_ids[r],:]; addr[init_ids[r]] = r
+__global__ __launch_bounds__(THREADS) void k_cache_fill(
+    chunk_t* __restrict__ rows, int32_t* __restrict__ addr, const chunk_t* __restrict__ slow,
+    const int32_t* __restrict__ init_ids, int64_t count, int32_t cpr) {
+  const int64_t total = count * cpr;
+  const int64_t span = (int64_t)gridDim.x * THREADS;
+  int64_t c0 = (int64_t)blockIdx.x * THREADS + threadIdx.x;
+  for (; c0 < total; c0 += span * UNROLL) {
+    chunk_t v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int64_t c = c0 + u * span;
+      if (c < total) {
+        const int64_t r = c / cpr;
+        const int32_t col = (int32_t)(c - r * cpr);
+        const int32_t id = init_ids[r];
+        v[u] = slow[(int64_t)id * cpr + col];
+        if (col == 0) addr[id] = (int32_t)r;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int64_t c = c0 + u * span;
+      if (c < total) rows[c] = v[u];
+    }
+  }
+}
+
+inline unsigned grid_for(int64_t items, int per_thread) {
+  int64_t blocks = ceil_div(items, (int64_t)THREADS * per_thread);
+  if (blocks < 1) blocks = 1;
+  if (blocks > (1 << 20)) blocks = 1 << 20;
+  return (unsigned)blocks;
+}
+
+int32_t check_cache(const ginex_cache_t* c, const char* who) {
+  if (!c) return fail(GINEX_ERR_ARG, "%s: cache descriptor is null", who);
+  if (c->cap < 0 || c->num_nodes <= 0 || c->num_nodes > INT32_MAX || c->cap > INT32_MAX)
+    return fail(GINEX_ERR_ARG, "%s: cap=%lld num_nodes=%lld out of range", who,
+                (long long)c->cap, (long long)c->num_nodes);
+  if (c->row_bytes <= 0 || c->row_bytes % 16 != 0 || c->row_bytes / 16 > INT32_MAX)
+    return fail(GINEX_ERR_ARG, "%s: row_bytes=%lld must be a positive multiple of 16", who,
+                (long long)c->row_bytes);
+  if (!c->addr || !c->slow || (c->cap > 0 && !c->rows))
+    return fail(GINEX_ERR_ARG, "%s: null rows/addr/slow pointer", who);
+  if (((uintptr_t)c->rows | (uintptr_t)c->slow) & 15)
+    return fail(GINEX_ERR_ARG, "%s: rows and slow must be 16-byte aligned", who);
+  return GINEX_OK;
+}
+
+}  // namespace
+}  // namespace ginex
+
+using namespace ginex;
+
+extern "C" int32_t ginex_cache_init(const ginex_cache_t* c, const int32_t* init_ids,
+                                    int64_t init_count, void* stream) {
+  if (int32_t rc = check_cache(c, "ginex_cache_init")) return rc;
+  if (init_count < 0 || init_count > c->cap)
+    return fail(GINEX_ERR_ARG, "ginex_cache_init: init_count=%lld outside [0, cap=%lld]",
+                (long long)init_count, (long long)c->cap);
+  if (init_count > 0 && !init_ids) return fail(GINEX_ERR_ARG, "ginex_cache_init: init_ids is null");
+  hipStream_t st = (hipStream_t)stream;
+  GINEX_HIP(fill_async<int32_t>(c->addr, c->num_nodes, -1, st));
+  if (init_count > 0) {
+    const int32_t cpr = (int32_t)(c->row_bytes / 16);
+    hipLaunchKernelGGL(k_cache_fill, dim3(grid_for(init_count * cpr, UNROLL)), dim3(THREADS), 0,
+                       st, (chunk_t*)c->rows, c->addr, (const chunk_t*)c->slow, init_ids,
+                       init_count, cpr);
+    GINEX_LAUNCH_CHECK();
+  }
+  return GINEX_OK;
+}
+
+extern "C" int32_t ginex_gather(const ginex_cache_t* c, const int32_t* ids, int64_t n, void* out,
+                                const int32_t* in_ids, const int32_t* out_ids,
+                                const int32_t* in_positions, int64_t n_change, void* stream) {
+  if (int32_t rc = check_cache(c, "ginex_gather")) return rc;
+  if (n < 0 || n_change < 0 || n_change > n || n_change > c->cap)
+    return fail(GINEX_ERR_ARG, "ginex_gather: n=%lld n_change=%lld (cap=%lld) inconsistent",
+                (long long)n, (long long)n_change, (long long)c->cap);
+  if (n > 0 && (!ids || !out)) return fail(GINEX_ERR_ARG, "ginex_gather: ids/out is null");
+  if (((uintptr_t)out) & 15) return fail(GINEX_ERR_ARG, "ginex_gather: out must be 16-byte aligned");
+  if (n_change > 0 && (!in_ids || !out_ids || !in_positions))
+    return fail(GINEX_ERR_ARG, "ginex_gather: a changeset list is null");
+  hipStream_t st = (hipStream_t)stream;
+  const int32_t cpr = (int32_t)(c->row_bytes / 16);
+  if (n > 0) {
+    hipLaunchKernelGGL(k_gather, dim3(grid_for(n * cpr, UNROLL)), dim3(THREADS), 0, st,
+                       (const chunk_t*)c->rows, c->addr, (const chunk_t*)c->slow, ids, n, cpr,
+                       (chunk_t*)out);
+    GINEX_LAUNCH_CHECK();
+  }
+  if (n_change > 0) {
+    hipLaunchKernelGGL(k_update_rows, dim3(grid_for(n_change * cpr, 1)), dim3(THREADS), 0, st,
+                       (chunk_t*)c->rows, c->addr, (const chunk_t*)out, out_ids, in_positions,
+                       n_change, cpr);
+    GINEX_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_update_addr, dim3(grid_for(n_change, 1)), dim3(THREADS), 0, st, c->addr,
+                       in_ids, out_ids, n_change);
+    GINEX_LAUNCH_CHECK();
+  }
+  return GINEX_OK;
+}

@@ -1,0 +1,582 @@
+// Superbatch neighbour sampling on gfx950 (Ginex Section 3.1 "Superbatch Sample";
+// sampling rule of Section 2.1 "Neighborhood Sampling").
+//
+// All S batches of the superbatch advance hop by hop in the same launches, so a hop is a
+// handful of grid-wide kernels over (batch, frontier slot) instead of S small ones:
+//
+//   pick    a group of G lanes (G = 16/32/64 >= fanout) serves one frontier node: the
+//           lanes draw their Philox words in parallel, resolve Floyd's subset rule with
+//           group ballots, rank the picks, read the neighbours and insert them into the
+//           batch's open-addressing hash table with atomicMin(candidate rank).  The rank
+//           (frontier slot * fanout + pick slot) is exactly the order in which a
+//           sequential scan would meet the candidate, so after the kernel every new id
+//           holds the rank of its first occurrence.
+//   count   per 256 frontier slots: number of picks and number of first occurrences.
+//   scan    one block per batch scans its tile counts; one block turns the per-batch
+//           totals into output offsets.
+//   emit    recomputes the first-occurrence flags, appends the new ids to the batch's
+//           list at their scanned positions, stores their final list position in the
+//           hash table and writes the hop's rowptr.
+//   col     every pick looks its final position up and writes adj_col.
+//
+// The seeds go through the same count/scan/emit path as a stage with one candidate per
+// slot, which also removes repeated seeds.
+#include "common.hpp"
+
+namespace ginex {
+namespace {
+
+constexpr int TB = 256;                  // threads per block everywhere in this file
+constexpr uint32_t EMPTY = 0xFFFFFFFFu;  // free hash slot / "no value yet"
+constexpr uint32_t PEND = 0x40000000u;   // value = PEND + rank while an id is new in this stage
+
+// Philox4x32-10 (Salmon et al., SC'11), counter (node, batch, hop, draw), key = seed.
+// Returns words 0 (low) and 1 (high) of the block as one 64-bit draw.
+__device__ __forceinline__ uint64_t philox_draw(uint64_t seed, uint32_t node, uint32_t batch,
+                                                uint32_t hop, uint32_t draw) {
+  uint32_t c0 = node, c1 = batch, c2 = hop, c3 = draw;
+  uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return ((uint64_t)c1 << 32) | c0;
+}
+
+struct Tables {
+  uint32_t* tab;         // [S][table_slots][2]: key, value
+  int64_t table_slots;   // power of two
+  uint32_t mask;
+  int shift;             // 32 - log2(table_slots)
+  int32_t* cand;         // [S][cand_slots] candidate node ids of the running stage
+  uint32_t* hslot;       // [S][cand_slots] hash slot of each candidate
+  uint8_t* cnt;          // [S][fr_slots] picks per frontier slot
+  int64_t cand_slots, fr_slots;
+  int32_t* wlist;        // [S][stride_ids] the growing list of every batch
+  int64_t stride_ids;
+};
+
+__device__ __forceinline__ uint32_t table_insert(uint32_t* t, uint32_t mask, int shift,
+                                                 uint32_t id, uint32_t value) {
+  uint32_t h = (id * 2654435761u) >> shift;
+  while (true) {
+    const uint32_t old = atomicCAS(&t[2 * (size_t)h], EMPTY, id);
+    if (old == EMPTY || old == id) break;
+    h = (h + 1) & mask;
+  }
+  atomicMin(&t[2 * (size_t)h + 1], value);
+  return h;
+}
+
+// Stage "seeds": slot j of batch b holds seed j.
+__global__ __launch_bounds__(TB) void k_seed_stage(Tables T, const int32_t* __restrict__ seeds,
+                                                   const int64_t* __restrict__ seed_off,
+                                                   const int32_t* __restrict__ nfront) {
+  const int b = blockIdx.y;
+  const int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (j >= nfront[b]) return;
+  const uint32_t id = (uint32_t)seeds[seed_off[b] + j];
+  uint32_t* t = T.tab + (size_t)b * T.table_slots * 2;
+  T.cand[b * T.cand_slots + j] = (int32_t)id;
+  T.hslot[b * T.cand_slots + j] = table_insert(t, T.mask, T.shift, id, PEND + (uint32_t)j);
+  T.cnt[b * T.fr_slots + j] = 1;
+}
+
+template <int G, typename OffT>
+__global__ __launch_bounds__(TB) void k_pick(Tables T, const OffT* __restrict__ offsets,
+                                             const int32_t* __restrict__ indices,
+                                             const int32_t* __restrict__ nfront, int k, int hop,
+                                             uint64_t seed, uint32_t first_batch) {
+  const int b = blockIdx.y;
+  const int lane = lane_id();
+  const int sub = threadIdx.x & (G - 1);
+  const int64_t idx = (int64_t)blockIdx.x * (TB / G) + threadIdx.x / G;
+  const bool active = idx < nfront[b];
+  const uint32_t v = active ? (uint32_t)T.wlist[b * T.stride_ids + idx] : 0u;
+  int64_t lo = 0, deg = 0;
+  if (active) {
+    lo = (int64_t)offsets[v];
+    deg = (int64_t)offsets[v + 1] - lo;
+  }
+  const int c = deg < k ? (int)deg : k;
+  int64_t pick = sub;   // row position taken by this lane
+  int slot = sub;       // its place among the node's picks (ascending position)
+  if (__any(deg > k)) {
+    // Floyd's subset rule, every lane of the wave takes part so that the group
+    // shuffles and ballots stay convergent; groups with deg <= k discard the result.
+    const int64_t d = deg > k ? deg : (int64_t)k + 1;
+    const int64_t j = d - k + sub;
+    const uint64_t r = philox_draw(seed, v, first_batch + (uint32_t)b, (uint32_t)hop, (uint32_t)sub);
+    const int64_t t = (int64_t)__umul64hi(r, (uint64_t)(j + 1));
+    int64_t mine = t;
+    const int group_shift = lane & ~(G - 1);
+    const uint64_t group_mask = G == 64 ? ~0ull : ((1ull << G) - 1);
+    for (int i = 1; i < k; ++i) {
+      const int64_t ti = __shfl(t, i, G);
+      const uint64_t hit = (__ballot(sub < i && mine == ti) >> group_shift) & group_mask;
+      if (sub == i && hit) mine = j;
+    }
+    int rank = 0;
+    for (int m = 0; m < k; ++m) rank += __shfl(mine, m, G) < mine;
+    if (deg > k) {
+      pick = mine;
+      slot = rank;
+    }
+  }
+  if (active && sub < c) {
+    const uint32_t u = (uint32_t)indices[lo + pick];
+    const int64_t at = b * T.cand_slots + idx * k + slot;
+    uint32_t* t = T.tab + (size_t)b * T.table_slots * 2;
+    T.cand[at] = (int32_t)u;
+    T.hslot[at] = table_insert(t, T.mask, T.shift, u, PEND + (uint32_t)(idx * k + slot));
+  }
+  if (active && sub == 0) T.cnt[b * T.fr_slots + idx] = (uint8_t)c;
+}
+
+// Per frontier slot: picks made and first occurrences among them (bit t of `first`).
+__device__ __forceinline__ int slot_flags(const Tables& T, int b, int64_t idx, int k, int active,
+                                          uint64_t& first) {
+  first = 0;
+  if (!active) return 0;
+  const int c = T.cnt[b * T.fr_slots + idx];
+  const uint32_t* t = T.tab + (size_t)b * T.table_slots * 2;
+  const int64_t at = b * T.cand_slots + idx * k;
+  for (int s = 0; s < c; ++s)
+    if (t[2 * (size_t)T.hslot[at + s] + 1] == PEND + (uint32_t)(idx * k + s)) first |= 1ull << s;
+  return c;
+}
+
+// tile_sums[b][tile] = (picks << 32 | first occurrences) of 256 frontier slots
+__global__ __launch_bounds__(TB) void k_count(Tables T, const int32_t* __restrict__ nfront, int k,
+                                              uint64_t* __restrict__ tile_sums, int64_t tiles) {
+  __shared__ uint64_t red[TB / WAVE];
+  const int b = blockIdx.y;
+  const int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x;
+  uint64_t first;
+  const int c = slot_flags(T, b, idx, k, idx < nfront[b], first);
+  uint64_t packed = ((uint64_t)c << 32) | (uint64_t)__popcll(first);
+  packed = wave_reduce_sum(packed);
+  if (lane_id() == 0) red[threadIdx.x / WAVE] = packed;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint64_t s = 0;
+    for (int w = 0; w < TB / WAVE; ++w) s += red[w];
+    tile_sums[b * tiles + blockIdx.x] = s;
+  }
+}
+
+// One block per batch: exclusive scan of the batch's tile sums, in place; totals out.
+__global__ __launch_bounds__(TB) void k_scan_batch(uint64_t* __restrict__ tile_sums, int64_t tiles,
+                                                   const int32_t* __restrict__ nfront,
+                                                   uint64_t* __restrict__ batch_total) {
+  __shared__ uint64_t smem[TB / WAVE + 1];
+  const int b = blockIdx.x;
+  const int64_t used = ((int64_t)nfront[b] + TB - 1) / TB;
+  uint64_t carry = 0;
+  for (int64_t base = 0; base < used; base += TB) {
+    const int64_t i = base + threadIdx.x;
+    const uint64_t v = i < used ? tile_sums[b * tiles + i] : 0;
+    uint64_t total;
+    const uint64_t ex = block_exclusive_scan<uint64_t, TB>(v, smem, total);
+    if (i < used) tile_sums[b * tiles + i] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) batch_total[b] = carry;
+}
+
+struct Meta {            // device mirror of the small host outputs
+  int64_t* ids_offsets;  // [S+1]
+  int64_t* hop_sizes;    // [S*(H+1)]
+  int64_t* row_off;      // [S*H+1]
+  int64_t* col_off;      // [S*H+1]
+  int64_t* totals;       // [0] ids, [1] rowptr entries, [2] col entries
+};
+
+// Single block: per-batch output bases of the stage, new list lengths, running totals.
+// stage < 0 is the seed stage.
+__global__ __launch_bounds__(TB) void k_stage_offsets(
+    Meta M, int S, int H, int stage, const uint64_t* __restrict__ batch_total,
+    const int32_t* __restrict__ nfront, const int32_t* __restrict__ nlist,
+    int32_t* __restrict__ nlist_next, int64_t* __restrict__ row_base,
+    int64_t* __restrict__ col_base) {
+  __shared__ int64_t smem[TB / WAVE + 1];
+  int64_t row_run = stage < 0 ? 0 : M.totals[1];
+  int64_t col_run = stage < 0 ? 0 : M.totals[2];
+  for (int base = 0; base < S; base += TB) {
+    const int b = base + threadIdx.x;
+    const bool ok = b < S;
+    const uint64_t tot = ok ? batch_total[b] : 0;
+    const int64_t rows = ok ? (int64_t)nfront[b] + 1 : 0;
+    const int64_t cols = (int64_t)(tot >> 32);
+    int64_t rt, ct;
+    const int64_t rex = block_exclusive_scan<int64_t, TB>(rows, smem, rt);
+    const int64_t cex = block_exclusive_scan<int64_t, TB>(cols, smem, ct);
+    if (ok) {
+      const int32_t grown = nlist[b] + (int32_t)(tot & 0xFFFFFFFFu);
+      nlist_next[b] = grown;
+      M.hop_sizes[(int64_t)b * (H + 1) + stage + 1] = grown;
+      if (stage >= 0) {
+        row_base[b] = row_run + rex;
+        col_base[b] = col_run + cex;
+        M.row_off[(int64_t)stage * S + b] = row_run + rex;
+        M.col_off[(int64_t)stage * S + b] = col_run + cex;
+      }
+    }
+    row_run += rt;
+    col_run += ct;
+  }
+  if (threadIdx.x == 0) {
+    if (stage < 0) {
+      M.totals[1] = 0;
+      M.totals[2] = 0;
+    } else {
+      M.totals[1] = row_run;
+      M.totals[2] = col_run;
+      if (stage == H - 1) {
+        M.row_off[(int64_t)S * H] = row_run;
+        M.col_off[(int64_t)S * H] = col_run;
+      }
+    }
+  }
+}
+
+// Appends first occurrences to the lists, fixes their table values, writes rowptr.
+__global__ __launch_bounds__(TB) void k_emit(Tables T, const int32_t* __restrict__ nfront,
+                                             const int32_t* __restrict__ nlist, int k,
+                                             const uint64_t* __restrict__ tile_sums, int64_t tiles,
+                                             int64_t* __restrict__ rowptr, int64_t rowptr_capacity,
+                                             const int64_t* __restrict__ row_base) {
+  __shared__ uint64_t smem[TB / WAVE + 1];
+  const int b = blockIdx.y;
+  const int nf = nfront[b];
+  if ((int64_t)blockIdx.x * TB >= nf && !(blockIdx.x == 0)) return;
+  const int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x;
+  const bool active = idx < nf;
+  uint64_t first;
+  const int c = slot_flags(T, b, idx, k, active, first);
+  const uint64_t packed = ((uint64_t)c << 32) | (uint64_t)__popcll(first);
+  uint64_t total;
+  const uint64_t ex = block_exclusive_scan<uint64_t, TB>(packed, smem, total) +
+                      tile_sums[b * tiles + blockIdx.x];
+  const int64_t edges_before = (int64_t)(ex >> 32);
+  if (rowptr) {
+    const int64_t rb = row_base[b];
+    if (active && rb + idx < rowptr_capacity) rowptr[rb + idx] = edges_before;
+    if ((active && idx == nf - 1) || (nf == 0 && idx == 0)) {
+      const int64_t last = nf == 0 ? 0 : idx + 1;
+      if (rb + last < rowptr_capacity) rowptr[rb + last] = edges_before + c;
+    }
+  }
+  if (first) {
+    uint32_t at_list = (uint32_t)nlist[b] + (uint32_t)(ex & 0xFFFFFFFFu);
+    uint32_t* t = T.tab + (size_t)b * T.table_slots * 2;
+    const int64_t at = b * T.cand_slots + idx * k;
+    for (int s = 0; s < c; ++s)
+      if (first >> s & 1) {
+        T.wlist[b * T.stride_ids + at_list] = T.cand[at + s];
+        t[2 * (size_t)T.hslot[at + s] + 1] = at_list;
+        ++at_list;
+      }
+  }
+}
+
+__global__ __launch_bounds__(TB) void k_col(Tables T, const int32_t* __restrict__ nfront, int k,
+                                            const int64_t* __restrict__ rowptr,
+                                            int64_t rowptr_capacity,
+                                            const int64_t* __restrict__ row_base,
+                                            int32_t* __restrict__ col, int64_t col_capacity,
+                                            const int64_t* __restrict__ col_base) {
+  const int b = blockIdx.y;
+  const int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (idx >= nfront[b] || row_base[b] + idx >= rowptr_capacity) return;
+  const int c = T.cnt[b * T.fr_slots + idx];
+  const uint32_t* t = T.tab + (size_t)b * T.table_slots * 2;
+  const int64_t at = b * T.cand_slots + idx * k;
+  const int64_t dst = col_base[b] + rowptr[row_base[b] + idx];
+  for (int s = 0; s < c; ++s)
+    if (dst + s < col_capacity) col[dst + s] = (int32_t)t[2 * (size_t)T.hslot[at + s] + 1];
+}
+
+__global__ __launch_bounds__(TB) void k_ids_offsets(Meta M, int S, const int32_t* __restrict__ nlist) {
+  __shared__ int64_t smem[TB / WAVE + 1];
+  int64_t run = 0;
+  for (int base = 0; base < S; base += TB) {
+    const int b = base + threadIdx.x;
+    const int64_t n = b < S ? nlist[b] : 0;
+    int64_t total;
+    const int64_t ex = block_exclusive_scan<int64_t, TB>(n, smem, total);
+    if (b < S) M.ids_offsets[b] = run + ex;
+    run += total;
+  }
+  if (threadIdx.x == 0) {
+    M.ids_offsets[S] = run;
+    M.totals[0] = run;
+  }
+}
+
+__global__ __launch_bounds__(TB) void k_copy_ids(Tables T, Meta M, const int32_t* __restrict__ nlist,
+                                                 int32_t* __restrict__ ids, int64_t ids_capacity) {
+  const int b = blockIdx.y;
+  const int64_t n = nlist[b];
+  const int64_t dst = M.ids_offsets[b];
+  for (int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x; j < n; j += (int64_t)gridDim.x * TB)
+    if (dst + j < ids_capacity) ids[dst + j] = T.wlist[b * T.stride_ids + j];
+}
+
+__global__ void k_seed_counts(const int64_t* __restrict__ seed_off, int S, int32_t* nfront,
+                              int32_t* nlist) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < S) {
+    nfront[b] = (int32_t)(seed_off[b + 1] - seed_off[b]);
+    nlist[b] = 0;
+  }
+}
+
+struct Plan {
+  int64_t stride_front[GINEX_MAX_HOPS];  // bound on the frontier at hop h, per batch
+  int64_t stride_ids;                    // bound on the final list, per batch
+  int64_t cand_slots, fr_slots, tiles, table_slots;
+  int shift;
+  bool ok;
+};
+
+Plan make_plan(int64_t num_nodes, int64_t max_batch, const int32_t* fanout, int32_t H) {
+  Plan p{};
+  p.ok = true;
+  // the seed stage has one slot per given seed (repeats included); after it a list never
+  // holds more than num_nodes entries
+  p.cand_slots = p.fr_slots = max_batch > 1 ? max_batch : 1;
+  int64_t front = max_batch < num_nodes ? max_batch : num_nodes;
+  if (front < 1) front = 1;
+  for (int h = 0; h < H; ++h) {
+    p.stride_front[h] = front;
+    if (front * fanout[h] > p.cand_slots) p.cand_slots = front * fanout[h];
+    if (front > p.fr_slots) p.fr_slots = front;
+    int64_t next = front * (1 + (int64_t)fanout[h]);
+    front = next < num_nodes ? next : num_nodes;
+  }
+  p.stride_ids = front;
+  if (p.cand_slots >= (int64_t)PEND || p.stride_ids >= (int64_t)PEND) p.ok = false;
+  p.tiles = ceil_div(p.fr_slots, TB);
+  p.table_slots = 16;
+  int lg = 4;
+  while (p.table_slots < 2 * p.stride_ids) {
+    p.table_slots <<= 1;
+    ++lg;
+  }
+  p.shift = 32 - lg;
+  return p;
+}
+
+struct Workspace {
+  uint32_t* tab;
+  int32_t* wlist;
+  int32_t* cand;
+  uint32_t* hslot;
+  uint8_t* cnt;
+  uint64_t* tile_sums;
+  uint64_t* batch_total;
+  int32_t *nfront, *nlist_a, *nlist_b;
+  int64_t *row_base, *col_base, *seed_off;
+  int64_t* meta;
+  size_t bytes;
+};
+
+int64_t meta_elems(int32_t S, int32_t H) {
+  return (int64_t)(S + 1) + (int64_t)S * (H + 1) + 2 * ((int64_t)S * H + 1) + 4;
+}
+
+Workspace carve(void* base, const Plan& p, int32_t S, int32_t H) {
+  Arena a(base);
+  Workspace w;
+  w.tab = a.take<uint32_t>((size_t)S * p.table_slots * 2);
+  w.wlist = a.take<int32_t>((size_t)S * p.stride_ids);
+  w.cand = a.take<int32_t>((size_t)S * p.cand_slots);
+  w.hslot = a.take<uint32_t>((size_t)S * p.cand_slots);
+  w.cnt = a.take<uint8_t>((size_t)S * p.fr_slots);
+  w.tile_sums = a.take<uint64_t>((size_t)S * p.tiles);
+  w.batch_total = a.take<uint64_t>(S);
+  w.nfront = a.take<int32_t>(S);
+  w.nlist_a = a.take<int32_t>(S);
+  w.nlist_b = a.take<int32_t>(S);
+  w.row_base = a.take<int64_t>(S);
+  w.col_base = a.take<int64_t>(S);
+  w.seed_off = a.take<int64_t>(S + 1);
+  w.meta = a.take<int64_t>(meta_elems(S, H));
+  w.bytes = (a.used + 255) & ~size_t(255);
+  return w;
+}
+
+int32_t check_shape(int64_t num_nodes, int32_t S, int64_t max_batch, const int32_t* fanout,
+                    int32_t H, const char* who) {
+  if (num_nodes <= 0 || num_nodes > INT32_MAX)
+    return fail(GINEX_ERR_ARG, "%s: num_nodes=%lld out of range", who, (long long)num_nodes);
+  if (S < 1 || S > 65535) return fail(GINEX_ERR_ARG, "%s: S=%d outside [1, 65535]", who, S);
+  if (max_batch < 0) return fail(GINEX_ERR_ARG, "%s: negative batch size", who);
+  if (H < 1 || H > GINEX_MAX_HOPS || !fanout)
+    return fail(GINEX_ERR_ARG, "%s: H=%d outside [1, %d] or fanout null", who, H, GINEX_MAX_HOPS);
+  for (int h = 0; h < H; ++h)
+    if (fanout[h] < 1 || fanout[h] > GINEX_MAX_FANOUT)
+      return fail(GINEX_ERR_ARG, "%s: fanout[%d]=%d outside [1, %d]", who, h, fanout[h],
+                  GINEX_MAX_FANOUT);
+  return GINEX_OK;
+}
+
+template <typename OffT>
+void launch_pick(const Tables& T, const Plan& p, const void* offsets, const int32_t* indices,
+                 const int32_t* nfront, int k, int hop, int32_t S, uint64_t seed,
+                 uint32_t first_batch, hipStream_t st) {
+  const OffT* off = static_cast<const OffT*>(offsets);
+  const int64_t front = p.stride_front[hop];
+  if (k <= 16)
+    hipLaunchKernelGGL((k_pick<16, OffT>), dim3((unsigned)ceil_div(front, TB / 16), S), dim3(TB), 0,
+                       st, T, off, indices, nfront, k, hop, seed, first_batch);
+  else if (k <= 32)
+    hipLaunchKernelGGL((k_pick<32, OffT>), dim3((unsigned)ceil_div(front, TB / 32), S), dim3(TB), 0,
+                       st, T, off, indices, nfront, k, hop, seed, first_batch);
+  else
+    hipLaunchKernelGGL((k_pick<64, OffT>), dim3((unsigned)ceil_div(front, TB / 64), S), dim3(TB), 0,
+                       st, T, off, indices, nfront, k, hop, seed, first_batch);
+}
+
+}  // namespace
+}  // namespace ginex
+
+using namespace ginex;
+
+extern "C" size_t ginex_sample_workspace_bytes(int64_t num_nodes, int32_t S, int64_t max_batch,
+                                               const int32_t* fanout, int32_t H) {
+  if (check_shape(num_nodes, S, max_batch, fanout, H, "ginex_sample_workspace_bytes")) return 0;
+  const Plan p = make_plan(num_nodes, max_batch, fanout, H);
+  if (!p.ok) {
+    set_error("ginex_sample_workspace_bytes: a batch could exceed 2^30 list entries");
+    return 0;
+  }
+  return carve(nullptr, p, S, H).bytes;
+}
+
+extern "C" int32_t ginex_sample_superbatch(
+    const ginex_csr_t* g, const int32_t* seeds, const int64_t* seed_offsets, int32_t S,
+    const int32_t* fanout, int32_t H, uint64_t rng_seed, uint32_t first_batch_index,
+    int32_t* ids, int64_t ids_capacity, int64_t* ids_offsets, int64_t* hop_sizes,
+    int64_t* adj_rowptr, int64_t rowptr_capacity, int32_t* adj_col, int64_t col_capacity,
+    int64_t* adj_row_offsets, int64_t* adj_col_offsets, int64_t* totals, void* ws,
+    size_t ws_bytes, void* stream) {
+  const char* who = "ginex_sample_superbatch";
+  if (!g || !g->offsets || (g->num_edges > 0 && !g->indices))
+    return fail(GINEX_ERR_ARG, "%s: graph descriptor or its arrays are null", who);
+  if (!seed_offsets || !ids_offsets || !hop_sizes || !adj_row_offsets || !adj_col_offsets ||
+      !totals || !ws)
+    return fail(GINEX_ERR_ARG, "%s: a required pointer is null", who);
+  if ((adj_rowptr == nullptr) != (adj_col == nullptr))
+    return fail(GINEX_ERR_ARG, "%s: adj_rowptr and adj_col must both be given or both be null", who);
+  if (ids_capacity < 0 || rowptr_capacity < 0 || col_capacity < 0 || (ids_capacity > 0 && !ids))
+    return fail(GINEX_ERR_ARG, "%s: bad output capacity", who);
+  int64_t max_batch = 0;
+  if (S >= 1) {
+    if (seed_offsets[0] != 0) return fail(GINEX_ERR_INPUT, "%s: seed_offsets[0] must be 0", who);
+    for (int b = 0; b < S; ++b) {
+      const int64_t n = seed_offsets[b + 1] - seed_offsets[b];
+      if (n < 0) return fail(GINEX_ERR_INPUT, "%s: seed_offsets not monotone at %d", who, b);
+      if (n > max_batch) max_batch = n;
+    }
+  }
+  if (int32_t rc = check_shape(g->num_nodes, S, max_batch, fanout, H, who)) return rc;
+  if (seed_offsets[S] > 0 && !seeds) return fail(GINEX_ERR_ARG, "%s: seeds is null", who);
+  const Plan p = make_plan(g->num_nodes, max_batch, fanout, H);
+  if (!p.ok) return fail(GINEX_ERR_ARG, "%s: a batch could exceed 2^30 list entries", who);
+  const Workspace w = carve(ws, p, S, H);
+  if (ws_bytes < w.bytes)
+    return fail(GINEX_ERR_WORKSPACE, "%s: workspace of %zu bytes given, %zu needed", who, ws_bytes,
+                w.bytes);
+  if ((uintptr_t)ws & 255) return fail(GINEX_ERR_ARG, "%s: workspace must be 256-byte aligned", who);
+
+  hipStream_t st = (hipStream_t)stream;
+  Tables T;
+  T.tab = w.tab; T.table_slots = p.table_slots; T.mask = (uint32_t)(p.table_slots - 1);
+  T.shift = p.shift; T.cand = w.cand; T.hslot = w.hslot; T.cnt = w.cnt;
+  T.cand_slots = p.cand_slots; T.fr_slots = p.fr_slots; T.wlist = w.wlist;
+  T.stride_ids = p.stride_ids;
+  Meta M;
+  M.ids_offsets = w.meta;
+  M.hop_sizes = M.ids_offsets + (S + 1);
+  M.row_off = M.hop_sizes + (int64_t)S * (H + 1);
+  M.col_off = M.row_off + ((int64_t)S * H + 1);
+  M.totals = M.col_off + ((int64_t)S * H + 1);
+
+  GINEX_HIP(hipMemcpyAsync(w.seed_off, seed_offsets, sizeof(int64_t) * (S + 1),
+                           hipMemcpyHostToDevice, st));
+  GINEX_HIP(fill_async<uint32_t>(w.tab, (int64_t)S * p.table_slots * 2, EMPTY, st));
+  hipLaunchKernelGGL(k_seed_counts, dim3((unsigned)ceil_div(S, TB)), dim3(TB), 0, st, w.seed_off, S,
+                     w.nfront, w.nlist_a);
+  GINEX_LAUNCH_CHECK();
+
+  int32_t* nlist = w.nlist_a;
+  int32_t* nlist_next = w.nlist_b;
+  for (int stage = -1; stage < H; ++stage) {
+    const int k = stage < 0 ? 1 : fanout[stage];
+    const int64_t front = stage < 0 ? (max_batch > 0 ? max_batch : 1) : p.stride_front[stage];
+    // in a hop the frontier is the whole list as it stands when the hop starts
+    const int32_t* nfront = stage < 0 ? w.nfront : nlist;
+    const dim3 grid_slots((unsigned)ceil_div(front, TB), S);
+    if (stage < 0) {
+      hipLaunchKernelGGL(k_seed_stage, grid_slots, dim3(TB), 0, st, T, seeds, w.seed_off, nfront);
+    } else if (g->offsets_64) {
+      launch_pick<int64_t>(T, p, g->offsets, g->indices, nfront, k, stage, S, rng_seed,
+                           first_batch_index, st);
+    } else {
+      launch_pick<int32_t>(T, p, g->offsets, g->indices, nfront, k, stage, S, rng_seed,
+                           first_batch_index, st);
+    }
+    GINEX_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_count, grid_slots, dim3(TB), 0, st, T, nfront, k, w.tile_sums, p.tiles);
+    GINEX_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_scan_batch, dim3(S), dim3(TB), 0, st, w.tile_sums, p.tiles, nfront,
+                       w.batch_total);
+    GINEX_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_stage_offsets, dim3(1), dim3(TB), 0, st, M, S, H, stage, w.batch_total,
+                       nfront, nlist, nlist_next, w.row_base, w.col_base);
+    GINEX_LAUNCH_CHECK();
+    const bool adj = stage >= 0 && adj_rowptr != nullptr;
+    hipLaunchKernelGGL(k_emit, grid_slots, dim3(TB), 0, st, T, nfront, nlist, k, w.tile_sums,
+                       p.tiles, adj ? adj_rowptr : (int64_t*)nullptr, rowptr_capacity, w.row_base);
+    GINEX_LAUNCH_CHECK();
+    if (adj) {
+      hipLaunchKernelGGL(k_col, grid_slots, dim3(TB), 0, st, T, nfront, k, adj_rowptr,
+                         rowptr_capacity, w.row_base, adj_col, col_capacity, w.col_base);
+      GINEX_LAUNCH_CHECK();
+    }
+    int32_t* t = nlist; nlist = nlist_next; nlist_next = t;
+  }
+  hipLaunchKernelGGL(k_ids_offsets, dim3(1), dim3(TB), 0, st, M, S, nlist);
+  GINEX_LAUNCH_CHECK();
+  if (ids_capacity > 0) {
+    hipLaunchKernelGGL(k_copy_ids, dim3((unsigned)ceil_div(p.stride_ids, TB * 4), S), dim3(TB), 0,
+                       st, T, M, nlist, ids, ids_capacity);
+    GINEX_LAUNCH_CHECK();
+  }
+  GINEX_HIP(hipMemcpyAsync(ids_offsets, M.ids_offsets, sizeof(int64_t) * (S + 1),
+                           hipMemcpyDeviceToHost, st));
+  GINEX_HIP(hipMemcpyAsync(hop_sizes, M.hop_sizes, sizeof(int64_t) * S * (H + 1),
+                           hipMemcpyDeviceToHost, st));
+  GINEX_HIP(hipMemcpyAsync(adj_row_offsets, M.row_off, sizeof(int64_t) * ((int64_t)S * H + 1),
+                           hipMemcpyDeviceToHost, st));
+  GINEX_HIP(hipMemcpyAsync(adj_col_offsets, M.col_off, sizeof(int64_t) * ((int64_t)S * H + 1),
+                           hipMemcpyDeviceToHost, st));
+  GINEX_HIP(hipMemcpyAsync(totals, M.totals, sizeof(int64_t) * 3, hipMemcpyDeviceToHost, st));
+  GINEX_HIP(hipStreamSynchronize(st));
+  if (totals[0] > ids_capacity)
+    return fail(GINEX_ERR_CAPACITY, "%s: ids needs %lld entries, capacity %lld", who,
+                (long long)totals[0], (long long)ids_capacity);
+  if (adj_rowptr && (totals[1] > rowptr_capacity || totals[2] > col_capacity))
+    return fail(GINEX_ERR_CAPACITY, "%s: adj needs %lld rowptr / %lld col entries", who,
+                (long long)totals[1], (long long)totals[2]);
+  return GINEX_OK;
+}

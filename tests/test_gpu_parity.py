@@ -1,0 +1,281 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
+
+Tolerance is zero: everything on this path is integer work or byte copies.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workload import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a, dtype=None):
+    t = torch.as_tensor(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+@pytest.fixture(scope="module")
+def ginex():
+    import paper_2208_09151_amd as g
+    assert torch.cuda.is_available()
+    print("library:", g.library_path(), "version", g.version(), flush=True)
+    return g
+
+
+class Case:
+    """A workload plus the oracle's results for it."""
+
+    def __init__(self, index, S=None):
+        print(f"[case] building workload {index}", flush=True)
+        w = make_workload(index, device="cuda", S=S)
+        self.w, self.cfg = w, w.cfg
+        self.off = w.offsets.cpu().numpy()
+        self.ind = w.indices.cpu().numpy()
+        self.seeds = w.seeds.numpy()
+        self.seed_off = w.seed_offsets.numpy()
+        print(f"[case] oracle sampling {index}", flush=True)
+        self.samp = oracle.sample_superbatch(self.off, self.ind, self.seeds, self.seed_off,
+                                             self.cfg.fanout, rng_seed=0)
+        print(f"[case] oracle changeset {index}", flush=True)
+        self.cs = oracle.changeset(self.cfg.num_nodes, self.samp["ids"],
+                                   self.samp["ids_offsets"], self.cfg.cap)
+
+
+@pytest.fixture(scope="module")
+def case1():
+    return Case(1)
+
+
+@pytest.fixture(scope="module")
+def case2():
+    return Case(2)
+
+
+def check_sample(res, ref, S, H):
+    assert np.array_equal(res.ids_offsets, ref["ids_offsets"])
+    assert np.array_equal(res.hop_sizes, ref["hop_sizes"])
+    assert np.array_equal(res.ids.cpu().numpy(), ref["ids"])
+    assert res.totals[0] == len(ref["ids"])
+    assert res.totals[1] == len(ref["adj_rowptr"]) and res.totals[2] == len(ref["adj_col"])
+    rp, col = res.adj_rowptr.cpu().numpy(), res.adj_col.cpu().numpy()
+    for b in range(S):
+        for h in range(H):
+            g_ref, g = b * H + h, h * S + b
+            a = ref["adj_rowptr"][ref["adj_row_offsets"][g_ref]:ref["adj_row_offsets"][g_ref + 1]]
+            c = ref["adj_col"][ref["adj_col_offsets"][g_ref]:ref["adj_col_offsets"][g_ref + 1]]
+            assert np.array_equal(rp[res.adj_row_offsets[g]:res.adj_row_offsets[g + 1]], a), (b, h)
+            assert np.array_equal(col[res.adj_col_offsets[g]:res.adj_col_offsets[g + 1]], c), (b, h)
+
+
+def run_sample(ginex, c, **kw):
+    return ginex.sample_superbatch(c.w.offsets, c.w.indices, c.w.seeds.cuda(), c.seed_off,
+                                   c.cfg.fanout, rng_seed=0, **kw)
+
+
+@pytest.mark.parametrize("which", ["case1", "case2"])
+def test_sampler_matches_oracle(ginex, which, request):
+    c = request.getfixturevalue(which)
+    res = run_sample(ginex, c)
+    check_sample(res, c.samp, c.cfg.S, len(c.cfg.fanout))
+    again = run_sample(ginex, c)          # atomics must not make the result order-dependent
+    assert torch.equal(res.ids, again.ids) and torch.equal(res.adj_col, again.adj_col)
+    no_adj = run_sample(ginex, c, with_adj=False)
+    assert torch.equal(res.ids, no_adj.ids)
+    assert np.array_equal(res.adj_col_offsets, no_adj.adj_col_offsets)
+
+
+def check_changeset(res, ref):
+    assert np.array_equal(res.miss_count, ref["miss_count"])
+    assert np.array_equal(res.cs_offsets, ref["cs_offsets"])
+    assert np.array_equal(res.init_ids.cpu().numpy(), ref["init_ids"])
+    assert np.array_equal(res.in_ids.cpu().numpy(), ref["in_ids"])
+    assert np.array_equal(res.out_ids.cpu().numpy(), ref["out_ids"])
+    assert np.array_equal(res.in_positions.cpu().numpy(), ref["in_positions"])
+
+
+@pytest.mark.parametrize("which", ["case1", "case2"])
+def test_changeset_matches_oracle(ginex, which, request):
+    c = request.getfixturevalue(which)
+    res = ginex.changeset(c.cfg.num_nodes, dev(c.samp["ids"]), c.samp["ids_offsets"], c.cfg.cap)
+    check_changeset(res, c.cs)
+
+
+@pytest.mark.parametrize("which", ["case1", "case2"])
+def test_gather_and_cache_update_match_oracle(ginex, which, request):
+    c = request.getfixturevalue(which)
+    slow = c.w.features
+    assert slow.is_pinned()
+    sb = slow.numpy().view(np.uint8).reshape(slow.shape[0], -1)
+    cache = ginex.FeatureCache(slow, c.cfg.cap)
+    ids_d = dev(c.samp["ids"])
+    cs = {k: dev(c.cs[k]) for k in ("init_ids", "in_ids", "out_ids", "in_positions")}
+    cache.init(cs["init_ids"])
+    ref = oracle.Cache(slow.numpy(), c.cfg.cap)
+    ref.init(c.cs["init_ids"])
+    assert np.array_equal(cache.addr.cpu().numpy(), ref.addr)
+    io, co = c.samp["ids_offsets"], c.cs["cs_offsets"]
+    for i in range(c.cfg.S):
+        out = cache.gather(ids_d[io[i]:io[i + 1]], None, cs["in_ids"][co[i]:co[i + 1]],
+                           cs["out_ids"][co[i]:co[i + 1]], cs["in_positions"][co[i]:co[i + 1]])
+        got = out.cpu().numpy().view(np.uint8).reshape(out.shape[0], -1)
+        assert np.array_equal(got, sb[c.samp["ids"][io[i]:io[i + 1]]]), i
+        ref.gather_update(c.samp["ids"][io[i]:io[i + 1]], c.cs["in_ids"][co[i]:co[i + 1]],
+                          c.cs["out_ids"][co[i]:co[i + 1]], c.cs["in_positions"][co[i]:co[i + 1]])
+        if i % 5 == 0 or i == c.cfg.S - 1:
+            assert np.array_equal(cache.addr.cpu().numpy(), ref.addr), i
+    rows = cache.rows.cpu().numpy().view(np.uint8).reshape(cache.rows.shape[0], -1)
+    res = np.nonzero(ref.addr >= 0)[0]
+    assert np.array_equal(rows[ref.addr[res]], sb[res])
+    assert np.array_equal(rows[:c.cfg.cap], ref.rows[:c.cfg.cap])
+
+
+def test_whole_path_end_to_end(ginex, case1):
+    """sample -> changeset -> init -> gather chained on device data only."""
+    c = case1
+    res = run_sample(ginex, c)
+    cs = ginex.changeset(c.cfg.num_nodes, res.ids, res.ids_offsets, c.cfg.cap)
+    check_changeset(cs, c.cs)
+    cache = ginex.FeatureCache(c.w.features, c.cfg.cap)
+    cache.init(cs.init_ids)
+    sb = c.w.features.numpy().view(np.uint8).reshape(c.cfg.num_nodes, -1)
+    io, co = res.ids_offsets, cs.cs_offsets
+    for i in range(c.cfg.S):
+        out = cache.gather(res.ids[io[i]:io[i + 1]], None, cs.in_ids[co[i]:co[i + 1]],
+                           cs.out_ids[co[i]:co[i + 1]], cs.in_positions[co[i]:co[i + 1]])
+        got = out.cpu().numpy().view(np.uint8).reshape(out.shape[0], -1)
+        assert np.array_equal(got, sb[c.samp["ids"][io[i]:io[i + 1]]])
+
+
+# ---- edge cases ------------------------------------------------------------------------
+
+def small_graph(n=300, e=6000, seed=5, offsets_64=False):
+    from workload import rmat_csr
+    off, ind = rmat_csr(n, e, (0.5, 0.2, 0.2), seed, "cpu", offsets_64=offsets_64)
+    return off, ind
+
+
+@pytest.mark.parametrize("fanout", [(1,), (3, 2), (16, 16), (25, 10), (40, 2), (64,)])
+@pytest.mark.parametrize("offsets_64", [False, True])
+def test_sampler_fanouts_and_offset_widths(ginex, fanout, offsets_64):
+    off, ind = small_graph(offsets_64=offsets_64)
+    rng = np.random.default_rng(len(fanout) + fanout[0])
+    batches = [rng.choice(300, size=s, replace=False) for s in (7, 0, 64, 1, 33)]
+    seeds = np.concatenate(batches).astype(np.int32)
+    so = np.cumsum([0] + [len(b) for b in batches])
+    ref = oracle.sample_superbatch(off.numpy(), ind.numpy(), seeds, so, fanout, rng_seed=77,
+                                   first_batch_index=9)
+    res = ginex.sample_superbatch(off.cuda(), ind.cuda(), dev(seeds), so, fanout, rng_seed=77,
+                                  first_batch_index=9)
+    check_sample(res, ref, len(batches), len(fanout))
+
+
+def test_sampler_repeated_seeds_and_partition_independence(ginex):
+    off, ind = small_graph()
+    seeds = np.array([5, 9, 5, 5, 100, 9, 17], dtype=np.int32)
+    so = np.array([0, 7])
+    ref = oracle.sample_superbatch(off.numpy(), ind.numpy(), seeds, so, (4, 4))
+    res = ginex.sample_superbatch(off.cuda(), ind.cuda(), dev(seeds), so, (4, 4))
+    check_sample(res, ref, 1, 2)
+    assert res.hop_sizes[0][0] == 4
+    # batch b sampled alone, under its global index, equals batch b inside a superbatch
+    rng = np.random.default_rng(0)
+    batches = [rng.choice(300, size=20, replace=False).astype(np.int32) for _ in range(6)]
+    allb = ginex.sample_superbatch(off.cuda(), ind.cuda(), dev(np.concatenate(batches)),
+                                   np.arange(7) * 20, (5, 5, 5), rng_seed=3, first_batch_index=100)
+    for b in (0, 3, 5):
+        one = ginex.sample_superbatch(off.cuda(), ind.cuda(), dev(batches[b]), [0, 20], (5, 5, 5),
+                                      rng_seed=3, first_batch_index=100 + b)
+        lo, hi = allb.ids_offsets[b], allb.ids_offsets[b + 1]
+        assert torch.equal(one.ids, allb.ids[lo:hi])
+
+
+def test_sampler_reports_required_capacity(ginex):
+    off, ind = small_graph()
+    seeds = dev(np.arange(50, dtype=np.int32))
+    full = ginex.sample_superbatch(off.cuda(), ind.cuda(), seeds, [0, 50], (5, 5))
+    tiny = (torch.empty(10, dtype=torch.int32, device="cuda"),
+            torch.empty(10, dtype=torch.int64, device="cuda"),
+            torch.empty(10, dtype=torch.int32, device="cuda"))
+    with pytest.raises(ginex.GinexError) as e:
+        ginex.sample_superbatch(off.cuda(), ind.cuda(), seeds, [0, 50], (5, 5), out=tiny)
+    assert e.value.code == -2 and str(full.totals[0]) in str(e.value)
+
+
+def random_trace(rng, n, S, max_len):
+    tr = [rng.choice(n, size=rng.integers(0, min(max_len, n) + 1), replace=False)
+          for _ in range(S)]
+    off = np.cumsum([0] + [len(x) for x in tr]).astype(np.int64)
+    ids = np.concatenate(tr).astype(np.int32) if off[-1] else np.zeros(0, dtype=np.int32)
+    return ids, off
+
+
+def test_changeset_random_small_traces(ginex):
+    rng = np.random.default_rng(11)
+    for trial in range(60):
+        n = int(rng.integers(1, 400))
+        S = int(rng.integers(1, 14))
+        cap = int(rng.integers(0, n + 2))
+        ids, off = random_trace(rng, n, S, int(rng.integers(1, 200)))
+        ref = oracle.changeset(n, ids, off, cap)
+        ids_d = dev(ids) if len(ids) else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
+        res = ginex.changeset(n, ids_d, off, cap)
+        try:
+            check_changeset(res, ref)
+        except AssertionError:
+            print("failing trial", trial, n, S, cap, flush=True)
+            raise
+
+
+def test_changeset_degenerate_capacities(ginex, case1):
+    c = case1
+    ids, io = c.samp["ids"], c.samp["ids_offsets"]
+    distinct = len(np.unique(ids))
+    for cap in (0, 1, 7, distinct - 1, distinct, distinct + 5):
+        ref = oracle.changeset(c.cfg.num_nodes, ids, io, cap)
+        res = ginex.changeset(c.cfg.num_nodes, dev(ids), io, cap)
+        check_changeset(res, ref)
+    # one iteration only, and a trace whose ties all fall into one bucket
+    one = oracle.changeset(c.cfg.num_nodes, ids[:io[1]], io[:2], 100)
+    check_changeset(ginex.changeset(c.cfg.num_nodes, dev(ids[:io[1]]), io[:2], 100), one)
+
+
+@pytest.mark.parametrize("row_bytes", [16, 48, 256, 1024, 3072])
+def test_gather_row_sizes_and_empty_changesets(ginex, row_bytes):
+    rng = np.random.default_rng(row_bytes)
+    n, cap = 500, 60
+    slow = torch.from_numpy(rng.integers(0, 255, size=(n, row_bytes), dtype=np.uint8)).pin_memory()
+    ids, off = random_trace(rng, n, 6, 200)
+    ref_cs = oracle.changeset(n, ids, off, cap)
+    cache = ginex.FeatureCache(slow, cap)
+    cache.init(dev(ref_cs["init_ids"]))
+    ref = oracle.Cache(slow.numpy(), cap)
+    ref.init(ref_cs["init_ids"])
+    co = ref_cs["cs_offsets"]
+    for i in range(6):
+        cur = ids[off[i]:off[i + 1]]
+        sl = slice(co[i], co[i + 1])
+        out = cache.gather(dev(cur) if len(cur) else torch.zeros(0, dtype=torch.int32, device="cuda"),
+                           None, dev(ref_cs["in_ids"][sl]) if co[i + 1] > co[i] else None,
+                           dev(ref_cs["out_ids"][sl]) if co[i + 1] > co[i] else None,
+                           dev(ref_cs["in_positions"][sl]) if co[i + 1] > co[i] else None)
+        want, _ = ref.gather_update(cur, ref_cs["in_ids"][sl], ref_cs["out_ids"][sl],
+                                    ref_cs["in_positions"][sl])
+        assert np.array_equal(out.cpu().numpy(), want)
+        assert np.array_equal(out.cpu().numpy(), slow.numpy()[cur])
+    assert np.array_equal(cache.addr.cpu().numpy(), ref.addr)
+    assert np.array_equal(cache.rows.cpu().numpy()[:cap], ref.rows[:cap])
+
+
+def test_gather_reads_a_device_resident_slow_tier_too(ginex):
+    rng = np.random.default_rng(2)
+    slow = torch.from_numpy(rng.standard_normal((1000, 32)).astype(np.float32)).cuda()
+    cache = ginex.FeatureCache(slow, 10)
+    cache.init(dev(np.arange(10, dtype=np.int32)))
+    ids = rng.permutation(1000)[:300].astype(np.int32)
+    out = cache.gather(dev(ids))
+    assert torch.equal(out, slow[torch.from_numpy(ids).long().cuda()])
