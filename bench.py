@@ -1,0 +1,285 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+A step is one pass of the inspector-executor path over one superbatch:
+  ginex_sample_superbatch -> ginex_changeset -> ginex_cache_init ->
+  S x (ginex_gather + ginex_cache_update)
+on a synthetic R-MAT workload (default: configuration 4, the 111M-node graph with the
+feature table in host-pinned memory).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "sampled edges/s; Belady changeset accesses/s; gather GB/s vs HBM peak"
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+class Runner:
+    """Holds every buffer of the path so that steps allocate (almost) nothing."""
+
+    def __init__(self, ginex, w):
+        from paper_2208_09151_amd import _lib, api
+        self.g, self.w, self.cfg = ginex, w, w.cfg
+        cfg = w.cfg
+        self.seeds = w.seeds.cuda()
+        self.seed_off = w.seed_offsets.numpy()
+        self.S = len(self.seed_off) - 1
+        lib = _lib.load()
+        fo = np.asarray(cfg.fanout, dtype=np.int32)
+        max_batch = int(np.max(np.diff(self.seed_off)))
+        ws_s = lib.ginex_sample_workspace_bytes(cfg.num_nodes, self.S, max_batch,
+                                                fo.ctypes.data, len(fo))
+        ci, cr, cc = api.sample_capacity(cfg.num_nodes, self.seed_off, cfg.fanout)
+        ws_c = lib.ginex_changeset_workspace_bytes(cfg.num_nodes, ci, self.S, cfg.cap)
+        log(f"workspace: sample {ws_s / 2**30:.2f} GiB, changeset {ws_c / 2**30:.2f} GiB")
+        # the two stages run one after the other: one workspace serves both
+        self.ws = torch.empty(max(ws_s, ws_c), dtype=torch.uint8, device="cuda")
+        self.out_bufs = (torch.empty(ci, dtype=torch.int32, device="cuda"),
+                         torch.empty(cr, dtype=torch.int64, device="cuda"),
+                         torch.empty(cc, dtype=torch.int32, device="cuda"))
+        self.cache = ginex.FeatureCache(w.features, cfg.cap)
+        self.batch_input = None
+        self.last = None
+
+    def step(self, timers=None, events=None):
+        g, cfg = self.g, self.cfg
+        t0 = time.perf_counter()
+        samp = g.sample_superbatch(self.w.offsets, self.w.indices, self.seeds, self.seed_off,
+                                   cfg.fanout, rng_seed=0, workspace=self.ws, out=self.out_bufs)
+        t1 = time.perf_counter()
+        cs = g.changeset(cfg.num_nodes, samp.ids, samp.ids_offsets, cfg.cap, workspace=self.ws)
+        t2 = time.perf_counter()
+        io, co = samp.ids_offsets, cs.cs_offsets
+        max_n = int(np.max(np.diff(io)))
+        if self.batch_input is None or self.batch_input.shape[0] < max_n:
+            self.batch_input = torch.empty((max_n, cfg.feat_dim), dtype=torch.float32, device="cuda")
+        ev = torch.cuda.Event
+        e_init0, e_init1, e_end = ev(enable_timing=True), ev(enable_timing=True), ev(enable_timing=True)
+        e_init0.record()
+        self.cache.init(cs.init_ids)
+        e_init1.record()
+        pairs = []
+        for i in range(self.S):
+            ids_i = samp.ids[io[i]:io[i + 1]]
+            sl = slice(co[i], co[i + 1])
+            if events is not None:
+                a, b = ev(enable_timing=True), ev(enable_timing=True)
+                a.record()
+                self.cache.gather(ids_i, self.batch_input)      # exactly one kernel launch
+                b.record()
+                pairs.append((a, b))
+            else:
+                self.cache.gather(ids_i, self.batch_input)
+            self.cache.update(self.batch_input, cs.in_ids[sl], cs.out_ids[sl], cs.in_positions[sl])
+        e_end.record()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        if timers is not None:
+            timers["sample_s"].append(t1 - t0)
+            timers["changeset_s"].append(t2 - t1)
+            timers["cache_init_s"].append(e_init0.elapsed_time(e_init1) / 1e3)
+            timers["gather_update_s"].append(e_init1.elapsed_time(e_end) / 1e3)
+            timers["executor_wall_s"].append(t3 - t2)
+        if events is not None:
+            events.extend(a.elapsed_time(b) for a, b in pairs)
+        self.last = (samp, cs)
+        return samp, cs
+
+
+def cpu_baseline(w, n_batches):
+    """The oracle, as it stands, on the first `n_batches` batches of the same workload,
+    one thread: sample, changeset (cache scaled to the sample), gather + cache update."""
+    import oracle
+    cfg = w.cfg
+    S = len(w.seed_offsets) - 1
+    nb = min(n_batches, S)
+    off = w.offsets.cpu().numpy()
+    ind = w.indices.cpu().numpy()
+    so = w.seed_offsets.numpy()[:nb + 1]
+    seeds = w.seeds.numpy()[:so[-1]]
+    try:
+        os.sched_setaffinity(0, {sorted(os.sched_getaffinity(0))[0]})
+    except OSError:
+        pass
+    t0 = time.perf_counter()
+    s = oracle.sample_superbatch(off, ind, seeds, so, cfg.fanout, rng_seed=0)
+    t1 = time.perf_counter()
+    cap = max(1, cfg.cap * nb // S)
+    c = oracle.changeset(cfg.num_nodes, s["ids"], s["ids_offsets"], cap)
+    t2 = time.perf_counter()
+    slow = w.features.numpy()
+    cache = oracle.Cache(slow, cap)
+    cache.init(c["init_ids"])
+    rows = 0
+    for i in range(nb):
+        sl = slice(c["cs_offsets"][i], c["cs_offsets"][i + 1])
+        ids_i = s["ids"][s["ids_offsets"][i]:s["ids_offsets"][i + 1]]
+        cache.gather_update(ids_i, c["in_ids"][sl], c["out_ids"][sl], c["in_positions"][sl])
+        rows += len(ids_i)
+    t3 = time.perf_counter()
+    edges = int(len(s["adj_col"]))
+    row_bytes = cfg.feat_dim * 4
+    return {
+        "value": edges / (t3 - t0),
+        "unit": "sampled edges/s (whole hot path)",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": f"first {nb} of {S} batches of the same workload; cache scaled to "
+                  f"{cap} rows; sample {t1 - t0:.2f}s, changeset {t2 - t1:.2f}s, "
+                  f"init+gather+update {t3 - t2:.2f}s",
+        "sample_edges_per_s": edges / (t1 - t0),
+        "changeset_accesses_per_s": len(s["ids"]) / (t2 - t1),
+        "gather_GBps": 2 * rows * row_bytes / (t3 - t2) / 1e9,
+        "host_cpus": os.cpu_count(),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--cpu-batches", type=int, default=6,
+                    help="batches of the workload the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-allhit", action="store_true",
+                    help="skip the all-in-HBM gather measurement")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+
+    import paper_2208_09151_amd as ginex
+    from workload import make_workload
+
+    t = time.perf_counter()
+    log(f"building workload {args.config} on the GPU ...")
+    w = make_workload(args.config, device="cuda")
+    cfg = w.cfg
+    torch.cuda.synchronize()
+    log(f"workload ready in {time.perf_counter() - t:.1f}s: N={cfg.num_nodes} "
+        f"E={w.indices.numel()} F={cfg.feat_dim} S={cfg.S} cap={cfg.cap}")
+    run = Runner(ginex, w)
+
+    for i in range(args.warmup):
+        t = time.perf_counter()
+        run.step()
+        log(f"warmup step {i}: {time.perf_counter() - t:.3f}s")
+    timers = {k: [] for k in ("sample_s", "changeset_s", "cache_init_s", "gather_update_s",
+                              "executor_wall_s")}
+    gather_ms = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        run.step(timers, gather_ms)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    samp, cs = run.last
+    S = run.S
+    row_bytes = cfg.feat_dim * 4
+    edges = int(samp.totals[2])
+    accesses = int(samp.totals[0])
+    misses = int(cs.miss_count.sum())
+    changes = int(cs.cs_offsets[-1])
+    mean = {k: float(np.mean(v)) for k, v in timers.items()}
+    step_s = elapsed / args.steps
+    g_ms = float(np.mean(gather_ms))
+    rows_per_launch = accesses / S
+    miss_per_launch = misses / S
+    # algorithmic bytes of one gather launch: id + address-table entry + row in + row out
+    algo_bytes = rows_per_launch * (4 + 4 + 2 * row_bytes)
+    roof = {
+        "kernel": "k_gather (real hit/miss mix; misses are read from host-pinned memory)",
+        "bound": "hbm", "achieved": algo_bytes / (g_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s", "traffic": None,
+        "avg_launch_ms": g_ms, "launches": len(gather_ms),
+        "rows_per_launch": rows_per_launch, "miss_fraction": misses / max(accesses, 1),
+        "host_link_GBps": miss_per_launch * row_bytes / (g_ms * 1e-3) / 1e9,
+    }
+    roof["frac"] = roof["achieved"] / roof["peak"]
+
+    stages = {
+        "sample_edges_per_s": edges / mean["sample_s"],
+        "sample_ms": mean["sample_s"] * 1e3,
+        "changeset_accesses_per_s": accesses / mean["changeset_s"],
+        "changeset_ms": mean["changeset_s"] * 1e3,
+        "cache_init_ms": mean["cache_init_s"] * 1e3,
+        "cache_init_GBps": len(cs.init_ids) * row_bytes / mean["cache_init_s"] / 1e9,
+        "gather_update_ms": mean["gather_update_s"] * 1e3,
+        "gather_mix_GBps": roof["achieved"],
+        "sampled_edges": edges, "accesses": accesses, "misses": misses, "changes": changes,
+    }
+
+    if not args.no_allhit:
+        # the same kernel on the same ids with every row in HBM (pure HBM number)
+        free, _ = torch.cuda.mem_get_info()
+        need = w.features.numel() * 4
+        if need + (8 << 30) < free:
+            hbm_tier = w.features.cuda()
+            c2 = ginex.FeatureCache(hbm_tier, cfg.cap)
+            c2.init(cs.init_ids)
+            io = samp.ids_offsets
+            ms = []
+            for rep in range(2):
+                for i in range(S):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    c2.gather(samp.ids[io[i]:io[i + 1]], run.batch_input)
+                    b.record()
+                    if rep:
+                        ms.append((a, b))
+            torch.cuda.synchronize()
+            t_ms = float(np.mean([a.elapsed_time(b) for a, b in ms]))
+            stages["gather_all_in_hbm_GBps"] = algo_bytes / (t_ms * 1e-3) / 1e9
+            stages["gather_all_in_hbm_frac_of_peak"] = stages["gather_all_in_hbm_GBps"] / HBM_PEAK_GBPS
+            stages["gather_all_in_hbm_ms"] = t_ms
+            del c2, hbm_tier
+        else:
+            log("not enough free HBM for the all-in-HBM gather measurement; skipped")
+
+    result = {
+        "metric": METRIC,
+        "value": edges / step_s,
+        "unit": "sampled edges/s (whole hot path: sample + changeset + cache init + S x (gather + update))",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": step_s * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: R-MAT N={cfg.num_nodes} E={w.indices.numel()} "
+                               f"feat={cfg.feat_dim}xfp32 (slow tier host-pinned) batch={cfg.batch} "
+                               f"fanout={list(cfg.fanout)} S={S} cache_rows={cfg.cap}"},
+        "stages": stages,
+        "roofline": roof,
+    }
+    if args.cpu_batches > 0:
+        log("timing the CPU oracle on a bounded sample ...")
+        result["cpu_baseline"] = cpu_baseline(w, args.cpu_batches)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

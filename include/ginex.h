@@ -71,12 +71,13 @@ typedef struct ginex_csr {
  * Outputs
  *   ids[ids_offsets[b] .. ids_offsets[b+1])   the list of batch b (seeds first, a seed
  *                                              repeated within a batch is kept once)
- *   hop_sizes[b*(H+1)+h]                       list length after the seeds (h=0) and
+ *   ids_offsets (host, [S+1]), hop_sizes (host, [S*(H+1)]): hop_sizes[b*(H+1)+h] is the
+ *                                              list length after the seeds (h=0) and
  *                                              after hop h-1 (h>=1)
  *   adj: segment g = h*S + b (hop-major) describes hop h of batch b as a CSR over the
  *   frontier: adj_rowptr[adj_row_offsets[g] + r], r = 0..frontier, starts at 0, and
  *   adj_col[adj_col_offsets[g] + e] is the position inside the batch's ids of pick e;
- *   row r belongs to ids[r].  adj_row_offsets/adj_col_offsets have S*H+1 entries.
+ *   row r belongs to ids[r].  adj_row_offsets/adj_col_offsets (host) have S*H+1 entries.
  *   Pass adj_rowptr = adj_col = NULL to skip adj (offset arrays are still filled).
  *   totals (host, [3]): number of ids, of rowptr entries and of col entries (= sampled
  *   edges) produced, or required on GINEX_ERR_CAPACITY.
@@ -91,10 +92,10 @@ int32_t ginex_sample_superbatch(
     const int32_t* seeds, const int64_t* seed_offsets /*host [S+1]*/, int32_t S,
     const int32_t* fanout /*host [H]*/, int32_t H,
     uint64_t rng_seed, uint32_t first_batch_index,
-    int32_t* ids, int64_t ids_capacity, int64_t* ids_offsets /*[S+1]*/,
-    int64_t* hop_sizes /*[S*(H+1)]*/,
+    int32_t* ids, int64_t ids_capacity, int64_t* ids_offsets /*host [S+1]*/,
+    int64_t* hop_sizes /*host [S*(H+1)]*/,
     int64_t* adj_rowptr, int64_t rowptr_capacity, int32_t* adj_col, int64_t col_capacity,
-    int64_t* adj_row_offsets /*[S*H+1]*/, int64_t* adj_col_offsets /*[S*H+1]*/,
+    int64_t* adj_row_offsets /*host [S*H+1]*/, int64_t* adj_col_offsets /*host [S*H+1]*/,
     int64_t* totals /*host [3]*/,
     void* ws, size_t ws_bytes, void* stream);
 
@@ -155,6 +156,14 @@ int32_t ginex_cache_init(const ginex_cache_t* c /*host struct*/, const int32_t* 
 int32_t ginex_gather(const ginex_cache_t* c /*host struct*/, const int32_t* ids, int64_t n,
                      void* out, const int32_t* in_ids, const int32_t* out_ids,
                      const int32_t* in_positions, int64_t n_change, void* stream);
+
+/* The cache update of one iteration on its own (Section 3.1 "Main Loop": the step between
+ * gather and transfer; Section 3.3 "Feature Cache Update"): exactly the second half of
+ * ginex_gather, for callers that gather with n_change = 0 and update separately.  `out`
+ * is the batch input that the gather of the same iteration produced. */
+int32_t ginex_cache_update(const ginex_cache_t* c /*host struct*/, const void* out,
+                           const int32_t* in_ids, const int32_t* out_ids,
+                           const int32_t* in_positions, int64_t n_change, void* stream);
 
 #ifdef __cplusplus
 }

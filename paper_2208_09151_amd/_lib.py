@@ -31,6 +31,7 @@ SIGNATURES = {
                               sz, vp]),
     "ginex_cache_init": (i32, [C.POINTER(CacheDesc), vp, i64, vp]),
     "ginex_gather": (i32, [C.POINTER(CacheDesc), vp, i64, vp, vp, vp, vp, i64, vp]),
+    "ginex_cache_update": (i32, [C.POINTER(CacheDesc), vp, vp, vp, vp, i64, vp]),
 }
 
 _lib = None

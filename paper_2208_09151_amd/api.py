@@ -210,3 +210,11 @@ class FeatureCache:
                                         _ptr(out_ids) if nc else None,
                                         _ptr(in_positions) if nc else None, nc, _stream()))
         return out
+
+    def update(self, out, in_ids, out_ids, in_positions):
+        """The cache update alone, for a gather that was issued without a changeset."""
+        nc = in_ids.numel() if in_ids is not None else 0
+        _check(_lib.load().ginex_cache_update(C.byref(self._desc), _ptr(out),
+                                              _ptr(in_ids) if nc else None,
+                                              _ptr(out_ids) if nc else None,
+                                              _ptr(in_positions) if nc else None, nc, _stream()))

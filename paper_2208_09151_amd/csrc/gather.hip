@@ -148,33 +148,67 @@ extern "C" int32_t ginex_cache_init(const ginex_cache_t* c, const int32_t* init_
   return GINEX_OK;
 }
 
+namespace ginex {
+namespace {
+
+int32_t check_update(const ginex_cache_t* c, const void* out, const int32_t* in_ids,
+                     const int32_t* out_ids, const int32_t* in_positions, int64_t n_change,
+                     const char* who) {
+  if (n_change < 0 || n_change > c->cap)
+    return fail(GINEX_ERR_ARG, "%s: n_change=%lld outside [0, cap=%lld]", who,
+                (long long)n_change, (long long)c->cap);
+  if (n_change > 0 && (!in_ids || !out_ids || !in_positions || !out))
+    return fail(GINEX_ERR_ARG, "%s: a changeset list or the batch input is null", who);
+  if (((uintptr_t)out) & 15) return fail(GINEX_ERR_ARG, "%s: out must be 16-byte aligned", who);
+  return GINEX_OK;
+}
+
+int32_t launch_update(const ginex_cache_t* c, const void* out, const int32_t* in_ids,
+                      const int32_t* out_ids, const int32_t* in_positions, int64_t n_change,
+                      hipStream_t st) {
+  if (n_change == 0) return GINEX_OK;
+  const int32_t cpr = (int32_t)(c->row_bytes / 16);
+  hipLaunchKernelGGL(k_update_rows, dim3(grid_for(n_change * cpr, 1)), dim3(THREADS), 0, st,
+                     (chunk_t*)c->rows, c->addr, (const chunk_t*)out, out_ids, in_positions,
+                     n_change, cpr);
+  GINEX_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_update_addr, dim3(grid_for(n_change, 1)), dim3(THREADS), 0, st, c->addr,
+                     in_ids, out_ids, n_change);
+  GINEX_LAUNCH_CHECK();
+  return GINEX_OK;
+}
+
+}  // namespace
+}  // namespace ginex
+
+extern "C" int32_t ginex_cache_update(const ginex_cache_t* c, const void* out,
+                                      const int32_t* in_ids, const int32_t* out_ids,
+                                      const int32_t* in_positions, int64_t n_change,
+                                      void* stream) {
+  if (int32_t rc = check_cache(c, "ginex_cache_update")) return rc;
+  if (int32_t rc = check_update(c, out, in_ids, out_ids, in_positions, n_change,
+                                "ginex_cache_update"))
+    return rc;
+  return launch_update(c, out, in_ids, out_ids, in_positions, n_change, (hipStream_t)stream);
+}
+
 extern "C" int32_t ginex_gather(const ginex_cache_t* c, const int32_t* ids, int64_t n, void* out,
                                 const int32_t* in_ids, const int32_t* out_ids,
                                 const int32_t* in_positions, int64_t n_change, void* stream) {
   if (int32_t rc = check_cache(c, "ginex_gather")) return rc;
-  if (n < 0 || n_change < 0 || n_change > n || n_change > c->cap)
-    return fail(GINEX_ERR_ARG, "ginex_gather: n=%lld n_change=%lld (cap=%lld) inconsistent",
-                (long long)n, (long long)n_change, (long long)c->cap);
+  if (n < 0 || n_change > n)
+    return fail(GINEX_ERR_ARG, "ginex_gather: n=%lld n_change=%lld inconsistent", (long long)n,
+                (long long)n_change);
   if (n > 0 && (!ids || !out)) return fail(GINEX_ERR_ARG, "ginex_gather: ids/out is null");
-  if (((uintptr_t)out) & 15) return fail(GINEX_ERR_ARG, "ginex_gather: out must be 16-byte aligned");
-  if (n_change > 0 && (!in_ids || !out_ids || !in_positions))
-    return fail(GINEX_ERR_ARG, "ginex_gather: a changeset list is null");
+  if (int32_t rc = check_update(c, out, in_ids, out_ids, in_positions, n_change, "ginex_gather"))
+    return rc;
   hipStream_t st = (hipStream_t)stream;
-  const int32_t cpr = (int32_t)(c->row_bytes / 16);
   if (n > 0) {
+    const int32_t cpr = (int32_t)(c->row_bytes / 16);
     hipLaunchKernelGGL(k_gather, dim3(grid_for(n * cpr, UNROLL)), dim3(THREADS), 0, st,
                        (const chunk_t*)c->rows, c->addr, (const chunk_t*)c->slow, ids, n, cpr,
                        (chunk_t*)out);
     GINEX_LAUNCH_CHECK();
   }
-  if (n_change > 0) {
-    hipLaunchKernelGGL(k_update_rows, dim3(grid_for(n_change * cpr, 1)), dim3(THREADS), 0, st,
-                       (chunk_t*)c->rows, c->addr, (const chunk_t*)out, out_ids, in_positions,
-                       n_change, cpr);
-    GINEX_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_update_addr, dim3(grid_for(n_change, 1)), dim3(THREADS), 0, st, c->addr,
-                       in_ids, out_ids, n_change);
-    GINEX_LAUNCH_CHECK();
-  }
-  return GINEX_OK;
+  return launch_update(c, out, in_ids, out_ids, in_positions, n_change, st);
 }

@@ -271,6 +271,23 @@ def test_gather_row_sizes_and_empty_changesets(ginex, row_bytes):
     assert np.array_equal(cache.rows.cpu().numpy()[:cap], ref.rows[:cap])
 
 
+def test_separate_update_equals_fused_gather_update(ginex, case1):
+    c = case1
+    cs = {k: dev(c.cs[k]) for k in ("init_ids", "in_ids", "out_ids", "in_positions")}
+    a, b = ginex.FeatureCache(c.w.features, c.cfg.cap), ginex.FeatureCache(c.w.features, c.cfg.cap)
+    a.init(cs["init_ids"])
+    b.init(cs["init_ids"])
+    ids_d, io, co = dev(c.samp["ids"]), c.samp["ids_offsets"], c.cs["cs_offsets"]
+    for i in range(c.cfg.S):
+        sl = slice(co[i], co[i + 1])
+        oa = a.gather(ids_d[io[i]:io[i + 1]], None, cs["in_ids"][sl], cs["out_ids"][sl],
+                      cs["in_positions"][sl])
+        ob = b.gather(ids_d[io[i]:io[i + 1]])
+        b.update(ob, cs["in_ids"][sl], cs["out_ids"][sl], cs["in_positions"][sl])
+        assert torch.equal(oa, ob)
+    assert torch.equal(a.addr, b.addr) and torch.equal(a.rows, b.rows)
+
+
 def test_gather_reads_a_device_resident_slow_tier_too(ginex):
     rng = np.random.default_rng(2)
     slow = torch.from_numpy(rng.standard_normal((1000, 32)).astype(np.float32)).cuda()
