@@ -159,8 +159,8 @@ def main():
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--cpu-batches", type=int, default=6,
                     help="batches of the workload the CPU oracle is timed on (0 = skip)")
-    ap.add_argument("--no-allhit", action="store_true",
-                    help="skip the all-in-HBM gather measurement")
+    ap.add_argument("--allhit", action="store_true",
+                    help="also time the gather kernel with the whole feature table in HBM")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -175,7 +175,7 @@ def main():
 
     t = time.perf_counter()
     log(f"building workload {args.config} on the GPU ...")
-    w = make_workload(args.config, device="cuda")
+    w = make_workload(args.config, device="cuda", verbose=True)
     cfg = w.cfg
     torch.cuda.synchronize()
     log(f"workload ready in {time.perf_counter() - t:.1f}s: N={cfg.num_nodes} "
@@ -232,7 +232,7 @@ def main():
         "sampled_edges": edges, "accesses": accesses, "misses": misses, "changes": changes,
     }
 
-    if not args.no_allhit:
+    if args.allhit:
         # the same kernel on the same ids with every row in HBM (pure HBM number)
         free, _ = torch.cuda.mem_get_info()
         need = w.features.numel() * 4

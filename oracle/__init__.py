@@ -95,21 +95,25 @@ def sample_superbatch(offsets, indices, seeds, seed_offsets, fanout, rng_seed=0,
     row_off = np.zeros(S * H + 1, dtype=np.int64)
     col_off = np.zeros(S * H + 1, dtype=np.int64)
     need = np.zeros(3, dtype=np.int64)
+    # upper bounds: a list grows by at most (1 + fanout) per hop and never beyond n
     caps = [0, 0, 0]
-    for _ in range(2):
-        ids = np.zeros(max(caps[0], 1), dtype=np.int32)
-        rowptr = np.zeros(max(caps[1], 1), dtype=np.int64)
-        col = np.zeros(max(caps[2], 1), dtype=np.int32)
-        rc = lib().oracle_sample_superbatch(
-            C.c_int64(n), _p(offsets), C.c_int32(offsets.dtype == np.int64), _p(indices),
-            _p(seeds), _p(seed_offsets), C.c_int32(S), _p(fanout), C.c_int32(H),
-            C.c_uint64(rng_seed), C.c_uint32(first_batch_index),
-            _p(ids), C.c_int64(caps[0]), _p(ids_offsets), _p(hop_sizes),
-            _p(rowptr), C.c_int64(caps[1]), _p(col), C.c_int64(caps[2]),
-            _p(row_off), _p(col_off), _p(need))
-        if rc == 0:
-            break
-        caps = [int(x) for x in need]
+    for b in range(S):
+        cur = min(int(seed_offsets[b + 1] - seed_offsets[b]), n)
+        for k in fanout:
+            caps[1] += cur + 1
+            caps[2] += cur * int(k)
+            cur = min(cur * (1 + int(k)), n)
+        caps[0] += cur
+    ids = np.zeros(max(caps[0], 1), dtype=np.int32)
+    rowptr = np.zeros(max(caps[1], 1), dtype=np.int64)
+    col = np.zeros(max(caps[2], 1), dtype=np.int32)
+    rc = lib().oracle_sample_superbatch(
+        C.c_int64(n), _p(offsets), C.c_int32(offsets.dtype == np.int64), _p(indices),
+        _p(seeds), _p(seed_offsets), C.c_int32(S), _p(fanout), C.c_int32(H),
+        C.c_uint64(rng_seed), C.c_uint32(first_batch_index),
+        _p(ids), C.c_int64(caps[0]), _p(ids_offsets), _p(hop_sizes),
+        _p(rowptr), C.c_int64(caps[1]), _p(col), C.c_int64(caps[2]),
+        _p(row_off), _p(col_off), _p(need))
     assert rc == 0
     return dict(ids=ids[:need[0]], ids_offsets=ids_offsets,
                 hop_sizes=hop_sizes.reshape(S, H + 1),
@@ -136,17 +140,13 @@ def _changeset(fn, num_nodes, ids, ids_offsets, cap):
     init_count = np.zeros(1, dtype=np.int64)
     cs_offsets = np.zeros(S + 1, dtype=np.int64)
     miss = np.zeros(max(S, 1), dtype=np.int64)
-    capacity = 0
-    for _ in range(2):
-        a = np.zeros(max(capacity, 1), dtype=np.int32)
-        b = np.zeros(max(capacity, 1), dtype=np.int32)
-        c = np.zeros(max(capacity, 1), dtype=np.int32)
-        rc = fn(C.c_int64(num_nodes), _p(ids), _p(ids_offsets), C.c_int32(S), C.c_int64(cap),
-                _p(init_ids), _p(init_count), _p(a), _p(b), _p(c), C.c_int64(capacity),
-                _p(cs_offsets), _p(miss))
-        if rc == 0:
-            break
-        capacity = int(cs_offsets[S])
+    capacity = max(len(ids), 1)     # every changeset record is a miss, so this suffices
+    a = np.zeros(capacity, dtype=np.int32)
+    b = np.zeros(capacity, dtype=np.int32)
+    c = np.zeros(capacity, dtype=np.int32)
+    rc = fn(C.c_int64(num_nodes), _p(ids), _p(ids_offsets), C.c_int32(S), C.c_int64(cap),
+            _p(init_ids), _p(init_count), _p(a), _p(b), _p(c), C.c_int64(capacity),
+            _p(cs_offsets), _p(miss))
     assert rc == 0
     n = int(cs_offsets[S])
     return dict(init_ids=init_ids[:int(init_count[0])], in_ids=a[:n], out_ids=b[:n],

@@ -7,6 +7,7 @@ short); a superbatch of ``S`` batches runs on into the next epoch when the epoch
 """
 from __future__ import annotations
 
+import sys
 from dataclasses import dataclass, field
 
 import torch
@@ -96,12 +97,16 @@ def make_features(num_nodes: int, feat_dim: int, seed: int, device="cpu",
 
 
 def make_workload(index: int, device="cpu", features: bool = True, S: int | None = None,
-                  first_batch: int = 0) -> Workload:
+                  first_batch: int = 0, verbose: bool = False) -> Workload:
     """Build workload ``index`` (1-based, as the configs are numbered)."""
     cfg = CONFIGS[index - 1]
     offsets, indices = rmat_csr(cfg.num_nodes, cfg.num_edges, cfg.abc, cfg.seed, device,
-                                symmetrise=cfg.symmetrise, offsets_64=cfg.offsets_64)
+                                symmetrise=cfg.symmetrise, offsets_64=cfg.offsets_64,
+                                verbose=verbose)
     train = train_nodes(cfg.num_nodes, cfg.train_frac, cfg.seed, device)
     seeds, seed_offsets = seed_batches(train, cfg.batch, S or cfg.S, cfg.seed, first_batch)
+    if verbose:
+        print("[workload] graph and seeds ready; filling the feature table", file=sys.stderr,
+              flush=True)
     feats = make_features(cfg.num_nodes, cfg.feat_dim, cfg.seed, device) if features else None
     return Workload(cfg, offsets, indices, seeds, seed_offsets, feats)
