@@ -75,19 +75,28 @@ class Runner:
         e_init0.record()
         self.cache.init(cs.init_ids)
         e_init1.record()
+        # the executor loop on raw addresses: per iteration one ginex_gather (one kernel) and,
+        # when the changeset is not empty, one ginex_cache_update
         pairs = []
+        stream = torch.cuda.current_stream().cuda_stream
+        ids_base, out_ptr = samp.ids.data_ptr(), self.batch_input.data_ptr()
+        in_base, oid_base, pos_base = (cs.in_ids.data_ptr(), cs.out_ids.data_ptr(),
+                                       cs.in_positions.data_ptr())
+        cache = self.cache
         for i in range(self.S):
-            ids_i = samp.ids[io[i]:io[i + 1]]
-            sl = slice(co[i], co[i + 1])
+            lo, n = int(io[i]), int(io[i + 1] - io[i])
+            c0, nc = int(co[i]), int(co[i + 1] - co[i])
             if events is not None:
                 a, b = ev(enable_timing=True), ev(enable_timing=True)
                 a.record()
-                self.cache.gather(ids_i, self.batch_input)      # exactly one kernel launch
+                cache.gather_raw(ids_base + 4 * lo, n, out_ptr, stream)
                 b.record()
                 pairs.append((a, b))
             else:
-                self.cache.gather(ids_i, self.batch_input)
-            self.cache.update(self.batch_input, cs.in_ids[sl], cs.out_ids[sl], cs.in_positions[sl])
+                cache.gather_raw(ids_base + 4 * lo, n, out_ptr, stream)
+            if nc:
+                cache.update_raw(out_ptr, in_base + 4 * c0, oid_base + 4 * c0, pos_base + 4 * c0,
+                                 nc, stream)
         e_end.record()
         torch.cuda.synchronize()
         t3 = time.perf_counter()

@@ -191,6 +191,9 @@ class FeatureCache:
         self.addr = torch.empty(self.num_nodes, dtype=torch.int32, device=device)
         self._desc = CacheDesc(self.rows.data_ptr(), cap, self.row_bytes, self.addr.data_ptr(),
                                self.num_nodes, slow.data_ptr())
+        self._desc_ref = C.byref(self._desc)
+        self._gather = _lib.load().ginex_gather
+        self._update = _lib.load().ginex_cache_update
 
     def init(self, init_ids: torch.Tensor):
         _dev(init_ids, torch.int32)
@@ -210,6 +213,20 @@ class FeatureCache:
                                         _ptr(out_ids) if nc else None,
                                         _ptr(in_positions) if nc else None, nc, _stream()))
         return out
+
+    def gather_raw(self, ids_ptr: int, n: int, out_ptr: int, stream_ptr: int):
+        """ginex_gather with an empty changeset, on raw device addresses (for tight loops)."""
+        rc = self._gather(self._desc_ref, ids_ptr, n, out_ptr, None, None, None, 0, stream_ptr)
+        if rc:
+            _check(rc)
+
+    def update_raw(self, out_ptr: int, in_ptr: int, outids_ptr: int, pos_ptr: int,
+                   n_change: int, stream_ptr: int):
+        """ginex_cache_update on raw device addresses (for tight loops)."""
+        rc = self._update(self._desc_ref, out_ptr, in_ptr, outids_ptr, pos_ptr, n_change,
+                          stream_ptr)
+        if rc:
+            _check(rc)
 
     def update(self, out, in_ids, out_ids, in_positions):
         """The cache update alone, for a gather that was issued without a changeset."""

@@ -49,14 +49,14 @@ struct State {
   uint32_t* bitmap;     // [ceil(N/32)] select scratch, all zero between iterations
   uint32_t* bit_part;   // popcount of each block of bitmap words
   Ctrl* ctrl;
-  uint32_t* evict_tiles;  // tile counts / scanned bases, by cache line
+  uint64_t* evict_words;  // bit l%64 of word l/64: line l is evicted in this iteration
+  uint32_t* evict_tiles;  // evictions per tile of EVICT_TILE lines, then their scanned bases
   uint32_t* in_tiles;     // the same by position in ids_i
   int32_t* out_slot;      // line of the t-th eviction
   int32_t* in_id;         // node of the t-th insertion
   int32_t* in_next;       // its next accessed iteration
   int64_t cap, num_nodes;
   int32_t S;
-  int32_t tile_items;     // cache lines per thread in the compaction kernels
   int64_t max_change;     // entries of out_slot / in_id / in_next
 };
 
@@ -174,25 +174,56 @@ __global__ __launch_bounds__(TB) void k_copy_init(const uint64_t* __restrict__ h
 }
 
 // ---- part 3 -----------------------------------------------------------------------
+//
+// Every phase of an iteration is a device function over "virtual blocks" of TB threads; the
+// kernels below pack phases that do not depend on each other into one launch (seven
+// launches per iteration).  A single cooperative kernel with grid-wide barriers between
+// the phases was measured too: hipcc's grid.sync() costs about 0.1 ms per barrier on 1024
+// blocks, twelve times slower overall than the launches, so it is not used.
+
+struct Iter {           // what a phase needs to know about the running iteration
+  const int32_t* ids;   // ids_i
+  const int32_t* next;  // next accessed iteration of each access of ids_i
+  int64_t n;            // |ids_i|
+  int32_t i;
+};
+
+struct Outputs {
+  int32_t* in_ids;
+  int32_t* out_ids;
+  int32_t* in_positions;
+  int64_t cs_capacity;
+  int64_t* cs_offsets;
+  int64_t* miss_count;
+};
+
+__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* red) {
+  v = wave_reduce_sum(v);
+  __syncthreads();  // red may still be read from an earlier call
+  if (lane_id() == 0) red[threadIdx.x / WAVE] = v;
+  __syncthreads();
+  uint32_t s = 0;
+  for (int w = 0; w < (int)blockDim.x / WAVE; ++w) s += red[w];
+  return s;
+}
 
 // Refresh the keys of the hits, histogram hits and misses by next iteration.
-__global__ __launch_bounds__(TB) void k_touch(const int32_t* __restrict__ ids,
-                                              const int32_t* __restrict__ next_iter, int64_t n,
-                                              State st, unsigned long long* __restrict__ miss_out) {
-  extern __shared__ uint32_t lds[];  // [S+1] hits, [S+1] misses
+// lds: 2*(S+1) counters.  One virtual block covers TB*TOUCH_ITEMS accesses.
+__device__ void p_touch(const State& st, const Iter& it, unsigned long long* miss_out,
+                        uint32_t* lds, int64_t vb) {
   __shared__ uint32_t red[TB / WAVE];
   uint32_t* hr = lds;
   uint32_t* hi = lds + st.S + 1;
   for (int j = threadIdx.x; j < 2 * (st.S + 1); j += TB) lds[j] = 0;
   __syncthreads();
   uint32_t misses = 0;
-  const int64_t base = (int64_t)blockIdx.x * (TB * TOUCH_ITEMS);
+  const int64_t base = vb * (TB * TOUCH_ITEMS);
 #pragma unroll
-  for (int i = 0; i < TOUCH_ITEMS; ++i) {
-    const int64_t p = base + i * TB + threadIdx.x;
-    if (p < n) {
-      const int32_t nx = next_iter[p];
-      const int32_t line = st.addr[ids[p]];
+  for (int t = 0; t < TOUCH_ITEMS; ++t) {
+    const int64_t p = base + t * TB + threadIdx.x;
+    if (p < it.n) {
+      const int32_t nx = it.next[p];
+      const int32_t line = st.addr[it.ids[p]];
       if (line >= 0) {
         st.res_next[line] = nx;
         atomicAdd(&hr[nx], 1u);
@@ -202,39 +233,34 @@ __global__ __launch_bounds__(TB) void k_touch(const int32_t* __restrict__ ids,
       }
     }
   }
-  misses = wave_reduce_sum(misses);
-  if (lane_id() == 0) red[threadIdx.x / WAVE] = misses;
-  __syncthreads();
-  for (int j = threadIdx.x; j <= st.S; j += TB) {
+  const uint32_t total = block_sum_u32(misses, red);
+  for (int j = it.i + 1 + threadIdx.x; j <= st.S; j += TB) {
     if (hr[j]) atomicAdd(&st.rhist[j], hr[j]);
     if (hi[j]) atomicAdd(&st.ihist[j], hi[j]);
   }
-  if (threadIdx.x == 0) {
-    uint32_t s = 0;
-    for (int w = 0; w < TB / WAVE; ++w) s += red[w];
-    if (s) atomicAdd(miss_out, (unsigned long long)s);
-  }
+  if (threadIdx.x == 0 && total) atomicAdd(miss_out, (unsigned long long)total);
+  __syncthreads();
 }
 
-// Single block.  Walks the buckets from "never" downwards until as many candidates as
-// there were misses are dropped; fixes the threshold bucket, what happens inside it, the
-// size of the changeset, and rolls the resident histogram forward to C_{i+1}.
-__global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i,
-                                                   const int64_t* __restrict__ miss_count,
-                                                   int64_t* __restrict__ cs_offsets) {
-  __shared__ int64_t smem[BIG / WAVE + 1];
+// One block of NT threads.  Walks the buckets from "never" downwards until as many
+// candidates as there were misses are dropped; fixes the threshold bucket, what happens
+// inside it, the size of the changeset, and rolls the resident histogram forward to C_{i+1}.
+template <int NT>
+__device__ void p_threshold(const State& st, int32_t i, const int64_t* miss_count,
+                            int64_t* cs_offsets) {
+  __shared__ int64_t smem[NT / WAVE + 1];
   __shared__ int32_t s_jstar;
   __shared__ uint32_t s_kept;
   const int32_t S = st.S;
   const int64_t n_drop = miss_count[i];
   const int32_t bins = S - i;                     // buckets i+1 .. S, walked as r = S - j
-  const int32_t per = (bins + BIG - 1) / BIG;
+  const int32_t per = (bins + NT - 1) / NT;
   const int32_t r0 = threadIdx.x * per;
   int64_t mine = 0;
   for (int32_t r = r0; r < r0 + per && r < bins; ++r)
     mine += (int64_t)st.rhist[S - r] + st.ihist[S - r];
   int64_t total;
-  int64_t before = block_exclusive_scan<int64_t, BIG>(mine, smem, total);
+  int64_t before = block_exclusive_scan<int64_t, NT>(mine, smem, total);
   if (threadIdx.x == 0) {
     // default: nothing is dropped (no misses); overwritten below by the thread that
     // finds the threshold bucket
@@ -273,7 +299,7 @@ __global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i,
         // evictions inside j*; those of the buckets above j* are added after the barrier
         s_jstar = j;
         s_kept = (uint32_t)(R + I - rem);
-        c.n_change = (int32_t)from_res;  // completed after the barrier
+        c.n_change = (int32_t)from_res;
         *st.ctrl = c;
       }
       before += R + I;
@@ -296,70 +322,67 @@ __global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i,
     st.ihist[j] = 0;
   }
   int64_t above_total;
-  block_exclusive_scan<int64_t, BIG>(above, smem, above_total);
+  block_exclusive_scan<int64_t, NT>(above, smem, above_total);
   if (threadIdx.x == 0 && n_drop > 0) {
     st.ctrl->n_change += (int32_t)above_total;
     cs_offsets[i + 1] = cs_offsets[i] + st.ctrl->n_change;
   }
+  __syncthreads();
 }
 
+constexpr int MARK_ITEMS = 8;   // lines / accesses per thread in the mark phases
+
 // Set the bit of every member of the selected class in bucket j*.
-__global__ __launch_bounds__(TB) void k_mark_residents(State st) {
-  const Ctrl c = *st.ctrl;
-  if (c.mode_res != MODE_SELECT) return;
-  const int64_t span = (int64_t)gridDim.x * TB;
-  for (int64_t s = (int64_t)blockIdx.x * TB + threadIdx.x; s < st.cap; s += span)
-    if (st.res_next[s] == c.jstar) {
+__device__ void p_mark_residents(const State& st, const Ctrl& c, int64_t vb) {
+  const int64_t base = vb * (TB * MARK_ITEMS);
+#pragma unroll
+  for (int t = 0; t < MARK_ITEMS; ++t) {
+    const int64_t s = base + t * TB + threadIdx.x;
+    if (s < st.cap && st.res_next[s] == c.jstar) {
       const uint32_t v = (uint32_t)st.res_id[s];
       atomicOr(&st.bitmap[v >> 5], 1u << (v & 31));
     }
-}
-
-__global__ __launch_bounds__(TB) void k_mark_incoming(State st, const int32_t* __restrict__ ids,
-                                                      const int32_t* __restrict__ next_iter,
-                                                      int64_t n) {
-  const Ctrl c = *st.ctrl;
-  if (c.mode_in != MODE_SELECT) return;
-  const int64_t p = (int64_t)blockIdx.x * TB + threadIdx.x;
-  if (p < n && next_iter[p] == c.jstar) {
-    const uint32_t v = (uint32_t)ids[p];
-    if (st.addr[v] < 0) atomicOr(&st.bitmap[v >> 5], 1u << (v & 31));
   }
 }
 
-__global__ __launch_bounds__(TB) void k_bits_count(State st, int64_t words) {
-  const Ctrl c = *st.ctrl;
-  if (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT) return;
+__device__ void p_mark_incoming(const State& st, const Ctrl& c, const Iter& it, int64_t vb) {
+  const int64_t base = vb * (TB * MARK_ITEMS);
+#pragma unroll
+  for (int t = 0; t < MARK_ITEMS; ++t) {
+    const int64_t p = base + t * TB + threadIdx.x;
+    if (p < it.n && it.next[p] == c.jstar) {
+      const uint32_t v = (uint32_t)it.ids[p];
+      if (st.addr[v] < 0) atomicOr(&st.bitmap[v >> 5], 1u << (v & 31));
+    }
+  }
+}
+
+// popcount of one part (TB*BITS_WORDS words) of the bitmap
+__device__ void p_bits_count(const State& st, int64_t words, int64_t vb) {
   __shared__ uint32_t red[TB / WAVE];
-  const int64_t base = ((int64_t)blockIdx.x * TB + threadIdx.x) * BITS_WORDS;
+  const int64_t base = (vb * TB + threadIdx.x) * BITS_WORDS;
   uint32_t cnt = 0;
 #pragma unroll
-  for (int i = 0; i < BITS_WORDS; ++i)
-    if (base + i < words) cnt += __popc(st.bitmap[base + i]);
-  cnt = wave_reduce_sum(cnt);
-  if (lane_id() == 0) red[threadIdx.x / WAVE] = cnt;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t s = 0;
-    for (int w = 0; w < TB / WAVE; ++w) s += red[w];
-    st.bit_part[blockIdx.x] = s;
-  }
+  for (int t = 0; t < BITS_WORDS; ++t)
+    if (base + t < words) cnt += __popc(st.bitmap[base + t]);
+  const uint32_t total = block_sum_u32(cnt, red);
+  if (threadIdx.x == 0) st.bit_part[vb] = total;
 }
 
-// Single block: T = the id whose bit is the keep-th set bit of the bitmap.
-__global__ __launch_bounds__(BIG) void k_bits_find(State st, int64_t words, int64_t parts) {
+// One block of NT threads: T = the id whose bit is the keep-th set bit of the bitmap.
+template <int NT>
+__device__ void p_bits_find(const State& st, int64_t words, int64_t parts) {
   Ctrl* c = st.ctrl;
-  if (c->mode_res != MODE_SELECT && c->mode_in != MODE_SELECT) return;
-  __shared__ int64_t smem[BIG / WAVE + 1];
+  __shared__ int64_t smem[NT / WAVE + 1];
   __shared__ int64_t s_part, s_before;
   const int64_t keep = c->keep;
-  // 1. the block of words that holds the keep-th set bit
-  const int64_t per = (parts + BIG - 1) / BIG;
+  // 1. the part that holds the keep-th set bit
+  const int64_t per = (parts + NT - 1) / NT;
   const int64_t q0 = threadIdx.x * per;
   int64_t mine = 0;
   for (int64_t q = q0; q < q0 + per && q < parts; ++q) mine += st.bit_part[q];
   int64_t total;
-  int64_t before = block_exclusive_scan<int64_t, BIG>(mine, smem, total);
+  int64_t before = block_exclusive_scan<int64_t, NT>(mine, smem, total);
   if (threadIdx.x == 0) s_part = -1;
   __syncthreads();
   for (int64_t q = q0; q < q0 + per && q < parts; ++q) {
@@ -371,19 +394,18 @@ __global__ __launch_bounds__(BIG) void k_bits_find(State st, int64_t words, int6
     before += cnt;
   }
   __syncthreads();
-  if (s_part < 0) return;  // fewer set bits than asked for: cannot happen, keep T = -1
-  // 2. the word inside that block (TB*BITS_WORDS words, two per thread of this block)
-  const int64_t wbase = s_part * (TB * BITS_WORDS);
-  constexpr int WPT = TB * BITS_WORDS / BIG;
-  const int64_t w0 = wbase + (int64_t)threadIdx.x * WPT;
+  if (s_part < 0) return;  // fewer set bits than asked for: cannot happen, T stays -1
+  // 2. the word inside that part, then the bit inside the word
+  constexpr int WPT = TB * BITS_WORDS / NT;
+  const int64_t w0 = s_part * (TB * BITS_WORDS) + (int64_t)threadIdx.x * WPT;
   int64_t cntw = 0;
-  for (int i = 0; i < WPT; ++i)
-    if (w0 + i < words) cntw += __popc(st.bitmap[w0 + i]);
+  for (int t = 0; t < WPT; ++t)
+    if (w0 + t < words) cntw += __popc(st.bitmap[w0 + t]);
   int64_t tot2;
-  int64_t bw = s_before + block_exclusive_scan<int64_t, BIG>(cntw, smem, tot2);
-  for (int i = 0; i < WPT; ++i)
-    if (w0 + i < words) {
-      uint32_t word = st.bitmap[w0 + i];
+  int64_t bw = s_before + block_exclusive_scan<int64_t, NT>(cntw, smem, tot2);
+  for (int t = 0; t < WPT; ++t)
+    if (w0 + t < words) {
+      uint32_t word = st.bitmap[w0 + t];
       const int pc = __popc(word);
       if (bw < keep && bw + pc >= keep) {
         int need = (int)(keep - bw);  // the need-th set bit of this word, 1-based
@@ -393,17 +415,20 @@ __global__ __launch_bounds__(BIG) void k_bits_find(State st, int64_t words, int6
           if (--need == 0) break;
           word &= word - 1;
         }
-        c->T = (int32_t)((w0 + i) * 32 + bit);
+        c->T = (int32_t)((w0 + t) * 32 + bit);
       }
       bw += pc;
     }
+  __syncthreads();
 }
 
-__global__ __launch_bounds__(TB) void k_bits_clear(State st, int64_t words) {
-  const Ctrl c = *st.ctrl;
-  if (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT) return;
-  const int64_t span = (int64_t)gridDim.x * TB;
-  for (int64_t w = (int64_t)blockIdx.x * TB + threadIdx.x; w < words; w += span) st.bitmap[w] = 0;
+__device__ void p_bits_clear(const State& st, int64_t words, int64_t vb) {
+  const int64_t base = vb * (TB * BITS_WORDS);
+#pragma unroll
+  for (int t = 0; t < BITS_WORDS; ++t) {
+    const int64_t w = base + t * TB + threadIdx.x;
+    if (w < words) st.bitmap[w] = 0;
+  }
 }
 
 __device__ __forceinline__ bool evicts(const Ctrl& c, int32_t next, int32_t id) {
@@ -415,142 +440,125 @@ __device__ __forceinline__ bool inserts(const Ctrl& c, int32_t next, int32_t id)
          (next == c.jstar && (c.mode_in == MODE_ALL || (c.mode_in == MODE_SELECT && id <= c.T)));
 }
 
-// Evictions per tile of cache lines.
-__global__ __launch_bounds__(TB) void k_evict_count(State st) {
-  const Ctrl c = *st.ctrl;
+__device__ __forceinline__ bool line_evicted(const State& st, const Ctrl& c, int64_t s) {
+  const int32_t next = st.res_next[s];
+  if (next < c.jstar) return false;   // the common case needs no look at the node id
+  return evicts(c, next, st.res_id[s]);
+}
+
+constexpr int EVICT_TILE = WAVE * WAVE;   // cache lines per tile: 64 flag words of 64 lines
+
+// Eviction flags of one tile of cache lines.  A wave reads 64 consecutive lines at a time
+// (coalesced) and its ballot is a 64-bit flag word; the four waves of the block share the
+// tile's 64 words.  The tile's total goes to evict_tiles.
+__device__ void p_evict_flags(const State& st, const Ctrl& c, int64_t vb) {
   __shared__ uint32_t red[TB / WAVE];
-  const int64_t base = (int64_t)blockIdx.x * TB * st.tile_items + (int64_t)threadIdx.x * st.tile_items;
+  constexpr int PER_WAVE = WAVE / (TB / WAVE);
+  const int64_t first_word = vb * WAVE + (threadIdx.x / WAVE) * PER_WAVE;
   uint32_t cnt = 0;
-  if (c.n_change > 0)
-    for (int t = 0; t < st.tile_items; ++t) {
-      const int64_t s = base + t;
-      if (s < st.cap) cnt += evicts(c, st.res_next[s], st.res_id[s]);
+#pragma unroll 4
+  for (int g = 0; g < PER_WAVE; ++g) {
+    const int64_t line = (first_word + g) * WAVE + lane_id();
+    const bool out = line < st.cap && line_evicted(st, c, line);
+    const uint64_t word = __ballot(out);
+    if ((first_word + g) * WAVE < st.cap && lane_id() == 0) {
+      st.evict_words[first_word + g] = word;
+      cnt += __popcll(word);
     }
-  cnt = wave_reduce_sum(cnt);
-  if (lane_id() == 0) red[threadIdx.x / WAVE] = cnt;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t s = 0;
-    for (int w = 0; w < TB / WAVE; ++w) s += red[w];
-    st.evict_tiles[blockIdx.x] = s;
   }
+  const uint32_t total = block_sum_u32(cnt, red);
+  if (threadIdx.x == 0) st.evict_tiles[vb] = total;
 }
 
 constexpr int IN_ITEMS = 8;
 
-__global__ __launch_bounds__(TB) void k_in_count(State st, const int32_t* __restrict__ ids,
-                                                 const int32_t* __restrict__ next_iter, int64_t n) {
-  const Ctrl c = *st.ctrl;
+__device__ void p_in_count(const State& st, const Ctrl& c, const Iter& it, int64_t vb) {
   __shared__ uint32_t red[TB / WAVE];
-  const int64_t base = ((int64_t)blockIdx.x * TB + threadIdx.x) * IN_ITEMS;
+  const int64_t base = (vb * TB + threadIdx.x) * IN_ITEMS;
   uint32_t cnt = 0;
-  if (c.n_change > 0)
-    for (int t = 0; t < IN_ITEMS; ++t) {
-      const int64_t p = base + t;
-      if (p < n) {
-        const int32_t v = ids[p];
-        cnt += st.addr[v] < 0 && inserts(c, next_iter[p], v);
-      }
+  for (int t = 0; t < IN_ITEMS; ++t) {
+    const int64_t p = base + t;
+    if (p < it.n) {
+      const int32_t v = it.ids[p];
+      cnt += inserts(c, it.next[p], v) && st.addr[v] < 0;
     }
-  cnt = wave_reduce_sum(cnt);
-  if (lane_id() == 0) red[threadIdx.x / WAVE] = cnt;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t s = 0;
-    for (int w = 0; w < TB / WAVE; ++w) s += red[w];
-    st.in_tiles[blockIdx.x] = s;
   }
+  const uint32_t total = block_sum_u32(cnt, red);
+  if (threadIdx.x == 0) st.in_tiles[vb] = total;
 }
 
-// Two blocks: block 0 scans the eviction tile counts, block 1 the insertion tile counts.
-__global__ __launch_bounds__(BIG) void k_scan_two(uint32_t* a, int64_t na, uint32_t* b, int64_t nb) {
-  __shared__ uint32_t smem[BIG / WAVE + 1];
-  uint32_t* data = blockIdx.x == 0 ? a : b;
-  const int64_t n = blockIdx.x == 0 ? na : nb;
+// One block of NT threads: exclusive scan of n counters in place.
+template <int NT>
+__device__ void p_scan_counts(uint32_t* data, int64_t n) {
+  __shared__ uint32_t smem[NT / WAVE + 1];
   uint32_t carry = 0;
-  for (int64_t base = 0; base < n; base += BIG) {
-    const int64_t i = base + threadIdx.x;
-    const uint32_t v = i < n ? data[i] : 0;
+  for (int64_t base = 0; base < n; base += NT) {
+    const int64_t j = base + threadIdx.x;
+    const uint32_t v = j < n ? data[j] : 0;
     uint32_t total;
-    const uint32_t ex = block_exclusive_scan<uint32_t, BIG>(v, smem, total);
-    if (i < n) data[i] = carry + ex;
+    const uint32_t ex = block_exclusive_scan<uint32_t, NT>(v, smem, total);
+    if (j < n) data[j] = carry + ex;
     carry += total;
   }
 }
 
-__global__ __launch_bounds__(TB) void k_evict_emit(State st, int32_t i,
-                                                   const int64_t* __restrict__ cs_offsets,
-                                                   int32_t* __restrict__ out_ids,
-                                                   int64_t cs_capacity) {
-  const Ctrl c = *st.ctrl;
-  if (c.n_change <= 0) return;
-  __shared__ uint32_t smem[TB / WAVE + 1];
-  const int64_t base = (int64_t)blockIdx.x * TB * st.tile_items + (int64_t)threadIdx.x * st.tile_items;
-  uint32_t cnt = 0;
-  for (int t = 0; t < st.tile_items; ++t) {
-    const int64_t s = base + t;
-    if (s < st.cap) cnt += evicts(c, st.res_next[s], st.res_id[s]);
-  }
-  uint32_t total;
-  uint32_t at = st.evict_tiles[blockIdx.x] + block_exclusive_scan<uint32_t, TB>(cnt, smem, total);
-  if (!cnt) return;
-  const int64_t dst = cs_offsets[i];
-  for (int t = 0; t < st.tile_items; ++t) {
-    const int64_t s = base + t;
-    if (s < st.cap && evicts(c, st.res_next[s], st.res_id[s])) {
-      if (at < st.max_change) st.out_slot[at] = (int32_t)s;
-      if (dst + at < cs_capacity) out_ids[dst + at] = st.res_id[s];
-      ++at;
-    }
+// One thread per flag word, one wave per tile: the evicted lines in line order.
+__device__ void p_evict_emit(const State& st, int32_t i, const Outputs& o, int64_t vb,
+                             int64_t tiles) {
+  const int64_t tile = vb * (TB / WAVE) + threadIdx.x / WAVE;
+  if (tile >= tiles) return;
+  const int64_t word_at = tile * WAVE + lane_id();
+  uint64_t word = word_at * WAVE < st.cap ? st.evict_words[word_at] : 0;
+  const uint32_t mine = (uint32_t)__popcll(word);
+  uint32_t at = st.evict_tiles[tile] + wave_inclusive_scan(mine) - mine;
+  const int64_t dst = o.cs_offsets[i];
+  while (word) {
+    const int64_t line = word_at * WAVE + (__ffsll((unsigned long long)word) - 1);
+    word &= word - 1;
+    if (at < st.max_change) st.out_slot[at] = (int32_t)line;
+    if (dst + at < o.cs_capacity) o.out_ids[dst + at] = st.res_id[line];
+    ++at;
   }
 }
 
-__global__ __launch_bounds__(TB) void k_in_emit(State st, int32_t i,
-                                                const int32_t* __restrict__ ids,
-                                                const int32_t* __restrict__ next_iter, int64_t n,
-                                                const int64_t* __restrict__ cs_offsets,
-                                                int32_t* __restrict__ in_ids,
-                                                int32_t* __restrict__ in_positions,
-                                                int64_t cs_capacity) {
-  const Ctrl c = *st.ctrl;
-  if (c.n_change <= 0) return;
+__device__ void p_in_emit(const State& st, const Ctrl& c, const Iter& it, const Outputs& o,
+                          int64_t vb) {
   __shared__ uint32_t smem[TB / WAVE + 1];
-  const int64_t base = ((int64_t)blockIdx.x * TB + threadIdx.x) * IN_ITEMS;
+  const int64_t base = (vb * TB + threadIdx.x) * IN_ITEMS;
   uint32_t flags = 0, cnt = 0;
   for (int t = 0; t < IN_ITEMS; ++t) {
     const int64_t p = base + t;
-    if (p < n) {
-      const int32_t v = ids[p];
-      if (st.addr[v] < 0 && inserts(c, next_iter[p], v)) {
+    if (p < it.n) {
+      const int32_t v = it.ids[p];
+      if (inserts(c, it.next[p], v) && st.addr[v] < 0) {
         flags |= 1u << t;
         ++cnt;
       }
     }
   }
   uint32_t total;
-  uint32_t at = st.in_tiles[blockIdx.x] + block_exclusive_scan<uint32_t, TB>(cnt, smem, total);
+  uint32_t at = st.in_tiles[vb] + block_exclusive_scan<uint32_t, TB>(cnt, smem, total);
   if (!cnt) return;
-  const int64_t dst = cs_offsets[i];
+  const int64_t dst = o.cs_offsets[it.i];
   for (int t = 0; t < IN_ITEMS; ++t)
     if (flags >> t & 1) {
       const int64_t p = base + t;
       if (at < st.max_change) {
-        st.in_id[at] = ids[p];
-        st.in_next[at] = next_iter[p];
+        st.in_id[at] = it.ids[p];
+        st.in_next[at] = it.next[p];
       }
-      if (dst + at < cs_capacity) {
-        in_ids[dst + at] = ids[p];
-        in_positions[dst + at] = (int32_t)p;
+      if (dst + at < o.cs_capacity) {
+        o.in_ids[dst + at] = it.ids[p];
+        o.in_positions[dst + at] = (int32_t)p;
       }
       ++at;
     }
 }
 
 // The t-th inserted row takes the line of the t-th evicted one.
-__global__ __launch_bounds__(TB) void k_apply(State st) {
-  const int32_t n = st.ctrl->n_change;
-  const int64_t t = (int64_t)blockIdx.x * TB + threadIdx.x;
-  if (t >= n || t >= st.max_change) return;
+__device__ void p_apply(const State& st, int32_t n_change, int64_t vb) {
+  const int64_t t = vb * TB + threadIdx.x;
+  if (t >= n_change || t >= st.max_change) return;
   const int32_t line = st.out_slot[t];
   const int32_t gone = st.res_id[line];
   const int32_t v = st.in_id[t];
@@ -558,6 +566,72 @@ __global__ __launch_bounds__(TB) void k_apply(State st) {
   st.res_next[line] = st.in_next[t];
   st.addr[gone] = -1;
   st.addr[v] = line;
+}
+
+// ---- the launches of one iteration -----------------------------------------------------
+
+__global__ __launch_bounds__(TB) void k_touch(State st, Iter it, unsigned long long* miss_out) {
+  extern __shared__ uint32_t lds[];
+  p_touch(st, it, miss_out, lds, blockIdx.x);
+}
+
+__global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i, Outputs o) {
+  p_threshold<BIG>(st, i, o.miss_count, o.cs_offsets);
+}
+
+// blocks [0, res_blocks) mark residents, the rest incoming rows; only one class is selected
+__global__ __launch_bounds__(TB) void k_mark(State st, Iter it, int64_t res_blocks) {
+  const Ctrl c = *st.ctrl;
+  if ((int64_t)blockIdx.x < res_blocks) {
+    if (c.mode_res == MODE_SELECT) p_mark_residents(st, c, blockIdx.x);
+  } else if (c.mode_in == MODE_SELECT) {
+    p_mark_incoming(st, c, it, blockIdx.x - res_blocks);
+  }
+}
+
+__global__ __launch_bounds__(TB) void k_bits_count(State st, int64_t words) {
+  const Ctrl c = *st.ctrl;
+  if (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT) return;
+  p_bits_count(st, words, blockIdx.x);
+}
+
+__global__ __launch_bounds__(BIG) void k_bits_find(State st, int64_t words, int64_t parts) {
+  const Ctrl c = *st.ctrl;
+  if (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT) return;
+  p_bits_find<BIG>(st, words, parts);
+}
+
+// blocks [0, evict_tiles): evictions per tile; next in_tiles blocks: insertions per tile;
+// the remaining blocks clear the select bitmap
+__global__ __launch_bounds__(TB) void k_tile_count(State st, Iter it, int64_t evict_tiles,
+                                              int64_t in_tiles, int64_t words) {
+  const Ctrl c = *st.ctrl;
+  const int64_t vb = blockIdx.x;
+  if (vb < evict_tiles) {
+    if (c.n_change > 0) p_evict_flags(st, c, vb);
+  } else if (vb < evict_tiles + in_tiles) {
+    if (c.n_change > 0) p_in_count(st, c, it, vb - evict_tiles);
+  } else if (c.mode_res == MODE_SELECT || c.mode_in == MODE_SELECT) {
+    p_bits_clear(st, words, vb - evict_tiles - in_tiles);
+  }
+}
+
+__global__ __launch_bounds__(BIG) void k_scan_two(State st, int64_t evict_tiles, int64_t in_tiles) {
+  if (st.ctrl->n_change <= 0) return;
+  if (blockIdx.x == 0) p_scan_counts<BIG>(st.evict_tiles, evict_tiles);
+  else p_scan_counts<BIG>(st.in_tiles, in_tiles);
+}
+
+__global__ __launch_bounds__(TB) void k_tile_emit(State st, Iter it, Outputs o, int64_t evict_tiles) {
+  const Ctrl c = *st.ctrl;
+  if (c.n_change <= 0) return;
+  const int64_t evict_blocks = (evict_tiles + TB / WAVE - 1) / (TB / WAVE);
+  if ((int64_t)blockIdx.x < evict_blocks) p_evict_emit(st, it.i, o, blockIdx.x, evict_tiles);
+  else p_in_emit(st, c, it, o, blockIdx.x - evict_blocks);
+}
+
+__global__ __launch_bounds__(TB) void k_apply(State st) {
+  p_apply(st, st.ctrl->n_change, blockIdx.x);
 }
 
 struct Workspace {
@@ -609,10 +683,8 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   st.bitmap = a.take<uint32_t>(w.bit_words);
   st.bit_part = a.take<uint32_t>(w.bit_parts);
   st.ctrl = a.take<Ctrl>(1);
-  int64_t items = ceil_div(c, (int64_t)TB * 65536);
-  if (items < 8) items = 8;
-  st.tile_items = (int32_t)items;
-  w.evict_tiles = ceil_div(c, (int64_t)TB * items);
+  w.evict_tiles = ceil_div(c, (int64_t)EVICT_TILE);
+  st.evict_words = a.take<uint64_t>(w.evict_tiles * WAVE);
   w.in_tiles = ceil_div(max_n > 0 ? max_n : 1, (int64_t)TB * IN_ITEMS);
   st.evict_tiles = a.take<uint32_t>(w.evict_tiles);
   st.in_tiles = a.take<uint32_t>(w.in_tiles);
@@ -760,47 +832,44 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
     GINEX_LAUNCH_CHECK();
   }
 
-  // part 3: one round of kernels per iteration, no host round trip in between
+  // part 3: the recurrence, with no host round trip between iterations
   const size_t touch_lds = sizeof(uint32_t) * 2 * (S + 1);
-  int64_t slot_blocks = ceil_div(cap, TB * 8);
-  if (slot_blocks > 8192) slot_blocks = 8192;
-  int64_t word_blocks = ceil_div(w.bit_words, TB * 8);
-  if (word_blocks > 8192) word_blocks = 8192;
-  for (int32_t i = 0; i < S; ++i) {
-    const int64_t lo = ids_offsets[i];
-    const int64_t n = ids_offsets[i + 1] - lo;
-    const int32_t* ids_i = ids + lo;
-    const int32_t* next_i = w.next_iter + lo;
-    if (n > 0) {
-      hipLaunchKernelGGL(k_touch, dim3((unsigned)ceil_div(n, TB * TOUCH_ITEMS)), dim3(TB), touch_lds,
-                         st, ids_i, next_i, n, state, (unsigned long long*)(miss_count + i));
+  Outputs outs{in_ids, out_ids, in_positions, cs_capacity, cs_offsets, miss_count};
+  {
+    const int64_t res_blocks = ceil_div(cap, TB * MARK_ITEMS);
+    const int64_t clear_blocks = ceil_div(w.bit_words, TB * BITS_WORDS);
+    for (int32_t i = 0; i < S; ++i) {
+      Iter it;
+      const int64_t lo = ids_offsets[i];
+      it.ids = ids + lo;
+      it.next = w.next_iter + lo;
+      it.n = ids_offsets[i + 1] - lo;
+      it.i = i;
+      if (it.n > 0) {
+        hipLaunchKernelGGL(k_touch, dim3((unsigned)ceil_div(it.n, TB * TOUCH_ITEMS)), dim3(TB),
+                           touch_lds, st, state, it, (unsigned long long*)(miss_count + i));
+        GINEX_LAUNCH_CHECK();
+      }
+      hipLaunchKernelGGL(k_threshold, dim3(1), dim3(BIG), 0, st, state, i, outs);
+      GINEX_LAUNCH_CHECK();
+      if (it.n == 0) continue;  // nothing missed, nothing changes
+      const int64_t in_tiles = ceil_div(it.n, (int64_t)TB * IN_ITEMS);
+      hipLaunchKernelGGL(k_mark, dim3((unsigned)(res_blocks + ceil_div(it.n, TB * MARK_ITEMS))),
+                         dim3(TB), 0, st, state, it, res_blocks);
+      hipLaunchKernelGGL(k_bits_count, dim3((unsigned)w.bit_parts), dim3(TB), 0, st, state,
+                         w.bit_words);
+      hipLaunchKernelGGL(k_bits_find, dim3(1), dim3(BIG), 0, st, state, w.bit_words, w.bit_parts);
+      GINEX_LAUNCH_CHECK();
+      hipLaunchKernelGGL(k_tile_count, dim3((unsigned)(w.evict_tiles + in_tiles + clear_blocks)),
+                         dim3(TB), 0, st, state, it, w.evict_tiles, in_tiles, w.bit_words);
+      hipLaunchKernelGGL(k_scan_two, dim3(2), dim3(BIG), 0, st, state, w.evict_tiles, in_tiles);
+      hipLaunchKernelGGL(k_tile_emit,
+                         dim3((unsigned)(ceil_div(w.evict_tiles, TB / WAVE) + in_tiles)), dim3(TB), 0,
+                         st, state, it, outs, w.evict_tiles);
+      const int64_t most = it.n < cap ? it.n : cap;
+      hipLaunchKernelGGL(k_apply, dim3((unsigned)ceil_div(most, TB)), dim3(TB), 0, st, state);
       GINEX_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(k_threshold, dim3(1), dim3(BIG), 0, st, state, i, miss_count, cs_offsets);
-    GINEX_LAUNCH_CHECK();
-    if (n == 0) continue;  // nothing missed, nothing changes
-    hipLaunchKernelGGL(k_mark_residents, dim3((unsigned)slot_blocks), dim3(TB), 0, st, state);
-    hipLaunchKernelGGL(k_mark_incoming, dim3((unsigned)ceil_div(n, TB)), dim3(TB), 0, st, state,
-                       ids_i, next_i, n);
-    hipLaunchKernelGGL(k_bits_count, dim3((unsigned)w.bit_parts), dim3(TB), 0, st, state,
-                       w.bit_words);
-    hipLaunchKernelGGL(k_bits_find, dim3(1), dim3(BIG), 0, st, state, w.bit_words, w.bit_parts);
-    hipLaunchKernelGGL(k_bits_clear, dim3((unsigned)word_blocks), dim3(TB), 0, st, state,
-                       w.bit_words);
-    GINEX_LAUNCH_CHECK();
-    const int64_t in_tiles = ceil_div(n, (int64_t)TB * IN_ITEMS);
-    hipLaunchKernelGGL(k_evict_count, dim3((unsigned)w.evict_tiles), dim3(TB), 0, st, state);
-    hipLaunchKernelGGL(k_in_count, dim3((unsigned)in_tiles), dim3(TB), 0, st, state, ids_i, next_i,
-                       n);
-    hipLaunchKernelGGL(k_scan_two, dim3(2), dim3(BIG), 0, st, state.evict_tiles, w.evict_tiles,
-                       state.in_tiles, in_tiles);
-    hipLaunchKernelGGL(k_evict_emit, dim3((unsigned)w.evict_tiles), dim3(TB), 0, st, state, i,
-                       cs_offsets, out_ids, cs_capacity);
-    hipLaunchKernelGGL(k_in_emit, dim3((unsigned)in_tiles), dim3(TB), 0, st, state, i, ids_i, next_i,
-                       n, cs_offsets, in_ids, in_positions, cs_capacity);
-    const int64_t most = n < cap ? n : cap;
-    hipLaunchKernelGGL(k_apply, dim3((unsigned)ceil_div(most, TB)), dim3(TB), 0, st, state);
-    GINEX_LAUNCH_CHECK();
   }
   GINEX_HIP(hipMemcpyAsync(total_changes, cs_offsets + S, sizeof(int64_t), hipMemcpyDeviceToHost,
                            st));

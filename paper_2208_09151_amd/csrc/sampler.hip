@@ -4,6 +4,11 @@
 // All S batches of the superbatch advance hop by hop in the same launches, so a hop is a
 // handful of grid-wide kernels over (batch, frontier slot) instead of S small ones:
 //
+//   plan    every batch gets a hash table sized for what the hop can add at most
+//           (list + frontier * fanout, two slots per possible entry), packed back to back;
+//           the used region is cleared and the batch's current list re-inserted.  Tables
+//           sized to the need instead of the worst case keep many entries per cache line
+//           and the working set of the batches in flight inside L2 / Infinity Cache.
 //   pick    a group of G lanes (G = 16/32/64 >= fanout) serves one frontier node: the
 //           lanes draw their Philox words in parallel, resolve Floyd's subset rule with
 //           group ballots, rank the picks, read the neighbours and insert them into the
@@ -11,13 +16,14 @@
 //           (frontier slot * fanout + pick slot) is exactly the order in which a
 //           sequential scan would meet the candidate, so after the kernel every new id
 //           holds the rank of its first occurrence.
-//   count   per 256 frontier slots: number of picks and number of first occurrences.
+//   count   per frontier slot: which picks are first occurrences (bit mask); per 256
+//           slots: number of picks and number of first occurrences.
 //   scan    one block per batch scans its tile counts; one block turns the per-batch
 //           totals into output offsets.
-//   emit    recomputes the first-occurrence flags, appends the new ids to the batch's
-//           list at their scanned positions, stores their final list position in the
-//           hash table and writes the hop's rowptr.
-//   col     every pick looks its final position up and writes adj_col.
+//   emit    appends the first occurrences to the batch's list at their scanned positions,
+//           writes the hop's rowptr and the adj_col entries of the first occurrences.
+//   col     the remaining picks (ids seen before, or seen earlier in this hop) look their
+//           position up for adj_col.
 //
 // The seeds go through the same count/scan/emit path as a stage with one candidate per
 // slot, which also removes repeated seeds.
@@ -27,7 +33,6 @@ namespace ginex {
 namespace {
 
 constexpr int TB = 256;                  // threads per block everywhere in this file
-constexpr uint32_t EMPTY = 0xFFFFFFFFu;  // free hash slot / "no value yet"
 constexpr uint32_t PEND = 0x40000000u;   // value = PEND + rank while an id is new in this stage
 
 // Philox4x32-10 (Salmon et al., SC'11), counter (node, batch, hop, draw), key = seed.
@@ -51,10 +56,10 @@ __device__ __forceinline__ uint64_t philox_draw(uint64_t seed, uint32_t node, ui
 }
 
 struct Tables {
-  uint32_t* tab;         // [S][table_slots][2]: key, value
-  int64_t table_slots;   // power of two
-  uint32_t mask;
-  int shift;             // 32 - log2(table_slots)
+  uint64_t* tab;         // packed per-batch tables, one 64-bit (key, value) word per slot
+  int64_t* tab_off;      // [S] first slot of batch b's table
+  uint32_t* tab_slots;   // [S] its number of slots
+  uint64_t* first;       // [S][fr_slots] bit s set: pick s of the slot is a first occurrence
   int32_t* cand;         // [S][cand_slots] candidate node ids of the running stage
   uint32_t* hslot;       // [S][cand_slots] hash slot of each candidate
   uint8_t* cnt;          // [S][fr_slots] picks per frontier slot
@@ -63,16 +68,71 @@ struct Tables {
   int64_t stride_ids;
 };
 
-__device__ __forceinline__ uint32_t table_insert(uint32_t* t, uint32_t mask, int shift,
-                                                 uint32_t id, uint32_t value) {
-  uint32_t h = (id * 2654435761u) >> shift;
+// A slot is one 64-bit word: key in the high half, value in the low half, all ones = free.
+// Inserting costs one 64-bit compare-and-swap when the key is new (the usual case); a key
+// that is present already keeps the smaller value, which needs a second atomic only when
+// this candidate's value is smaller than the stored one.
+__device__ __forceinline__ uint32_t table_insert(uint64_t* t, uint32_t slots, uint32_t id,
+                                                 uint32_t value) {
+  const unsigned long long mine = ((unsigned long long)id << 32) | value;
+  unsigned long long* tab = reinterpret_cast<unsigned long long*>(t);
+  uint32_t h = __umulhi(id * 2654435761u, slots);
   while (true) {
-    const uint32_t old = atomicCAS(&t[2 * (size_t)h], EMPTY, id);
-    if (old == EMPTY || old == id) break;
-    h = (h + 1) & mask;
+    const unsigned long long old = atomicCAS(&tab[h], ~0ull, mine);
+    if (old == ~0ull) break;
+    if ((uint32_t)(old >> 32) == id) {
+      if ((uint32_t)old > value) atomicMin(&tab[h], mine);
+      break;
+    }
+    h = h + 1 == slots ? 0 : h + 1;
   }
-  atomicMin(&t[2 * (size_t)h + 1], value);
   return h;
+}
+
+__device__ __forceinline__ uint32_t table_value(const uint64_t* t, uint32_t h) {
+  return (uint32_t)t[h];
+}
+
+// Single block: table sizes and offsets for the stage that is about to run.
+__global__ __launch_bounds__(TB) void k_table_plan(Tables T, int S, int64_t num_nodes, int k,
+                                                   const int32_t* __restrict__ nfront,
+                                                   const int32_t* __restrict__ nlist,
+                                                   int64_t* __restrict__ total_slots) {
+  __shared__ int64_t smem[TB / WAVE + 1];
+  int64_t run = 0;
+  for (int base = 0; base < S; base += TB) {
+    const int b = base + threadIdx.x;
+    int64_t slots = 0;
+    if (b < S) {
+      int64_t bound = (int64_t)nlist[b] + (int64_t)nfront[b] * k;
+      if (bound > num_nodes) bound = num_nodes;
+      slots = 2 * bound < 32 ? 32 : 2 * bound;
+    }
+    int64_t total;
+    const int64_t ex = block_exclusive_scan<int64_t, TB>(slots, smem, total);
+    if (b < S) {
+      T.tab_off[b] = run + ex;
+      T.tab_slots[b] = (uint32_t)slots;
+    }
+    run += total;
+  }
+  if (threadIdx.x == 0) *total_slots = run;
+}
+
+__global__ __launch_bounds__(TB) void k_table_clear(uint64_t* __restrict__ tab,
+                                                    const int64_t* __restrict__ total_slots) {
+  const int64_t n = *total_slots;
+  const int64_t span = (int64_t)gridDim.x * TB;
+  for (int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x; i < n; i += span) tab[i] = ~0ull;
+}
+
+// Put the list a batch has so far back into its freshly sized table.
+__global__ __launch_bounds__(TB) void k_reinsert(Tables T, const int32_t* __restrict__ nlist) {
+  const int b = blockIdx.y;
+  const int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (j >= nlist[b]) return;
+  uint64_t* t = T.tab + T.tab_off[b];
+  table_insert(t, T.tab_slots[b], (uint32_t)T.wlist[b * T.stride_ids + j], (uint32_t)j);
 }
 
 // Stage "seeds": slot j of batch b holds seed j.
@@ -83,9 +143,9 @@ __global__ __launch_bounds__(TB) void k_seed_stage(Tables T, const int32_t* __re
   const int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
   if (j >= nfront[b]) return;
   const uint32_t id = (uint32_t)seeds[seed_off[b] + j];
-  uint32_t* t = T.tab + (size_t)b * T.table_slots * 2;
+  uint64_t* t = T.tab + T.tab_off[b];
   T.cand[b * T.cand_slots + j] = (int32_t)id;
-  T.hslot[b * T.cand_slots + j] = table_insert(t, T.mask, T.shift, id, PEND + (uint32_t)j);
+  T.hslot[b * T.cand_slots + j] = table_insert(t, T.tab_slots[b], id, PEND + (uint32_t)j);
   T.cnt[b * T.fr_slots + j] = 1;
 }
 
@@ -133,34 +193,30 @@ __global__ __launch_bounds__(TB) void k_pick(Tables T, const OffT* __restrict__ 
   if (active && sub < c) {
     const uint32_t u = (uint32_t)indices[lo + pick];
     const int64_t at = b * T.cand_slots + idx * k + slot;
-    uint32_t* t = T.tab + (size_t)b * T.table_slots * 2;
+    uint64_t* t = T.tab + T.tab_off[b];
     T.cand[at] = (int32_t)u;
-    T.hslot[at] = table_insert(t, T.mask, T.shift, u, PEND + (uint32_t)(idx * k + slot));
+    T.hslot[at] = table_insert(t, T.tab_slots[b], u, PEND + (uint32_t)(idx * k + slot));
   }
   if (active && sub == 0) T.cnt[b * T.fr_slots + idx] = (uint8_t)c;
 }
 
-// Per frontier slot: picks made and first occurrences among them (bit t of `first`).
-__device__ __forceinline__ int slot_flags(const Tables& T, int b, int64_t idx, int k, int active,
-                                          uint64_t& first) {
-  first = 0;
-  if (!active) return 0;
-  const int c = T.cnt[b * T.fr_slots + idx];
-  const uint32_t* t = T.tab + (size_t)b * T.table_slots * 2;
-  const int64_t at = b * T.cand_slots + idx * k;
-  for (int s = 0; s < c; ++s)
-    if (t[2 * (size_t)T.hslot[at + s] + 1] == PEND + (uint32_t)(idx * k + s)) first |= 1ull << s;
-  return c;
-}
-
-// tile_sums[b][tile] = (picks << 32 | first occurrences) of 256 frontier slots
+// tile_sums[b][tile] = (picks << 32 | first occurrences) of 256 frontier slots, and the
+// first-occurrence mask of every slot
 __global__ __launch_bounds__(TB) void k_count(Tables T, const int32_t* __restrict__ nfront, int k,
                                               uint64_t* __restrict__ tile_sums, int64_t tiles) {
   __shared__ uint64_t red[TB / WAVE];
   const int b = blockIdx.y;
   const int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x;
-  uint64_t first;
-  const int c = slot_flags(T, b, idx, k, idx < nfront[b], first);
+  uint64_t first = 0;
+  int c = 0;
+  if (idx < nfront[b]) {
+    c = T.cnt[b * T.fr_slots + idx];
+    const uint64_t* t = T.tab + T.tab_off[b];
+    const int64_t at = b * T.cand_slots + idx * k;
+    for (int s = 0; s < c; ++s)
+      if (table_value(t, T.hslot[at + s]) == PEND + (uint32_t)(idx * k + s)) first |= 1ull << s;
+    T.first[b * T.fr_slots + idx] = first;
+  }
   uint64_t packed = ((uint64_t)c << 32) | (uint64_t)__popcll(first);
   packed = wave_reduce_sum(packed);
   if (lane_id() == 0) red[threadIdx.x / WAVE] = packed;
@@ -247,20 +303,23 @@ __global__ __launch_bounds__(TB) void k_stage_offsets(
   }
 }
 
-// Appends first occurrences to the lists, fixes their table values, writes rowptr.
+// Appends first occurrences to the lists, fixes their table values, writes rowptr and the
+// adj_col entries of the first occurrences.
 __global__ __launch_bounds__(TB) void k_emit(Tables T, const int32_t* __restrict__ nfront,
                                              const int32_t* __restrict__ nlist, int k,
                                              const uint64_t* __restrict__ tile_sums, int64_t tiles,
                                              int64_t* __restrict__ rowptr, int64_t rowptr_capacity,
-                                             const int64_t* __restrict__ row_base) {
+                                             const int64_t* __restrict__ row_base,
+                                             int32_t* __restrict__ col, int64_t col_capacity,
+                                             const int64_t* __restrict__ col_base) {
   __shared__ uint64_t smem[TB / WAVE + 1];
   const int b = blockIdx.y;
   const int nf = nfront[b];
-  if ((int64_t)blockIdx.x * TB >= nf && !(blockIdx.x == 0)) return;
+  if ((int64_t)blockIdx.x * TB >= nf && blockIdx.x != 0) return;
   const int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x;
   const bool active = idx < nf;
-  uint64_t first;
-  const int c = slot_flags(T, b, idx, k, active, first);
+  const uint64_t first = active ? T.first[b * T.fr_slots + idx] : 0;
+  const int c = active ? T.cnt[b * T.fr_slots + idx] : 0;
   const uint64_t packed = ((uint64_t)c << 32) | (uint64_t)__popcll(first);
   uint64_t total;
   const uint64_t ex = block_exclusive_scan<uint64_t, TB>(packed, smem, total) +
@@ -276,17 +335,22 @@ __global__ __launch_bounds__(TB) void k_emit(Tables T, const int32_t* __restrict
   }
   if (first) {
     uint32_t at_list = (uint32_t)nlist[b] + (uint32_t)(ex & 0xFFFFFFFFu);
-    uint32_t* t = T.tab + (size_t)b * T.table_slots * 2;
+    // A first occurrence's slot in `cand` is overwritten with its list position: the table
+    // keeps PEND + its rank, so later duplicates find the position through the rank without
+    // a scattered write into the table here (the next stage rebuilds the tables anyway).
     const int64_t at = b * T.cand_slots + idx * k;
+    const int64_t dst = col ? col_base[b] + edges_before : 0;
     for (int s = 0; s < c; ++s)
       if (first >> s & 1) {
         T.wlist[b * T.stride_ids + at_list] = T.cand[at + s];
-        t[2 * (size_t)T.hslot[at + s] + 1] = at_list;
+        T.cand[at + s] = (int32_t)at_list;
+        if (col && dst + s < col_capacity) col[dst + s] = (int32_t)at_list;
         ++at_list;
       }
   }
 }
 
+// adj_col of the picks that are not first occurrences: their id is in the table already.
 __global__ __launch_bounds__(TB) void k_col(Tables T, const int32_t* __restrict__ nfront, int k,
                                             const int64_t* __restrict__ rowptr,
                                             int64_t rowptr_capacity,
@@ -297,11 +361,19 @@ __global__ __launch_bounds__(TB) void k_col(Tables T, const int32_t* __restrict_
   const int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x;
   if (idx >= nfront[b] || row_base[b] + idx >= rowptr_capacity) return;
   const int c = T.cnt[b * T.fr_slots + idx];
-  const uint32_t* t = T.tab + (size_t)b * T.table_slots * 2;
+  const uint64_t first = T.first[b * T.fr_slots + idx];
+  if (__popcll(first) == c) return;
+  const uint64_t* t = T.tab + T.tab_off[b];
   const int64_t at = b * T.cand_slots + idx * k;
   const int64_t dst = col_base[b] + rowptr[row_base[b] + idx];
   for (int s = 0; s < c; ++s)
-    if (dst + s < col_capacity) col[dst + s] = (int32_t)t[2 * (size_t)T.hslot[at + s] + 1];
+    if (!(first >> s & 1) && dst + s < col_capacity) {
+      // an id of an earlier stage carries its list position; an id that is new in this
+      // stage carries PEND + rank of its first occurrence, whose slot in `cand` now holds
+      // the position
+      const uint32_t v = table_value(t, T.hslot[at + s]);
+      col[dst + s] = v < PEND ? (int32_t)v : T.cand[b * T.cand_slots + (v - PEND)];
+    }
 }
 
 __global__ __launch_bounds__(TB) void k_ids_offsets(Meta M, int S, const int32_t* __restrict__ nlist) {
@@ -342,8 +414,8 @@ __global__ void k_seed_counts(const int64_t* __restrict__ seed_off, int S, int32
 struct Plan {
   int64_t stride_front[GINEX_MAX_HOPS];  // bound on the frontier at hop h, per batch
   int64_t stride_ids;                    // bound on the final list, per batch
-  int64_t cand_slots, fr_slots, tiles, table_slots;
-  int shift;
+  int64_t cand_slots, fr_slots, tiles;
+  int64_t table_slots;                   // per batch, worst case (2 per list entry)
   bool ok;
 };
 
@@ -365,24 +437,23 @@ Plan make_plan(int64_t num_nodes, int64_t max_batch, const int32_t* fanout, int3
   p.stride_ids = front;
   if (p.cand_slots >= (int64_t)PEND || p.stride_ids >= (int64_t)PEND) p.ok = false;
   p.tiles = ceil_div(p.fr_slots, TB);
-  p.table_slots = 16;
-  int lg = 4;
-  while (p.table_slots < 2 * p.stride_ids) {
-    p.table_slots <<= 1;
-    ++lg;
-  }
-  p.shift = 32 - lg;
+  // a stage's table holds at most min(num_nodes, list + frontier * fanout) <= stride_ids ids
+  p.table_slots = 2 * p.stride_ids + 32;
   return p;
 }
 
 struct Workspace {
-  uint32_t* tab;
+  uint64_t* tab;
   int32_t* wlist;
   int32_t* cand;
   uint32_t* hslot;
   uint8_t* cnt;
   uint64_t* tile_sums;
   uint64_t* batch_total;
+  uint64_t* first;
+  int64_t* tab_off;
+  uint32_t* tab_slots;
+  int64_t* tab_total;
   int32_t *nfront, *nlist_a, *nlist_b;
   int64_t *row_base, *col_base, *seed_off;
   int64_t* meta;
@@ -396,13 +467,17 @@ int64_t meta_elems(int32_t S, int32_t H) {
 Workspace carve(void* base, const Plan& p, int32_t S, int32_t H) {
   Arena a(base);
   Workspace w;
-  w.tab = a.take<uint32_t>((size_t)S * p.table_slots * 2);
+  w.tab = a.take<uint64_t>((size_t)S * p.table_slots);
   w.wlist = a.take<int32_t>((size_t)S * p.stride_ids);
   w.cand = a.take<int32_t>((size_t)S * p.cand_slots);
   w.hslot = a.take<uint32_t>((size_t)S * p.cand_slots);
   w.cnt = a.take<uint8_t>((size_t)S * p.fr_slots);
   w.tile_sums = a.take<uint64_t>((size_t)S * p.tiles);
   w.batch_total = a.take<uint64_t>(S);
+  w.first = a.take<uint64_t>((size_t)S * p.fr_slots);
+  w.tab_off = a.take<int64_t>(S);
+  w.tab_slots = a.take<uint32_t>(S);
+  w.tab_total = a.take<int64_t>(1);
   w.nfront = a.take<int32_t>(S);
   w.nlist_a = a.take<int32_t>(S);
   w.nlist_b = a.take<int32_t>(S);
@@ -500,8 +575,8 @@ extern "C" int32_t ginex_sample_superbatch(
 
   hipStream_t st = (hipStream_t)stream;
   Tables T;
-  T.tab = w.tab; T.table_slots = p.table_slots; T.mask = (uint32_t)(p.table_slots - 1);
-  T.shift = p.shift; T.cand = w.cand; T.hslot = w.hslot; T.cnt = w.cnt;
+  T.tab = w.tab; T.tab_off = w.tab_off; T.tab_slots = w.tab_slots; T.first = w.first;
+  T.cand = w.cand; T.hslot = w.hslot; T.cnt = w.cnt;
   T.cand_slots = p.cand_slots; T.fr_slots = p.fr_slots; T.wlist = w.wlist;
   T.stride_ids = p.stride_ids;
   Meta M;
@@ -513,7 +588,6 @@ extern "C" int32_t ginex_sample_superbatch(
 
   GINEX_HIP(hipMemcpyAsync(w.seed_off, seed_offsets, sizeof(int64_t) * (S + 1),
                            hipMemcpyHostToDevice, st));
-  GINEX_HIP(fill_async<uint32_t>(w.tab, (int64_t)S * p.table_slots * 2, EMPTY, st));
   hipLaunchKernelGGL(k_seed_counts, dim3((unsigned)ceil_div(S, TB)), dim3(TB), 0, st, w.seed_off, S,
                      w.nfront, w.nlist_a);
   GINEX_LAUNCH_CHECK();
@@ -526,6 +600,14 @@ extern "C" int32_t ginex_sample_superbatch(
     // in a hop the frontier is the whole list as it stands when the hop starts
     const int32_t* nfront = stage < 0 ? w.nfront : nlist;
     const dim3 grid_slots((unsigned)ceil_div(front, TB), S);
+    hipLaunchKernelGGL(k_table_plan, dim3(1), dim3(TB), 0, st, T, S, g->num_nodes, k, nfront,
+                       nlist, w.tab_total);
+    hipLaunchKernelGGL(k_table_clear, dim3(4096), dim3(TB), 0, st, w.tab, w.tab_total);
+    GINEX_LAUNCH_CHECK();
+    if (stage >= 0) {
+      hipLaunchKernelGGL(k_reinsert, grid_slots, dim3(TB), 0, st, T, nlist);
+      GINEX_LAUNCH_CHECK();
+    }
     if (stage < 0) {
       hipLaunchKernelGGL(k_seed_stage, grid_slots, dim3(TB), 0, st, T, seeds, w.seed_off, nfront);
     } else if (g->offsets_64) {
@@ -546,7 +628,8 @@ extern "C" int32_t ginex_sample_superbatch(
     GINEX_LAUNCH_CHECK();
     const bool adj = stage >= 0 && adj_rowptr != nullptr;
     hipLaunchKernelGGL(k_emit, grid_slots, dim3(TB), 0, st, T, nfront, nlist, k, w.tile_sums,
-                       p.tiles, adj ? adj_rowptr : (int64_t*)nullptr, rowptr_capacity, w.row_base);
+                       p.tiles, adj ? adj_rowptr : (int64_t*)nullptr, rowptr_capacity, w.row_base,
+                       adj ? adj_col : (int32_t*)nullptr, col_capacity, w.col_base);
     GINEX_LAUNCH_CHECK();
     if (adj) {
       hipLaunchKernelGGL(k_col, grid_slots, dim3(TB), 0, st, T, nfront, k, adj_rowptr,

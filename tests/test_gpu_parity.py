@@ -103,6 +103,10 @@ def test_changeset_matches_oracle(ginex, which, request):
     c = request.getfixturevalue(which)
     res = ginex.changeset(c.cfg.num_nodes, dev(c.samp["ids"]), c.samp["ids_offsets"], c.cfg.cap)
     check_changeset(res, c.cs)
+    # a small cache puts every iteration under pressure
+    ref = oracle.changeset(c.cfg.num_nodes, c.samp["ids"], c.samp["ids_offsets"], 1000)
+    check_changeset(ginex.changeset(c.cfg.num_nodes, dev(c.samp["ids"]),
+                                    c.samp["ids_offsets"], 1000), ref)
 
 
 @pytest.mark.parametrize("which", ["case1", "case2"])
