@@ -60,13 +60,21 @@ struct State {
   int64_t max_change;     // entries of out_slot / in_id / in_next
 };
 
-__device__ __forceinline__ int32_t iter_of(const int64_t* __restrict__ off, int32_t S, int64_t p) {
-  int32_t lo = 0, hi = S;  // largest i with off[i] <= p
+// Iteration that holds flat position p: the largest i with off[i] <= p.  `off` is the
+// block's LDS copy of ids_offsets (total ids < 2^31, so 32 bits do).
+__device__ __forceinline__ int32_t iter_of(const int32_t* off, int32_t S, int32_t p) {
+  int32_t lo = 0, hi = S;
   while (hi - lo > 1) {
     const int32_t mid = (lo + hi) >> 1;
     if (off[mid] <= p) lo = mid; else hi = mid;
   }
   return lo;
+}
+
+__device__ __forceinline__ void load_offsets(int32_t* lds_off, const int64_t* __restrict__ off,
+                                             int32_t S) {
+  for (int j = threadIdx.x; j <= S; j += blockDim.x) lds_off[j] = (int32_t)off[j];
+  __syncthreads();
 }
 
 // ---- part 1 -----------------------------------------------------------------------
@@ -80,28 +88,20 @@ __global__ __launch_bounds__(TB) void k_make_pairs(const int32_t* __restrict__ i
 constexpr int LOOK_ITEMS = 8;
 constexpr int LOOK_TILE = TB * LOOK_ITEMS;
 
-// next_iter of every access + number of run heads per tile
-__global__ __launch_bounds__(TB) void k_look_right(const uint64_t* __restrict__ sorted, int64_t n,
-                                                   const int64_t* __restrict__ off, int32_t S,
-                                                   int32_t* __restrict__ next_iter,
-                                                   uint32_t* __restrict__ head_tiles) {
+__device__ __forceinline__ bool run_head(const uint64_t* __restrict__ sorted, int64_t j) {
+  return j == 0 || (uint32_t)(sorted[j - 1] >> 32) != (uint32_t)(sorted[j] >> 32);
+}
+
+// number of run heads (= distinct nodes) per tile of the sorted pairs
+__global__ __launch_bounds__(TB) void k_count_heads(const uint64_t* __restrict__ sorted, int64_t n,
+                                                    uint32_t* __restrict__ head_tiles) {
   __shared__ uint32_t red[TB / WAVE];
   uint32_t heads = 0;
   const int64_t base = (int64_t)blockIdx.x * LOOK_TILE;
 #pragma unroll
   for (int i = 0; i < LOOK_ITEMS; ++i) {
     const int64_t j = base + i * TB + threadIdx.x;
-    if (j < n) {
-      const uint64_t cur = sorted[j];
-      const uint32_t v = (uint32_t)(cur >> 32);
-      int32_t nxt = S;
-      if (j + 1 < n) {
-        const uint64_t r = sorted[j + 1];
-        if ((uint32_t)(r >> 32) == v) nxt = iter_of(off, S, (int64_t)(r & 0xFFFFFFFFu));
-      }
-      next_iter[cur & 0xFFFFFFFFu] = nxt;
-      heads += (j == 0) || ((uint32_t)(sorted[j - 1] >> 32) != v);
-    }
+    if (j < n) heads += run_head(sorted, j);
   }
   heads = wave_reduce_sum(heads);
   if (lane_id() == 0) red[threadIdx.x / WAVE] = heads;
@@ -113,23 +113,46 @@ __global__ __launch_bounds__(TB) void k_look_right(const uint64_t* __restrict__ 
   }
 }
 
+// next_iter of every access: the iteration of its right neighbour in the sorted order if
+// that is the same node, else S ("never")
+__global__ __launch_bounds__(TB) void k_look_right(const uint64_t* __restrict__ sorted, int64_t n,
+                                                   const int64_t* __restrict__ off, int32_t S,
+                                                   int32_t* __restrict__ next_iter) {
+  extern __shared__ int32_t lds_off[];
+  load_offsets(lds_off, off, S);
+  const int64_t base = (int64_t)blockIdx.x * LOOK_TILE;
+#pragma unroll
+  for (int i = 0; i < LOOK_ITEMS; ++i) {
+    const int64_t j = base + i * TB + threadIdx.x;
+    if (j < n) {
+      const uint64_t cur = sorted[j];
+      int32_t nxt = S;
+      if (j + 1 < n) {
+        const uint64_t r = sorted[j + 1];
+        if ((uint32_t)(r >> 32) == (uint32_t)(cur >> 32))
+          nxt = iter_of(lds_off, S, (int32_t)(r & 0xFFFFFFFFu));
+      }
+      next_iter[cur & 0xFFFFFFFFu] = nxt;
+    }
+  }
+}
+
 // heads[r] = (first iteration << 32 | node) for the r-th distinct node (ascending id)
 __global__ __launch_bounds__(TB) void k_heads_write(const uint64_t* __restrict__ sorted, int64_t n,
                                                     const int64_t* __restrict__ off, int32_t S,
                                                     const uint32_t* __restrict__ head_bases,
                                                     uint64_t* __restrict__ heads) {
+  extern __shared__ int32_t lds_off[];
   __shared__ uint32_t smem[TB / WAVE + 1];
+  load_offsets(lds_off, off, S);
   const int64_t base = (int64_t)blockIdx.x * LOOK_TILE + (int64_t)threadIdx.x * LOOK_ITEMS;
   uint32_t flags = 0, cnt = 0;
 #pragma unroll
   for (int i = 0; i < LOOK_ITEMS; ++i) {
     const int64_t j = base + i;
-    if (j < n) {
-      const uint32_t v = (uint32_t)(sorted[j] >> 32);
-      if (j == 0 || (uint32_t)(sorted[j - 1] >> 32) != v) {
-        flags |= 1u << i;
-        ++cnt;
-      }
+    if (j < n && run_head(sorted, j)) {
+      flags |= 1u << i;
+      ++cnt;
     }
   }
   uint32_t total;
@@ -138,7 +161,7 @@ __global__ __launch_bounds__(TB) void k_heads_write(const uint64_t* __restrict__
   for (int i = 0; i < LOOK_ITEMS; ++i)
     if (flags >> i & 1) {
       const uint64_t cur = sorted[base + i];
-      const uint32_t first = (uint32_t)iter_of(off, S, (int64_t)(cur & 0xFFFFFFFFu));
+      const uint32_t first = (uint32_t)iter_of(lds_off, S, (int32_t)(cur & 0xFFFFFFFFu));
       heads[at++] = ((uint64_t)first << 32) | (cur >> 32);
     }
 }
@@ -776,8 +799,8 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
   uint64_t* sorted = nullptr;
   GINEX_HIP(radix_sort_u64(w.pairs_a, w.pairs_b, total, 32, 32 + bits_for(num_nodes), w.hist, st,
                            &sorted));
-  hipLaunchKernelGGL(k_look_right, dim3((unsigned)w.look_tiles), dim3(TB), 0, st, sorted, total,
-                     w.d_offsets, S, w.next_iter, w.head_tiles);
+  hipLaunchKernelGGL(k_count_heads, dim3((unsigned)w.look_tiles), dim3(TB), 0, st, sorted, total,
+                     w.head_tiles);
   GINEX_LAUNCH_CHECK();
   GINEX_HIP(fill_async<uint32_t>(w.head_tiles + w.look_tiles, 1, 0u, st));
   GINEX_HIP(exclusive_scan_inplace<uint32_t>(w.head_tiles, w.look_tiles + 1,
@@ -792,8 +815,9 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
                 (long long)distinct, (long long)num_nodes);
 
   // part 2: C_0
-  hipLaunchKernelGGL(k_heads_write, dim3((unsigned)w.look_tiles), dim3(TB), 0, st, sorted, total,
-                     w.d_offsets, S, w.head_tiles, w.heads_a);
+  const size_t off_lds = sizeof(int32_t) * (S + 1);
+  hipLaunchKernelGGL(k_heads_write, dim3((unsigned)w.look_tiles), dim3(TB), off_lds, st, sorted,
+                     total, w.d_offsets, S, w.head_tiles, w.heads_a);
   GINEX_LAUNCH_CHECK();
   uint64_t* heads = nullptr;
   GINEX_HIP(radix_sort_u64(w.heads_a, w.heads_b, distinct, 32, 32 + bits_for(S), w.hist, st,
@@ -820,6 +844,10 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
     GINEX_HIP(hipStreamSynchronize(st));
     return GINEX_OK;
   }
+  // the cache cannot hold every row: the next accessed iteration of every access is needed
+  hipLaunchKernelGGL(k_look_right, dim3((unsigned)w.look_tiles), dim3(TB), off_lds, st, sorted,
+                     total, w.d_offsets, S, w.next_iter);
+  GINEX_LAUNCH_CHECK();
   GINEX_HIP(fill_async<int32_t>(state.addr, num_nodes, -1, st));
   GINEX_HIP(fill_async<uint32_t>(state.rhist, S + 2, 0u, st));
   GINEX_HIP(fill_async<uint32_t>(state.ihist, S + 2, 0u, st));
