@@ -25,6 +25,19 @@ sys.path.insert(0, ROOT)
 
 METRIC = "sampled edges/s; Belady changeset accesses/s; gather GB/s vs HBM peak"
 HBM_PEAK_GBPS = 8000.0
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` from the rocprofv3 --pmc runs recorded under
+    profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by the plain-copy calibration), or None
+    when no counter run exists for this workload."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f)[workload][kernel]
+        return rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def log(*a):
@@ -222,7 +235,7 @@ def main():
     roof = {
         "kernel": "k_gather (real hit/miss mix; misses are read from host-pinned memory)",
         "bound": "hbm", "achieved": algo_bytes / (g_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS,
-        "unit": "GB/s", "traffic": None,
+        "unit": "GB/s", "traffic": measured_traffic(cfg.name, "k_gather"),
         "avg_launch_ms": g_ms, "launches": len(gather_ms),
         "rows_per_launch": rows_per_launch, "miss_fraction": misses / max(accesses, 1),
         "host_link_GBps": miss_per_launch * row_bytes / (g_ms * 1e-3) / 1e9,

@@ -37,7 +37,8 @@ struct Ctrl {        // decisions of the running iteration (device memory)
   int32_t keep;      // how many members of the selected class stay
   int32_t T;         // id threshold of the select
   int32_t n_change;  // evictions (= insertions) of the iteration
-  int32_t pad[2];
+  int32_t use_dead;  // the select runs on the standing bitmap of dead residents
+  int32_t pad;
 };
 
 struct State {
@@ -47,6 +48,7 @@ struct State {
   uint32_t* rhist;      // [S+1] residents per next iteration
   uint32_t* ihist;      // [S+1] incoming rows of the running iteration per next iteration
   uint32_t* bitmap;     // [ceil(N/32)] select scratch, all zero between iterations
+  uint32_t* dead_bits;  // [ceil(N/32)] residents that are never accessed again, kept up to date
   uint32_t* bit_part;   // popcount of each block of bitmap words
   Ctrl* ctrl;
   uint64_t* evict_words;  // bit l%64 of word l/64: line l is evicted in this iteration
@@ -250,6 +252,10 @@ __device__ void p_touch(const State& st, const Iter& it, unsigned long long* mis
       if (line >= 0) {
         st.res_next[line] = nx;
         atomicAdd(&hr[nx], 1u);
+        if (nx == st.S) {   // the row's last access: it is a dead resident from now on
+          const uint32_t v = (uint32_t)it.ids[p];
+          atomicOr(&st.dead_bits[v >> 5], 1u << (v & 31));
+        }
       } else {
         atomicAdd(&hi[nx], 1u);
         ++misses;
@@ -317,6 +323,9 @@ __device__ void p_threshold(const State& st, int32_t i, const int64_t* miss_coun
           c.mode_in = MODE_NONE; c.mode_res = MODE_SELECT;
           from_res = rem - I;
           c.keep = (int32_t)(R - from_res);
+          // in the "never" bucket the members are exactly the dead residents, whose
+          // bitmap is maintained incrementally: no marking pass is needed
+          c.use_dead = j == S;
         }
         c.T = -1;
         // evictions inside j*; those of the buckets above j* are added after the barrier
@@ -381,20 +390,22 @@ __device__ void p_mark_incoming(const State& st, const Ctrl& c, const Iter& it, 
 }
 
 // popcount of one part (TB*BITS_WORDS words) of the bitmap
-__device__ void p_bits_count(const State& st, int64_t words, int64_t vb) {
+__device__ void p_bits_count(const State& st, const uint32_t* __restrict__ bits, int64_t words,
+                             int64_t vb) {
   __shared__ uint32_t red[TB / WAVE];
   const int64_t base = (vb * TB + threadIdx.x) * BITS_WORDS;
   uint32_t cnt = 0;
 #pragma unroll
   for (int t = 0; t < BITS_WORDS; ++t)
-    if (base + t < words) cnt += __popc(st.bitmap[base + t]);
+    if (base + t < words) cnt += __popc(bits[base + t]);
   const uint32_t total = block_sum_u32(cnt, red);
   if (threadIdx.x == 0) st.bit_part[vb] = total;
 }
 
 // One block of NT threads: T = the id whose bit is the keep-th set bit of the bitmap.
 template <int NT>
-__device__ void p_bits_find(const State& st, int64_t words, int64_t parts) {
+__device__ void p_bits_find(const State& st, const uint32_t* __restrict__ bits, int64_t words,
+                            int64_t parts) {
   Ctrl* c = st.ctrl;
   __shared__ int64_t smem[NT / WAVE + 1];
   __shared__ int64_t s_part, s_before;
@@ -423,12 +434,12 @@ __device__ void p_bits_find(const State& st, int64_t words, int64_t parts) {
   const int64_t w0 = s_part * (TB * BITS_WORDS) + (int64_t)threadIdx.x * WPT;
   int64_t cntw = 0;
   for (int t = 0; t < WPT; ++t)
-    if (w0 + t < words) cntw += __popc(st.bitmap[w0 + t]);
+    if (w0 + t < words) cntw += __popc(bits[w0 + t]);
   int64_t tot2;
   int64_t bw = s_before + block_exclusive_scan<int64_t, NT>(cntw, smem, tot2);
   for (int t = 0; t < WPT; ++t)
     if (w0 + t < words) {
-      uint32_t word = st.bitmap[w0 + t];
+      uint32_t word = bits[w0 + t];
       const int pc = __popc(word);
       if (bw < keep && bw + pc >= keep) {
         int need = (int)(keep - bw);  // the need-th set bit of this word, 1-based
@@ -585,6 +596,8 @@ __device__ void p_apply(const State& st, int32_t n_change, int64_t vb) {
   const int32_t line = st.out_slot[t];
   const int32_t gone = st.res_id[line];
   const int32_t v = st.in_id[t];
+  if (st.res_next[line] == st.S)   // a dead resident leaves: drop it from the standing bitmap
+    atomicAnd(&st.dead_bits[(uint32_t)gone >> 5], ~(1u << ((uint32_t)gone & 31)));
   st.res_id[line] = v;
   st.res_next[line] = st.in_next[t];
   st.addr[gone] = -1;
@@ -606,7 +619,7 @@ __global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i, Outputs 
 __global__ __launch_bounds__(TB) void k_mark(State st, Iter it, int64_t res_blocks) {
   const Ctrl c = *st.ctrl;
   if ((int64_t)blockIdx.x < res_blocks) {
-    if (c.mode_res == MODE_SELECT) p_mark_residents(st, c, blockIdx.x);
+    if (c.mode_res == MODE_SELECT && !c.use_dead) p_mark_residents(st, c, blockIdx.x);
   } else if (c.mode_in == MODE_SELECT) {
     p_mark_incoming(st, c, it, blockIdx.x - res_blocks);
   }
@@ -615,13 +628,13 @@ __global__ __launch_bounds__(TB) void k_mark(State st, Iter it, int64_t res_bloc
 __global__ __launch_bounds__(TB) void k_bits_count(State st, int64_t words) {
   const Ctrl c = *st.ctrl;
   if (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT) return;
-  p_bits_count(st, words, blockIdx.x);
+  p_bits_count(st, c.use_dead ? st.dead_bits : st.bitmap, words, blockIdx.x);
 }
 
 __global__ __launch_bounds__(BIG) void k_bits_find(State st, int64_t words, int64_t parts) {
   const Ctrl c = *st.ctrl;
   if (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT) return;
-  p_bits_find<BIG>(st, words, parts);
+  p_bits_find<BIG>(st, c.use_dead ? st.dead_bits : st.bitmap, words, parts);
 }
 
 // blocks [0, evict_tiles): evictions per tile; next in_tiles blocks: insertions per tile;
@@ -634,7 +647,7 @@ __global__ __launch_bounds__(TB) void k_tile_count(State st, Iter it, int64_t ev
     if (c.n_change > 0) p_evict_flags(st, c, vb);
   } else if (vb < evict_tiles + in_tiles) {
     if (c.n_change > 0) p_in_count(st, c, it, vb - evict_tiles);
-  } else if (c.mode_res == MODE_SELECT || c.mode_in == MODE_SELECT) {
+  } else if ((c.mode_res == MODE_SELECT || c.mode_in == MODE_SELECT) && !c.use_dead) {
     p_bits_clear(st, words, vb - evict_tiles - in_tiles);
   }
 }
@@ -704,6 +717,7 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   w.bit_words = ceil_div(num_nodes, 32);
   w.bit_parts = ceil_div(w.bit_words, TB * BITS_WORDS);
   st.bitmap = a.take<uint32_t>(w.bit_words);
+  st.dead_bits = a.take<uint32_t>(w.bit_words);
   st.bit_part = a.take<uint32_t>(w.bit_parts);
   st.ctrl = a.take<Ctrl>(1);
   w.evict_tiles = ceil_div(c, (int64_t)EVICT_TILE);
@@ -852,6 +866,7 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
   GINEX_HIP(fill_async<uint32_t>(state.rhist, S + 2, 0u, st));
   GINEX_HIP(fill_async<uint32_t>(state.ihist, S + 2, 0u, st));
   GINEX_HIP(fill_async<uint32_t>(state.bitmap, w.bit_words, 0u, st));
+  GINEX_HIP(fill_async<uint32_t>(state.dead_bits, w.bit_words, 0u, st));
   {
     int64_t blocks = ceil_div(cap, TB * 8);
     if (blocks > 4096) blocks = 4096;
