@@ -93,6 +93,32 @@ __device__ __forceinline__ uint32_t table_value(const uint64_t* t, uint32_t h) {
   return (uint32_t)t[h];
 }
 
+// Which (batch, tile) a block works on.  Grids are one-dimensional and the hardware deals
+// consecutive workgroups round-robin to the 8 XCDs, each with its own L2; block n therefore
+// takes a tile of a batch whose index is congruent to n modulo 8, so that all tiles of a
+// batch, and with them the batch's hash table, stay in one XCD's L2 instead of being
+// fetched by all eight.  (Only locality depends on the dealing order, not correctness.)
+constexpr int XCDS = 8;
+
+struct Where {
+  int b;          // batch, or -1 if the block has none
+  int64_t tile;   // tile of the batch's frontier slots
+};
+
+__device__ __forceinline__ Where where_am_i(int S, int64_t tiles_per_batch) {
+  const int64_t n = blockIdx.x;
+  const int64_t m = n / XCDS;
+  Where w;
+  w.tile = m % tiles_per_batch;
+  const int64_t b = (m / tiles_per_batch) * XCDS + n % XCDS;
+  w.b = b < S ? (int)b : -1;
+  return w;
+}
+
+inline unsigned grid_blocks(int S, int64_t tiles_per_batch) {
+  return (unsigned)(XCDS * ceil_div(S, XCDS) * tiles_per_batch);
+}
+
 // Single block: table sizes and offsets for the stage that is about to run.
 __global__ __launch_bounds__(TB) void k_table_plan(Tables T, int S, int64_t num_nodes, int k,
                                                    const int32_t* __restrict__ nfront,
@@ -127,9 +153,12 @@ __global__ __launch_bounds__(TB) void k_table_clear(uint64_t* __restrict__ tab,
 }
 
 // Put the list a batch has so far back into its freshly sized table.
-__global__ __launch_bounds__(TB) void k_reinsert(Tables T, const int32_t* __restrict__ nlist) {
-  const int b = blockIdx.y;
-  const int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
+__global__ __launch_bounds__(TB) void k_reinsert(Tables T, const int32_t* __restrict__ nlist,
+                                                 int S, int64_t tpb) {
+  const Where at = where_am_i(S, tpb);
+  if (at.b < 0) return;
+  const int b = at.b;
+  const int64_t j = at.tile * TB + threadIdx.x;
   if (j >= nlist[b]) return;
   uint64_t* t = T.tab + T.tab_off[b];
   table_insert(t, T.tab_slots[b], (uint32_t)T.wlist[b * T.stride_ids + j], (uint32_t)j);
@@ -138,9 +167,12 @@ __global__ __launch_bounds__(TB) void k_reinsert(Tables T, const int32_t* __rest
 // Stage "seeds": slot j of batch b holds seed j.
 __global__ __launch_bounds__(TB) void k_seed_stage(Tables T, const int32_t* __restrict__ seeds,
                                                    const int64_t* __restrict__ seed_off,
-                                                   const int32_t* __restrict__ nfront) {
-  const int b = blockIdx.y;
-  const int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
+                                                   const int32_t* __restrict__ nfront, int S,
+                                                   int64_t tpb) {
+  const Where at = where_am_i(S, tpb);
+  if (at.b < 0) return;
+  const int b = at.b;
+  const int64_t j = at.tile * TB + threadIdx.x;
   if (j >= nfront[b]) return;
   const uint32_t id = (uint32_t)seeds[seed_off[b] + j];
   uint64_t* t = T.tab + T.tab_off[b];
@@ -153,11 +185,14 @@ template <int G, typename OffT>
 __global__ __launch_bounds__(TB) void k_pick(Tables T, const OffT* __restrict__ offsets,
                                              const int32_t* __restrict__ indices,
                                              const int32_t* __restrict__ nfront, int k, int hop,
-                                             uint64_t seed, uint32_t first_batch) {
-  const int b = blockIdx.y;
+                                             uint64_t seed, uint32_t first_batch, int S,
+                                             int64_t tpb) {
+  const Where here = where_am_i(S, tpb);
+  if (here.b < 0) return;
+  const int b = here.b;
   const int lane = lane_id();
   const int sub = threadIdx.x & (G - 1);
-  const int64_t idx = (int64_t)blockIdx.x * (TB / G) + threadIdx.x / G;
+  const int64_t idx = here.tile * (TB / G) + threadIdx.x / G;
   const bool active = idx < nfront[b];
   const uint32_t v = active ? (uint32_t)T.wlist[b * T.stride_ids + idx] : 0u;
   int64_t lo = 0, deg = 0;
@@ -177,7 +212,7 @@ __global__ __launch_bounds__(TB) void k_pick(Tables T, const OffT* __restrict__ 
     const int64_t t = (int64_t)__umul64hi(r, (uint64_t)(j + 1));
     int64_t mine = t;
     const int group_shift = lane & ~(G - 1);
-    const uint64_t group_mask = G == 64 ? ~0ull : ((1ull << G) - 1);
+    const uint64_t group_mask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1);
     for (int i = 1; i < k; ++i) {
       const int64_t ti = __shfl(t, i, G);
       const uint64_t hit = (__ballot(sub < i && mine == ti) >> group_shift) & group_mask;
@@ -203,10 +238,13 @@ __global__ __launch_bounds__(TB) void k_pick(Tables T, const OffT* __restrict__ 
 // tile_sums[b][tile] = (picks << 32 | first occurrences) of 256 frontier slots, and the
 // first-occurrence mask of every slot
 __global__ __launch_bounds__(TB) void k_count(Tables T, const int32_t* __restrict__ nfront, int k,
-                                              uint64_t* __restrict__ tile_sums, int64_t tiles) {
+                                              uint64_t* __restrict__ tile_sums, int64_t tiles,
+                                              int S, int64_t tpb) {
   __shared__ uint64_t red[TB / WAVE];
-  const int b = blockIdx.y;
-  const int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x;
+  const Where here = where_am_i(S, tpb);
+  if (here.b < 0) return;
+  const int b = here.b;
+  const int64_t idx = here.tile * TB + threadIdx.x;
   uint64_t first = 0;
   int c = 0;
   if (idx < nfront[b]) {
@@ -224,7 +262,7 @@ __global__ __launch_bounds__(TB) void k_count(Tables T, const int32_t* __restric
   if (threadIdx.x == 0) {
     uint64_t s = 0;
     for (int w = 0; w < TB / WAVE; ++w) s += red[w];
-    tile_sums[b * tiles + blockIdx.x] = s;
+    tile_sums[b * tiles + here.tile] = s;
   }
 }
 
@@ -311,19 +349,22 @@ __global__ __launch_bounds__(TB) void k_emit(Tables T, const int32_t* __restrict
                                              int64_t* __restrict__ rowptr, int64_t rowptr_capacity,
                                              const int64_t* __restrict__ row_base,
                                              int32_t* __restrict__ col, int64_t col_capacity,
-                                             const int64_t* __restrict__ col_base) {
+                                             const int64_t* __restrict__ col_base, int S,
+                                             int64_t tpb) {
   __shared__ uint64_t smem[TB / WAVE + 1];
-  const int b = blockIdx.y;
+  const Where here = where_am_i(S, tpb);
+  if (here.b < 0) return;
+  const int b = here.b;
   const int nf = nfront[b];
-  if ((int64_t)blockIdx.x * TB >= nf && blockIdx.x != 0) return;
-  const int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (here.tile * TB >= nf && here.tile != 0) return;
+  const int64_t idx = here.tile * TB + threadIdx.x;
   const bool active = idx < nf;
   const uint64_t first = active ? T.first[b * T.fr_slots + idx] : 0;
   const int c = active ? T.cnt[b * T.fr_slots + idx] : 0;
   const uint64_t packed = ((uint64_t)c << 32) | (uint64_t)__popcll(first);
   uint64_t total;
   const uint64_t ex = block_exclusive_scan<uint64_t, TB>(packed, smem, total) +
-                      tile_sums[b * tiles + blockIdx.x];
+                      tile_sums[b * tiles + here.tile];
   const int64_t edges_before = (int64_t)(ex >> 32);
   if (rowptr) {
     const int64_t rb = row_base[b];
@@ -356,9 +397,12 @@ __global__ __launch_bounds__(TB) void k_col(Tables T, const int32_t* __restrict_
                                             int64_t rowptr_capacity,
                                             const int64_t* __restrict__ row_base,
                                             int32_t* __restrict__ col, int64_t col_capacity,
-                                            const int64_t* __restrict__ col_base) {
-  const int b = blockIdx.y;
-  const int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x;
+                                            const int64_t* __restrict__ col_base, int S,
+                                            int64_t tpb) {
+  const Where here = where_am_i(S, tpb);
+  if (here.b < 0) return;
+  const int b = here.b;
+  const int64_t idx = here.tile * TB + threadIdx.x;
   if (idx >= nfront[b] || row_base[b] + idx >= rowptr_capacity) return;
   const int c = T.cnt[b * T.fr_slots + idx];
   const uint64_t first = T.first[b * T.fr_slots + idx];
@@ -510,15 +554,19 @@ void launch_pick(const Tables& T, const Plan& p, const void* offsets, const int3
                  uint32_t first_batch, hipStream_t st) {
   const OffT* off = static_cast<const OffT*>(offsets);
   const int64_t front = p.stride_front[hop];
-  if (k <= 16)
-    hipLaunchKernelGGL((k_pick<16, OffT>), dim3((unsigned)ceil_div(front, TB / 16), S), dim3(TB), 0,
-                       st, T, off, indices, nfront, k, hop, seed, first_batch);
-  else if (k <= 32)
-    hipLaunchKernelGGL((k_pick<32, OffT>), dim3((unsigned)ceil_div(front, TB / 32), S), dim3(TB), 0,
-                       st, T, off, indices, nfront, k, hop, seed, first_batch);
-  else
-    hipLaunchKernelGGL((k_pick<64, OffT>), dim3((unsigned)ceil_div(front, TB / 64), S), dim3(TB), 0,
-                       st, T, off, indices, nfront, k, hop, seed, first_batch);
+  if (k <= 16) {
+    const int64_t tpb = ceil_div(front, TB / 16);
+    hipLaunchKernelGGL((k_pick<16, OffT>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
+                       indices, nfront, k, hop, seed, first_batch, S, tpb);
+  } else if (k <= 32) {
+    const int64_t tpb = ceil_div(front, TB / 32);
+    hipLaunchKernelGGL((k_pick<32, OffT>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
+                       indices, nfront, k, hop, seed, first_batch, S, tpb);
+  } else {
+    const int64_t tpb = ceil_div(front, TB / 64);
+    hipLaunchKernelGGL((k_pick<64, OffT>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
+                       indices, nfront, k, hop, seed, first_batch, S, tpb);
+  }
 }
 
 }  // namespace
@@ -599,17 +647,19 @@ extern "C" int32_t ginex_sample_superbatch(
     const int64_t front = stage < 0 ? (max_batch > 0 ? max_batch : 1) : p.stride_front[stage];
     // in a hop the frontier is the whole list as it stands when the hop starts
     const int32_t* nfront = stage < 0 ? w.nfront : nlist;
-    const dim3 grid_slots((unsigned)ceil_div(front, TB), S);
+    const int64_t tpb = ceil_div(front, TB);
+    const dim3 grid_slots(grid_blocks(S, tpb));
     hipLaunchKernelGGL(k_table_plan, dim3(1), dim3(TB), 0, st, T, S, g->num_nodes, k, nfront,
                        nlist, w.tab_total);
     hipLaunchKernelGGL(k_table_clear, dim3(4096), dim3(TB), 0, st, w.tab, w.tab_total);
     GINEX_LAUNCH_CHECK();
     if (stage >= 0) {
-      hipLaunchKernelGGL(k_reinsert, grid_slots, dim3(TB), 0, st, T, nlist);
+      hipLaunchKernelGGL(k_reinsert, grid_slots, dim3(TB), 0, st, T, nlist, S, tpb);
       GINEX_LAUNCH_CHECK();
     }
     if (stage < 0) {
-      hipLaunchKernelGGL(k_seed_stage, grid_slots, dim3(TB), 0, st, T, seeds, w.seed_off, nfront);
+      hipLaunchKernelGGL(k_seed_stage, grid_slots, dim3(TB), 0, st, T, seeds, w.seed_off, nfront, S,
+                         tpb);
     } else if (g->offsets_64) {
       launch_pick<int64_t>(T, p, g->offsets, g->indices, nfront, k, stage, S, rng_seed,
                            first_batch_index, st);
@@ -618,7 +668,8 @@ extern "C" int32_t ginex_sample_superbatch(
                            first_batch_index, st);
     }
     GINEX_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_count, grid_slots, dim3(TB), 0, st, T, nfront, k, w.tile_sums, p.tiles);
+    hipLaunchKernelGGL(k_count, grid_slots, dim3(TB), 0, st, T, nfront, k, w.tile_sums, p.tiles, S,
+                       tpb);
     GINEX_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_scan_batch, dim3(S), dim3(TB), 0, st, w.tile_sums, p.tiles, nfront,
                        w.batch_total);
@@ -629,11 +680,11 @@ extern "C" int32_t ginex_sample_superbatch(
     const bool adj = stage >= 0 && adj_rowptr != nullptr;
     hipLaunchKernelGGL(k_emit, grid_slots, dim3(TB), 0, st, T, nfront, nlist, k, w.tile_sums,
                        p.tiles, adj ? adj_rowptr : (int64_t*)nullptr, rowptr_capacity, w.row_base,
-                       adj ? adj_col : (int32_t*)nullptr, col_capacity, w.col_base);
+                       adj ? adj_col : (int32_t*)nullptr, col_capacity, w.col_base, S, tpb);
     GINEX_LAUNCH_CHECK();
     if (adj) {
       hipLaunchKernelGGL(k_col, grid_slots, dim3(TB), 0, st, T, nfront, k, adj_rowptr,
-                         rowptr_capacity, w.row_base, adj_col, col_capacity, w.col_base);
+                         rowptr_capacity, w.row_base, adj_col, col_capacity, w.col_base, S, tpb);
       GINEX_LAUNCH_CHECK();
     }
     int32_t* t = nlist; nlist = nlist_next; nlist_next = t;
