@@ -173,6 +173,27 @@ def cpu_baseline(w, n_batches):
     }
 
 
+def pipeline_leg(ginex, w, K):
+    """Inspector of K consecutive superbatches, three ways: sampling only, sampling and
+    changesets one after the other, changeset(k) overlapped with sample(k+1)."""
+    from workload.configs import seed_batches, train_nodes
+    cfg = w.cfg
+    train = train_nodes(cfg.num_nodes, cfg.train_frac, cfg.seed, device="cuda")
+    sbs = []
+    for k in range(K):
+        seeds, so = seed_batches(train, cfg.batch, cfg.S, cfg.seed, first_batch=k * cfg.S)
+        sbs.append((seeds.cuda(), so.numpy(), k * cfg.S))
+    pipe = ginex.InspectorPipeline(w.offsets, w.indices, cfg.num_nodes, cfg.fanout, cfg.cap,
+                                   cfg.batch, cfg.S)
+    out = {"superbatches": K}
+    for mode in ("sample_only", "sequential", "overlap"):
+        pipe.run(sbs[:2], mode=mode)                       # warm-up
+        out[mode + "_ms"] = min(pipe.run(sbs, mode=mode) for _ in range(3)) * 1e3
+    out["changeset_hidden_ms"] = out["sequential_ms"] - out["overlap_ms"]
+    out["changeset_exposed_ms"] = out["overlap_ms"] - out["sample_only_ms"]
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -181,6 +202,9 @@ def main():
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--cpu-batches", type=int, default=6,
                     help="batches of the workload the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--pipeline", type=int, default=0, metavar="K",
+                    help="also run K superbatches through the superbatch-level pipeline "
+                         "(changeset of k under the sampling of k+1) and report the overlap")
     ap.add_argument("--allhit", action="store_true",
                     help="also time the gather kernel with the whole feature table in HBM")
     args = ap.parse_args()
@@ -280,6 +304,9 @@ def main():
             del c2, hbm_tier
         else:
             log("not enough free HBM for the all-in-HBM gather measurement; skipped")
+
+    if args.pipeline > 0:
+        stages["pipeline"] = pipeline_leg(ginex, w, args.pipeline)
 
     result = {
         "metric": METRIC,

@@ -7,3 +7,4 @@ There is no CPU fallback: without the built library, or without a GPU, calls rai
 """
 from .api import (GinexError, FeatureCache, SampleResult, ChangesetResult,  # noqa: F401
                   sample_superbatch, changeset, library_path, version)
+from .pipeline import InspectorPipeline  # noqa: F401

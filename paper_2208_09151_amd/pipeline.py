@@ -1,0 +1,97 @@
+"""Superbatch-level pipeline (paper Section 3.1 "Superbatch-level Pipeline"): the changeset
+precomputation of superbatch k runs while superbatch k+1 is being sampled.
+
+In the paper the two stages sit on different processors (CPU sampling, GPU changesets); here
+both are GPU work, so the overlap only fills the gaps each stage leaves (host round trips,
+small dependent launches).  Each stage runs on its own HIP stream (default priority) from
+its own host thread, with its own workspace and output buffers (double buffering); the
+library keeps no global state, and ctypes drops the GIL during the calls.
+
+This module only sequences calls of the binding: no step of the path runs here.
+"""
+from __future__ import annotations
+
+import threading
+import time
+
+import numpy as np
+import torch
+
+from . import _lib, api
+
+
+class InspectorPipeline:
+    def __init__(self, offsets, indices, num_nodes, fanout, cap, max_batch, S):
+        lib = _lib.load()
+        self.offsets, self.indices = offsets, indices
+        self.num_nodes, self.fanout, self.cap, self.S = num_nodes, tuple(fanout), cap, S
+        fo = np.asarray(fanout, dtype=np.int32)
+        so = np.arange(S + 1, dtype=np.int64) * max_batch
+        ci, cr, cc = api.sample_capacity(num_nodes, so, fanout)
+        dev = offsets.device
+        ws_s = lib.ginex_sample_workspace_bytes(num_nodes, S, max_batch, fo.ctypes.data, len(fo))
+        ws_c = lib.ginex_changeset_workspace_bytes(num_nodes, ci, S, cap)
+        self.ws_sample = torch.empty(ws_s, dtype=torch.uint8, device=dev)
+        self.ws_changeset = torch.empty(ws_c, dtype=torch.uint8, device=dev)
+        # two sets of sampler outputs: one being filled while the other is consumed
+        self.bufs = [(torch.empty(ci, dtype=torch.int32, device=dev),
+                      torch.empty(cr, dtype=torch.int64, device=dev),
+                      torch.empty(cc, dtype=torch.int32, device=dev)) for _ in range(2)]
+        self.streams = (torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev))
+
+    def _sample(self, k, seeds, seed_offsets, first_batch, rng_seed):
+        with torch.cuda.stream(self.streams[0]):
+            return api.sample_superbatch(self.offsets, self.indices, seeds, seed_offsets, self.fanout,
+                                         rng_seed=rng_seed, first_batch_index=first_batch,
+                                         workspace=self.ws_sample, out=self.bufs[k % 2])
+
+    def _changeset(self, samp):
+        with torch.cuda.stream(self.streams[1]):
+            return api.changeset(self.num_nodes, samp.ids, samp.ids_offsets, self.cap,
+                                 workspace=self.ws_changeset)
+
+    def run(self, superbatches, rng_seed=0, mode="overlap", consume=None):
+        """``superbatches``: list of (seeds device tensor, seed_offsets host array, first global
+        batch index).  ``mode``: "overlap" (changeset of k under the sampling of k+1),
+        "sequential" (one after the other) or "sample_only".  ``consume(k, samp, cs)`` is
+        called once superbatch k is inspected and before its buffers go back to the sampler
+        (the executor would run there); results are only valid inside that call.
+        Returns the wall time in seconds."""
+        if mode not in ("overlap", "sequential", "sample_only"):
+            raise ValueError(mode)
+        box = {}
+
+        def sample(k):
+            try:
+                box["samp"] = self._sample(k, *superbatches[k], rng_seed)
+            except BaseException as e:      # re-raised on the calling thread
+                box["error"] = e
+
+        n = len(superbatches)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        sample(0)
+        for k in range(n):
+            if "error" in box:
+                raise box["error"]
+            samp, cs = box["samp"], None
+            if mode == "overlap" and k + 1 < n:
+                th = threading.Thread(target=sample, args=(k + 1,))
+                th.start()
+                try:
+                    cs = self._changeset(samp)
+                finally:
+                    th.join()
+                if consume:
+                    consume(k, samp, cs)
+            else:
+                if mode != "sample_only":
+                    cs = self._changeset(samp)
+                if consume:
+                    consume(k, samp, cs)
+                if k + 1 < n:
+                    sample(k + 1)
+        if "error" in box:
+            raise box["error"]
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0

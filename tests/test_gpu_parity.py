@@ -300,3 +300,31 @@ def test_gather_reads_a_device_resident_slow_tier_too(ginex):
     ids = rng.permutation(1000)[:300].astype(np.int32)
     out = cache.gather(dev(ids))
     assert torch.equal(out, slow[torch.from_numpy(ids).long().cuda()])
+
+
+def test_pipelined_inspector_equals_sequential(ginex, case2):
+    """Superbatch-level pipeline: changeset(k) under sample(k+1), on two streams and two
+    host threads, must give exactly what the oracle gives for every superbatch."""
+    from workload.configs import seed_batches, train_nodes
+    c = case2
+    cfg, S = c.cfg, 6
+    train = train_nodes(cfg.num_nodes, cfg.train_frac, cfg.seed)
+    sbs, refs = [], []
+    for k in range(4):
+        seeds, so = seed_batches(train, cfg.batch, S, cfg.seed, first_batch=k * S)
+        sbs.append((seeds.cuda(), so.numpy(), k * S))
+        r = oracle.sample_superbatch(c.off, c.ind, seeds.numpy(), so.numpy(), cfg.fanout,
+                                     rng_seed=0, first_batch_index=k * S)
+        refs.append((r, oracle.changeset(cfg.num_nodes, r["ids"], r["ids_offsets"], 20000)))
+    pipe = ginex.InspectorPipeline(c.w.offsets, c.w.indices, cfg.num_nodes, cfg.fanout, 20000,
+                                   cfg.batch, S)
+    for mode in ("overlap", "sequential"):
+        seen = []
+
+        def consume(k, samp, cs):
+            assert np.array_equal(samp.ids.cpu().numpy(), refs[k][0]["ids"]), (mode, k)
+            check_changeset(cs, refs[k][1])
+            seen.append(k)
+
+        pipe.run(sbs, rng_seed=0, mode=mode, consume=consume)
+        assert seen == [0, 1, 2, 3]
