@@ -82,7 +82,9 @@ typedef struct ginex_csr {
  *   totals (host, [3]): number of ids, of rowptr entries and of col entries (= sampled
  *   edges) produced, or required on GINEX_ERR_CAPACITY.
  * Limits: 1 <= H <= GINEX_MAX_HOPS, 1 <= fanout[h] <= GINEX_MAX_FANOUT, and a batch's
- * list must stay below 2^30 entries.
+ * list must stay below 2^30 entries.  Seeds must lie in [0, num_nodes): unchecked by
+ * default, checked on the device first (GINEX_ERR_INPUT) when GINEX_VALIDATE=1 is set in
+ * the environment.  The CSR itself is trusted.
  * ------------------------------------------------------------------------------- */
 size_t ginex_sample_workspace_bytes(int64_t num_nodes, int32_t S, int64_t max_batch,
                                     const int32_t* fanout /*host [H]*/, int32_t H);
@@ -112,6 +114,9 @@ int32_t ginex_sample_superbatch(
  *   miss_count[i] = |ids_i \ C_i|.
  * init_count and total_changes are host outputs.  cs_capacity >= total_changes is
  * required (ids_offsets[S] always suffices).
+ * Preconditions (ids in range, ids distinct inside an iteration) are the caller's duty and
+ * unchecked by default; with GINEX_VALIDATE=1 in the environment they are checked on the
+ * device first and a violation returns GINEX_ERR_INPUT before anything else runs.
  * Limits: 1 <= S <= 8191, total ids < 2^31.
  * ------------------------------------------------------------------------------- */
 size_t ginex_changeset_workspace_bytes(int64_t num_nodes, int64_t total_ids, int32_t S,

@@ -15,6 +15,7 @@
 //   j* does the id order matter, and there the k-th smallest id is found by setting the
 //   members' bits in a bitmap over node ids and locating the k-th set bit.
 //   Evicted lines and inserted positions are then compacted in line / position order.
+#include <cstdlib>
 #include <vector>
 
 #include "common.hpp"
@@ -112,6 +113,30 @@ __global__ __launch_bounds__(TB) void k_count_heads(const uint64_t* __restrict__
     uint32_t s = 0;
     for (int w = 0; w < TB / WAVE; ++w) s += red[w];
     head_tiles[blockIdx.x] = s;
+  }
+}
+
+// Precondition check (only when asked for): ids inside [0, num_nodes) and no id twice in
+// one iteration.  In the node-sorted pairs a repeated id shows up as two neighbours of the
+// same node whose positions fall into the same iteration.  counts[0] = out of range,
+// counts[1] = repeats.
+__global__ __launch_bounds__(TB) void k_validate(const uint64_t* __restrict__ sorted, int64_t n,
+                                                 const int64_t* __restrict__ off, int32_t S,
+                                                 int64_t num_nodes,
+                                                 unsigned long long* __restrict__ counts) {
+  extern __shared__ int32_t lds_off[];
+  load_offsets(lds_off, off, S);
+  const int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (j >= n) return;
+  const uint64_t cur = sorted[j];
+  const uint32_t v = (uint32_t)(cur >> 32);
+  if ((int64_t)v >= num_nodes) atomicAdd(&counts[0], 1ull);
+  if (j + 1 < n) {
+    const uint64_t r = sorted[j + 1];
+    if ((uint32_t)(r >> 32) == v &&
+        iter_of(lds_off, S, (int32_t)(r & 0xFFFFFFFFu)) ==
+            iter_of(lds_off, S, (int32_t)(cur & 0xFFFFFFFFu)))
+      atomicAdd(&counts[1], 1ull);
   }
 }
 
@@ -677,6 +702,7 @@ struct Workspace {
   int32_t* next_iter;
   int64_t* d_offsets;
   int64_t* d_cs_offsets;
+  unsigned long long* d_counts;
   State st;
   int64_t look_tiles, evict_tiles, in_tiles, bit_words, bit_parts, max_heads, max_change;
   size_t bytes;
@@ -704,6 +730,7 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   w.next_iter = a.take<int32_t>(t);
   w.d_offsets = a.take<int64_t>(S + 1);
   w.d_cs_offsets = a.take<int64_t>(S + 1);
+  w.d_counts = a.take<unsigned long long>(2);
   State& st = w.st;
   const int64_t c = cap > 0 ? cap : 1;
   st.cap = cap;
@@ -811,8 +838,24 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
                      w.pairs_a);
   GINEX_LAUNCH_CHECK();
   uint64_t* sorted = nullptr;
-  GINEX_HIP(radix_sort_u64(w.pairs_a, w.pairs_b, total, 32, 32 + bits_for(num_nodes), w.hist, st,
-                           &sorted));
+  const char* validate_env = getenv("GINEX_VALIDATE");
+  const bool validate = validate_env && validate_env[0] == '1';
+  // when validating, sort on all 32 id bits so that ids beyond num_nodes are ordered too
+  GINEX_HIP(radix_sort_u64(w.pairs_a, w.pairs_b, total, 32,
+                           validate ? 64 : 32 + bits_for(num_nodes), w.hist, st, &sorted));
+  if (validate) {
+    unsigned long long bad[2] = {0, 0};
+    GINEX_HIP(fill_async<unsigned long long>(w.d_counts, 2, 0ull, st));
+    hipLaunchKernelGGL(k_validate, dim3((unsigned)ceil_div(total, TB)), dim3(TB),
+                       sizeof(int32_t) * (S + 1), st, sorted, total, w.d_offsets, S, num_nodes,
+                       w.d_counts);
+    GINEX_LAUNCH_CHECK();
+    GINEX_HIP(hipMemcpyAsync(bad, w.d_counts, sizeof(bad), hipMemcpyDeviceToHost, st));
+    GINEX_HIP(hipStreamSynchronize(st));
+    if (bad[0] || bad[1])
+      return fail(GINEX_ERR_INPUT, "%s: %llu ids outside [0, %lld), %llu ids repeated inside an "
+                  "iteration", who, bad[0], (long long)num_nodes, bad[1]);
+  }
   hipLaunchKernelGGL(k_count_heads, dim3((unsigned)w.look_tiles), dim3(TB), 0, st, sorted, total,
                      w.head_tiles);
   GINEX_LAUNCH_CHECK();

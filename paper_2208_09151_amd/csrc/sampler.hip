@@ -27,6 +27,8 @@
 //
 // The seeds go through the same count/scan/emit path as a stage with one candidate per
 // slot, which also removes repeated seeds.
+#include <cstdlib>
+
 #include "common.hpp"
 
 namespace ginex {
@@ -446,6 +448,14 @@ __global__ __launch_bounds__(TB) void k_copy_ids(Tables T, Meta M, const int32_t
     if (dst + j < ids_capacity) ids[dst + j] = T.wlist[b * T.stride_ids + j];
 }
 
+// Precondition check (only when asked for): every seed inside [0, num_nodes).
+__global__ __launch_bounds__(TB) void k_validate_seeds(const int32_t* __restrict__ seeds, int64_t n,
+                                                       int64_t num_nodes,
+                                                       unsigned long long* __restrict__ bad) {
+  const int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (j < n && (uint32_t)seeds[j] >= (uint64_t)num_nodes) atomicAdd(bad, 1ull);
+}
+
 __global__ void k_seed_counts(const int64_t* __restrict__ seed_off, int S, int32_t* nfront,
                               int32_t* nlist) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -636,6 +646,21 @@ extern "C" int32_t ginex_sample_superbatch(
 
   GINEX_HIP(hipMemcpyAsync(w.seed_off, seed_offsets, sizeof(int64_t) * (S + 1),
                            hipMemcpyHostToDevice, st));
+  const char* validate_env = getenv("GINEX_VALIDATE");
+  if (validate_env && validate_env[0] == '1' && seed_offsets[S] > 0) {
+    // the first slot of the (not yet used) batch_total array serves as the counter
+    unsigned long long bad = 0;
+    unsigned long long* d_bad = reinterpret_cast<unsigned long long*>(w.batch_total);
+    GINEX_HIP(fill_async<unsigned long long>(d_bad, 1, 0ull, st));
+    hipLaunchKernelGGL(k_validate_seeds, dim3((unsigned)ceil_div(seed_offsets[S], TB)), dim3(TB), 0,
+                       st, seeds, seed_offsets[S], g->num_nodes, d_bad);
+    GINEX_LAUNCH_CHECK();
+    GINEX_HIP(hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, st));
+    GINEX_HIP(hipStreamSynchronize(st));
+    if (bad)
+      return fail(GINEX_ERR_INPUT, "%s: %llu seeds outside [0, %lld)", who, bad,
+                  (long long)g->num_nodes);
+  }
   hipLaunchKernelGGL(k_seed_counts, dim3((unsigned)ceil_div(S, TB)), dim3(TB), 0, st, w.seed_off, S,
                      w.nfront, w.nlist_a);
   GINEX_LAUNCH_CHECK();

@@ -328,3 +328,19 @@ def test_pipelined_inspector_equals_sequential(ginex, case2):
 
         pipe.run(sbs, rng_seed=0, mode=mode, consume=consume)
         assert seen == [0, 1, 2, 3]
+
+
+def test_validation_mode_rejects_bad_traces(ginex, monkeypatch):
+    monkeypatch.setenv("GINEX_VALIDATE", "1")
+    good = np.array([3, 4, 2, 0, 3, 1], dtype=np.int32)
+    off = np.array([0, 2, 4, 6])
+    check_changeset(ginex.changeset(5, dev(good), off, 2), oracle.changeset(5, good, off, 2))
+    off_g, ind_g = small_graph()
+    with pytest.raises(ginex.GinexError) as e:
+        ginex.sample_superbatch(off_g.cuda(), ind_g.cuda(), dev(np.array([1, 300], dtype=np.int32)),
+                                [0, 2], (3,))
+    assert e.value.code == -4 and "seeds outside" in str(e.value)
+    for bad in ([3, 3, 2, 0, 3, 1], [3, 4, 2, 0, 9, 1]):     # a repeat / an id >= num_nodes
+        with pytest.raises(ginex.GinexError) as e:
+            ginex.changeset(5, dev(np.array(bad, dtype=np.int32)), off, 2)
+        assert e.value.code == -4

@@ -48,3 +48,54 @@ def test_host_side_argument_checks_need_no_gpu():
     desc = _lib.CacheDesc(0, 4, 24, 0, 10, 0)
     assert lib.ginex_cache_init(ctypes.byref(desc), None, 0, None) == -1
     assert b"multiple of 16" in lib.ginex_last_error()
+
+
+def test_precondition_and_workspace_errors_are_reported_before_any_launch():
+    """Host-side validation: every error below is returned before the first HIP call, so
+    fake device addresses are never touched."""
+    from paper_2208_09151_amd import _lib
+    lib = _lib.load()
+    fake = ctypes.c_void_p(0x1000)
+    fan = np.array([10, 10], dtype=np.int32)
+    so = np.array([0, 5, 12], dtype=np.int64)
+    host = lambda n: np.zeros(n, dtype=np.int64)
+    ids_off, hops, ro, co, tot = host(3), host(6), host(5), host(5), host(3)
+    g = _lib.CsrDesc(100, 1000, 0x1000, 0, 0x1000)
+    P = lambda a: ctypes.c_void_p(a.ctypes.data)
+
+    def sample(seed_offsets=so, S=2, ws_bytes=16, fanout=fan, ws=fake):
+        return lib.ginex_sample_superbatch(
+            ctypes.byref(g), fake, P(seed_offsets), S, P(fanout), len(fanout), 0, 0,
+            fake, 1000, P(ids_off), P(hops), fake, 1000, fake, 1000, P(ro), P(co), P(tot),
+            ws, ws_bytes, None)
+
+    assert sample() == -3 and b"workspace" in lib.ginex_last_error()
+    assert sample(seed_offsets=np.array([0, 7, 3], dtype=np.int64)) == -4
+    assert b"not monotone" in lib.ginex_last_error()
+    assert sample(seed_offsets=np.array([1, 5, 12], dtype=np.int64)) == -4
+    assert sample(fanout=np.array([10, 0], dtype=np.int32)) == -1
+    assert sample(ws=None) == -1
+    need = lib.ginex_sample_workspace_bytes(100, 2, 7, P(fan), 2)
+    assert sample(ws=ctypes.c_void_p(0x1010), ws_bytes=need) == -1   # misaligned workspace
+    assert b"aligned" in lib.ginex_last_error()
+
+    io = np.array([0, 4, 9], dtype=np.int64)
+    ic, tc = host(1), host(1)
+
+    def changeset(ids_offsets=io, S=2, cap=3, ws_bytes=16, n=100):
+        return lib.ginex_changeset(n, fake, P(ids_offsets), S, cap, fake, P(ic), fake, fake, fake,
+                                   100, fake, fake, P(tc), fake, ws_bytes, None)
+
+    assert changeset() == -3
+    assert changeset(ids_offsets=np.array([0, 9, 4], dtype=np.int64)) == -4
+    assert changeset(ids_offsets=np.array([0, 200, 300], dtype=np.int64)) == -4   # > nodes
+    assert b"more ids than nodes" in lib.ginex_last_error()
+    assert changeset(cap=-1) == -1
+    assert changeset(S=0) == -1
+
+    c = _lib.CacheDesc(0x1000, 4, 64, 0x1000, 10, 0x1000)
+    assert lib.ginex_cache_init(ctypes.byref(c), fake, 5, None) == -1      # more rows than lines
+    assert lib.ginex_gather(ctypes.byref(c), fake, 2, fake, fake, fake, fake, 3, None) == -1
+    assert lib.ginex_cache_update(ctypes.byref(c), fake, fake, fake, fake, 9, None) == -1
+    assert lib.ginex_gather(ctypes.byref(c), fake, 2, ctypes.c_void_p(0x1008), None, None, None,
+                            0, None) == -1                                   # out misaligned
