@@ -344,3 +344,23 @@ def test_validation_mode_rejects_bad_traces(ginex, monkeypatch):
         with pytest.raises(ginex.GinexError) as e:
             ginex.changeset(5, dev(np.array(bad, dtype=np.int32)), off, 2)
         assert e.value.code == -4
+
+
+@pytest.mark.parametrize("fanout,batch,S", [((10, 10, 10), 8, 1500), ((15, 10, 5), 64, 300),
+                                            ((25, 10), 128, 100)])
+def test_many_small_batches_whole_path(ginex, case1, fanout, batch, S):
+    """Superbatches of the size the paper uses (thousands of batches), other popular
+    sampling sizes, with the cache under pressure in every iteration."""
+    from workload.configs import seed_batches, train_nodes
+    c = case1
+    cfg = c.cfg
+    train = train_nodes(cfg.num_nodes, cfg.train_frac, cfg.seed)
+    seeds, so = seed_batches(train, batch, S, cfg.seed)
+    ref = oracle.sample_superbatch(c.off, c.ind, seeds.numpy(), so.numpy(), fanout, rng_seed=5)
+    res = ginex.sample_superbatch(c.w.offsets, c.w.indices, seeds.cuda(), so.numpy(), fanout,
+                                  rng_seed=5)
+    check_sample(res, ref, S, len(fanout))
+    for cap in (300, 3000):
+        rcs = oracle.changeset(cfg.num_nodes, ref["ids"], ref["ids_offsets"], cap)
+        cs = ginex.changeset(cfg.num_nodes, res.ids, res.ids_offsets, cap)
+        check_changeset(cs, rcs)
