@@ -226,10 +226,12 @@ __global__ __launch_bounds__(TB) void k_copy_init(const uint64_t* __restrict__ h
 // ---- part 3 -----------------------------------------------------------------------
 //
 // Every phase of an iteration is a device function over "virtual blocks" of TB threads; the
-// kernels below pack phases that do not depend on each other into one launch (seven
-// launches per iteration).  A single cooperative kernel with grid-wide barriers between
-// the phases was measured too: hipcc's grid.sync() costs about 0.1 ms per barrier on 1024
-// blocks, twelve times slower overall than the launches, so it is not used.
+// kernels below pack phases that do not depend on each other into one launch (nine
+// launches per iteration).  Two ways of saving launches were measured and dropped: a single
+// cooperative kernel with grid.sync() between the phases (about 0.1 ms per barrier on 1024
+// blocks, twelve times slower overall), and running the single-block phases in the last
+// block to finish of the launch before them (the device-wide fence every block then needs
+// writes back and invalidates L2 on this multi-XCD part: three to four times slower).
 
 struct Iter {           // what a phase needs to know about the running iteration
   const int32_t* ids;   // ids_i
