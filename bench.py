@@ -173,6 +173,44 @@ def cpu_baseline(w, n_batches):
     }
 
 
+def pressure_leg(ginex, w, run, samp, divisor):
+    """The same superbatch with a cache of distinct/divisor rows: every iteration evicts."""
+    cfg = w.cfg
+    distinct = int(torch.unique(samp.ids).numel())
+    cap = max(1, distinct // divisor)
+    times = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        cs = ginex.changeset(cfg.num_nodes, samp.ids, samp.ids_offsets, cap, workspace=run.ws)
+        torch.cuda.synchronize()
+        times.append(time.perf_counter() - t)
+    cache = ginex.FeatureCache(w.features, cap)
+    io, co = samp.ids_offsets, cs.cs_offsets
+    ev = torch.cuda.Event
+    e0, e1, e2 = ev(enable_timing=True), ev(enable_timing=True), ev(enable_timing=True)
+    e0.record()
+    cache.init(cs.init_ids)
+    e1.record()
+    for i in range(run.S):
+        sl = slice(co[i], co[i + 1])
+        cache.gather(samp.ids[io[i]:io[i + 1]], run.batch_input, cs.in_ids[sl], cs.out_ids[sl],
+                     cs.in_positions[sl])
+    e2.record()
+    torch.cuda.synchronize()
+    accesses, misses = int(samp.totals[0]), int(cs.miss_count.sum())
+    row_bytes = cfg.feat_dim * 4
+    loop_s = e1.elapsed_time(e2) / 1e3
+    return {"cache_rows": cap, "distinct_rows": distinct, "misses": misses,
+            "miss_ratio": misses / accesses, "changes": int(co[-1]),
+            "changeset_ms": min(times) * 1e3,
+            "changeset_accesses_per_s": accesses / min(times),
+            "cache_init_ms": e0.elapsed_time(e1),
+            "gather_update_ms": loop_s * 1e3,
+            "host_link_GBps": misses * row_bytes / loop_s / 1e9,
+            "gather_algorithmic_GBps": accesses * (8 + 2 * row_bytes) / loop_s / 1e9}
+
+
 def pipeline_leg(ginex, w, K):
     """Inspector of K consecutive superbatches, three ways: sampling only, sampling and
     changesets one after the other, changeset(k) overlapped with sample(k+1)."""
@@ -205,6 +243,9 @@ def main():
     ap.add_argument("--pipeline", type=int, default=0, metavar="K",
                     help="also run K superbatches through the superbatch-level pipeline "
                          "(changeset of k under the sampling of k+1) and report the overlap")
+    ap.add_argument("--pressure", type=int, default=0, metavar="D",
+                    help="also run changesets and the executor with a cache of distinct/D rows "
+                         "(configurations 3 and 4 never miss with their own cache size)")
     ap.add_argument("--allhit", action="store_true",
                     help="also time the gather kernel with the whole feature table in HBM")
     args = ap.parse_args()
@@ -307,6 +348,8 @@ def main():
 
     if args.pipeline > 0:
         stages["pipeline"] = pipeline_leg(ginex, w, args.pipeline)
+    if args.pressure > 0:
+        stages["pressure"] = pressure_leg(ginex, w, run, samp, args.pressure)
 
     result = {
         "metric": METRIC,
