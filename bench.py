@@ -232,6 +232,35 @@ def pipeline_leg(ginex, w, K):
         out[mode + "_ms"] = min(pipe.run(sbs, mode=mode) for _ in range(3)) * 1e3
     out["changeset_hidden_ms"] = out["sequential_ms"] - out["overlap_ms"]
     out["changeset_exposed_ms"] = out["overlap_ms"] - out["sample_only_ms"]
+
+    # the whole path: executor of superbatch k under the inspector of superbatch k+1
+    cache = ginex.FeatureCache(w.features, cfg.cap)
+    batch_input = torch.empty((min(cfg.num_nodes, cfg.batch * 11 ** len(cfg.fanout)), cfg.feat_dim),
+                              dtype=torch.float32, device="cuda")
+    edges = [0]
+
+    def execute(k, samp, cs):
+        io, co = samp.ids_offsets.tolist(), cs.cs_offsets.tolist()
+        stream = torch.cuda.current_stream().cuda_stream
+        cache.init(cs.init_ids)
+        ids_base, out_ptr = samp.ids.data_ptr(), batch_input.data_ptr()
+        bases = (cs.in_ids.data_ptr(), cs.out_ids.data_ptr(), cs.in_positions.data_ptr())
+        for i in range(len(io) - 1):
+            cache.gather_raw(ids_base + 4 * io[i], io[i + 1] - io[i], out_ptr, stream)
+            nc = co[i + 1] - co[i]
+            if nc:
+                cache.update_raw(out_ptr, bases[0] + 4 * co[i], bases[1] + 4 * co[i],
+                                 bases[2] + 4 * co[i], nc, stream)
+        torch.cuda.current_stream().synchronize()
+        edges[0] += int(samp.totals[2])
+
+    for overlap in (False, True):
+        pipe.run_with_executor(sbs[:2], execute, overlap=overlap)      # warm-up
+        edges[0] = 0
+        t = pipe.run_with_executor(sbs, execute, overlap=overlap)
+        key = "whole_path_overlapped" if overlap else "whole_path_sequential"
+        out[key + "_ms_per_superbatch"] = t * 1e3 / K
+        out[key + "_edges_per_s"] = edges[0] / t
     return out
 
 

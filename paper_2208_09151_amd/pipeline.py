@@ -7,6 +7,10 @@ small dependent launches).  Each stage runs on its own HIP stream (default prior
 its own host thread, with its own workspace and output buffers (double buffering); the
 library keeps no global state, and ctypes drops the GIL during the calls.
 
+``run_with_executor`` goes one step further than the paper: the whole inspector of
+superbatch k+1 (sampling and changesets, bound by HBM and atomics) runs under the executor
+of superbatch k (cache initialization and gathers, bound by the host link).
+
 This module only sequences calls of the binding: no step of the path runs here.
 """
 from __future__ import annotations
@@ -91,6 +95,49 @@ class InspectorPipeline:
                     consume(k, samp, cs)
                 if k + 1 < n:
                     sample(k + 1)
+        if "error" in box:
+            raise box["error"]
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    def inspect(self, k, seeds, seed_offsets, first_batch, rng_seed=0):
+        """Sampling then changesets of one superbatch on the inspector streams."""
+        samp = self._sample(k, seeds, seed_offsets, first_batch, rng_seed)
+        return samp, self._changeset(samp)
+
+    def run_with_executor(self, superbatches, execute, rng_seed=0, overlap=True):
+        """Two-stage pipeline over superbatches: ``execute(k, samp, cs)`` (cache init,
+        gathers, updates; it must finish its GPU work before returning) runs on the calling
+        thread while, with ``overlap``, the inspector of superbatch k+1 runs on a second
+        thread and its own streams.  Returns the wall time in seconds."""
+        box = {}
+
+        def inspect(k):
+            try:
+                box["next"] = self.inspect(k, *superbatches[k], rng_seed)
+            except BaseException as e:
+                box["error"] = e
+
+        n = len(superbatches)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        inspect(0)
+        for k in range(n):
+            if "error" in box:
+                raise box["error"]
+            samp, cs = box["next"]
+            th = None
+            if k + 1 < n:
+                if overlap:
+                    th = threading.Thread(target=inspect, args=(k + 1,))
+                    th.start()
+            try:
+                execute(k, samp, cs)
+            finally:
+                if th is not None:
+                    th.join()
+            if k + 1 < n and not overlap:
+                inspect(k + 1)
         if "error" in box:
             raise box["error"]
         torch.cuda.synchronize()

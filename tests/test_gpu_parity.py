@@ -364,3 +364,43 @@ def test_many_small_batches_whole_path(ginex, case1, fanout, batch, S):
         rcs = oracle.changeset(cfg.num_nodes, ref["ids"], ref["ids_offsets"], cap)
         cs = ginex.changeset(cfg.num_nodes, res.ids, res.ids_offsets, cap)
         check_changeset(cs, rcs)
+
+
+def test_executor_under_next_inspector_gathers_the_right_bytes(ginex, case2):
+    """Executor of superbatch k while superbatch k+1 is inspected on other streams: every
+    gathered batch input must still be slow[ids]."""
+    from workload.configs import seed_batches, train_nodes
+    c = case2
+    cfg, S, cap = c.cfg, 5, 15000
+    train = train_nodes(cfg.num_nodes, cfg.train_frac, cfg.seed)
+    sbs, refs = [], []
+    for k in range(3):
+        seeds, so = seed_batches(train, cfg.batch, S, cfg.seed, first_batch=k * S)
+        sbs.append((seeds.cuda(), so.numpy(), k * S))
+        refs.append(oracle.sample_superbatch(c.off, c.ind, seeds.numpy(), so.numpy(), cfg.fanout,
+                                             rng_seed=0, first_batch_index=k * S))
+    pipe = ginex.InspectorPipeline(c.w.offsets, c.w.indices, cfg.num_nodes, cfg.fanout, cap,
+                                   cfg.batch, S)
+    cache = ginex.FeatureCache(c.w.features, cap)
+    feats = c.w.features.numpy()
+    done = []
+
+    def execute(k, samp, cs):
+        assert np.array_equal(samp.ids.cpu().numpy(), refs[k]["ids"])
+        check_changeset(cs, oracle.changeset(cfg.num_nodes, refs[k]["ids"],
+                                             refs[k]["ids_offsets"], cap))
+        cache.init(cs.init_ids)
+        io, co = samp.ids_offsets, cs.cs_offsets
+        for i in range(S):
+            sl = slice(co[i], co[i + 1])
+            out = cache.gather(samp.ids[io[i]:io[i + 1]], None, cs.in_ids[sl], cs.out_ids[sl],
+                               cs.in_positions[sl])
+            want = oracle.gather(feats, refs[k]["ids"][io[i]:io[i + 1]])
+            got = out.cpu().numpy().view(np.uint8).reshape(out.shape[0], -1)
+            assert np.array_equal(got, want), (k, i)
+        done.append(k)
+
+    for overlap in (True, False):
+        del done[:]
+        pipe.run_with_executor(sbs, execute, overlap=overlap)
+        assert done == [0, 1, 2]
