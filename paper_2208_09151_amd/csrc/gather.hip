@@ -140,13 +140,13 @@ extern "C" int32_t ginex_cache_init(const ginex_cache_t* c, const int32_t* init_
   GINEX_HIP(fill_async<int32_t>(c->addr, c->num_nodes, -1, st));
   if (init_count > 0) {
     const int32_t cpr = (int32_t)(c->row_bytes / 16);
-    // The fill is bound by the host link, which 128 blocks (2 MB of reads in flight) keep
-    // as busy as a full grid does (54 GB/s either way).  A full grid parks hundreds of
+    // The fill is bound by the host link, which 64 blocks (1 MB of reads in flight) keep
+    // busier than a full grid does (57 against 54.6 GB/s).  A full grid parks hundreds of
     // thousands of slow link reads in the memory pipeline and kernels on other streams
     // (the inspector of the next superbatch) then make no progress until the fill ends;
     // behind the small grid they run concurrently.
     unsigned blocks = grid_for(init_count * cpr, UNROLL);
-    if (blocks > 128) blocks = 128;
+    if (blocks > 64) blocks = 64;
     hipLaunchKernelGGL(k_cache_fill, dim3(blocks), dim3(THREADS), 0, st, (chunk_t*)c->rows,
                        c->addr, (const chunk_t*)c->slow, init_ids, init_count, cpr);
     GINEX_LAUNCH_CHECK();
