@@ -131,6 +131,21 @@ int32_t ginex_changeset(
     int64_t* total_changes /*host*/,
     void* ws, size_t ws_bytes, void* stream);
 
+/* The same precomputation for the LRU policy (Section 2.3 and Figure 2: the policy that
+ * Belady's is compared with), so that both run through the same executor and their miss
+ * counts can be compared on one trace.  Arguments, outputs, workspace and limits are those
+ * of ginex_changeset.  C_0 is the same prefetch as above, its rows counting as not used yet;
+ * C_{i+1} keeps the cap elements of union(C_i, ids_i) used most recently (ties: a resident
+ * row before an incoming one, then smaller id), so the rows of ids_i outrank every other. */
+int32_t ginex_changeset_lru(
+    int64_t num_nodes, const int32_t* ids, const int64_t* ids_offsets /*host [S+1]*/,
+    int32_t S, int64_t cap,
+    int32_t* init_ids /*[cap]*/, int64_t* init_count /*host*/,
+    int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
+    int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
+    int64_t* total_changes /*host*/,
+    void* ws, size_t ws_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------------
  * Feature cache (Section 3.3 "Feature Cache Structure"): a 2-D array of `cap` rows in
  * HBM plus an address table with one entry per node (cache line, or -1).  `slow` is the

@@ -163,6 +163,16 @@ def changeset_by_sorting(num_nodes, ids, ids_offsets, cap):
     return _changeset(lib().oracle_changeset_by_sorting, num_nodes, ids, ids_offsets, cap)
 
 
+def changeset_lru(num_nodes, ids, ids_offsets, cap):
+    """The same lists under the LRU policy (heap variant)."""
+    return _changeset(lib().oracle_changeset_lru, num_nodes, ids, ids_offsets, cap)
+
+
+def changeset_lru_by_sorting(num_nodes, ids, ids_offsets, cap):
+    """LRU straight from the definition."""
+    return _changeset(lib().oracle_changeset_lru_by_sorting, num_nodes, ids, ids_offsets, cap)
+
+
 def lru_misses(num_nodes, ids, ids_offsets, cap, init_ids):
     ids, ids_offsets, init_ids = _i32(ids), _i64(ids_offsets), _i32(init_ids)
     return int(lib().oracle_lru_misses(

@@ -14,6 +14,9 @@
 //   next_use               naive forward scan, the worked five-node example of the paper
 //   changeset (heap)       the sort-based definition, exhaustive search of all eviction
 //                          choices on tiny traces, LRU and static-cache upper bounds
+//   changeset_lru          a textbook LRU list on single-access traces, the closed form of a
+//                          cyclic trace, the sort-based definition, the stand-alone LRU
+//                          miss counter, Belady's miss count as a lower bound
 //   gather / cache replay  the worked ten-node example of the paper, out[p] == slow[ids[p]]
 //
 // Build: g++ -O2 -std=c++17 -shared -fPIC ginex_oracle.cpp -o libginex_oracle.so
@@ -265,6 +268,32 @@ struct ChangesetOut {
   }
 };
 
+// Replacement policies.  Both keep, out of union(C_i, ids_i), the `cap` elements with
+// the smallest key; they differ only in the key an access leaves on a row.
+//   Belady (Section 3.4): the iteration of the row's next access (NEVER if none).
+//   LRU (Section 2.3, the policy Belady's is measured against): S-1-i for an access in
+//   iteration i, so that a row used longer ago has a larger key; a prefetched row that
+//   has not been used yet has key S, larger than any used row's.
+enum Policy { BELADY = 0, LRU = 1 };
+
+inline int32_t key_after_access(Policy policy, int32_t S, int32_t i, int32_t next) {
+  return policy == BELADY ? next : S - 1 - i;
+}
+inline int32_t key_of_prefetched(Policy policy, int32_t S, int32_t first) {
+  return policy == BELADY ? first : S;
+}
+
+int32_t changeset_with_heap(Policy policy, int64_t num_nodes, const int32_t* ids,
+                            const int64_t* ids_offsets, int32_t S, int64_t cap,
+                            int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
+                            int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
+                            int64_t* cs_offsets, int64_t* miss_count);
+int32_t changeset_from_definition(Policy policy, int64_t num_nodes, const int32_t* ids,
+                                  const int64_t* ids_offsets, int32_t S, int64_t cap,
+                                  int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
+                                  int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
+                                  int64_t* cs_offsets, int64_t* miss_count);
+
 }  // namespace
 
 extern "C" {
@@ -288,6 +317,29 @@ int32_t oracle_changeset(int64_t num_nodes, const int32_t* ids, const int64_t* i
                          int32_t* init_ids, int64_t* init_count,
                          int32_t* in_ids, int32_t* out_ids, int32_t* in_positions,
                          int64_t cs_capacity, int64_t* cs_offsets, int64_t* miss_count) {
+  return changeset_with_heap(BELADY, num_nodes, ids, ids_offsets, S, cap, init_ids, init_count,
+                             in_ids, out_ids, in_positions, cs_capacity, cs_offsets, miss_count);
+}
+
+// The same lists for the LRU policy (Section 2.3), same C_0, same list order.
+int32_t oracle_changeset_lru(int64_t num_nodes, const int32_t* ids, const int64_t* ids_offsets,
+                             int32_t S, int64_t cap,
+                             int32_t* init_ids, int64_t* init_count,
+                             int32_t* in_ids, int32_t* out_ids, int32_t* in_positions,
+                             int64_t cs_capacity, int64_t* cs_offsets, int64_t* miss_count) {
+  return changeset_with_heap(LRU, num_nodes, ids, ids_offsets, S, cap, init_ids, init_count,
+                             in_ids, out_ids, in_positions, cs_capacity, cs_offsets, miss_count);
+}
+
+}  // extern "C"
+
+namespace {
+
+int32_t changeset_with_heap(Policy policy, int64_t num_nodes, const int32_t* ids,
+                            const int64_t* ids_offsets, int32_t S, int64_t cap,
+                            int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
+                            int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
+                            int64_t* cs_offsets, int64_t* miss_count) {
   const int64_t total = ids_offsets[S];
   std::vector<int32_t> next_iter(total > 0 ? total : 1), first_iter(num_nodes);
   oracle_next_use(num_nodes, ids, ids_offsets, S, next_iter.data(), first_iter.data());
@@ -302,7 +354,7 @@ int32_t oracle_changeset(int64_t num_nodes, const int32_t* ids, const int64_t* i
   for (size_t r = 0; r < init.size(); ++r) {
     init_ids[r] = init[r];
     line_of[init[r]] = (int32_t)r;
-    key_of[init[r]] = first_iter[init[r]];
+    key_of[init[r]] = key_of_prefetched(policy, S, first_iter[init[r]]);
     heap.push({key_of[init[r]], init[r]});
   }
   int64_t occupancy = (int64_t)init.size();
@@ -316,11 +368,12 @@ int32_t oracle_changeset(int64_t num_nodes, const int32_t* ids, const int64_t* i
     evicted.clear();
     for (int64_t p = ids_offsets[i]; p < ids_offsets[i + 1]; ++p) {
       const int32_t v = ids[p];
+      const int32_t key = key_after_access(policy, S, i, next_iter[p]);
       if (line_of[v] >= 0) {
-        key_of[v] = next_iter[p];
-        heap.push({next_iter[p], v});
+        key_of[v] = key;
+        heap.push({key, v});
       } else {
-        incoming.push_back({Key{next_iter[p], 1, v}, (int32_t)(p - ids_offsets[i])});
+        incoming.push_back({Key{key, 1, v}, (int32_t)(p - ids_offsets[i])});
       }
     }
     miss_count[i] = (int64_t)incoming.size();
@@ -381,12 +434,11 @@ int32_t oracle_changeset(int64_t num_nodes, const int32_t* ids, const int64_t* i
 // The same result computed straight from the definition: every iteration the
 // whole candidate set is sorted by the keeping order and cut at `cap`.
 // O(S * cap log cap); for small inputs and for checking the heap variant.
-int32_t oracle_changeset_by_sorting(int64_t num_nodes, const int32_t* ids,
-                                    const int64_t* ids_offsets, int32_t S, int64_t cap,
-                                    int32_t* init_ids, int64_t* init_count,
-                                    int32_t* in_ids, int32_t* out_ids, int32_t* in_positions,
-                                    int64_t cs_capacity, int64_t* cs_offsets,
-                                    int64_t* miss_count) {
+int32_t changeset_from_definition(Policy policy, int64_t num_nodes, const int32_t* ids,
+                                  const int64_t* ids_offsets, int32_t S, int64_t cap,
+                                  int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
+                                  int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
+                                  int64_t* cs_offsets, int64_t* miss_count) {
   const int64_t total = ids_offsets[S];
   std::vector<int32_t> next_iter(total > 0 ? total : 1), first_iter(num_nodes);
   oracle_next_use(num_nodes, ids, ids_offsets, S, next_iter.data(), first_iter.data());
@@ -399,7 +451,7 @@ int32_t oracle_changeset_by_sorting(int64_t num_nodes, const int32_t* ids,
   for (size_t r = 0; r < init.size(); ++r) {
     init_ids[r] = init[r];
     line_id[r] = init[r];
-    line_next[r] = first_iter[init[r]];
+    line_next[r] = key_of_prefetched(policy, S, first_iter[init[r]]);
     line_of[init[r]] = (int32_t)r;
   }
   struct Cand { Key key; int32_t pos; int32_t line; };
@@ -408,14 +460,16 @@ int32_t oracle_changeset_by_sorting(int64_t num_nodes, const int32_t* ids,
   for (int32_t i = 0; i < S; ++i) {
     const int64_t lo = ids_offsets[i], hi = ids_offsets[i + 1];
     for (int64_t p = lo; p < hi; ++p)
-      if (line_of[ids[p]] >= 0) line_next[line_of[ids[p]]] = next_iter[p];
+      if (line_of[ids[p]] >= 0)
+        line_next[line_of[ids[p]]] = key_after_access(policy, S, i, next_iter[p]);
     cand.clear();
     for (int64_t l = 0; l < cap; ++l)
       if (line_id[l] >= 0) cand.push_back({Key{line_next[l], 0, line_id[l]}, -1, (int32_t)l});
     int64_t misses = 0;
     for (int64_t p = lo; p < hi; ++p)
       if (line_of[ids[p]] < 0) {
-        cand.push_back({Key{next_iter[p], 1, ids[p]}, (int32_t)(p - lo), -1});
+        cand.push_back({Key{key_after_access(policy, S, i, next_iter[p]), 1, ids[p]},
+                        (int32_t)(p - lo), -1});
         ++misses;
       }
     miss_count[i] = misses;
@@ -449,6 +503,32 @@ int32_t oracle_changeset_by_sorting(int64_t num_nodes, const int32_t* ids,
     cs_offsets[i + 1] = o.written;
   }
   return o.fits ? 0 : -1;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t oracle_changeset_by_sorting(int64_t num_nodes, const int32_t* ids,
+                                    const int64_t* ids_offsets, int32_t S, int64_t cap,
+                                    int32_t* init_ids, int64_t* init_count,
+                                    int32_t* in_ids, int32_t* out_ids, int32_t* in_positions,
+                                    int64_t cs_capacity, int64_t* cs_offsets,
+                                    int64_t* miss_count) {
+  return changeset_from_definition(BELADY, num_nodes, ids, ids_offsets, S, cap, init_ids,
+                                   init_count, in_ids, out_ids, in_positions, cs_capacity,
+                                   cs_offsets, miss_count);
+}
+
+int32_t oracle_changeset_lru_by_sorting(int64_t num_nodes, const int32_t* ids,
+                                        const int64_t* ids_offsets, int32_t S, int64_t cap,
+                                        int32_t* init_ids, int64_t* init_count,
+                                        int32_t* in_ids, int32_t* out_ids, int32_t* in_positions,
+                                        int64_t cs_capacity, int64_t* cs_offsets,
+                                        int64_t* miss_count) {
+  return changeset_from_definition(LRU, num_nodes, ids, ids_offsets, S, cap, init_ids,
+                                   init_count, in_ids, out_ids, in_positions, cs_capacity,
+                                   cs_offsets, miss_count);
 }
 
 // Miss count of a least-recently-used cache started from the same C_0 under

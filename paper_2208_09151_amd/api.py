@@ -144,9 +144,13 @@ class ChangesetResult:
     miss_count: np.ndarray      # [S] host
 
 
-def changeset(num_nodes, ids, ids_offsets, cap, workspace=None):
-    """ginex_changeset.  ``ids`` is a device int32 tensor, ``ids_offsets`` a host array."""
+def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady"):
+    """ginex_changeset (``policy="belady"``) or ginex_changeset_lru (``policy="lru"``).
+    ``ids`` is a device int32 tensor, ``ids_offsets`` a host array."""
     lib = _lib.load()
+    if policy not in ("belady", "lru"):
+        raise ValueError(f"unknown policy {policy!r}")
+    entry = lib.ginex_changeset if policy == "belady" else lib.ginex_changeset_lru
     _dev(ids, torch.int32)
     io = np.ascontiguousarray(np.asarray(ids_offsets), dtype=np.int64)
     S = len(io) - 1
@@ -165,10 +169,9 @@ def changeset(num_nodes, ids, ids_offsets, cap, workspace=None):
     miss = torch.empty(max(S, 1), dtype=torch.int64, device=dev)
     init_count = np.zeros(1, dtype=np.int64)
     total_changes = np.zeros(1, dtype=np.int64)
-    rc = lib.ginex_changeset(num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(init_ids),
-                             _np_ptr(init_count), _ptr(in_ids), _ptr(out_ids), _ptr(in_pos),
-                             cs_cap, _ptr(cs_off), _ptr(miss), _np_ptr(total_changes), _ptr(ws),
-                             ws.numel(), _stream())
+    rc = entry(num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(init_ids), _np_ptr(init_count),
+               _ptr(in_ids), _ptr(out_ids), _ptr(in_pos), cs_cap, _ptr(cs_off), _ptr(miss),
+               _np_ptr(total_changes), _ptr(ws), ws.numel(), _stream())
     _check(rc)
     n = int(total_changes[0])
     return ChangesetResult(init_ids[:int(init_count[0])], in_ids[:n], out_ids[:n], in_pos[:n],

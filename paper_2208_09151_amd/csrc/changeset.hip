@@ -61,6 +61,7 @@ struct State {
   int64_t cap, num_nodes;
   int32_t S;
   int64_t max_change;     // entries of out_slot / in_id / in_next
+  int32_t lru;            // 0: Belady keys (next accessed iteration), 1: LRU keys
 };
 
 // Iteration that holds flat position p: the largest i with off[i] <= p.  `off` is the
@@ -205,7 +206,9 @@ __global__ __launch_bounds__(TB) void k_init_state(const uint64_t* __restrict__ 
   for (int64_t s = (int64_t)blockIdx.x * TB + threadIdx.x; s < count; s += span) {
     const uint64_t h = heads[s];
     const int32_t v = (int32_t)(h & 0xFFFFFFFFu);
-    const int32_t first = (int32_t)(h >> 32);
+    // Belady: the key of a prefetched row is its first access; LRU: it has not been used
+    // yet, which is the oldest possible key
+    const int32_t first = st.lru ? st.S : (int32_t)(h >> 32);
     init_ids[s] = v;
     st.res_id[s] = v;
     st.res_next[s] = first;
@@ -235,10 +238,17 @@ __global__ __launch_bounds__(TB) void k_copy_init(const uint64_t* __restrict__ h
 
 struct Iter {           // what a phase needs to know about the running iteration
   const int32_t* ids;   // ids_i
-  const int32_t* next;  // next accessed iteration of each access of ids_i
+  const int32_t* next;  // next accessed iteration of each access of ids_i (Belady keys)
   int64_t n;            // |ids_i|
   int32_t i;
+  int32_t key;          // >= 0: every access of the iteration takes this key (LRU: S-1-i,
+                        // smaller = used more recently); < 0: the key is next[p]
+  int32_t lo_bin;       // smallest bucket a candidate of this iteration can fall into
 };
+
+__device__ __forceinline__ int32_t key_of(const Iter& it, int64_t p) {
+  return it.key >= 0 ? it.key : it.next[p];
+}
 
 struct Outputs {
   int32_t* in_ids;
@@ -274,12 +284,16 @@ __device__ void p_touch(const State& st, const Iter& it, unsigned long long* mis
   for (int t = 0; t < TOUCH_ITEMS; ++t) {
     const int64_t p = base + t * TB + threadIdx.x;
     if (p < it.n) {
-      const int32_t nx = it.next[p];
+      const int32_t nx = key_of(it, p);
       const int32_t line = st.addr[it.ids[p]];
       if (line >= 0) {
+        // An LRU hit leaves a bucket that is still walked (an older one): take it out of
+        // the count there; counters wrap, the flush below adds them modulo 2^32.  A Belady
+        // hit leaves bucket i, which no later iteration looks at.
+        if (st.lru) atomicSub(&hr[st.res_next[line]], 1u);
         st.res_next[line] = nx;
         atomicAdd(&hr[nx], 1u);
-        if (nx == st.S) {   // the row's last access: it is a dead resident from now on
+        if (nx == st.S && !st.lru) {   // the row's last access: a dead resident from now on
           const uint32_t v = (uint32_t)it.ids[p];
           atomicOr(&st.dead_bits[v >> 5], 1u << (v & 31));
         }
@@ -290,7 +304,7 @@ __device__ void p_touch(const State& st, const Iter& it, unsigned long long* mis
     }
   }
   const uint32_t total = block_sum_u32(misses, red);
-  for (int j = it.i + 1 + threadIdx.x; j <= st.S; j += TB) {
+  for (int j = it.lo_bin + threadIdx.x; j <= st.S; j += TB) {
     if (hr[j]) atomicAdd(&st.rhist[j], hr[j]);
     if (hi[j]) atomicAdd(&st.ihist[j], hi[j]);
   }
@@ -302,14 +316,14 @@ __device__ void p_touch(const State& st, const Iter& it, unsigned long long* mis
 // candidates as there were misses are dropped; fixes the threshold bucket, what happens
 // inside it, the size of the changeset, and rolls the resident histogram forward to C_{i+1}.
 template <int NT>
-__device__ void p_threshold(const State& st, int32_t i, const int64_t* miss_count,
+__device__ void p_threshold(const State& st, int32_t i, int32_t lo_bin, const int64_t* miss_count,
                             int64_t* cs_offsets) {
   __shared__ int64_t smem[NT / WAVE + 1];
   __shared__ int32_t s_jstar;
   __shared__ uint32_t s_kept;
   const int32_t S = st.S;
   const int64_t n_drop = miss_count[i];
-  const int32_t bins = S - i;                     // buckets i+1 .. S, walked as r = S - j
+  const int32_t bins = S - lo_bin + 1;            // buckets lo_bin .. S, walked as r = S - j
   const int32_t per = (bins + NT - 1) / NT;
   const int32_t r0 = threadIdx.x * per;
   int64_t mine = 0;
@@ -352,7 +366,7 @@ __device__ void p_threshold(const State& st, int32_t i, const int64_t* miss_coun
           c.keep = (int32_t)(R - from_res);
           // in the "never" bucket the members are exactly the dead residents, whose
           // bitmap is maintained incrementally: no marking pass is needed
-          c.use_dead = j == S;
+          c.use_dead = j == S && !st.lru;
         }
         c.T = -1;
         // evictions inside j*; those of the buckets above j* are added after the barrier
@@ -409,7 +423,7 @@ __device__ void p_mark_incoming(const State& st, const Ctrl& c, const Iter& it, 
 #pragma unroll
   for (int t = 0; t < MARK_ITEMS; ++t) {
     const int64_t p = base + t * TB + threadIdx.x;
-    if (p < it.n && it.next[p] == c.jstar) {
+    if (p < it.n && key_of(it, p) == c.jstar) {
       const uint32_t v = (uint32_t)it.ids[p];
       if (st.addr[v] < 0) atomicOr(&st.bitmap[v >> 5], 1u << (v & 31));
     }
@@ -541,7 +555,7 @@ __device__ void p_in_count(const State& st, const Ctrl& c, const Iter& it, int64
     const int64_t p = base + t;
     if (p < it.n) {
       const int32_t v = it.ids[p];
-      cnt += inserts(c, it.next[p], v) && st.addr[v] < 0;
+      cnt += inserts(c, key_of(it, p), v) && st.addr[v] < 0;
     }
   }
   const uint32_t total = block_sum_u32(cnt, red);
@@ -591,7 +605,7 @@ __device__ void p_in_emit(const State& st, const Ctrl& c, const Iter& it, const 
     const int64_t p = base + t;
     if (p < it.n) {
       const int32_t v = it.ids[p];
-      if (inserts(c, it.next[p], v) && st.addr[v] < 0) {
+      if (inserts(c, key_of(it, p), v) && st.addr[v] < 0) {
         flags |= 1u << t;
         ++cnt;
       }
@@ -606,7 +620,7 @@ __device__ void p_in_emit(const State& st, const Ctrl& c, const Iter& it, const 
       const int64_t p = base + t;
       if (at < st.max_change) {
         st.in_id[at] = it.ids[p];
-        st.in_next[at] = it.next[p];
+        st.in_next[at] = key_of(it, p);
       }
       if (dst + at < o.cs_capacity) {
         o.in_ids[dst + at] = it.ids[p];
@@ -623,7 +637,7 @@ __device__ void p_apply(const State& st, int32_t n_change, int64_t vb) {
   const int32_t line = st.out_slot[t];
   const int32_t gone = st.res_id[line];
   const int32_t v = st.in_id[t];
-  if (st.res_next[line] == st.S)   // a dead resident leaves: drop it from the standing bitmap
+  if (st.res_next[line] == st.S && !st.lru)   // a dead resident leaves the standing bitmap
     atomicAnd(&st.dead_bits[(uint32_t)gone >> 5], ~(1u << ((uint32_t)gone & 31)));
   st.res_id[line] = v;
   st.res_next[line] = st.in_next[t];
@@ -638,8 +652,8 @@ __global__ __launch_bounds__(TB) void k_touch(State st, Iter it, unsigned long l
   p_touch(st, it, miss_out, lds, blockIdx.x);
 }
 
-__global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i, Outputs o) {
-  p_threshold<BIG>(st, i, o.miss_count, o.cs_offsets);
+__global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i, int32_t lo_bin, Outputs o) {
+  p_threshold<BIG>(st, i, lo_bin, o.miss_count, o.cs_offsets);
 }
 
 // blocks [0, res_blocks) mark residents, the rest incoming rows; only one class is selected
@@ -789,14 +803,18 @@ extern "C" size_t ginex_changeset_workspace_bytes(int64_t num_nodes, int64_t tot
   return carve(nullptr, num_nodes, total_ids, S, cap, max_n).bytes;
 }
 
-extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
-                                   const int64_t* ids_offsets, int32_t S, int64_t cap,
-                                   int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
-                                   int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
-                                   int64_t* cs_offsets, int64_t* miss_count,
-                                   int64_t* total_changes, void* ws, size_t ws_bytes,
-                                   void* stream) {
-  const char* who = "ginex_changeset";
+namespace ginex {
+namespace {
+
+// Both replacement policies share every kernel: a policy only decides the key an access
+// leaves behind (Belady: its next accessed iteration; LRU: S-1-i, so that the least
+// recently used rows hold the largest keys) and the key of the prefetched rows.
+int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_t* ids,
+                      const int64_t* ids_offsets, int32_t S, int64_t cap, int32_t* init_ids,
+                      int64_t* init_count, int32_t* in_ids, int32_t* out_ids,
+                      int32_t* in_positions, int64_t cs_capacity, int64_t* cs_offsets,
+                      int64_t* miss_count, int64_t* total_changes, void* ws, size_t ws_bytes,
+                      void* stream) {
   if (!ids_offsets || !init_count || !cs_offsets || !miss_count || !total_changes || !ws)
     return fail(GINEX_ERR_ARG, "%s: a required pointer is null", who);
   if (S >= 1 && ids_offsets[0] != 0)
@@ -823,6 +841,7 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
   if ((uintptr_t)ws & 255) return fail(GINEX_ERR_ARG, "%s: workspace must be 256-byte aligned", who);
   hipStream_t st = (hipStream_t)stream;
   State& state = w.st;
+  state.lru = lru ? 1 : 0;
 
   GINEX_HIP(hipMemcpyAsync(w.d_offsets, ids_offsets, sizeof(int64_t) * (S + 1),
                            hipMemcpyHostToDevice, st));
@@ -903,10 +922,12 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
     GINEX_HIP(hipStreamSynchronize(st));
     return GINEX_OK;
   }
-  // the cache cannot hold every row: the next accessed iteration of every access is needed
-  hipLaunchKernelGGL(k_look_right, dim3((unsigned)w.look_tiles), dim3(TB), off_lds, st, sorted,
-                     total, w.d_offsets, S, w.next_iter);
-  GINEX_LAUNCH_CHECK();
+  // the cache cannot hold every row: Belady needs the next accessed iteration of every access
+  if (!lru) {
+    hipLaunchKernelGGL(k_look_right, dim3((unsigned)w.look_tiles), dim3(TB), off_lds, st, sorted,
+                       total, w.d_offsets, S, w.next_iter);
+    GINEX_LAUNCH_CHECK();
+  }
   GINEX_HIP(fill_async<int32_t>(state.addr, num_nodes, -1, st));
   GINEX_HIP(fill_async<uint32_t>(state.rhist, S + 2, 0u, st));
   GINEX_HIP(fill_async<uint32_t>(state.ihist, S + 2, 0u, st));
@@ -933,12 +954,14 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
       it.next = w.next_iter + lo;
       it.n = ids_offsets[i + 1] - lo;
       it.i = i;
+      it.key = lru ? S - 1 - i : -1;
+      it.lo_bin = lru ? S - 1 - i : i + 1;
       if (it.n > 0) {
         hipLaunchKernelGGL(k_touch, dim3((unsigned)ceil_div(it.n, TB * TOUCH_ITEMS)), dim3(TB),
                            touch_lds, st, state, it, (unsigned long long*)(miss_count + i));
         GINEX_LAUNCH_CHECK();
       }
-      hipLaunchKernelGGL(k_threshold, dim3(1), dim3(BIG), 0, st, state, i, outs);
+      hipLaunchKernelGGL(k_threshold, dim3(1), dim3(BIG), 0, st, state, i, it.lo_bin, outs);
       GINEX_LAUNCH_CHECK();
       if (it.n == 0) continue;  // nothing missed, nothing changes
       const int64_t in_tiles = ceil_div(it.n, (int64_t)TB * IN_ITEMS);
@@ -966,4 +989,31 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
     return fail(GINEX_ERR_CAPACITY, "%s: %lld changeset records, capacity %lld", who,
                 (long long)*total_changes, (long long)cs_capacity);
   return GINEX_OK;
+}
+
+}  // namespace
+}  // namespace ginex
+
+extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
+                                   const int64_t* ids_offsets, int32_t S, int64_t cap,
+                                   int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
+                                   int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
+                                   int64_t* cs_offsets, int64_t* miss_count,
+                                   int64_t* total_changes, void* ws, size_t ws_bytes,
+                                   void* stream) {
+  return changeset_run("ginex_changeset", false, num_nodes, ids, ids_offsets, S, cap, init_ids,
+                       init_count, in_ids, out_ids, in_positions, cs_capacity, cs_offsets,
+                       miss_count, total_changes, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t ginex_changeset_lru(int64_t num_nodes, const int32_t* ids,
+                                       const int64_t* ids_offsets, int32_t S, int64_t cap,
+                                       int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
+                                       int32_t* out_ids, int32_t* in_positions,
+                                       int64_t cs_capacity, int64_t* cs_offsets,
+                                       int64_t* miss_count, int64_t* total_changes, void* ws,
+                                       size_t ws_bytes, void* stream) {
+  return changeset_run("ginex_changeset_lru", true, num_nodes, ids, ids_offsets, S, cap, init_ids,
+                       init_count, in_ids, out_ids, in_positions, cs_capacity, cs_offsets,
+                       miss_count, total_changes, ws, ws_bytes, stream);
 }

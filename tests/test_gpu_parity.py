@@ -404,3 +404,56 @@ def test_executor_under_next_inspector_gathers_the_right_bytes(ginex, case2):
         del done[:]
         pipe.run_with_executor(sbs, execute, overlap=overlap)
         assert done == [0, 1, 2]
+
+
+# ---- LRU changesets through the same kernels (Section 2.3) -------------------------------
+
+def test_lru_changeset_random_small_traces(ginex):
+    rng = np.random.default_rng(31)
+    for trial in range(60):
+        n = int(rng.integers(1, 400))
+        S = int(rng.integers(1, 14))
+        cap = int(rng.integers(0, n + 2))
+        ids, off = random_trace(rng, n, S, int(rng.integers(1, 200)))
+        ref = oracle.changeset_lru(n, ids, off, cap)
+        ids_d = dev(ids) if len(ids) else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
+        res = ginex.changeset(n, ids_d, off, cap, policy="lru")
+        try:
+            check_changeset(res, ref)
+        except AssertionError:
+            print("failing trial", trial, n, S, cap, flush=True)
+            raise
+
+
+@pytest.mark.parametrize("which", ["case1", "case2"])
+def test_lru_changeset_matches_oracle_and_feeds_the_executor(ginex, which, request):
+    c = request.getfixturevalue(which)
+    ids, io = c.samp["ids"], c.samp["ids_offsets"]
+    n, S = c.cfg.num_nodes, c.cfg.S
+    distinct = len(np.unique(ids))
+    longest = int(np.diff(io).max())
+    ids_d = dev(ids)
+    sb = c.w.features.numpy().view(np.uint8).reshape(n, -1)
+    for cap in (1, 1000, c.cfg.cap, longest + 1, distinct // 2, distinct - 1, distinct):
+        ref = oracle.changeset_lru(n, ids, io, cap)
+        res = ginex.changeset(n, ids_d, io, cap, policy="lru")
+        check_changeset(res, ref)
+        bel = ginex.changeset(n, ids_d, io, cap)
+        assert bel.miss_count.sum() <= res.miss_count.sum()
+    # the executor runs an LRU changeset like any other
+    cap = max(1000, distinct // 8)
+    res = ginex.changeset(n, ids_d, io, cap, policy="lru")
+    cache = ginex.FeatureCache(c.w.features, cap)
+    cache.init(res.init_ids)
+    co = res.cs_offsets
+    for i in range(S):
+        sl = slice(co[i], co[i + 1])
+        out = cache.gather(ids_d[io[i]:io[i + 1]], None, res.in_ids[sl], res.out_ids[sl],
+                           res.in_positions[sl])
+        if i % 7 == 0 or i == S - 1:
+            got = out.cpu().numpy().view(np.uint8).reshape(out.shape[0], -1)
+            assert np.array_equal(got, sb[ids[io[i]:io[i + 1]]]), i
+    addr = cache.addr.cpu().numpy()
+    resident = np.nonzero(addr >= 0)[0]
+    rows = cache.rows.cpu().numpy().view(np.uint8).reshape(cache.rows.shape[0], -1)
+    assert np.array_equal(rows[addr[resident]], sb[resident])

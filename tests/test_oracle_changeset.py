@@ -236,3 +236,94 @@ def test_lru_helper_counts_misses_of_a_plain_lru():
     ids, off = flat(tr)
     # start empty: 1,2,3 miss; 1 hit; 4 miss (evicts 2); 2 miss (evicts 3); 1 hit
     assert oracle.lru_misses(5, ids, off, 3, np.array([], dtype=np.int32)) == 5
+
+
+# ---- LRU changesets (Section 2.3: the policy Belady's is compared with) -----------------
+
+def list_lru(cap, init, trace):
+    """A textbook LRU list for one id per iteration: front = most recently used.  The
+    prefetched rows have not been used: among them the larger id leaves first."""
+    order = sorted(init)
+    misses, states = 0, [set(order)]
+    for v in trace:
+        if v in order:
+            order.remove(v)
+        else:
+            misses += 1
+            if len(order) == cap:
+                order.pop()
+        order.insert(0, v)
+        states.append(set(order))
+    return misses, states
+
+
+def test_lru_changesets_on_a_cyclic_trace_miss_every_access_after_the_prefetch():
+    # cap rows, cap+1 ids accessed round-robin, one per iteration: after the cap prefetched
+    # rows are used once, LRU always evicts the row needed next, Belady one row per cycle
+    for cap in (1, 2, 3, 5):
+        S = 6 * (cap + 1)
+        tr = [[i % (cap + 1)] for i in range(S)]
+        ids, off = flat(tr)
+        lru = oracle.changeset_lru(cap + 1, ids, off, cap)
+        assert list(lru["init_ids"]) == list(range(cap))
+        assert list(lru["miss_count"]) == [0] * cap + [1] * (S - cap)
+        # every miss is inserted and evicts the row that is accessed next
+        assert list(lru["in_ids"]) == [i % (cap + 1) for i in range(cap, S)]
+        assert list(lru["out_ids"]) == [(i + 1) % (cap + 1) for i in range(cap, S)]
+        bel = oracle.changeset(cap + 1, ids, off, cap)
+        assert bel["miss_count"].sum() < lru["miss_count"].sum() or cap == 1
+
+
+def test_lru_changesets_equal_a_textbook_lru_list_for_single_accesses():
+    rng = np.random.default_rng(21)
+    for _ in range(300):
+        n, S, cap = int(rng.integers(1, 12)), int(rng.integers(1, 40)), int(rng.integers(1, 8))
+        trace = [int(v) for v in rng.integers(0, n, size=S)]
+        tr = [[v] for v in trace]
+        ids, off = flat(tr)
+        cs = oracle.changeset_lru(n, ids, off, cap)
+        states, total = replay(n, cap, tr, cs)
+        misses, want = list_lru(cap, [int(v) for v in cs["init_ids"]], trace)
+        assert total == misses
+        assert states == want
+
+
+def test_lru_heap_variant_equals_the_definition_and_the_miss_counter():
+    rng = np.random.default_rng(22)
+    for _ in range(300):
+        n, S, cap = int(rng.integers(1, 40)), int(rng.integers(1, 12)), int(rng.integers(0, 12))
+        tr = [[int(v) for v in x] for x in random_trace(rng, n, S, 15)]
+        ids, off = flat(tr)
+        a = oracle.changeset_lru(n, ids, off, cap)
+        b = oracle.changeset_lru_by_sorting(n, ids, off, cap)
+        for k in a:
+            assert np.array_equal(a[k], b[k]), k
+        bel = oracle.changeset(n, ids, off, cap)
+        assert np.array_equal(a["init_ids"], bel["init_ids"])        # the same prefetch
+        states, total = replay(n, cap, tr, a)
+        assert bel["miss_count"].sum() <= total                       # Belady is optimal
+        # the state after iteration i: the cap most recently used rows of union(C_i, ids_i);
+        # never-used prefetched rows are the oldest; ties: resident first, then smaller id
+        last = {int(v): -1 for v in a["init_ids"]}
+        for i, cur in enumerate(tr):
+            for v in cur:
+                last[v] = i
+            cand = sorted((-last[v], v not in states[i], v) for v in states[i] | set(cur))
+            assert {v for _, _, v in cand[:cap]} == states[i + 1]
+        # the stand-alone LRU miss counter knows no resident-before-incoming rule: the two
+        # agree whenever no iteration is longer than the cache
+        if cap > 0 and all(len(x) <= cap for x in tr):
+            assert total == oracle.lru_misses(n, ids, off, cap, a["init_ids"])
+
+
+def test_lru_on_tiny_config_sits_between_belady_and_all_miss(tiny):
+    w, r = tiny
+    n = w.cfg.num_nodes
+    tr = [r["ids"][r["ids_offsets"][i]:r["ids_offsets"][i + 1]].tolist() for i in range(w.cfg.S)]
+    for cap in (w.cfg.cap, 4 * max(len(x) for x in tr)):
+        lru = oracle.changeset_lru(n, r["ids"], r["ids_offsets"], cap)
+        _, total = replay(n, cap, tr, lru)
+        bel = oracle.changeset(n, r["ids"], r["ids_offsets"], cap)
+        assert bel["miss_count"].sum() <= total <= len(r["ids"])
+        if cap >= max(len(x) for x in tr):
+            assert total == oracle.lru_misses(n, r["ids"], r["ids_offsets"], cap, lru["init_ids"])
