@@ -4,9 +4,12 @@ superbatch size, cache size and feature dimension.  Prints markdown tables.
 
   python -m paper_2208_09151_amd.sweeps [--config 3]
 
-Only the binding is called; the static-cache column (rows of the highest out-degree nodes
-pinned, the policy the paper compares with in Section 2.3) is counted with two torch ops on
-the sampled ids, it is not part of the path.
+Only the binding is called.  The policy tables put Belady's changesets next to LRU
+changesets (ginex_changeset_lru) and a static cache of the highest out-degree rows (the two
+policies the paper compares with, Section 2.3 and Figures 2 and 5); in the first table the
+static column is counted with two torch ops on the sampled ids, in the last one all three
+run through the same executor (cache initialization, then S gathers with their changesets;
+a static cache has none) and the miss counts come from the address table.
 """
 from __future__ import annotations
 
@@ -42,6 +45,8 @@ def main():
 
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--no-executor", action="store_true",
+                    help="skip the last table (it needs the feature table in host memory)")
     args = ap.parse_args()
     w = make_workload(args.config, device="cuda", features=False)
     cfg = w.cfg
@@ -65,16 +70,20 @@ def main():
     out_degree = torch.bincount(w.indices, minlength=cfg.num_nodes)
     order = torch.argsort(out_degree, descending=True)
     print(f"## Cache size (batch {cfg.batch}, S={cfg.S}; {accesses} accesses, {distinct} distinct rows)\n")
-    print("| cache rows | % of distinct | Belady miss ratio | static out-degree miss ratio | changeset ms | G accesses/s |")
-    print("|---:|---:|---:|---:|---:|---:|")
+    print("| cache rows | % of distinct | Belady miss ratio | LRU miss ratio | static out-degree miss ratio "
+          "| Belady changeset ms | G accesses/s | LRU changeset ms |")
+    print("|---:|---:|---:|---:|---:|---:|---:|---:|")
     for pct in (1, 2, 5, 10, 20, 50, 100):
         cap = max(1, distinct * pct // 100)
         tc, cs = timed(lambda: ginex.changeset(cfg.num_nodes, samp.ids, samp.ids_offsets, cap))
+        tl, lru = timed(lambda: ginex.changeset(cfg.num_nodes, samp.ids, samp.ids_offsets, cap,
+                                                policy="lru"))
         pinned = torch.zeros(cfg.num_nodes, dtype=torch.bool, device="cuda")
         pinned[order[:cap]] = True
         static_miss = int((~pinned[samp.ids.long()]).sum())
-        print(f"| {cap} | {pct} | {cs.miss_count.sum() / accesses:.4f} | {static_miss / accesses:.4f} "
-              f"| {tc * 1e3:.2f} | {accesses / tc / 1e9:.2f} |")
+        print(f"| {cap} | {pct} | {cs.miss_count.sum() / accesses:.4f} | {lru.miss_count.sum() / accesses:.4f} "
+              f"| {static_miss / accesses:.4f} | {tc * 1e3:.2f} | {accesses / tc / 1e9:.2f} | {tl * 1e3:.2f} |")
+        del cs, lru
 
     # 2. batch size at a fixed number of seeds per superbatch
     cap = max(1, distinct // 10)
@@ -125,6 +134,53 @@ def main():
         gbps = rows_n * (8 + 2 * dim * 4) / us / 1e3
         print(f"| {dim} | {dim * 4} | {rows_n} | {us:.1f} | {gbps:.0f} | {gbps / 8000:.3f} |")
         del table, cache, out
+
+    # 5. the three policies through the same executor, features in pinned host memory
+    if args.no_executor:
+        return
+    from workload.configs import make_features
+    feats = make_features(cfg.num_nodes, cfg.feat_dim, cfg.seed, "cuda")
+    row_bytes = cfg.feat_dim * 4
+    print(f"\n## Policies through the executor (rows of {row_bytes} B in pinned host memory; "
+          f"cache initialization + {cfg.S} gathers with their changesets)\n")
+    print("| cache rows | % of distinct | policy | misses | miss ratio | init ms | gathers ms | total ms "
+          "| slow-tier GB |")
+    print("|---:|---:|---|---:|---:|---:|---:|---:|---:|")
+    io = samp.ids_offsets
+    longest = int(np.diff(io).max())
+    out = torch.empty((longest, cfg.feat_dim), dtype=torch.float32, device="cuda")
+    for pct in (5, 20, 50):
+        cap = max(1, distinct * pct // 100)
+        plans = {
+            "Belady": ginex.changeset(cfg.num_nodes, samp.ids, io, cap),
+            "LRU": ginex.changeset(cfg.num_nodes, samp.ids, io, cap, policy="lru"),
+        }
+        cache = ginex.FeatureCache(feats, cap)
+        for name in ("Belady", "LRU", "static"):
+            cs = plans.get(name)
+            init = cs.init_ids if cs is not None else order[:cap].to(torch.int32)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            cache.init(init)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            misses = torch.zeros((), dtype=torch.int64, device="cuda")
+            for i in range(cfg.S):
+                ids_i = samp.ids[io[i]:io[i + 1]]
+                if cs is None:
+                    misses += (cache.addr[ids_i.long()] < 0).sum()
+                    cache.gather(ids_i, out[:ids_i.numel()])
+                else:
+                    sl = slice(cs.cs_offsets[i], cs.cs_offsets[i + 1])
+                    cache.gather(ids_i, out[:ids_i.numel()], cs.in_ids[sl], cs.out_ids[sl],
+                                 cs.in_positions[sl])
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            m = int(cs.miss_count.sum()) if cs is not None else int(misses)
+            print(f"| {cap} | {pct} | {name} | {m} | {m / accesses:.4f} | {(t1 - t0) * 1e3:.1f} "
+                  f"| {(t2 - t1) * 1e3:.1f} | {(t2 - t0) * 1e3:.1f} "
+                  f"| {(m + init.numel()) * row_bytes / 1e9:.2f} |")
+        del cache, plans
 
 
 if __name__ == "__main__":
