@@ -77,9 +77,38 @@ def floyd_picks(seed, node, batch, hop, deg, k):
     return out[:n].copy()
 
 
+def neighbor_cache_build(offsets, indices, budget):
+    """Section 3.2: returns (address_table int64 [N], cache_array int32 [used], cached node
+    count)."""
+    offsets = np.ascontiguousarray(offsets)
+    assert offsets.dtype in (np.int32, np.int64)
+    indices = _i32(indices)
+    n = len(offsets) - 1
+    address_table = np.zeros(max(n, 1), dtype=np.int64)
+    cache_array = np.zeros(max(budget, 1), dtype=np.int32)
+    cached, used = C.c_int64(0), C.c_int64(0)
+    rc = lib().oracle_neighbor_cache_build(
+        C.c_int64(n), _p(offsets), C.c_int32(offsets.dtype == np.int64), _p(indices),
+        C.c_int64(budget), _p(address_table), _p(cache_array), C.byref(cached), C.byref(used))
+    assert rc == 0
+    return address_table[:n], cache_array[:used.value], cached.value
+
+
+def neighbor_lookup(address_table, cache_array, v):
+    """The neighbour list of ``v`` from the cache, or None on a miss (Figure 6b)."""
+    address_table, cache_array = _i64(address_table), _i32(cache_array)
+    deg = C.c_int64(0)
+    lib().oracle_neighbor_lookup.restype = C.c_int64
+    at = lib().oracle_neighbor_lookup(_p(address_table), _p(cache_array), C.c_int32(v),
+                                      C.byref(deg))
+    return None if at < 0 else cache_array[at:at + deg.value]
+
+
 def sample_superbatch(offsets, indices, seeds, seed_offsets, fanout, rng_seed=0,
-                      first_batch_index=0):
-    """Returns a dict with flat ``ids``, ``ids_offsets``, ``hop_sizes`` [S, H+1] and the
+                      first_batch_index=0, neighbor_cache=None):
+    """``neighbor_cache``: optional (address_table, cache_array); the result then also holds
+    ``lookups`` = (hits, misses).
+    Returns a dict with flat ``ids``, ``ids_offsets``, ``hop_sizes`` [S, H+1] and the
     per-(batch, hop) adjacency as flat ``adj_rowptr``/``adj_col`` with
     ``adj_row_offsets``/``adj_col_offsets`` of length S*H+1 (batch-major)."""
     offsets = np.ascontiguousarray(offsets)
@@ -107,15 +136,30 @@ def sample_superbatch(offsets, indices, seeds, seed_offsets, fanout, rng_seed=0,
     ids = np.zeros(max(caps[0], 1), dtype=np.int32)
     rowptr = np.zeros(max(caps[1], 1), dtype=np.int64)
     col = np.zeros(max(caps[2], 1), dtype=np.int32)
-    rc = lib().oracle_sample_superbatch(
-        C.c_int64(n), _p(offsets), C.c_int32(offsets.dtype == np.int64), _p(indices),
-        _p(seeds), _p(seed_offsets), C.c_int32(S), _p(fanout), C.c_int32(H),
-        C.c_uint64(rng_seed), C.c_uint32(first_batch_index),
-        _p(ids), C.c_int64(caps[0]), _p(ids_offsets), _p(hop_sizes),
-        _p(rowptr), C.c_int64(caps[1]), _p(col), C.c_int64(caps[2]),
-        _p(row_off), _p(col_off), _p(need))
+    if neighbor_cache is not None:
+        at, ca = _i64(neighbor_cache[0]), _i32(neighbor_cache[1])
+        if len(ca) == 0:
+            ca = np.zeros(1, dtype=np.int32)
+        lookups = np.zeros(2, dtype=np.int64)
+        rc = lib().oracle_sample_superbatch_cached(
+            C.c_int64(n), _p(offsets), C.c_int32(offsets.dtype == np.int64), _p(indices),
+            _p(at), _p(ca),
+            _p(seeds), _p(seed_offsets), C.c_int32(S), _p(fanout), C.c_int32(H),
+            C.c_uint64(rng_seed), C.c_uint32(first_batch_index),
+            _p(ids), C.c_int64(caps[0]), _p(ids_offsets), _p(hop_sizes),
+            _p(rowptr), C.c_int64(caps[1]), _p(col), C.c_int64(caps[2]),
+            _p(row_off), _p(col_off), _p(need), _p(lookups))
+    else:
+        lookups = None
+        rc = lib().oracle_sample_superbatch(
+            C.c_int64(n), _p(offsets), C.c_int32(offsets.dtype == np.int64), _p(indices),
+            _p(seeds), _p(seed_offsets), C.c_int32(S), _p(fanout), C.c_int32(H),
+            C.c_uint64(rng_seed), C.c_uint32(first_batch_index),
+            _p(ids), C.c_int64(caps[0]), _p(ids_offsets), _p(hop_sizes),
+            _p(rowptr), C.c_int64(caps[1]), _p(col), C.c_int64(caps[2]),
+            _p(row_off), _p(col_off), _p(need))
     assert rc == 0
-    return dict(ids=ids[:need[0]], ids_offsets=ids_offsets,
+    return dict(lookups=lookups, ids=ids[:need[0]], ids_offsets=ids_offsets,
                 hop_sizes=hop_sizes.reshape(S, H + 1),
                 adj_rowptr=rowptr[:need[1]], adj_col=col[:need[2]],
                 adj_row_offsets=row_off, adj_col_offsets=col_off)

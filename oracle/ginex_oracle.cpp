@@ -17,6 +17,9 @@
 //   changeset_lru          a textbook LRU list on single-access traces, the closed form of a
 //                          cyclic trace, the sort-based definition, the stand-alone LRU
 //                          miss counter, Belady's miss count as a lower bound
+//   neighbour cache        the layout values the paper states for its figure, an exact
+//                          rational ranking in Python, lookup == CSR row for every cached
+//                          node, sampling through the cache == sampling without it
 //   gather / cache replay  the worked ten-node example of the paper, out[p] == slow[ids[p]]
 //
 // Build: g++ -O2 -std=c++17 -shared -fPIC ginex_oracle.cpp -o libginex_oracle.so
@@ -103,7 +106,81 @@ inline int64_t off_at(const void* offsets, int offsets_64, int64_t v) {
 
 extern "C" {
 
+int64_t oracle_neighbor_lookup(const int64_t* address_table, const int32_t* cache_array,
+                               int32_t v, int64_t* degree);
+int32_t oracle_sample_superbatch_cached(
+    int64_t num_nodes, const void* offsets, int32_t offsets_64, const int32_t* indices,
+    const int64_t* address_table, const int32_t* cache_array,
+    const int32_t* seeds, const int64_t* seed_offsets, int32_t S,
+    const int32_t* fanout, int32_t H, uint64_t rng_seed, uint32_t first_batch_index,
+    int32_t* ids, int64_t ids_capacity, int64_t* ids_offsets, int64_t* hop_sizes,
+    int64_t* adj_rowptr, int64_t rowptr_capacity, int32_t* adj_col, int64_t col_capacity,
+    int64_t* adj_row_offsets, int64_t* adj_col_offsets, int64_t* need, int64_t* lookups);
+
 int32_t oracle_never(void) { return NEVER; }
+
+// ---------------------------------------------------------------------------
+// Neighbour cache (Section 3.2).
+//
+// Structure ("Neighbor Cache Structure", Figure 6a): address_table has one entry per
+// node, the index into cache_array where the node's record starts, or -1; a record is the
+// number of neighbours followed by the neighbour ids.
+//
+// Policy ("Neighbor Cache Policy"): nodes are ranked by the ratio of their number of
+// out-neighbours (how often the list is likely to be asked for) to their number of
+// in-neighbours (what the list costs to keep), larger first.  The CSR rows are the
+// in-neighbour lists, so in-degree = row length and out-degree = the number of times the
+// node occurs in `indices`.
+// Choices the paper leaves open: the ratio is compared as the integer
+// floor(out * 2^32 / in) so that no floating point decides the order; ties go to the
+// smaller id; nodes without in-neighbours are never cached (nothing to serve); records are
+// laid out in rank order from index 0; filling stops at the first node whose record does
+// not fit into the `budget` entries of cache_array.
+// ---------------------------------------------------------------------------
+int32_t oracle_neighbor_cache_build(int64_t num_nodes, const void* offsets, int32_t offsets_64,
+                                    const int32_t* indices, int64_t budget,
+                                    int64_t* address_table, int32_t* cache_array,
+                                    int64_t* cached_nodes, int64_t* used_entries) {
+  const int64_t num_edges = off_at(offsets, offsets_64, num_nodes);
+  std::vector<int64_t> out_degree(num_nodes, 0);
+  for (int64_t e = 0; e < num_edges; ++e) ++out_degree[indices[e]];
+  struct Ranked { uint64_t ratio; int32_t id; };
+  std::vector<Ranked> order;
+  for (int64_t v = 0; v < num_nodes; ++v) {
+    address_table[v] = -1;
+    const int64_t in_degree = off_at(offsets, offsets_64, v + 1) - off_at(offsets, offsets_64, v);
+    if (in_degree > 0)
+      order.push_back({((uint64_t)out_degree[v] << 32) / (uint64_t)in_degree, (int32_t)v});
+  }
+  std::sort(order.begin(), order.end(), [](const Ranked& a, const Ranked& b) {
+    if (a.ratio != b.ratio) return a.ratio > b.ratio;
+    return a.id < b.id;
+  });
+  int64_t used = 0, count = 0;
+  for (const Ranked& r : order) {
+    const int64_t lo = off_at(offsets, offsets_64, r.id);
+    const int64_t in_degree = off_at(offsets, offsets_64, r.id + 1) - lo;
+    if (used + 1 + in_degree > budget) break;
+    address_table[r.id] = used;
+    cache_array[used] = (int32_t)in_degree;
+    for (int64_t j = 0; j < in_degree; ++j) cache_array[used + 1 + j] = indices[lo + j];
+    used += 1 + in_degree;
+    ++count;
+  }
+  *cached_nodes = count;
+  *used_entries = used;
+  return 0;
+}
+
+// Lookup (Figure 6b): three reads.  Returns the index of the first neighbour inside
+// cache_array and the neighbour count, or -1 (miss).
+int64_t oracle_neighbor_lookup(const int64_t* address_table, const int32_t* cache_array,
+                               int32_t v, int64_t* degree) {
+  const int64_t at = address_table[v];   // read 1
+  if (at < 0) return -1;
+  *degree = cache_array[at];             // read 2
+  return at + 1;                         // read 3 is the caller's, from here on
+}
 
 void oracle_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) {
   philox4x32_10(ctr, key, out);
@@ -145,6 +222,26 @@ int32_t oracle_sample_superbatch(
     int32_t* ids, int64_t ids_capacity, int64_t* ids_offsets, int64_t* hop_sizes,
     int64_t* adj_rowptr, int64_t rowptr_capacity, int32_t* adj_col, int64_t col_capacity,
     int64_t* adj_row_offsets, int64_t* adj_col_offsets, int64_t* need /*[3]*/) {
+  return oracle_sample_superbatch_cached(
+      num_nodes, offsets, offsets_64, indices, nullptr, nullptr, seeds, seed_offsets, S, fanout, H,
+      rng_seed, first_batch_index, ids, ids_capacity, ids_offsets, hop_sizes, adj_rowptr,
+      rowptr_capacity, adj_col, col_capacity, adj_row_offsets, adj_col_offsets, need, nullptr);
+}
+
+// The same sampling with the neighbour lists fetched through the neighbour cache
+// (Section 3.2): a node whose list is cached is served from cache_array, any other from
+// the CSR.  address_table == nullptr means no cache.  lookups (optional, [2]) receives the
+// number of hits and misses.
+int32_t oracle_sample_superbatch_cached(
+    int64_t num_nodes, const void* offsets, int32_t offsets_64, const int32_t* indices,
+    const int64_t* address_table, const int32_t* cache_array,
+    const int32_t* seeds, const int64_t* seed_offsets, int32_t S,
+    const int32_t* fanout, int32_t H, uint64_t rng_seed, uint32_t first_batch_index,
+    int32_t* ids, int64_t ids_capacity, int64_t* ids_offsets, int64_t* hop_sizes,
+    int64_t* adj_rowptr, int64_t rowptr_capacity, int32_t* adj_col, int64_t col_capacity,
+    int64_t* adj_row_offsets, int64_t* adj_col_offsets, int64_t* need /*[3]*/,
+    int64_t* lookups /*[2] or null*/) {
+  int64_t hits = 0, misses = 0;
   std::vector<int32_t> local(num_nodes, -1);
   std::vector<int32_t> list;
   std::vector<int64_t> picks(64);
@@ -172,12 +269,23 @@ int32_t oracle_sample_superbatch(
         if (n_row < rowptr_capacity) adj_rowptr[n_row] = n_col - col_base; else fits = false;
         ++n_row;
         const int32_t v = list[r];
-        const int64_t lo = off_at(offsets, offsets_64, v);
-        const int64_t deg = off_at(offsets, offsets_64, v + 1) - lo;
+        int64_t deg;
+        const int32_t* row;
+        const int64_t at = address_table ? oracle_neighbor_lookup(address_table, cache_array, v, &deg)
+                                         : -1;
+        if (at >= 0) {
+          row = cache_array + at;
+          ++hits;
+        } else {
+          const int64_t lo = off_at(offsets, offsets_64, v);
+          deg = off_at(offsets, offsets_64, v + 1) - lo;
+          row = indices + lo;
+          ++misses;
+        }
         const int cnt = floyd_picks(rng_seed, (uint32_t)v, first_batch_index + (uint32_t)b,
                                     (uint32_t)h, deg, k, picks.data());
         for (int t = 0; t < cnt; ++t) {
-          const int32_t u = indices[lo + picks[t]];
+          const int32_t u = row[picks[t]];
           if (local[u] < 0) {
             local[u] = (int32_t)list.size();
             list.push_back(u);
@@ -200,6 +308,7 @@ int32_t oracle_sample_superbatch(
     ids_offsets[b + 1] = n_ids;
   }
   need[0] = n_ids; need[1] = n_row; need[2] = n_col;
+  if (lookups) { lookups[0] = hits; lookups[1] = misses; }
   return fits ? 0 : -1;
 }
 
