@@ -53,6 +53,12 @@ typedef struct ginex_csr {
   const void* offsets;     /* [num_nodes+1], int32 if offsets_64 == 0, else int64 */
   int32_t offsets_64;
   const int32_t* indices;  /* [num_edges] */
+  /* Optional neighbour cache (Section 3.2), both NULL or both set: built by
+   * ginex_neighbor_cache_build over this same graph.  The sampler then serves the rows of
+   * cached nodes from nc_cache_array (HBM) and only the others from offsets/indices, which
+   * may then live in host-pinned memory.  The sampled result does not depend on it. */
+  const int64_t* nc_address_table; /* device [num_nodes] */
+  const int32_t* nc_cache_array;   /* device */
 } ginex_csr_t;
 
 /* ---------------------------------------------------------------------------------
@@ -100,6 +106,27 @@ int32_t ginex_sample_superbatch(
     int64_t* adj_row_offsets /*host [S*H+1]*/, int64_t* adj_col_offsets /*host [S*H+1]*/,
     int64_t* totals /*host [3]*/,
     void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------
+ * Neighbour cache construction (Section 3.2 "Neighbor Cache Policy" and "Neighbor Cache
+ * Structure").  Ranks the nodes by out-degree / in-degree, larger first (in-degree = length
+ * of the node's CSR row, out-degree = number of times the node occurs in `indices`; the
+ * ratio is compared as the integer floor(out * 2^32 / in), ties go to the smaller id, nodes
+ * with an empty row are never cached) and stores the rows of the best-ranked nodes back to
+ * back from index 0 of cache_array, each as a record (neighbour count, neighbour ids),
+ * stopping at the first node whose record does not fit into `budget` entries.
+ *   address_table (device, [num_nodes]): index of the node's record in cache_array, or -1
+ *   cache_array   (device, [budget])
+ *   cached_nodes, used_entries (host): number of records and of cache_array entries used
+ * g->offsets and g->indices may be device or host-pinned memory; g's nc_* fields are
+ * ignored.  The call waits for the stream before it returns.
+ * ------------------------------------------------------------------------------- */
+size_t ginex_neighbor_cache_workspace_bytes(int64_t num_nodes);
+
+int32_t ginex_neighbor_cache_build(const ginex_csr_t* g /*host struct*/, int64_t budget,
+                                   int64_t* address_table, int32_t* cache_array,
+                                   int64_t* cached_nodes /*host*/, int64_t* used_entries /*host*/,
+                                   void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------
  * Changeset precomputation (Section 3.4; lists of Section 3.3 "Feature Cache Update").

@@ -6,5 +6,6 @@ path runs in the library's kernels.  PyTorch supplies device memory and streams.
 There is no CPU fallback: without the built library, or without a GPU, calls raise.
 """
 from .api import (GinexError, FeatureCache, SampleResult, ChangesetResult,  # noqa: F401
-                  sample_superbatch, changeset, library_path, version)
+                  NeighborCache, neighbor_cache_build, sample_superbatch, changeset,
+                  library_path, version)
 from .pipeline import InspectorPipeline  # noqa: F401

@@ -12,7 +12,7 @@ i32, i64, u32, u64, vp, sz = C.c_int32, C.c_int64, C.c_uint32, C.c_uint64, C.c_v
 
 class CsrDesc(C.Structure):
     _fields_ = [("num_nodes", i64), ("num_edges", i64), ("offsets", vp), ("offsets_64", i32),
-                ("indices", vp)]
+                ("indices", vp), ("nc_address_table", vp), ("nc_cache_array", vp)]
 
 
 class CacheDesc(C.Structure):
@@ -26,6 +26,8 @@ SIGNATURES = {
     "ginex_sample_workspace_bytes": (sz, [i64, i32, i64, vp, i32]),
     "ginex_sample_superbatch": (i32, [C.POINTER(CsrDesc), vp, vp, i32, vp, i32, u64, u32,
                                       vp, i64, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, sz, vp]),
+    "ginex_neighbor_cache_workspace_bytes": (sz, [i64]),
+    "ginex_neighbor_cache_build": (i32, [C.POINTER(CsrDesc), i64, vp, vp, vp, vp, vp, sz, vp]),
     "ginex_changeset_workspace_bytes": (sz, [i64, i64, i32, i64]),
     "ginex_changeset": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp,
                               sz, vp]),

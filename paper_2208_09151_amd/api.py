@@ -40,6 +40,17 @@ def _dev(t: torch.Tensor, dtype=None) -> torch.Tensor:
     return t
 
 
+def _readable(t: torch.Tensor, dtype=None) -> torch.Tensor:
+    """Memory the GPU can read: device memory or pinned host memory."""
+    if not (t.is_cuda or t.is_pinned()):
+        raise ValueError("expected a tensor in GPU memory or in pinned host memory")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError("expected a contiguous tensor")
+    return t
+
+
 def _ptr(t):
     return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
 
@@ -87,14 +98,49 @@ def sample_capacity(num_nodes, seed_offsets, fanout):
     return ids, rows, cols
 
 
-def sample_superbatch(offsets, indices, seeds, seed_offsets, fanout, rng_seed=0,
-                      first_batch_index=0, with_adj=True, workspace=None, out=None):
-    """ginex_sample_superbatch.  ``offsets``/``indices``/``seeds`` are device tensors,
-    ``seed_offsets`` and ``fanout`` host sequences.  ``out`` may carry preallocated
-    (ids, adj_rowptr, adj_col) device tensors to reuse."""
+@dataclass
+class NeighborCache:
+    address_table: torch.Tensor     # int64 [num_nodes], device
+    cache_array: torch.Tensor       # int32 [budget], device
+    cached_nodes: int
+    used_entries: int
+
+
+def neighbor_cache_build(offsets, indices, budget, device="cuda"):
+    """ginex_neighbor_cache_build.  ``offsets``/``indices`` in device or pinned host memory;
+    ``budget`` = entries of the cache array."""
     lib = _lib.load()
-    _dev(offsets)
-    _dev(indices, torch.int32)
+    _readable(offsets)
+    _readable(indices, torch.int32)
+    if offsets.dtype not in (torch.int32, torch.int64):
+        raise ValueError("offsets must be int32 or int64")
+    n = offsets.numel() - 1
+    need = lib.ginex_neighbor_cache_workspace_bytes(n)
+    if need == 0:
+        raise GinexError(-1, lib.ginex_last_error().decode())
+    ws = torch.empty(need, dtype=torch.uint8, device=device)
+    address_table = torch.empty(n, dtype=torch.int64, device=device)
+    cache_array = torch.empty(max(budget, 1), dtype=torch.int32, device=device)
+    cached = np.zeros(1, dtype=np.int64)
+    used = np.zeros(1, dtype=np.int64)
+    g = CsrDesc(n, indices.numel(), offsets.data_ptr(), int(offsets.dtype == torch.int64),
+                indices.data_ptr(), None, None)
+    _check(lib.ginex_neighbor_cache_build(C.byref(g), budget, _ptr(address_table),
+                                          _ptr(cache_array), _np_ptr(cached), _np_ptr(used),
+                                          _ptr(ws), ws.numel(), _stream()))
+    return NeighborCache(address_table, cache_array, int(cached[0]), int(used[0]))
+
+
+def sample_superbatch(offsets, indices, seeds, seed_offsets, fanout, rng_seed=0,
+                      first_batch_index=0, with_adj=True, workspace=None, out=None,
+                      neighbor_cache=None):
+    """ginex_sample_superbatch.  ``seeds`` is a device tensor, ``offsets``/``indices`` device
+    tensors or, for a graph that does not fit into HBM, pinned host tensors (then a
+    ``neighbor_cache`` keeps the hot rows in HBM); ``seed_offsets`` and ``fanout`` are host
+    sequences.  ``out`` may carry preallocated (ids, adj_rowptr, adj_col) device tensors."""
+    lib = _lib.load()
+    _readable(offsets)
+    _readable(indices, torch.int32)
     _dev(seeds, torch.int32)
     if offsets.dtype not in (torch.int32, torch.int64):
         raise ValueError("offsets must be int32 or int64")
@@ -102,7 +148,7 @@ def sample_superbatch(offsets, indices, seeds, seed_offsets, fanout, rng_seed=0,
     fo = np.ascontiguousarray(np.asarray(fanout), dtype=np.int32)
     S, H = len(so) - 1, len(fo)
     n = offsets.numel() - 1
-    dev = offsets.device
+    dev = seeds.device
     max_batch = int(np.max(np.diff(so))) if S > 0 else 0
     need = lib.ginex_sample_workspace_bytes(n, S, max_batch, _np_ptr(fo), H)
     if need == 0:
@@ -120,8 +166,10 @@ def sample_superbatch(offsets, indices, seeds, seed_offsets, fanout, rng_seed=0,
     row_off = np.zeros(S * H + 1, dtype=np.int64)
     col_off = np.zeros(S * H + 1, dtype=np.int64)
     totals = np.zeros(3, dtype=np.int64)
+    nc = neighbor_cache
     g = CsrDesc(n, indices.numel(), offsets.data_ptr(), int(offsets.dtype == torch.int64),
-                indices.data_ptr())
+                indices.data_ptr(), nc.address_table.data_ptr() if nc else None,
+                nc.cache_array.data_ptr() if nc else None)
     rc = lib.ginex_sample_superbatch(
         C.byref(g), _ptr(seeds), _np_ptr(so), S, _np_ptr(fo), H, rng_seed, first_batch_index,
         _ptr(ids), ids.numel(), _np_ptr(ids_offsets), _np_ptr(hop_sizes),

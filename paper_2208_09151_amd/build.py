@@ -16,7 +16,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libginex.so")
 CALIB = os.path.join(PKG, "calib_copy")
-SOURCES = ["core.cpp", "gather.hip", "sampler.hip", "changeset.hip"]
+SOURCES = ["core.cpp", "gather.hip", "sampler.hip", "changeset.hip", "neighbor_cache.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -89,7 +89,7 @@ constexpr int RS_ITEMS = 16;                    // keys per thread
 constexpr int RS_TILE = RS_THREADS * RS_ITEMS;  // 4096 keys, 32 KB of LDS staging
 constexpr int RS_BINS = 256;
 
-__global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t* __restrict__ in,
+static __global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t* __restrict__ in,
                                                            int64_t n, int shift, int64_t tiles,
                                                            uint32_t* __restrict__ hist) {
   __shared__ uint32_t bins[RS_BINS];
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t* __res
   hist[(int64_t)threadIdx.x * tiles + blockIdx.x] = bins[threadIdx.x];
 }
 
-__global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
+static __global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
     const uint64_t* __restrict__ in, uint64_t* __restrict__ out, int64_t n, int shift,
     int64_t tiles, const uint32_t* __restrict__ hist_scanned) {
   __shared__ uint64_t staged[RS_TILE];

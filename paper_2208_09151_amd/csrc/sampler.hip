@@ -183,9 +183,14 @@ __global__ __launch_bounds__(TB) void k_seed_stage(Tables T, const int32_t* __re
   T.cnt[b * T.fr_slots + j] = 1;
 }
 
-template <int G, typename OffT>
+// NC: neighbour lists are looked up in the neighbour cache first (Section 3.2: address
+// table, then the count in front of the record, then the neighbours); a miss falls back to
+// the CSR, which then may sit in host memory.
+template <int G, typename OffT, bool NC>
 __global__ __launch_bounds__(TB) void k_pick(Tables T, const OffT* __restrict__ offsets,
                                              const int32_t* __restrict__ indices,
+                                             const int64_t* __restrict__ nc_address_table,
+                                             const int32_t* __restrict__ nc_cache_array,
                                              const int32_t* __restrict__ nfront, int k, int hop,
                                              uint64_t seed, uint32_t first_batch, int S,
                                              int64_t tpb) {
@@ -198,9 +203,18 @@ __global__ __launch_bounds__(TB) void k_pick(Tables T, const OffT* __restrict__ 
   const bool active = idx < nfront[b];
   const uint32_t v = active ? (uint32_t)T.wlist[b * T.stride_ids + idx] : 0u;
   int64_t lo = 0, deg = 0;
+  const int32_t* row = indices;
   if (active) {
-    lo = (int64_t)offsets[v];
-    deg = (int64_t)offsets[v + 1] - lo;
+    int64_t at = -1;
+    if (NC) at = nc_address_table[v];
+    if (at >= 0) {
+      deg = nc_cache_array[at];
+      row = nc_cache_array;
+      lo = at + 1;
+    } else {
+      lo = (int64_t)offsets[v];
+      deg = (int64_t)offsets[v + 1] - lo;
+    }
   }
   const int c = deg < k ? (int)deg : k;
   int64_t pick = sub;   // row position taken by this lane
@@ -228,7 +242,7 @@ __global__ __launch_bounds__(TB) void k_pick(Tables T, const OffT* __restrict__ 
     }
   }
   if (active && sub < c) {
-    const uint32_t u = (uint32_t)indices[lo + pick];
+    const uint32_t u = (uint32_t)row[lo + pick];
     const int64_t at = b * T.cand_slots + idx * k + slot;
     uint64_t* t = T.tab + T.tab_off[b];
     T.cand[at] = (int32_t)u;
@@ -558,24 +572,26 @@ int32_t check_shape(int64_t num_nodes, int32_t S, int64_t max_batch, const int32
   return GINEX_OK;
 }
 
-template <typename OffT>
-void launch_pick(const Tables& T, const Plan& p, const void* offsets, const int32_t* indices,
-                 const int32_t* nfront, int k, int hop, int32_t S, uint64_t seed,
-                 uint32_t first_batch, hipStream_t st) {
-  const OffT* off = static_cast<const OffT*>(offsets);
+template <typename OffT, bool NC>
+void launch_pick(const Tables& T, const Plan& p, const ginex_csr_t* g, const int32_t* nfront, int k,
+                 int hop, int32_t S, uint64_t seed, uint32_t first_batch, hipStream_t st) {
+  const OffT* off = static_cast<const OffT*>(g->offsets);
   const int64_t front = p.stride_front[hop];
   if (k <= 16) {
     const int64_t tpb = ceil_div(front, TB / 16);
-    hipLaunchKernelGGL((k_pick<16, OffT>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
-                       indices, nfront, k, hop, seed, first_batch, S, tpb);
+    hipLaunchKernelGGL((k_pick<16, OffT, NC>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
+                       g->indices, g->nc_address_table, g->nc_cache_array, nfront, k, hop, seed,
+                       first_batch, S, tpb);
   } else if (k <= 32) {
     const int64_t tpb = ceil_div(front, TB / 32);
-    hipLaunchKernelGGL((k_pick<32, OffT>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
-                       indices, nfront, k, hop, seed, first_batch, S, tpb);
+    hipLaunchKernelGGL((k_pick<32, OffT, NC>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
+                       g->indices, g->nc_address_table, g->nc_cache_array, nfront, k, hop, seed,
+                       first_batch, S, tpb);
   } else {
     const int64_t tpb = ceil_div(front, TB / 64);
-    hipLaunchKernelGGL((k_pick<64, OffT>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
-                       indices, nfront, k, hop, seed, first_batch, S, tpb);
+    hipLaunchKernelGGL((k_pick<64, OffT, NC>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
+                       g->indices, g->nc_address_table, g->nc_cache_array, nfront, k, hop, seed,
+                       first_batch, S, tpb);
   }
 }
 
@@ -605,6 +621,9 @@ extern "C" int32_t ginex_sample_superbatch(
   const char* who = "ginex_sample_superbatch";
   if (!g || !g->offsets || (g->num_edges > 0 && !g->indices))
     return fail(GINEX_ERR_ARG, "%s: graph descriptor or its arrays are null", who);
+  if ((g->nc_address_table == nullptr) != (g->nc_cache_array == nullptr))
+    return fail(GINEX_ERR_ARG, "%s: neighbour cache needs both its address table and its array",
+                who);
   if (!seed_offsets || !ids_offsets || !hop_sizes || !adj_row_offsets || !adj_col_offsets ||
       !totals || !ws)
     return fail(GINEX_ERR_ARG, "%s: a required pointer is null", who);
@@ -685,12 +704,15 @@ extern "C" int32_t ginex_sample_superbatch(
     if (stage < 0) {
       hipLaunchKernelGGL(k_seed_stage, grid_slots, dim3(TB), 0, st, T, seeds, w.seed_off, nfront, S,
                          tpb);
+    } else if (g->nc_address_table) {
+      if (g->offsets_64)
+        launch_pick<int64_t, true>(T, p, g, nfront, k, stage, S, rng_seed, first_batch_index, st);
+      else
+        launch_pick<int32_t, true>(T, p, g, nfront, k, stage, S, rng_seed, first_batch_index, st);
     } else if (g->offsets_64) {
-      launch_pick<int64_t>(T, p, g->offsets, g->indices, nfront, k, stage, S, rng_seed,
-                           first_batch_index, st);
+      launch_pick<int64_t, false>(T, p, g, nfront, k, stage, S, rng_seed, first_batch_index, st);
     } else {
-      launch_pick<int32_t>(T, p, g->offsets, g->indices, nfront, k, stage, S, rng_seed,
-                           first_batch_index, st);
+      launch_pick<int32_t, false>(T, p, g, nfront, k, stage, S, rng_seed, first_batch_index, st);
     }
     GINEX_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_count, grid_slots, dim3(TB), 0, st, T, nfront, k, w.tile_sums, p.tiles, S,

@@ -457,3 +457,52 @@ def test_lru_changeset_matches_oracle_and_feeds_the_executor(ginex, which, reque
     resident = np.nonzero(addr >= 0)[0]
     rows = cache.rows.cpu().numpy().view(np.uint8).reshape(cache.rows.shape[0], -1)
     assert np.array_equal(rows[addr[resident]], sb[resident])
+
+
+# ---- neighbour cache (Section 3.2) ----------------------------------------------------------
+
+def check_neighbor_cache(nc, ref):
+    at, ca, cached = ref
+    assert nc.cached_nodes == cached and nc.used_entries == len(ca)
+    assert np.array_equal(nc.address_table.cpu().numpy(), at)
+    assert np.array_equal(nc.cache_array[:nc.used_entries].cpu().numpy(), ca)
+
+
+@pytest.mark.parametrize("offsets_64", [False, True])
+def test_neighbor_cache_build_matches_oracle_on_small_graphs(ginex, offsets_64):
+    rng = np.random.default_rng(41 + offsets_64)
+    for trial in range(12):
+        n = int(rng.integers(1, 3000))
+        e = int(rng.integers(0, 30000))
+        off, ind = small_graph(n, e, seed=trial, offsets_64=offsets_64)
+        e = int(off[-1])
+        for budget in (0, 1, int(rng.integers(0, e + n + 1)), e + n):
+            ref = oracle.neighbor_cache_build(off.numpy(), ind.numpy(), budget)
+            ind_d = ind.cuda() if e else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
+            nc = ginex.neighbor_cache_build(off.cuda(), ind_d, budget)
+            try:
+                check_neighbor_cache(nc, ref)
+            except AssertionError:
+                print("failing case", trial, n, e, budget, flush=True)
+                raise
+
+
+@pytest.mark.parametrize("which", ["case1", "case2"])
+def test_neighbor_cache_is_transparent_to_the_sampler(ginex, which, request):
+    c = request.getfixturevalue(which)
+    E = len(c.ind)
+    S, H = c.cfg.S, len(c.cfg.fanout)
+    # the graph as the neighbour cache is meant to see it: indices in pinned host memory
+    ind_host = torch.from_numpy(c.ind).pin_memory()
+    for budget in (E // 50, E // 4, E + c.cfg.num_nodes):
+        ref = oracle.neighbor_cache_build(c.off, c.ind, budget)
+        nc = ginex.neighbor_cache_build(c.w.offsets, ind_host, budget)
+        check_neighbor_cache(nc, ref)
+        for indices in (c.w.indices, ind_host):
+            res = ginex.sample_superbatch(c.w.offsets, indices, c.w.seeds.cuda(),
+                                          c.seed_off, c.cfg.fanout, rng_seed=0, neighbor_cache=nc)
+            check_sample(res, c.samp, S, H)
+    # without a cache the sampler reads a host-resident CSR just as well
+    res = ginex.sample_superbatch(c.w.offsets, ind_host, c.w.seeds.cuda(), c.seed_off,
+                                  c.cfg.fanout, rng_seed=0)
+    check_sample(res, c.samp, S, H)

@@ -18,7 +18,7 @@ def test_every_declared_symbol_is_exported_and_bound():
     from paper_2208_09151_amd import _lib
     lib = _lib.load()
     names = declared_symbols()
-    assert len(names) == 10
+    assert len(names) == 12
     assert sorted(_lib.SIGNATURES) == names
     for n in names:
         assert getattr(lib, n) is not None
@@ -60,7 +60,7 @@ def test_precondition_and_workspace_errors_are_reported_before_any_launch():
     so = np.array([0, 5, 12], dtype=np.int64)
     host = lambda n: np.zeros(n, dtype=np.int64)
     ids_off, hops, ro, co, tot = host(3), host(6), host(5), host(5), host(3)
-    g = _lib.CsrDesc(100, 1000, 0x1000, 0, 0x1000)
+    g = _lib.CsrDesc(100, 1000, 0x1000, 0, 0x1000, None, None)
     P = lambda a: ctypes.c_void_p(a.ctypes.data)
 
     def sample(seed_offsets=so, S=2, ws_bytes=16, fanout=fan, ws=fake):
