@@ -68,6 +68,7 @@ class Runner:
                          torch.empty(cr, dtype=torch.int64, device="cuda"),
                          torch.empty(cc, dtype=torch.int32, device="cuda"))
         self.cache = ginex.FeatureCache(w.features, cfg.cap)
+        self.executor = ginex.Executor(self.cache)
         self.batch_input = None
         self.last = None
         # event pairs around every gather launch, created once: the executor loop must
@@ -75,7 +76,7 @@ class Runner:
         ev = torch.cuda.Event
         self.pairs = [(ev(enable_timing=True), ev(enable_timing=True)) for _ in range(self.S)]
 
-    def step(self, timers=None, events=None):
+    def step(self, timers=None, events=None, streamed=False):
         g, cfg = self.g, self.cfg
         t0 = time.perf_counter()
         samp = g.sample_superbatch(self.w.offsets, self.w.indices, self.seeds, self.seed_off,
@@ -88,39 +89,25 @@ class Runner:
         if self.batch_input is None or self.batch_input.shape[0] < max_n:
             self.batch_input = torch.empty((max_n, cfg.feat_dim), dtype=torch.float32, device="cuda")
         ev = torch.cuda.Event
-        e_init0, e_init1, e_end = ev(enable_timing=True), ev(enable_timing=True), ev(enable_timing=True)
-        e_init0.record()
-        self.cache.init(cs.init_ids)
-        e_init1.record()
-        # the executor loop on raw addresses: per iteration one ginex_gather (one kernel) and,
-        # when the changeset is not empty, one ginex_cache_update
-        stream = torch.cuda.current_stream().cuda_stream
-        ids_base, out_ptr = samp.ids.data_ptr(), self.batch_input.data_ptr()
-        in_base, oid_base, pos_base = (cs.in_ids.data_ptr(), cs.out_ids.data_ptr(),
-                                       cs.in_positions.data_ptr())
-        gather, update = self.cache.gather_raw, self.cache.update_raw
-        los, cos = io.tolist(), co.tolist()
+        e_init0, e_end = ev(enable_timing=True), ev(enable_timing=True)
+        # the executor: cache initialization in pieces on a second stream and, per iteration,
+        # one ginex_gather (one kernel) as soon as the rows it can touch are loaded, then
+        # one ginex_cache_update when the changeset is not empty
         pairs = self.pairs if events is not None else None
-        for i in range(self.S):
-            lo, c0 = los[i], cos[i]
-            nc = cos[i + 1] - c0
-            if pairs is not None:
-                a, b = pairs[i]
-                a.record()
-                gather(ids_base + 4 * lo, los[i + 1] - lo, out_ptr, stream)
-                b.record()
-            else:
-                gather(ids_base + 4 * lo, los[i + 1] - lo, out_ptr, stream)
-            if nc:
-                update(out_ptr, in_base + 4 * c0, oid_base + 4 * c0, pos_base + 4 * c0, nc, stream)
+        before = (lambda i: pairs[i][0].record()) if pairs is not None else None
+        after = (lambda i, n: pairs[i][1].record()) if pairs is not None else None
+        e_init0.record()
+        fill_end = self.executor.run(samp, cs, self.batch_input, streamed=streamed,
+                                     before_gather=before, after_gather=after)
         e_end.record()
         torch.cuda.synchronize()
         t3 = time.perf_counter()
         if timers is not None:
             timers["sample_s"].append(t1 - t0)
             timers["changeset_s"].append(t2 - t1)
-            timers["cache_init_s"].append(e_init0.elapsed_time(e_init1) / 1e3)
-            timers["gather_update_s"].append(e_init1.elapsed_time(e_end) / 1e3)
+            timers["cache_init_s"].append(e_init0.elapsed_time(fill_end) / 1e3)
+            timers["gather_update_s"].append(fill_end.elapsed_time(e_end) / 1e3)
+            timers["executor_s"].append(e_init0.elapsed_time(e_end) / 1e3)
             timers["executor_wall_s"].append(t3 - t2)
         if events is not None:
             events.extend(a.elapsed_time(b) for a, b in self.pairs)
@@ -239,28 +226,82 @@ def pipeline_leg(ginex, w, K):
                               dtype=torch.float32, device="cuda")
     edges = [0]
 
+    executor = ginex.Executor(cache)
+    streamed = [True]
+
     def execute(k, samp, cs):
-        io, co = samp.ids_offsets.tolist(), cs.cs_offsets.tolist()
-        stream = torch.cuda.current_stream().cuda_stream
-        cache.init(cs.init_ids)
-        ids_base, out_ptr = samp.ids.data_ptr(), batch_input.data_ptr()
-        bases = (cs.in_ids.data_ptr(), cs.out_ids.data_ptr(), cs.in_positions.data_ptr())
-        for i in range(len(io) - 1):
-            cache.gather_raw(ids_base + 4 * io[i], io[i + 1] - io[i], out_ptr, stream)
-            nc = co[i + 1] - co[i]
-            if nc:
-                cache.update_raw(out_ptr, bases[0] + 4 * co[i], bases[1] + 4 * co[i],
-                                 bases[2] + 4 * co[i], nc, stream)
+        executor.run(samp, cs, batch_input, streamed=streamed[0])
         torch.cuda.current_stream().synchronize()
         edges[0] += int(samp.totals[2])
 
-    for overlap in (False, True):
+    for key, overlap, st in (("whole_path_stage_by_stage", False, False),
+                             ("whole_path_sequential", False, True),
+                             ("whole_path_overlapped", True, True)):
+        streamed[0] = st
         pipe.run_with_executor(sbs[:2], execute, overlap=overlap)      # warm-up
         edges[0] = 0
         t = pipe.run_with_executor(sbs, execute, overlap=overlap)
-        key = "whole_path_overlapped" if overlap else "whole_path_sequential"
         out[key + "_ms_per_superbatch"] = t * 1e3 / K
         out[key + "_edges_per_s"] = edges[0] / t
+    return out
+
+
+def neighbor_cache_leg(ginex, w, samp, run):
+    """Sampling with the adjacency lists outside HBM (Section 3.2): `indices` in pinned host
+    memory, first without, then with a neighbour cache of a fraction of the edges in HBM.
+    The sampled result is the same in every row (checked against the all-in-HBM ids)."""
+    cfg = w.cfg
+    E = w.indices.numel()
+    # this leg runs last and needs no features: hand their pinned memory back first
+    run.cache = run.batch_input = run.ws = None
+    w.features = None
+    import gc
+    gc.collect()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()
+    ind_host = torch.empty(E, dtype=torch.int32, pin_memory=True)
+    ind_host.copy_(w.indices)
+    seeds, so = w.seeds.cuda(), w.seed_offsets.numpy()
+
+    def timed_sample(indices, nc):
+        best, res = None, None
+        for _ in range(3):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            res = ginex.sample_superbatch(w.offsets, indices, seeds, so, cfg.fanout, rng_seed=0,
+                                          neighbor_cache=nc)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t
+            best = dt if best is None else min(best, dt)
+        assert torch.equal(res.ids, samp.ids)
+        return best
+
+    io, hs = samp.ids_offsets, samp.hop_sizes
+    ends = (io[:-1, None] + hs[:, :-1]).reshape(-1)         # one row fetch per frontier node
+    starts = np.repeat(io[:-1], hs.shape[1] - 1)
+    lookups = int((ends - starts).sum())
+    edges = int(samp.totals[2])
+    out = {"edges_in_graph": E, "row_lookups": lookups,
+           "all_in_hbm_ms": timed_sample(w.indices, None) * 1e3,
+           "host_csr_no_cache_ms": timed_sample(ind_host, None) * 1e3, "caches": []}
+    for frac in (0.05, 0.2, 0.5):
+        budget = int(E * frac)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        nc = ginex.neighbor_cache_build(w.offsets, ind_host, budget)
+        torch.cuda.synchronize()
+        build_s = time.perf_counter() - t
+        cached = torch.cumsum((nc.address_table[samp.ids.long()] >= 0).to(torch.int64), 0)
+        cached = torch.cat([cached.new_zeros(1), cached]).cpu().numpy()
+        hits = int((cached[ends] - cached[starts]).sum())
+        ms = timed_sample(ind_host, nc) * 1e3
+        out["caches"].append({"budget_entries": budget, "fraction_of_edges": frac,
+                              "cached_nodes": nc.cached_nodes, "used_entries": nc.used_entries,
+                              "build_ms": build_s * 1e3, "hit_ratio": hits / max(lookups, 1),
+                              "sample_ms": ms, "sample_edges_per_s": edges / (ms * 1e-3)})
+        del nc, cached
     return out
 
 
@@ -278,6 +319,12 @@ def main():
     ap.add_argument("--pressure", type=int, default=0, metavar="D",
                     help="also run changesets and the executor with a cache of distinct/D rows "
                          "(configurations 3 and 4 never miss with their own cache size)")
+    ap.add_argument("--streamed-init", action="store_true",
+                    help="also time the step with the main loop started under the cache "
+                         "initialization (Executor(streamed=True))")
+    ap.add_argument("--neighbor-cache", action="store_true",
+                    help="also sample with the adjacency lists in pinned host memory, without and "
+                         "with a neighbour cache in HBM")
     ap.add_argument("--allhit", action="store_true",
                     help="also time the gather kernel with the whole feature table in HBM")
     args = ap.parse_args()
@@ -306,7 +353,7 @@ def main():
         run.step()
         log(f"warmup step {i}: {time.perf_counter() - t:.3f}s")
     timers = {k: [] for k in ("sample_s", "changeset_s", "cache_init_s", "gather_update_s",
-                              "executor_wall_s")}
+                              "executor_s", "executor_wall_s")}
     gather_ms = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -346,10 +393,31 @@ def main():
         "changeset_ms": mean["changeset_s"] * 1e3,
         "cache_init_ms": mean["cache_init_s"] * 1e3,
         "cache_init_GBps": len(cs.init_ids) * row_bytes / mean["cache_init_s"] / 1e9,
-        "gather_update_ms": mean["gather_update_s"] * 1e3,
+        "gather_update_ms": mean["gather_update_s"] * 1e3,   # what is left after the fill ends
+        "executor_ms": mean["executor_s"] * 1e3,
         "gather_mix_GBps": roof["achieved"],
         "sampled_edges": edges, "accesses": accesses, "misses": misses, "changes": changes,
     }
+
+    # The timed steps run the executor stage by stage, as the paper does (the whole cache
+    # initialization in front of the main loop), which also times the gather kernel by
+    # itself.  The same step with the main loop started under the initialization:
+    if args.streamed_init:
+        run.step(streamed=True)
+        st = {k: [] for k in timers}
+        gather_streamed = []
+        t = time.perf_counter()
+        for _ in range(args.steps):
+            run.step(st, gather_streamed, streamed=True)
+        torch.cuda.synchronize()
+        streamed_step_s = (time.perf_counter() - t) / args.steps
+        stages["streamed_init"] = {
+            "ms_per_step": streamed_step_s * 1e3, "edges_per_s": edges / streamed_step_s,
+            "cache_init_ms": float(np.mean(st["cache_init_s"])) * 1e3,
+            "executor_ms": float(np.mean(st["executor_s"])) * 1e3,
+            "after_init_ms": float(np.mean(st["gather_update_s"])) * 1e3,
+            "gather_avg_launch_ms_beside_the_fill": float(np.mean(gather_streamed)),
+        }
 
     if args.allhit:
         # the same kernel on the same ids with every row in HBM (pure HBM number)
@@ -402,6 +470,8 @@ def main():
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_batches)
     else:
         result["cpu_baseline"] = None
+    if args.neighbor_cache:     # last: it gives the feature table's pinned memory back
+        stages["neighbor_cache"] = neighbor_cache_leg(ginex, w, samp, run)
     print(json.dumps(result), flush=True)
 
 

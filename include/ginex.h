@@ -141,6 +141,11 @@ int32_t ginex_neighbor_cache_build(const ginex_csr_t* g /*host struct*/, int64_t
  *   miss_count[i] = |ids_i \ C_i|.
  * init_count and total_changes are host outputs.  cs_capacity >= total_changes is
  * required (ids_offsets[S] always suffices).
+ * init_ready (host, [S], may be NULL): init_ready[i] = number of rows of C_0 first accessed
+ * in iterations 0..i.  C_0 is ordered by first access, so iteration i only reads cache
+ * lines below init_ready[i]: an executor may load C_0 in pieces (ginex_cache_init_part)
+ * and start iteration i as soon as that prefix is in place, provided no changeset has been
+ * applied yet (a changeset may evict a row that was not loaded yet).
  * Preconditions (ids in range, ids distinct inside an iteration) are the caller's duty and
  * unchecked by default; with GINEX_VALIDATE=1 in the environment they are checked on the
  * device first and a violation returns GINEX_ERR_INPUT before anything else runs.
@@ -155,7 +160,7 @@ int32_t ginex_changeset(
     int32_t* init_ids /*[cap]*/, int64_t* init_count /*host*/,
     int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
     int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
-    int64_t* total_changes /*host*/,
+    int64_t* total_changes /*host*/, int64_t* init_ready /*host [S] or NULL*/,
     void* ws, size_t ws_bytes, void* stream);
 
 /* The same precomputation for the LRU policy (Section 2.3 and Figure 2: the policy that
@@ -170,7 +175,7 @@ int32_t ginex_changeset_lru(
     int32_t* init_ids /*[cap]*/, int64_t* init_count /*host*/,
     int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
     int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
-    int64_t* total_changes /*host*/,
+    int64_t* total_changes /*host*/, int64_t* init_ready /*host [S] or NULL*/,
     void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------
@@ -193,6 +198,14 @@ typedef struct ginex_cache {
  * loaded into line r and addr[init_ids[r]] = r.  init_count <= cap. */
 int32_t ginex_cache_init(const ginex_cache_t* c /*host struct*/, const int32_t* init_ids,
                          int64_t init_count, void* stream);
+
+/* The same initialization in pieces (Section 3.1; the paper runs the initialization as one
+ * stage in front of the main loop, here the main loop may start under it): loads rows
+ * init_ids[begin .. end) into lines begin .. end-1.  The piece with begin == 0 resets the
+ * address table first, so pieces are issued in ascending order on one stream.
+ * 0 <= begin <= end <= cap. */
+int32_t ginex_cache_init_part(const ginex_cache_t* c /*host struct*/, const int32_t* init_ids,
+                              int64_t begin, int64_t end, void* stream);
 
 /* One executor iteration (Section 3.1 "Main Loop", Section 3.3 worked example):
  * gather   out[p,:] = addr[ids[p]] >= 0 ? rows[addr[ids[p]],:] : slow[ids[p],:]

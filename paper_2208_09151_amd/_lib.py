@@ -30,10 +30,11 @@ SIGNATURES = {
     "ginex_neighbor_cache_build": (i32, [C.POINTER(CsrDesc), i64, vp, vp, vp, vp, vp, sz, vp]),
     "ginex_changeset_workspace_bytes": (sz, [i64, i64, i32, i64]),
     "ginex_changeset": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp,
-                              sz, vp]),
+                              vp, sz, vp]),
     "ginex_changeset_lru": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp,
-                                  sz, vp]),
+                                  vp, sz, vp]),
     "ginex_cache_init": (i32, [C.POINTER(CacheDesc), vp, i64, vp]),
+    "ginex_cache_init_part": (i32, [C.POINTER(CacheDesc), vp, i64, i64, vp]),
     "ginex_gather": (i32, [C.POINTER(CacheDesc), vp, i64, vp, vp, vp, vp, i64, vp]),
     "ginex_cache_update": (i32, [C.POINTER(CacheDesc), vp, vp, vp, vp, i64, vp]),
 }

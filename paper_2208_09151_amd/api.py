@@ -190,6 +190,7 @@ class ChangesetResult:
     in_positions: torch.Tensor
     cs_offsets: np.ndarray      # [S+1] host
     miss_count: np.ndarray      # [S] host
+    init_ready: np.ndarray = None   # [S] host: rows of C_0 first accessed in iterations 0..i
 
 
 def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady"):
@@ -217,13 +218,14 @@ def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady")
     miss = torch.empty(max(S, 1), dtype=torch.int64, device=dev)
     init_count = np.zeros(1, dtype=np.int64)
     total_changes = np.zeros(1, dtype=np.int64)
+    init_ready = np.zeros(max(S, 1), dtype=np.int64)
     rc = entry(num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(init_ids), _np_ptr(init_count),
                _ptr(in_ids), _ptr(out_ids), _ptr(in_pos), cs_cap, _ptr(cs_off), _ptr(miss),
-               _np_ptr(total_changes), _ptr(ws), ws.numel(), _stream())
+               _np_ptr(total_changes), _np_ptr(init_ready), _ptr(ws), ws.numel(), _stream())
     _check(rc)
     n = int(total_changes[0])
     return ChangesetResult(init_ids[:int(init_count[0])], in_ids[:n], out_ids[:n], in_pos[:n],
-                           cs_off.cpu().numpy(), miss[:S].cpu().numpy())
+                           cs_off.cpu().numpy(), miss[:S].cpu().numpy(), init_ready[:S])
 
 
 class FeatureCache:
@@ -245,11 +247,18 @@ class FeatureCache:
         self._desc_ref = C.byref(self._desc)
         self._gather = _lib.load().ginex_gather
         self._update = _lib.load().ginex_cache_update
+        self._init_part = _lib.load().ginex_cache_init_part
 
     def init(self, init_ids: torch.Tensor):
         _dev(init_ids, torch.int32)
         _check(_lib.load().ginex_cache_init(C.byref(self._desc), _ptr(init_ids),
                                             init_ids.numel(), _stream()))
+
+    def init_part_raw(self, init_ptr: int, begin: int, end: int, stream_ptr: int):
+        """ginex_cache_init_part on raw device addresses: lines begin..end-1 of C_0."""
+        rc = self._init_part(self._desc_ref, init_ptr, begin, end, stream_ptr)
+        if rc:
+            _check(rc)
 
     def gather(self, ids, out=None, in_ids=None, out_ids=None, in_positions=None):
         """One executor iteration: gather the rows of ``ids`` then apply the changeset."""

@@ -236,6 +236,21 @@ __global__ __launch_bounds__(TB) void k_copy_init(const uint64_t* __restrict__ h
 // block to finish of the launch before them (the device-wide fence every block then needs
 // writes back and invalidates L2 on this multi-XCD part: three to four times slower).
 
+// ready[i] = number of prefetched rows whose first access lies in iterations 0..i: the
+// prefix of C_0 (it is ordered by first access) that iteration i can touch.
+__global__ __launch_bounds__(TB) void k_init_ready(const uint64_t* __restrict__ heads,
+                                                   int64_t n_init, int32_t S,
+                                                   int64_t* __restrict__ ready) {
+  const int32_t i = blockIdx.x * TB + threadIdx.x;
+  if (i >= S) return;
+  int64_t lo = 0, hi = n_init;   // first rank whose first access is later than i
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if ((int32_t)(heads[mid] >> 32) <= i) lo = mid + 1; else hi = mid;
+  }
+  ready[i] = lo;
+}
+
 struct Iter {           // what a phase needs to know about the running iteration
   const int32_t* ids;   // ids_i
   const int32_t* next;  // next accessed iteration of each access of ids_i (Belady keys)
@@ -717,6 +732,7 @@ struct Workspace {
   uint32_t* head_tiles;
   int32_t* next_iter;
   int64_t* d_offsets;
+  int64_t* d_ready;
   int64_t* d_cs_offsets;
   unsigned long long* d_counts;
   State st;
@@ -745,6 +761,7 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   w.head_tiles = a.take<uint32_t>(w.look_tiles + 1 + scan_scratch_elems(w.look_tiles + 1));
   w.next_iter = a.take<int32_t>(t);
   w.d_offsets = a.take<int64_t>(S + 1);
+  w.d_ready = a.take<int64_t>(S);
   w.d_cs_offsets = a.take<int64_t>(S + 1);
   w.d_counts = a.take<unsigned long long>(2);
   State& st = w.st;
@@ -813,8 +830,8 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                       const int64_t* ids_offsets, int32_t S, int64_t cap, int32_t* init_ids,
                       int64_t* init_count, int32_t* in_ids, int32_t* out_ids,
                       int32_t* in_positions, int64_t cs_capacity, int64_t* cs_offsets,
-                      int64_t* miss_count, int64_t* total_changes, void* ws, size_t ws_bytes,
-                      void* stream) {
+                      int64_t* miss_count, int64_t* total_changes, int64_t* init_ready,
+                      void* ws, size_t ws_bytes, void* stream) {
   if (!ids_offsets || !init_count || !cs_offsets || !miss_count || !total_changes || !ws)
     return fail(GINEX_ERR_ARG, "%s: a required pointer is null", who);
   if (S >= 1 && ids_offsets[0] != 0)
@@ -849,6 +866,8 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   GINEX_HIP(fill_async<int64_t>(cs_offsets, S + 1, 0, st));
   *init_count = 0;
   *total_changes = 0;
+  if (init_ready)
+    for (int32_t i = 0; i < S; ++i) init_ready[i] = 0;
   if (total == 0) {
     GINEX_HIP(hipStreamSynchronize(st));
     return GINEX_OK;
@@ -902,6 +921,13 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                            &heads));
   const int64_t n_init = distinct < cap ? distinct : cap;
   *init_count = n_init;
+  if (init_ready && n_init > 0) {   // every path below waits for the stream before it returns
+    hipLaunchKernelGGL(k_init_ready, dim3((unsigned)ceil_div(S, TB)), dim3(TB), 0, st, heads, n_init,
+                       S, w.d_ready);
+    GINEX_LAUNCH_CHECK();
+    GINEX_HIP(hipMemcpyAsync(init_ready, w.d_ready, sizeof(int64_t) * S, hipMemcpyDeviceToHost,
+                             st));
+  }
   if (distinct <= cap || cap == 0) {
     // everything fits (no row ever misses), or there is no cache (every row misses and
     // nothing is inserted): all changesets are empty
@@ -999,11 +1025,11 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
                                    int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
                                    int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
                                    int64_t* cs_offsets, int64_t* miss_count,
-                                   int64_t* total_changes, void* ws, size_t ws_bytes,
-                                   void* stream) {
+                                   int64_t* total_changes, int64_t* init_ready, void* ws,
+                                   size_t ws_bytes, void* stream) {
   return changeset_run("ginex_changeset", false, num_nodes, ids, ids_offsets, S, cap, init_ids,
                        init_count, in_ids, out_ids, in_positions, cs_capacity, cs_offsets,
-                       miss_count, total_changes, ws, ws_bytes, stream);
+                       miss_count, total_changes, init_ready, ws, ws_bytes, stream);
 }
 
 extern "C" int32_t ginex_changeset_lru(int64_t num_nodes, const int32_t* ids,
@@ -1011,9 +1037,10 @@ extern "C" int32_t ginex_changeset_lru(int64_t num_nodes, const int32_t* ids,
                                        int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
                                        int32_t* out_ids, int32_t* in_positions,
                                        int64_t cs_capacity, int64_t* cs_offsets,
-                                       int64_t* miss_count, int64_t* total_changes, void* ws,
-                                       size_t ws_bytes, void* stream) {
+                                       int64_t* miss_count, int64_t* total_changes,
+                                       int64_t* init_ready, void* ws, size_t ws_bytes,
+                                       void* stream) {
   return changeset_run("ginex_changeset_lru", true, num_nodes, ids, ids_offsets, S, cap, init_ids,
                        init_count, in_ids, out_ids, in_positions, cs_capacity, cs_offsets,
-                       miss_count, total_changes, ws, ws_bytes, stream);
+                       miss_count, total_changes, init_ready, ws, ws_bytes, stream);
 }

@@ -74,13 +74,13 @@ __global__ __launch_bounds__(THREADS) void k_update_addr(
   }
 }
 
-// rows[r,:] = slow[init_ids[r],:]; addr[init_ids[r]] = r
+// rows[r,:] = slow[init_ids[r],:]; addr[init_ids[r]] = r, for lines r in [begin, end)
 __global__ __launch_bounds__(THREADS) void k_cache_fill(
     chunk_t* __restrict__ rows, int32_t* __restrict__ addr, const chunk_t* __restrict__ slow,
-    const int32_t* __restrict__ init_ids, int64_t count, int32_t cpr) {
-  const int64_t total = count * cpr;
+    const int32_t* __restrict__ init_ids, int64_t begin, int64_t end, int32_t cpr) {
+  const int64_t total = end * cpr;
   const int64_t span = (int64_t)gridDim.x * THREADS;
-  int64_t c0 = (int64_t)blockIdx.x * THREADS + threadIdx.x;
+  int64_t c0 = begin * cpr + (int64_t)blockIdx.x * THREADS + threadIdx.x;
   for (; c0 < total; c0 += span * UNROLL) {
     chunk_t v[UNROLL];
 #pragma unroll
@@ -129,6 +129,30 @@ int32_t check_cache(const ginex_cache_t* c, const char* who) {
 
 using namespace ginex;
 
+namespace ginex {
+namespace {
+
+int32_t launch_fill(const ginex_cache_t* c, const int32_t* init_ids, int64_t begin, int64_t end,
+                    hipStream_t st) {
+  if (end <= begin) return GINEX_OK;
+  const int32_t cpr = (int32_t)(c->row_bytes / 16);
+  // The fill is bound by the host link, which 64 blocks (1 MB of reads in flight; a link
+  // read takes about 7 us) keep busier than a full grid does (57 against 54.6 GB/s); 32
+  // blocks reach 53 GB/s, 16 blocks 34.  Link reads in flight slow every other kernel's
+  // HBM traffic down: a gather that runs beside the fill takes 1.2x (32 blocks), 2x (64) or
+  // 6x (128) its time alone, and behind a full grid kernels on other streams make no
+  // progress at all until the fill ends.
+  unsigned blocks = grid_for((end - begin) * cpr, UNROLL);
+  if (blocks > 64) blocks = 64;
+  hipLaunchKernelGGL(k_cache_fill, dim3(blocks), dim3(THREADS), 0, st, (chunk_t*)c->rows, c->addr,
+                     (const chunk_t*)c->slow, init_ids, begin, end, cpr);
+  GINEX_LAUNCH_CHECK();
+  return GINEX_OK;
+}
+
+}  // namespace
+}  // namespace ginex
+
 extern "C" int32_t ginex_cache_init(const ginex_cache_t* c, const int32_t* init_ids,
                                     int64_t init_count, void* stream) {
   if (int32_t rc = check_cache(c, "ginex_cache_init")) return rc;
@@ -138,20 +162,20 @@ extern "C" int32_t ginex_cache_init(const ginex_cache_t* c, const int32_t* init_
   if (init_count > 0 && !init_ids) return fail(GINEX_ERR_ARG, "ginex_cache_init: init_ids is null");
   hipStream_t st = (hipStream_t)stream;
   GINEX_HIP(fill_async<int32_t>(c->addr, c->num_nodes, -1, st));
-  if (init_count > 0) {
-    const int32_t cpr = (int32_t)(c->row_bytes / 16);
-    // The fill is bound by the host link, which 64 blocks (1 MB of reads in flight) keep
-    // busier than a full grid does (57 against 54.6 GB/s).  A full grid parks hundreds of
-    // thousands of slow link reads in the memory pipeline and kernels on other streams
-    // (the inspector of the next superbatch) then make no progress until the fill ends;
-    // behind the small grid they run concurrently.
-    unsigned blocks = grid_for(init_count * cpr, UNROLL);
-    if (blocks > 64) blocks = 64;
-    hipLaunchKernelGGL(k_cache_fill, dim3(blocks), dim3(THREADS), 0, st, (chunk_t*)c->rows,
-                       c->addr, (const chunk_t*)c->slow, init_ids, init_count, cpr);
-    GINEX_LAUNCH_CHECK();
-  }
-  return GINEX_OK;
+  return launch_fill(c, init_ids, 0, init_count, st);
+}
+
+extern "C" int32_t ginex_cache_init_part(const ginex_cache_t* c, const int32_t* init_ids,
+                                         int64_t begin, int64_t end, void* stream) {
+  if (int32_t rc = check_cache(c, "ginex_cache_init_part")) return rc;
+  if (begin < 0 || end < begin || end > c->cap)
+    return fail(GINEX_ERR_ARG, "ginex_cache_init_part: [%lld, %lld) outside [0, cap=%lld]",
+                (long long)begin, (long long)end, (long long)c->cap);
+  if (end > begin && !init_ids)
+    return fail(GINEX_ERR_ARG, "ginex_cache_init_part: init_ids is null");
+  hipStream_t st = (hipStream_t)stream;
+  if (begin == 0) GINEX_HIP(fill_async<int32_t>(c->addr, c->num_nodes, -1, st));
+  return launch_fill(c, init_ids, begin, end, st);
 }
 
 namespace ginex {

@@ -11,6 +11,10 @@ library keeps no global state, and ctypes drops the GIL during the calls.
 superbatch k+1 (sampling and changesets, bound by HBM and atomics) runs under the executor
 of superbatch k (cache initialization and gathers, bound by the host link).
 
+``Executor`` runs one superbatch through the cache (initialization, then gather and update
+per iteration) and can start the main loop under the initialization: C_0 is ordered by
+first access, so iteration i needs only a prefix of it.
+
 This module only sequences calls of the binding: no step of the path runs here.
 """
 from __future__ import annotations
@@ -22,6 +26,88 @@ import numpy as np
 import torch
 
 from . import _lib, api
+
+
+class Executor:
+    """Cache initialization and main loop of one superbatch (paper Section 3.1).
+
+    With ``streamed=True`` the initialization is issued in pieces on a second stream
+    (default priority) and the gather of iteration i waits only for the piece that completes
+    the rows first accessed up to i (``ChangesetResult.init_ready``).  From the first
+    non-empty changeset on, iterations wait for the whole initialization, since an update may
+    evict a row that is not loaded yet.  The initialization is bound by the host link, the
+    gathers of resident rows by HBM, so the two overlap almost completely."""
+
+    def __init__(self, cache: api.FeatureCache, min_piece_rows: int = 1 << 16):
+        self.cache = cache
+        self.min_piece_rows = min_piece_rows
+        self.fill_stream = torch.cuda.Stream(device=cache.rows.device)
+        self.events = []
+
+    def _event(self, k):
+        while len(self.events) <= k:
+            self.events.append(torch.cuda.Event(enable_timing=True))
+        return self.events[k]
+
+    def run(self, samp, cs, out, streamed=True, before_gather=None, after_gather=None):
+        """``out``: device buffer [>= longest iteration, feat_dim] that receives every batch
+        input in turn; ``before_gather(i)`` / ``after_gather(i, n)`` are called right before
+        and after the gather kernel of iteration i is enqueued (timing events; the consumer
+        enqueues its own work on the current stream in ``after_gather``).  Returns the event
+        that marks the end of the initialization."""
+        cache = self.cache
+        main = torch.cuda.current_stream()
+        mp = main.cuda_stream
+        io, co = samp.ids_offsets.tolist(), cs.cs_offsets.tolist()
+        S = len(io) - 1
+        n_init = cs.init_ids.numel()
+        ids_base, out_ptr = samp.ids.data_ptr(), out.data_ptr()
+        bases = (cs.in_ids.data_ptr(), cs.out_ids.data_ptr(), cs.in_positions.data_ptr())
+        init_ptr = cs.init_ids.data_ptr()
+        wait_for = None
+        if streamed and cs.init_ready is not None and S > 0:
+            ready = cs.init_ready.tolist()
+            fs = self.fill_stream
+            fp = fs.cuda_stream
+            fs.wait_stream(main)        # earlier readers of the cache lines are done
+            first_change = next((i for i in range(S) if co[i + 1] > co[i]), S)
+            need = [ready[i] if i < first_change else n_init for i in range(S)]
+            need[S - 1] = n_init
+            # pieces end at iteration boundaries and hold at least min_piece_rows rows; the
+            # first one is always issued, since it resets the address table
+            cuts, done = [], 0
+            for i in range(S):
+                if i == 0 or need[i] - done >= self.min_piece_rows or \
+                        (need[i] == n_init and need[i] > done):
+                    cache.init_part_raw(init_ptr, done, need[i], fp)
+                    self._event(len(cuts)).record(fs)
+                    done = need[i]
+                    cuts.append(done)
+            wait_for, k = [0] * S, 0
+            for i in range(S):
+                while cuts[k] < need[i]:
+                    k += 1
+                wait_for[i] = k
+        else:
+            cache.init(cs.init_ids)
+            self._event(0).record(main)
+            cuts = [n_init]
+        waited = -1
+        for i in range(S):
+            if wait_for is not None and wait_for[i] > waited:
+                waited = wait_for[i]
+                main.wait_event(self.events[waited])
+            n = io[i + 1] - io[i]
+            if before_gather is not None:
+                before_gather(i)
+            cache.gather_raw(ids_base + 4 * io[i], n, out_ptr, mp)
+            if after_gather is not None:
+                after_gather(i, n)
+            nc = co[i + 1] - co[i]
+            if nc:
+                cache.update_raw(out_ptr, bases[0] + 4 * co[i], bases[1] + 4 * co[i],
+                                 bases[2] + 4 * co[i], nc, mp)
+        return self.events[len(cuts) - 1]
 
 
 class InspectorPipeline:

@@ -506,3 +506,52 @@ def test_neighbor_cache_is_transparent_to_the_sampler(ginex, which, request):
     res = ginex.sample_superbatch(c.w.offsets, ind_host, c.w.seeds.cuda(), c.seed_off,
                                   c.cfg.fanout, rng_seed=0)
     check_sample(res, c.samp, S, H)
+
+
+# ---- main loop started under the cache initialization ------------------------------------------
+
+@pytest.mark.parametrize("which", ["case1", "case2"])
+def test_streamed_initialization_gathers_the_same_bytes(ginex, which, request):
+    c = request.getfixturevalue(which)
+    n, S = c.cfg.num_nodes, c.cfg.S
+    ids, io = c.samp["ids"], c.samp["ids_offsets"]
+    distinct = len(np.unique(ids))
+    _, first = oracle.next_use(n, ids, io)
+    sb = c.w.features.numpy().view(np.uint8).reshape(n, -1)
+    res = run_sample(ginex, c)
+    longest = int(np.diff(io).max())
+    out = torch.empty((longest, c.cfg.feat_dim), dtype=torch.float32, device="cuda")
+    for cap in (distinct, distinct - 1, c.cfg.cap, 1000, 0):
+        ref = oracle.changeset(n, ids, io, cap)
+        cs = ginex.changeset(n, res.ids, res.ids_offsets, cap)
+        check_changeset(cs, ref)
+        # init_ready[i] = rows of C_0 first accessed in iterations 0..i
+        f = first[ref["init_ids"]]
+        want_ready = np.array([(f <= i).sum() for i in range(S)], dtype=np.int64)
+        assert np.array_equal(cs.init_ready, want_ready)
+        assert np.all(np.diff(f) >= 0)                     # C_0 is ordered by first access
+        cache = ginex.FeatureCache(c.w.features, cap)
+        replay = oracle.Cache(c.w.features.numpy(), cap)
+        replay.init(ref["init_ids"])
+        co = ref["cs_offsets"]
+        for i in range(S):
+            replay.gather_update(ids[io[i]:io[i + 1]], ref["in_ids"][co[i]:co[i + 1]],
+                                 ref["out_ids"][co[i]:co[i + 1]],
+                                 ref["in_positions"][co[i]:co[i + 1]])
+        for streamed, piece in ((True, 1), (True, 4096), (False, 1)):
+            ex = ginex.Executor(cache, min_piece_rows=piece)
+            cache.rows.fill_(float("nan"))                 # stale lines must never be read
+            got = {}
+
+            def keep(i, rows):
+                got[i] = out[:rows].clone()
+            ex.run(res, cs, out, streamed=streamed, after_gather=keep)
+            torch.cuda.synchronize()
+            for i in range(S):
+                g = got[i].cpu().numpy().view(np.uint8).reshape(got[i].shape[0], -1)
+                assert np.array_equal(g, sb[ids[io[i]:io[i + 1]]]), (cap, streamed, piece, i)
+            assert np.array_equal(cache.addr.cpu().numpy(), replay.addr), (cap, streamed, piece)
+            if cap:
+                rows = cache.rows.cpu().numpy().view(np.uint8).reshape(cache.rows.shape[0], -1)
+                held = np.nonzero(replay.addr >= 0)[0]
+                assert np.array_equal(rows[replay.addr[held]], sb[held])

@@ -18,7 +18,7 @@ def test_every_declared_symbol_is_exported_and_bound():
     from paper_2208_09151_amd import _lib
     lib = _lib.load()
     names = declared_symbols()
-    assert len(names) == 12
+    assert len(names) == 13
     assert sorted(_lib.SIGNATURES) == names
     for n in names:
         assert getattr(lib, n) is not None
@@ -84,7 +84,7 @@ def test_precondition_and_workspace_errors_are_reported_before_any_launch():
 
     def changeset(ids_offsets=io, S=2, cap=3, ws_bytes=16, n=100):
         return lib.ginex_changeset(n, fake, P(ids_offsets), S, cap, fake, P(ic), fake, fake, fake,
-                                   100, fake, fake, P(tc), fake, ws_bytes, None)
+                                   100, fake, fake, P(tc), None, fake, ws_bytes, None)
 
     assert changeset() == -3
     assert changeset(ids_offsets=np.array([0, 9, 4], dtype=np.int64)) == -4
@@ -95,6 +95,8 @@ def test_precondition_and_workspace_errors_are_reported_before_any_launch():
 
     c = _lib.CacheDesc(0x1000, 4, 64, 0x1000, 10, 0x1000)
     assert lib.ginex_cache_init(ctypes.byref(c), fake, 5, None) == -1      # more rows than lines
+    assert lib.ginex_cache_init_part(ctypes.byref(c), fake, 2, 5, None) == -1
+    assert lib.ginex_cache_init_part(ctypes.byref(c), fake, 3, 2, None) == -1
     assert lib.ginex_gather(ctypes.byref(c), fake, 2, fake, fake, fake, fake, 3, None) == -1
     assert lib.ginex_cache_update(ctypes.byref(c), fake, fake, fake, fake, 9, None) == -1
     assert lib.ginex_gather(ctypes.byref(c), fake, 2, ctypes.c_void_p(0x1008), None, None, None,
