@@ -228,21 +228,31 @@ def pipeline_leg(ginex, w, K):
 
     executor = ginex.Executor(cache)
     streamed = [True]
+    reuse = [0, 0]
 
     def execute(k, samp, cs):
+        if len(executor.caches) > 1 and executor.warm:
+            reuse[0] += int((executor.cache.addr[cs.init_ids.long()] >= 0).sum())
+            reuse[1] += cs.init_ids.numel()
         executor.run(samp, cs, batch_input, streamed=streamed[0])
         torch.cuda.current_stream().synchronize()
         edges[0] += int(samp.totals[2])
 
-    for key, overlap, st in (("whole_path_stage_by_stage", False, False),
-                             ("whole_path_sequential", False, True),
-                             ("whole_path_overlapped", True, True)):
+    for key, overlap, st, warm in (("whole_path_stage_by_stage", False, False, False),
+                                   ("whole_path_sequential", False, True, False),
+                                   ("whole_path_overlapped", True, True, False),
+                                   ("whole_path_overlapped_warm_init", True, True, True)):
         streamed[0] = st
+        if warm:
+            # a second cache array: rows that the previous superbatch's cache still holds
+            # are copied from it instead of crossing the host link again
+            executor = ginex.Executor(cache, second=ginex.FeatureCache(w.features, cfg.cap))
         pipe.run_with_executor(sbs[:2], execute, overlap=overlap)      # warm-up
         edges[0] = 0
         t = pipe.run_with_executor(sbs, execute, overlap=overlap)
         out[key + "_ms_per_superbatch"] = t * 1e3 / K
         out[key + "_edges_per_s"] = edges[0] / t
+    out["warm_init_rows_found_in_previous_cache"] = reuse[0] / max(reuse[1], 1)
     return out
 
 

@@ -207,6 +207,16 @@ int32_t ginex_cache_init(const ginex_cache_t* c /*host struct*/, const int32_t* 
 int32_t ginex_cache_init_part(const ginex_cache_t* c /*host struct*/, const int32_t* init_ids,
                               int64_t begin, int64_t end, void* stream);
 
+/* Initialization of the next superbatch's cache with the previous one still in HBM (the
+ * paper reloads every row from storage, Section 3.1; here a row of the new C_0 that `prev`
+ * still holds is copied from prev's line, HBM to HBM, and only the others cross the host
+ * link).  Same pieces and the same resulting cache content as ginex_cache_init_part.  `c`
+ * and `prev` front the same slow tier with the same row size and share no array; `prev` is
+ * only read. */
+int32_t ginex_cache_init_warm(const ginex_cache_t* c /*host struct*/,
+                              const ginex_cache_t* prev /*host struct*/,
+                              const int32_t* init_ids, int64_t begin, int64_t end, void* stream);
+
 /* One executor iteration (Section 3.1 "Main Loop", Section 3.3 worked example):
  * gather   out[p,:] = addr[ids[p]] >= 0 ? rows[addr[ids[p]],:] : slow[ids[p],:]
  * then the cache update  line = addr[out_ids[j]]; rows[line,:] = out[in_positions[j],:];

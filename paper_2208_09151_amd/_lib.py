@@ -35,6 +35,7 @@ SIGNATURES = {
                                   vp, sz, vp]),
     "ginex_cache_init": (i32, [C.POINTER(CacheDesc), vp, i64, vp]),
     "ginex_cache_init_part": (i32, [C.POINTER(CacheDesc), vp, i64, i64, vp]),
+    "ginex_cache_init_warm": (i32, [C.POINTER(CacheDesc), C.POINTER(CacheDesc), vp, i64, i64, vp]),
     "ginex_gather": (i32, [C.POINTER(CacheDesc), vp, i64, vp, vp, vp, vp, i64, vp]),
     "ginex_cache_update": (i32, [C.POINTER(CacheDesc), vp, vp, vp, vp, i64, vp]),
 }

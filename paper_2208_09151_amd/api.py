@@ -248,6 +248,7 @@ class FeatureCache:
         self._gather = _lib.load().ginex_gather
         self._update = _lib.load().ginex_cache_update
         self._init_part = _lib.load().ginex_cache_init_part
+        self._init_warm = _lib.load().ginex_cache_init_warm
 
     def init(self, init_ids: torch.Tensor):
         _dev(init_ids, torch.int32)
@@ -257,6 +258,13 @@ class FeatureCache:
     def init_part_raw(self, init_ptr: int, begin: int, end: int, stream_ptr: int):
         """ginex_cache_init_part on raw device addresses: lines begin..end-1 of C_0."""
         rc = self._init_part(self._desc_ref, init_ptr, begin, end, stream_ptr)
+        if rc:
+            _check(rc)
+
+    def init_warm_raw(self, prev: "FeatureCache", init_ptr: int, begin: int, end: int,
+                      stream_ptr: int):
+        """ginex_cache_init_warm: like init_part_raw, rows that ``prev`` holds come from it."""
+        rc = self._init_warm(self._desc_ref, prev._desc_ref, init_ptr, begin, end, stream_ptr)
         if rc:
             _check(rc)
 

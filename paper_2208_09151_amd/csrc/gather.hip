@@ -102,6 +102,38 @@ __global__ __launch_bounds__(THREADS) void k_cache_fill(
   }
 }
 
+// The same fill with a second source in front of the slow tier: a row that another cache
+// (the previous superbatch's) still holds is copied from there, HBM to HBM.
+__global__ __launch_bounds__(THREADS) void k_cache_fill_warm(
+    chunk_t* __restrict__ rows, int32_t* __restrict__ addr, const chunk_t* __restrict__ slow,
+    const chunk_t* __restrict__ prev_rows, const int32_t* __restrict__ prev_addr,
+    const int32_t* __restrict__ init_ids, int64_t begin, int64_t end, int32_t cpr) {
+  const int64_t total = end * cpr;
+  const int64_t span = (int64_t)gridDim.x * THREADS;
+  int64_t c0 = begin * cpr + (int64_t)blockIdx.x * THREADS + threadIdx.x;
+  for (; c0 < total; c0 += span * UNROLL) {
+    chunk_t v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int64_t c = c0 + u * span;
+      if (c < total) {
+        const int64_t r = c / cpr;
+        const int32_t col = (int32_t)(c - r * cpr);
+        const int32_t id = init_ids[r];
+        const int32_t line = prev_addr[id];
+        const chunk_t* src = line >= 0 ? prev_rows + (int64_t)line * cpr : slow + (int64_t)id * cpr;
+        v[u] = src[col];
+        if (col == 0) addr[id] = (int32_t)r;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int64_t c = c0 + u * span;
+      if (c < total) rows[c] = v[u];
+    }
+  }
+}
+
 inline unsigned grid_for(int64_t items, int per_thread) {
   int64_t blocks = ceil_div(items, (int64_t)THREADS * per_thread);
   if (blocks < 1) blocks = 1;
@@ -131,6 +163,10 @@ using namespace ginex;
 
 namespace ginex {
 namespace {
+
+// Grid of the warm fill: its link reads are diluted by HBM-to-HBM copies, so it takes more
+// blocks than the cold fill to keep the same number of link reads in flight.
+constexpr unsigned WARM_BLOCKS = 128;
 
 int32_t launch_fill(const ginex_cache_t* c, const int32_t* init_ids, int64_t begin, int64_t end,
                     hipStream_t st) {
@@ -163,6 +199,34 @@ extern "C" int32_t ginex_cache_init(const ginex_cache_t* c, const int32_t* init_
   hipStream_t st = (hipStream_t)stream;
   GINEX_HIP(fill_async<int32_t>(c->addr, c->num_nodes, -1, st));
   return launch_fill(c, init_ids, 0, init_count, st);
+}
+
+extern "C" int32_t ginex_cache_init_warm(const ginex_cache_t* c, const ginex_cache_t* prev,
+                                         const int32_t* init_ids, int64_t begin, int64_t end,
+                                         void* stream) {
+  const char* who = "ginex_cache_init_warm";
+  if (int32_t rc = check_cache(c, who)) return rc;
+  if (int32_t rc = check_cache(prev, who)) return rc;
+  if (prev->row_bytes != c->row_bytes || prev->num_nodes != c->num_nodes || prev->slow != c->slow)
+    return fail(GINEX_ERR_ARG, "%s: the two caches must front the same slow tier", who);
+  if (prev->rows == c->rows || prev->addr == c->addr)
+    return fail(GINEX_ERR_ARG, "%s: the two caches must not share their arrays", who);
+  if (begin < 0 || end < begin || end > c->cap)
+    return fail(GINEX_ERR_ARG, "%s: [%lld, %lld) outside [0, cap=%lld]", who, (long long)begin,
+                (long long)end, (long long)c->cap);
+  if (end > begin && !init_ids) return fail(GINEX_ERR_ARG, "%s: init_ids is null", who);
+  hipStream_t st = (hipStream_t)stream;
+  if (begin == 0) GINEX_HIP(fill_async<int32_t>(c->addr, c->num_nodes, -1, st));
+  if (end > begin) {
+    const int32_t cpr = (int32_t)(c->row_bytes / 16);
+    unsigned blocks = grid_for((end - begin) * cpr, UNROLL);
+    if (blocks > WARM_BLOCKS) blocks = WARM_BLOCKS;
+    hipLaunchKernelGGL(k_cache_fill_warm, dim3(blocks), dim3(THREADS), 0, st, (chunk_t*)c->rows,
+                       c->addr, (const chunk_t*)c->slow, (const chunk_t*)prev->rows, prev->addr,
+                       init_ids, begin, end, cpr);
+    GINEX_LAUNCH_CHECK();
+  }
+  return GINEX_OK;
 }
 
 extern "C" int32_t ginex_cache_init_part(const ginex_cache_t* c, const int32_t* init_ids,

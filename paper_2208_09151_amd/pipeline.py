@@ -38,11 +38,22 @@ class Executor:
     evict a row that is not loaded yet.  The initialization is bound by the host link, the
     gathers of resident rows by HBM, so the two overlap almost completely."""
 
-    def __init__(self, cache: api.FeatureCache, min_piece_rows: int = 1 << 16):
-        self.cache = cache
+    def __init__(self, cache: api.FeatureCache, min_piece_rows: int = 1 << 16,
+                 second: api.FeatureCache = None):
+        """``second``: another cache of the same shape over the same slow tier.  The two then
+        take turns from superbatch to superbatch, and the initialization copies every row the
+        previous superbatch's cache still holds from there instead of the slow tier."""
+        self.caches = [cache] if second is None else [cache, second]
+        self.turn = 0               # caches[turn] takes the next superbatch
+        self.warm = False           # the other cache holds a finished superbatch
         self.min_piece_rows = min_piece_rows
         self.fill_stream = torch.cuda.Stream(device=cache.rows.device)
         self.events = []
+
+    @property
+    def cache(self):
+        """The cache of the superbatch that ran last (or will run first)."""
+        return self.caches[self.turn - 1] if self.warm else self.caches[self.turn]
 
     def _event(self, k):
         while len(self.events) <= k:
@@ -55,7 +66,15 @@ class Executor:
         and after the gather kernel of iteration i is enqueued (timing events; the consumer
         enqueues its own work on the current stream in ``after_gather``).  Returns the event
         that marks the end of the initialization."""
-        cache = self.cache
+        cache = self.caches[self.turn]
+        prev = self.caches[self.turn - 1] if self.warm and len(self.caches) > 1 else None
+
+        def load(begin, end, stream_ptr):
+            if prev is not None:
+                cache.init_warm_raw(prev, init_ptr, begin, end, stream_ptr)
+            else:
+                cache.init_part_raw(init_ptr, begin, end, stream_ptr)
+
         main = torch.cuda.current_stream()
         mp = main.cuda_stream
         io, co = samp.ids_offsets.tolist(), cs.cs_offsets.tolist()
@@ -79,7 +98,7 @@ class Executor:
             for i in range(S):
                 if i == 0 or need[i] - done >= self.min_piece_rows or \
                         (need[i] == n_init and need[i] > done):
-                    cache.init_part_raw(init_ptr, done, need[i], fp)
+                    load(done, need[i], fp)
                     self._event(len(cuts)).record(fs)
                     done = need[i]
                     cuts.append(done)
@@ -89,7 +108,7 @@ class Executor:
                     k += 1
                 wait_for[i] = k
         else:
-            cache.init(cs.init_ids)
+            load(0, n_init, mp)
             self._event(0).record(main)
             cuts = [n_init]
         waited = -1
@@ -107,6 +126,9 @@ class Executor:
             if nc:
                 cache.update_raw(out_ptr, bases[0] + 4 * co[i], bases[1] + 4 * co[i],
                                  bases[2] + 4 * co[i], nc, mp)
+        if len(self.caches) > 1:
+            self.turn = 1 - self.turn
+            self.warm = True
         return self.events[len(cuts) - 1]
 
 

@@ -555,3 +555,50 @@ def test_streamed_initialization_gathers_the_same_bytes(ginex, which, request):
                 rows = cache.rows.cpu().numpy().view(np.uint8).reshape(cache.rows.shape[0], -1)
                 held = np.nonzero(replay.addr >= 0)[0]
                 assert np.array_equal(rows[replay.addr[held]], sb[held])
+
+
+def test_warm_initialization_leaves_the_same_cache_as_a_cold_one(ginex, case2):
+    """Consecutive superbatches with two caches taking turns: rows the previous cache holds
+    are copied from it, the cache content must not differ from a cold initialization."""
+    from workload.configs import seed_batches, train_nodes
+    c = case2
+    cfg, n = c.cfg, c.cfg.num_nodes
+    S = 6
+    train = train_nodes(n, cfg.train_frac, cfg.seed)
+    feats = c.w.features
+    sb = feats.numpy().view(np.uint8).reshape(n, -1)
+    for cap in (cfg.cap, 20000):
+        warm = ginex.Executor(ginex.FeatureCache(feats, cap), min_piece_rows=2048,
+                              second=ginex.FeatureCache(feats, cap))
+        cold = ginex.Executor(ginex.FeatureCache(feats, cap))
+        out = None
+        reused = 0
+        for k in range(4):
+            seeds, so = seed_batches(train, cfg.batch, S, cfg.seed, first_batch=k * S)
+            samp = ginex.sample_superbatch(c.w.offsets, c.w.indices, seeds.cuda(), so.numpy(),
+                                           cfg.fanout, rng_seed=0, first_batch_index=k * S)
+            cs = ginex.changeset(n, samp.ids, samp.ids_offsets, cap)
+            io = samp.ids_offsets
+            longest = int(np.diff(io).max())
+            if out is None or out.shape[0] < longest:
+                out = torch.empty((longest, cfg.feat_dim), dtype=torch.float32, device="cuda")
+            if k > 0:
+                held = warm.cache.addr[cs.init_ids.long()] >= 0
+                reused += int(held.sum())
+            ids_h = samp.ids.cpu().numpy()
+            for ex, streamed in ((warm, k % 2 == 0), (cold, False)):
+                got = {}
+
+                def keep(i, rows):
+                    got[i] = out[:rows].clone()
+                ex.run(samp, cs, out, streamed=streamed, after_gather=keep)
+                torch.cuda.synchronize()
+                for i in range(S):
+                    g = got[i].cpu().numpy().view(np.uint8).reshape(got[i].shape[0], -1)
+                    assert np.array_equal(g, sb[ids_h[io[i]:io[i + 1]]]), (cap, k, i)
+            a_w, a_c = warm.cache.addr.cpu().numpy(), cold.cache.addr.cpu().numpy()
+            assert np.array_equal(a_w, a_c), (cap, k)
+            held = np.nonzero(a_c >= 0)[0]
+            lines = torch.from_numpy(a_c[held]).long().cuda()
+            assert torch.equal(warm.cache.rows[lines], cold.cache.rows[lines]), (cap, k)
+        assert reused > 0      # the superbatches do share rows, so the warm path was taken
