@@ -263,7 +263,7 @@ def neighbor_cache_leg(ginex, w, samp, run):
     cfg = w.cfg
     E = w.indices.numel()
     # this leg runs last and needs no features: hand their pinned memory back first
-    run.cache = run.batch_input = run.ws = None
+    run.cache = run.executor = run.batch_input = run.ws = None
     w.features = None
     import gc
     gc.collect()
