@@ -197,6 +197,40 @@ def _changeset(fn, num_nodes, ids, ids_offsets, cap):
                 in_positions=c[:n], cs_offsets=cs_offsets, miss_count=miss[:S])
 
 
+def _changeset_resume(fn, num_nodes, ids, ids_offsets, cap, start_ids):
+    ids, ids_offsets, start_ids = _i32(ids), _i64(ids_offsets), _i32(start_ids)
+    assert len(start_ids) <= cap
+    S = len(ids_offsets) - 1
+    init_ids = np.zeros(max(cap, 1), dtype=np.int32)
+    final_ids = np.zeros(max(cap, 1), dtype=np.int32)
+    init_count = np.zeros(1, dtype=np.int64)
+    cs_offsets = np.zeros(S + 1, dtype=np.int64)
+    miss = np.zeros(max(S, 1), dtype=np.int64)
+    capacity = max(len(ids), 1)
+    a, b, c = (np.zeros(capacity, dtype=np.int32) for _ in range(3))
+    st = start_ids if len(start_ids) else np.zeros(1, dtype=np.int32)
+    rc = fn(C.c_int64(num_nodes), _p(ids), _p(ids_offsets), C.c_int32(S), C.c_int64(cap),
+            _p(st), C.c_int64(len(start_ids)), _p(final_ids), _p(init_ids), _p(init_count),
+            _p(a), _p(b), _p(c), C.c_int64(capacity), _p(cs_offsets), _p(miss))
+    assert rc == 0
+    n = int(cs_offsets[S])
+    return dict(init_ids=init_ids[:int(init_count[0])], in_ids=a[:n], out_ids=b[:n],
+                in_positions=c[:n], cs_offsets=cs_offsets, miss_count=miss[:S],
+                final_ids=final_ids[:cap])
+
+
+def changeset_resume(num_nodes, ids, ids_offsets, cap, start_ids):
+    """Belady changesets from a given cache state (line r holds start_ids[r]); the result also
+    holds ``final_ids``, the row of every line after the last iteration (-1 = empty)."""
+    return _changeset_resume(lib().oracle_changeset_resume, num_nodes, ids, ids_offsets, cap,
+                             start_ids)
+
+
+def changeset_resume_by_sorting(num_nodes, ids, ids_offsets, cap, start_ids):
+    return _changeset_resume(lib().oracle_changeset_resume_by_sorting, num_nodes, ids,
+                             ids_offsets, cap, start_ids)
+
+
 def changeset(num_nodes, ids, ids_offsets, cap):
     """Belady changesets with a priority queue (the variant used at scale)."""
     return _changeset(lib().oracle_changeset, num_nodes, ids, ids_offsets, cap)

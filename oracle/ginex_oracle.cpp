@@ -14,6 +14,9 @@
 //   next_use               naive forward scan, the worked five-node example of the paper
 //   changeset (heap)       the sort-based definition, exhaustive search of all eviction
 //                          choices on tiny traces, LRU and static-cache upper bounds
+//   changeset_resume       equals the standard changeset when started from the standard
+//                          prefetch, the sort-based definition, exhaustive search from the
+//                          given start state, a line-by-line replay of its final state
 //   changeset_lru          a textbook LRU list on single-access traces, the closed form of a
 //                          cyclic trace, the sort-based definition, the stand-alone LRU
 //                          miss counter, Belady's miss count as a lower bound
@@ -385,6 +388,17 @@ struct ChangesetOut {
 //   has not been used yet has key S, larger than any used row's.
 enum Policy { BELADY = 0, LRU = 1 };
 
+// Cache state carried from one superbatch into the next (an extension: the paper starts every
+// superbatch from a fresh prefetch, Section 3.1).  start_ids[r] is the row held by cache
+// line r when the superbatch begins (start_count <= cap lines are occupied, from line 0);
+// it replaces the prefetched C_0.  final_ids[line] receives the row each line holds after
+// the last iteration (-1 = empty).
+struct Carry {
+  const int32_t* start_ids;
+  int64_t start_count;
+  int32_t* final_ids;
+};
+
 inline int32_t key_after_access(Policy policy, int32_t S, int32_t i, int32_t next) {
   return policy == BELADY ? next : S - 1 - i;
 }
@@ -396,12 +410,13 @@ int32_t changeset_with_heap(Policy policy, int64_t num_nodes, const int32_t* ids
                             const int64_t* ids_offsets, int32_t S, int64_t cap,
                             int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
                             int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
-                            int64_t* cs_offsets, int64_t* miss_count);
+                            int64_t* cs_offsets, int64_t* miss_count, const Carry* carry = nullptr);
 int32_t changeset_from_definition(Policy policy, int64_t num_nodes, const int32_t* ids,
                                   const int64_t* ids_offsets, int32_t S, int64_t cap,
                                   int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
                                   int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
-                                  int64_t* cs_offsets, int64_t* miss_count);
+                                  int64_t* cs_offsets, int64_t* miss_count,
+                                  const Carry* carry = nullptr);
 
 }  // namespace
 
@@ -448,14 +463,16 @@ int32_t changeset_with_heap(Policy policy, int64_t num_nodes, const int32_t* ids
                             const int64_t* ids_offsets, int32_t S, int64_t cap,
                             int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
                             int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
-                            int64_t* cs_offsets, int64_t* miss_count) {
+                            int64_t* cs_offsets, int64_t* miss_count, const Carry* carry) {
   const int64_t total = ids_offsets[S];
   std::vector<int32_t> next_iter(total > 0 ? total : 1), first_iter(num_nodes);
   oracle_next_use(num_nodes, ids, ids_offsets, S, next_iter.data(), first_iter.data());
 
   ChangesetOut o{init_ids, init_count, in_ids, out_ids, in_positions, cs_capacity,
                  cs_offsets, miss_count};
-  std::vector<int32_t> init = initial_state(num_nodes, first_iter, cap);
+  std::vector<int32_t> init = carry ? std::vector<int32_t>(carry->start_ids,
+                                                           carry->start_ids + carry->start_count)
+                                    : initial_state(num_nodes, first_iter, cap);
   *init_count = (int64_t)init.size();
   std::vector<int32_t> line_of(num_nodes, -1), key_of(num_nodes, NEVER);
   typedef std::pair<int32_t, int32_t> Entry;  // (next, id); the largest is on top
@@ -537,6 +554,11 @@ int32_t changeset_with_heap(Policy policy, int64_t num_nodes, const int32_t* ids
     }
     cs_offsets[i + 1] = o.written;
   }
+  if (carry && carry->final_ids) {
+    for (int64_t l = 0; l < cap; ++l) carry->final_ids[l] = -1;
+    for (int64_t v = 0; v < num_nodes; ++v)
+      if (line_of[v] >= 0) carry->final_ids[line_of[v]] = (int32_t)v;
+  }
   return o.fits ? 0 : -1;
 }
 
@@ -547,13 +569,15 @@ int32_t changeset_from_definition(Policy policy, int64_t num_nodes, const int32_
                                   const int64_t* ids_offsets, int32_t S, int64_t cap,
                                   int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
                                   int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
-                                  int64_t* cs_offsets, int64_t* miss_count) {
+                                  int64_t* cs_offsets, int64_t* miss_count, const Carry* carry) {
   const int64_t total = ids_offsets[S];
   std::vector<int32_t> next_iter(total > 0 ? total : 1), first_iter(num_nodes);
   oracle_next_use(num_nodes, ids, ids_offsets, S, next_iter.data(), first_iter.data());
   ChangesetOut o{init_ids, init_count, in_ids, out_ids, in_positions, cs_capacity,
                  cs_offsets, miss_count};
-  std::vector<int32_t> init = initial_state(num_nodes, first_iter, cap);
+  std::vector<int32_t> init = carry ? std::vector<int32_t>(carry->start_ids,
+                                                           carry->start_ids + carry->start_count)
+                                    : initial_state(num_nodes, first_iter, cap);
   *init_count = (int64_t)init.size();
   // cache lines: node id and its next accessed iteration, -1 = empty line
   std::vector<int32_t> line_id(cap, -1), line_next(cap, NEVER), line_of(num_nodes, -1);
@@ -611,6 +635,8 @@ int32_t changeset_from_definition(Policy policy, int64_t num_nodes, const int32_
     }
     cs_offsets[i + 1] = o.written;
   }
+  if (carry && carry->final_ids)
+    for (int64_t l = 0; l < cap; ++l) carry->final_ids[l] = line_id[l];
   return o.fits ? 0 : -1;
 }
 
@@ -638,6 +664,33 @@ int32_t oracle_changeset_lru_by_sorting(int64_t num_nodes, const int32_t* ids,
   return changeset_from_definition(LRU, num_nodes, ids, ids_offsets, S, cap, init_ids,
                                    init_count, in_ids, out_ids, in_positions, cs_capacity,
                                    cs_offsets, miss_count);
+}
+
+// Belady changesets of a superbatch that starts from a given cache state instead of a
+// fresh prefetch (see Carry); init_ids/init_count echo the start state.
+int32_t oracle_changeset_resume(int64_t num_nodes, const int32_t* ids, const int64_t* ids_offsets,
+                                int32_t S, int64_t cap, const int32_t* start_ids,
+                                int64_t start_count, int32_t* final_ids, int32_t* init_ids,
+                                int64_t* init_count, int32_t* in_ids, int32_t* out_ids,
+                                int32_t* in_positions, int64_t cs_capacity, int64_t* cs_offsets,
+                                int64_t* miss_count) {
+  const Carry carry{start_ids, start_count, final_ids};
+  return changeset_with_heap(BELADY, num_nodes, ids, ids_offsets, S, cap, init_ids, init_count,
+                             in_ids, out_ids, in_positions, cs_capacity, cs_offsets, miss_count,
+                             &carry);
+}
+
+int32_t oracle_changeset_resume_by_sorting(int64_t num_nodes, const int32_t* ids,
+                                           const int64_t* ids_offsets, int32_t S, int64_t cap,
+                                           const int32_t* start_ids, int64_t start_count,
+                                           int32_t* final_ids, int32_t* init_ids,
+                                           int64_t* init_count, int32_t* in_ids, int32_t* out_ids,
+                                           int32_t* in_positions, int64_t cs_capacity,
+                                           int64_t* cs_offsets, int64_t* miss_count) {
+  const Carry carry{start_ids, start_count, final_ids};
+  return changeset_from_definition(BELADY, num_nodes, ids, ids_offsets, S, cap, init_ids,
+                                   init_count, in_ids, out_ids, in_positions, cs_capacity,
+                                   cs_offsets, miss_count, &carry);
 }
 
 // Miss count of a least-recently-used cache started from the same C_0 under

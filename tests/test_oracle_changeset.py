@@ -327,3 +327,100 @@ def test_lru_on_tiny_config_sits_between_belady_and_all_miss(tiny):
         assert bel["miss_count"].sum() <= total <= len(r["ids"])
         if cap >= max(len(x) for x in tr):
             assert total == oracle.lru_misses(n, r["ids"], r["ids_offsets"], cap, lru["init_ids"])
+
+
+# ---- changesets from a carried cache state (an extension; Section 3.1 re-initializes) ------
+
+def replay_lines(cap, start, tr, cs):
+    """Replays changesets on explicit cache lines; rows beyond the evicted ones take the free
+    lines in ascending order.  Returns the per-iteration states and the final line table."""
+    lines = [-1] * cap
+    for r, v in enumerate(start):
+        lines[r] = int(v)
+    where = {v: r for r, v in enumerate(lines) if v >= 0}
+    states, total = [set(where)], 0
+    for i, cur in enumerate(tr):
+        lo, hi = cs["cs_offsets"][i], cs["cs_offsets"][i + 1]
+        ins, outs, pos = cs["in_ids"][lo:hi], cs["out_ids"][lo:hi], cs["in_positions"][lo:hi]
+        misses = [v for v in cur if v not in where]
+        assert cs["miss_count"][i] == len(misses)
+        total += len(misses)
+        assert all(cur[p] == v for p, v in zip(pos, ins)) and list(pos) == sorted(pos)
+        freed = []
+        for o in outs:
+            if o >= 0:
+                freed.append(where.pop(int(o)))
+                lines[freed[-1]] = -1
+        assert freed == sorted(freed)
+        for j, v in enumerate(ins):
+            assert v in misses
+            line = freed[j] if j < len(freed) else lines.index(-1)
+            lines[line] = int(v)
+            where[int(v)] = line
+        assert len(where) <= cap
+        states.append(set(where))
+    return states, total, lines
+
+
+def test_resume_from_the_standard_prefetch_is_the_standard_changeset():
+    rng = np.random.default_rng(31)
+    for _ in range(200):
+        n, S, cap = int(rng.integers(1, 40)), int(rng.integers(1, 12)), int(rng.integers(0, 12))
+        tr = [[int(v) for v in x] for x in random_trace(rng, n, S, 15)]
+        ids, off = flat(tr)
+        std = oracle.changeset(n, ids, off, cap)
+        res = oracle.changeset_resume(n, ids, off, cap, std["init_ids"])
+        for k in std:
+            assert np.array_equal(std[k], res[k]), k
+        _, _, lines = replay_lines(cap, std["init_ids"], tr, std)
+        assert list(res["final_ids"]) == lines
+
+
+def test_resume_heap_equals_definition_and_is_optimal_for_its_start_state():
+    rng = np.random.default_rng(32)
+    pressure = 0
+    for trial in range(300):
+        small = trial % 2 == 0          # small cases also go through the exhaustive search
+        n = int(rng.integers(2, 7 if small else 40))
+        S = int(rng.integers(1, 6 if small else 12))
+        cap = int(rng.integers(0, 4 if small else 12))
+        tr = [[int(v) for v in x] for x in random_trace(rng, n, S, 3 if small else 15)]
+        ids, off = flat(tr)
+        start = rng.permutation(n)[:int(rng.integers(0, min(cap, n) + 1))].astype(np.int32)
+        a = oracle.changeset_resume(n, ids, off, cap, start)
+        b = oracle.changeset_resume_by_sorting(n, ids, off, cap, start)
+        for k in a:
+            assert np.array_equal(a[k], b[k]), k
+        assert np.array_equal(a["init_ids"], start)
+        states, total, lines = replay_lines(cap, start, tr, a)
+        assert list(a["final_ids"]) == lines
+        # the recurrence, with rows that are never accessed ranked last
+        nxt, first = oracle.next_use(n, ids, off)
+        key = {v: first[v] for v in range(n)}
+        p = 0
+        for i, cur in enumerate(tr):
+            for v in cur:
+                key[v] = nxt[p]
+                p += 1
+            cand = sorted((key[v], v not in states[i], v) for v in states[i] | set(cur))
+            assert {v for _, _, v in cand[:cap]} == states[i + 1]
+        if small:
+            assert total == optimal_misses(tr, cap, [int(v) for v in start])
+            pressure += total > 0
+    assert pressure > 50
+
+
+def test_resumed_superbatches_chain_through_their_final_states():
+    rng = np.random.default_rng(33)
+    for _ in range(50):
+        n, cap = 30, int(rng.integers(1, 12))
+        state = rng.permutation(n)[:cap].astype(np.int32)
+        for k in range(4):
+            tr = [[int(v) for v in x] for x in random_trace(rng, n, 6, 10)]
+            ids, off = flat(tr)
+            cs = oracle.changeset_resume(n, ids, off, cap, state)
+            _, _, lines = replay_lines(cap, state, tr, cs)
+            assert list(cs["final_ids"]) == lines and -1 not in lines   # a full cache stays full
+            # rows that both superbatches use and the cache kept are hits from the start
+            assert cs["miss_count"][0] == len(set(tr[0]) - set(state.tolist()))
+            state = cs["final_ids"]
