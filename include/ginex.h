@@ -178,6 +178,24 @@ int32_t ginex_changeset_lru(
     int64_t* total_changes /*host*/, int64_t* init_ready /*host [S] or NULL*/,
     void* ws, size_t ws_bytes, void* stream);
 
+/* Belady changesets of a superbatch that starts from the cache the previous superbatch left
+ * behind (an extension: the paper prefetches a fresh C_0 for every superbatch, Section 3.1,
+ * which costs one slow-tier read per distinct row per superbatch; carried over, only rows
+ * that are not resident any more are read, as ordinary misses).  C_0 is given: cache line r
+ * holds start_ids[r] (device, [cap], all distinct and in range: checked, GINEX_ERR_INPUT).
+ * The cache must be full, 1 <= cap.  A resident row that the superbatch never accesses has
+ * next accessed iteration "never" and is evicted first (larger id first).  The recurrence,
+ * the lists and their order are those of ginex_changeset.  final_ids (device, [cap], may be
+ * NULL) receives the row of every line after the last iteration: the start_ids of the next
+ * superbatch.  No cache initialization is needed between the two superbatches. */
+int32_t ginex_changeset_resume(
+    int64_t num_nodes, const int32_t* ids, const int64_t* ids_offsets /*host [S+1]*/,
+    int32_t S, int64_t cap, const int32_t* start_ids /*[cap]*/, int32_t* final_ids /*[cap]*/,
+    int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
+    int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
+    int64_t* total_changes /*host*/,
+    void* ws, size_t ws_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------------
  * Feature cache (Section 3.3 "Feature Cache Structure"): a 2-D array of `cap` rows in
  * HBM plus an address table with one entry per node (cache line, or -1).  `slow` is the

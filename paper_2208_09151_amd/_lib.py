@@ -33,6 +33,8 @@ SIGNATURES = {
                               vp, sz, vp]),
     "ginex_changeset_lru": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp,
                                   vp, sz, vp]),
+    "ginex_changeset_resume": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp,
+                                     vp, sz, vp]),
     "ginex_cache_init": (i32, [C.POINTER(CacheDesc), vp, i64, vp]),
     "ginex_cache_init_part": (i32, [C.POINTER(CacheDesc), vp, i64, i64, vp]),
     "ginex_cache_init_warm": (i32, [C.POINTER(CacheDesc), C.POINTER(CacheDesc), vp, i64, i64, vp]),

@@ -191,6 +191,7 @@ class ChangesetResult:
     cs_offsets: np.ndarray      # [S+1] host
     miss_count: np.ndarray      # [S] host
     init_ready: np.ndarray = None   # [S] host: rows of C_0 first accessed in iterations 0..i
+    final_ids: torch.Tensor = None  # resumed superbatches: row of every line after the last iteration
 
 
 def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady"):
@@ -226,6 +227,40 @@ def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady")
     n = int(total_changes[0])
     return ChangesetResult(init_ids[:int(init_count[0])], in_ids[:n], out_ids[:n], in_pos[:n],
                            cs_off.cpu().numpy(), miss[:S].cpu().numpy(), init_ready[:S])
+
+
+def changeset_resume(num_nodes, ids, ids_offsets, start_ids, workspace=None):
+    """ginex_changeset_resume: Belady changesets from the cache state ``start_ids`` (device
+    int32 [cap], line r holds start_ids[r]).  ``init_ids`` of the result echoes the start state,
+    ``final_ids`` is the start state of the next superbatch."""
+    lib = _lib.load()
+    _dev(ids, torch.int32)
+    _dev(start_ids, torch.int32)
+    io = np.ascontiguousarray(np.asarray(ids_offsets), dtype=np.int64)
+    S = len(io) - 1
+    total = int(io[-1]) if S >= 0 else 0
+    cap = start_ids.numel()
+    dev = ids.device
+    need = lib.ginex_changeset_workspace_bytes(num_nodes, total, S, cap)
+    if need == 0:
+        raise GinexError(-1, lib.ginex_last_error().decode())
+    ws = workspace if workspace is not None and workspace.numel() >= need else _workspace(need, dev)
+    final_ids = torch.empty(cap, dtype=torch.int32, device=dev)
+    cs_cap = max(total, 1)
+    in_ids = torch.empty(cs_cap, dtype=torch.int32, device=dev)
+    out_ids = torch.empty(cs_cap, dtype=torch.int32, device=dev)
+    in_pos = torch.empty(cs_cap, dtype=torch.int32, device=dev)
+    cs_off = torch.empty(S + 1, dtype=torch.int64, device=dev)
+    miss = torch.empty(max(S, 1), dtype=torch.int64, device=dev)
+    total_changes = np.zeros(1, dtype=np.int64)
+    rc = lib.ginex_changeset_resume(num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(start_ids),
+                                    _ptr(final_ids), _ptr(in_ids), _ptr(out_ids), _ptr(in_pos),
+                                    cs_cap, _ptr(cs_off), _ptr(miss), _np_ptr(total_changes),
+                                    _ptr(ws), ws.numel(), _stream())
+    _check(rc)
+    n = int(total_changes[0])
+    return ChangesetResult(start_ids, in_ids[:n], out_ids[:n], in_pos[:n], cs_off.cpu().numpy(),
+                           miss[:S].cpu().numpy(), np.full(S, cap, dtype=np.int64), final_ids)
 
 
 class FeatureCache:

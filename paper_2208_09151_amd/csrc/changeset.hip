@@ -220,6 +220,43 @@ __global__ __launch_bounds__(TB) void k_init_state(const uint64_t* __restrict__ 
     if (lds_hist[j]) atomicAdd(&st.rhist[j], lds_hist[j]);
 }
 
+// first_of[node] = first iteration that accesses the node (the array is preset to S, "never")
+__global__ __launch_bounds__(TB) void k_scatter_first(const uint64_t* __restrict__ heads,
+                                                      int64_t count,
+                                                      int32_t* __restrict__ first_of) {
+  const int64_t r = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (r < count) first_of[heads[r] & 0xFFFFFFFFu] = (int32_t)(heads[r] >> 32);
+}
+
+// The state a superbatch starts from when the cache is carried over: line s holds
+// start_ids[s], keyed by the row's first access in this superbatch.  A row that is never
+// accessed is a dead resident from the start.  bad[0] counts ids outside [0, num_nodes) and
+// ids that occur twice (both are skipped).
+__global__ __launch_bounds__(TB) void k_init_state_resume(const int32_t* __restrict__ start_ids,
+                                                          const int32_t* __restrict__ first_of,
+                                                          State st,
+                                                          unsigned long long* __restrict__ bad) {
+  extern __shared__ uint32_t lds_hist[];  // S+1 bins
+  for (int j = threadIdx.x; j <= st.S; j += TB) lds_hist[j] = 0;
+  __syncthreads();
+  const int64_t span = (int64_t)gridDim.x * TB;
+  for (int64_t s = (int64_t)blockIdx.x * TB + threadIdx.x; s < st.cap; s += span) {
+    const int32_t v = start_ids[s];
+    if (v < 0 || v >= st.num_nodes || atomicCAS(&st.addr[v], -1, (int32_t)s) != -1) {
+      atomicAdd(bad, 1ull);
+      continue;
+    }
+    const int32_t first = first_of[v];
+    st.res_id[s] = v;
+    st.res_next[s] = first;
+    atomicAdd(&lds_hist[first], 1u);
+    if (first == st.S) atomicOr(&st.dead_bits[(uint32_t)v >> 5], 1u << ((uint32_t)v & 31));
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j <= st.S; j += TB)
+    if (lds_hist[j]) atomicAdd(&st.rhist[j], lds_hist[j]);
+}
+
 __global__ __launch_bounds__(TB) void k_copy_init(const uint64_t* __restrict__ heads, int64_t count,
                                                   int32_t* __restrict__ init_ids) {
   const int64_t s = (int64_t)blockIdx.x * TB + threadIdx.x;
@@ -731,6 +768,7 @@ struct Workspace {
   uint32_t* hist;
   uint32_t* head_tiles;
   int32_t* next_iter;
+  int32_t* first_of;
   int64_t* d_offsets;
   int64_t* d_ready;
   int64_t* d_cs_offsets;
@@ -760,6 +798,7 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   w.look_tiles = ceil_div(t, LOOK_TILE);
   w.head_tiles = a.take<uint32_t>(w.look_tiles + 1 + scan_scratch_elems(w.look_tiles + 1));
   w.next_iter = a.take<int32_t>(t);
+  w.first_of = a.take<int32_t>(num_nodes);   // resumed superbatches only
   w.d_offsets = a.take<int64_t>(S + 1);
   w.d_ready = a.take<int64_t>(S);
   w.d_cs_offsets = a.take<int64_t>(S + 1);
@@ -831,7 +870,8 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                       int64_t* init_count, int32_t* in_ids, int32_t* out_ids,
                       int32_t* in_positions, int64_t cs_capacity, int64_t* cs_offsets,
                       int64_t* miss_count, int64_t* total_changes, int64_t* init_ready,
-                      void* ws, size_t ws_bytes, void* stream) {
+                      const int32_t* start_ids, int32_t* final_ids, void* ws, size_t ws_bytes,
+                      void* stream) {
   if (!ids_offsets || !init_count || !cs_offsets || !miss_count || !total_changes || !ws)
     return fail(GINEX_ERR_ARG, "%s: a required pointer is null", who);
   if (S >= 1 && ids_offsets[0] != 0)
@@ -847,7 +887,10 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   const int64_t total = S >= 1 ? ids_offsets[S] : 0;
   if (int32_t rc = check_shape(num_nodes, total, S, cap, who)) return rc;
   if (total > 0 && !ids) return fail(GINEX_ERR_ARG, "%s: ids is null", who);
-  if (cap > 0 && !init_ids) return fail(GINEX_ERR_ARG, "%s: init_ids is null", who);
+  if (cap > 0 && !init_ids && !start_ids)
+    return fail(GINEX_ERR_ARG, "%s: init_ids is null", who);
+  if (start_ids && cap < 1)
+    return fail(GINEX_ERR_ARG, "%s: a carried cache needs cap >= 1", who);
   if (cs_capacity < 0 || (cs_capacity > 0 && (!in_ids || !out_ids || !in_positions)))
     return fail(GINEX_ERR_ARG, "%s: bad changeset output arrays", who);
   const int64_t bound = total < num_nodes ? total : num_nodes;
@@ -864,11 +907,14 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                            hipMemcpyHostToDevice, st));
   GINEX_HIP(fill_async<int64_t>(miss_count, S, 0, st));
   GINEX_HIP(fill_async<int64_t>(cs_offsets, S + 1, 0, st));
-  *init_count = 0;
+  *init_count = start_ids ? cap : 0;
   *total_changes = 0;
   if (init_ready)
-    for (int32_t i = 0; i < S; ++i) init_ready[i] = 0;
+    for (int32_t i = 0; i < S; ++i) init_ready[i] = start_ids ? cap : 0;
   if (total == 0) {
+    if (start_ids && final_ids)
+      GINEX_HIP(hipMemcpyAsync(final_ids, start_ids, sizeof(int32_t) * cap,
+                               hipMemcpyDeviceToDevice, st));
     GINEX_HIP(hipStreamSynchronize(st));
     return GINEX_OK;
   }
@@ -916,19 +962,20 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   hipLaunchKernelGGL(k_heads_write, dim3((unsigned)w.look_tiles), dim3(TB), off_lds, st, sorted,
                      total, w.d_offsets, S, w.head_tiles, w.heads_a);
   GINEX_LAUNCH_CHECK();
-  uint64_t* heads = nullptr;
-  GINEX_HIP(radix_sort_u64(w.heads_a, w.heads_b, distinct, 32, 32 + bits_for(S), w.hist, st,
-                           &heads));
-  const int64_t n_init = distinct < cap ? distinct : cap;
+  uint64_t* heads = w.heads_a;
+  if (!start_ids)   // C_0: the heads in order of first access
+    GINEX_HIP(radix_sort_u64(w.heads_a, w.heads_b, distinct, 32, 32 + bits_for(S), w.hist, st,
+                             &heads));
+  const int64_t n_init = start_ids ? cap : (distinct < cap ? distinct : cap);
   *init_count = n_init;
-  if (init_ready && n_init > 0) {   // every path below waits for the stream before it returns
+  if (init_ready && n_init > 0 && !start_ids) {   // every path below waits for the stream before it returns
     hipLaunchKernelGGL(k_init_ready, dim3((unsigned)ceil_div(S, TB)), dim3(TB), 0, st, heads, n_init,
                        S, w.d_ready);
     GINEX_LAUNCH_CHECK();
     GINEX_HIP(hipMemcpyAsync(init_ready, w.d_ready, sizeof(int64_t) * S, hipMemcpyDeviceToHost,
                              st));
   }
-  if (distinct <= cap || cap == 0) {
+  if (!start_ids && (distinct <= cap || cap == 0)) {
     // everything fits (no row ever misses), or there is no cache (every row misses and
     // nothing is inserted): all changesets are empty
     if (n_init > 0) {
@@ -962,9 +1009,25 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   {
     int64_t blocks = ceil_div(cap, TB * 8);
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(k_init_state, dim3((unsigned)blocks), dim3(TB), sizeof(uint32_t) * (S + 1),
-                       st, heads, cap, init_ids, state);
-    GINEX_LAUNCH_CHECK();
+    if (start_ids) {
+      unsigned long long bad = 0;
+      GINEX_HIP(fill_async<int32_t>(w.first_of, num_nodes, S, st));
+      GINEX_HIP(fill_async<unsigned long long>(w.d_counts, 1, 0ull, st));
+      hipLaunchKernelGGL(k_scatter_first, dim3((unsigned)ceil_div(distinct, TB)), dim3(TB), 0, st,
+                         heads, distinct, w.first_of);
+      hipLaunchKernelGGL(k_init_state_resume, dim3((unsigned)blocks), dim3(TB),
+                         sizeof(uint32_t) * (S + 1), st, start_ids, w.first_of, state, w.d_counts);
+      GINEX_LAUNCH_CHECK();
+      GINEX_HIP(hipMemcpyAsync(&bad, w.d_counts, sizeof(bad), hipMemcpyDeviceToHost, st));
+      GINEX_HIP(hipStreamSynchronize(st));
+      if (bad)
+        return fail(GINEX_ERR_INPUT, "%s: %llu entries of start_ids are out of range or repeated",
+                    who, bad);
+    } else {
+      hipLaunchKernelGGL(k_init_state, dim3((unsigned)blocks), dim3(TB),
+                         sizeof(uint32_t) * (S + 1), st, heads, cap, init_ids, state);
+      GINEX_LAUNCH_CHECK();
+    }
   }
 
   // part 3: the recurrence, with no host round trip between iterations
@@ -1008,6 +1071,9 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       GINEX_LAUNCH_CHECK();
     }
   }
+  if (start_ids && final_ids)
+    GINEX_HIP(hipMemcpyAsync(final_ids, state.res_id, sizeof(int32_t) * cap,
+                             hipMemcpyDeviceToDevice, st));
   GINEX_HIP(hipMemcpyAsync(total_changes, cs_offsets + S, sizeof(int64_t), hipMemcpyDeviceToHost,
                            st));
   GINEX_HIP(hipStreamSynchronize(st));
@@ -1029,7 +1095,25 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
                                    size_t ws_bytes, void* stream) {
   return changeset_run("ginex_changeset", false, num_nodes, ids, ids_offsets, S, cap, init_ids,
                        init_count, in_ids, out_ids, in_positions, cs_capacity, cs_offsets,
-                       miss_count, total_changes, init_ready, ws, ws_bytes, stream);
+                       miss_count, total_changes, init_ready, nullptr, nullptr, ws, ws_bytes,
+                       stream);
+}
+
+extern "C" int32_t ginex_changeset_resume(int64_t num_nodes, const int32_t* ids,
+                                          const int64_t* ids_offsets, int32_t S, int64_t cap,
+                                          const int32_t* start_ids, int32_t* final_ids,
+                                          int32_t* in_ids, int32_t* out_ids,
+                                          int32_t* in_positions, int64_t cs_capacity,
+                                          int64_t* cs_offsets, int64_t* miss_count,
+                                          int64_t* total_changes, void* ws, size_t ws_bytes,
+                                          void* stream) {
+  if (!start_ids)
+    return fail(GINEX_ERR_ARG, "ginex_changeset_resume: start_ids is null");
+  int64_t init_count = 0;
+  return changeset_run("ginex_changeset_resume", false, num_nodes, ids, ids_offsets, S, cap,
+                       nullptr, &init_count, in_ids, out_ids, in_positions, cs_capacity,
+                       cs_offsets, miss_count, total_changes, nullptr, start_ids, final_ids, ws,
+                       ws_bytes, stream);
 }
 
 extern "C" int32_t ginex_changeset_lru(int64_t num_nodes, const int32_t* ids,
@@ -1042,5 +1126,6 @@ extern "C" int32_t ginex_changeset_lru(int64_t num_nodes, const int32_t* ids,
                                        void* stream) {
   return changeset_run("ginex_changeset_lru", true, num_nodes, ids, ids_offsets, S, cap, init_ids,
                        init_count, in_ids, out_ids, in_positions, cs_capacity, cs_offsets,
-                       miss_count, total_changes, init_ready, ws, ws_bytes, stream);
+                       miss_count, total_changes, init_ready, nullptr, nullptr, ws, ws_bytes,
+                       stream);
 }

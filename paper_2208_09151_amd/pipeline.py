@@ -60,12 +60,15 @@ class Executor:
             self.events.append(torch.cuda.Event(enable_timing=True))
         return self.events[k]
 
-    def run(self, samp, cs, out, streamed=True, before_gather=None, after_gather=None):
+    def run(self, samp, cs, out, streamed=True, before_gather=None, after_gather=None,
+            resumed=False):
         """``out``: device buffer [>= longest iteration, feat_dim] that receives every batch
         input in turn; ``before_gather(i)`` / ``after_gather(i, n)`` are called right before
         and after the gather kernel of iteration i is enqueued (timing events; the consumer
-        enqueues its own work on the current stream in ``after_gather``).  Returns the event
-        that marks the end of the initialization."""
+        enqueues its own work on the current stream in ``after_gather``).  With ``resumed``
+        the cache already holds ``cs.init_ids`` line by line (the changesets come from
+        ``changeset_resume`` on the state the last superbatch left) and nothing is loaded.
+        Returns the event that marks the end of the initialization."""
         cache = self.caches[self.turn]
         prev = self.caches[self.turn - 1] if self.warm and len(self.caches) > 1 else None
 
@@ -84,7 +87,10 @@ class Executor:
         bases = (cs.in_ids.data_ptr(), cs.out_ids.data_ptr(), cs.in_positions.data_ptr())
         init_ptr = cs.init_ids.data_ptr()
         wait_for = None
-        if streamed and cs.init_ready is not None and S > 0:
+        if resumed:
+            self._event(0).record(main)
+            cuts = [n_init]
+        elif streamed and cs.init_ready is not None and S > 0:
             ready = cs.init_ready.tolist()
             fs = self.fill_stream
             fp = fs.cuda_stream
@@ -126,7 +132,7 @@ class Executor:
             if nc:
                 cache.update_raw(out_ptr, bases[0] + 4 * co[i], bases[1] + 4 * co[i],
                                  bases[2] + 4 * co[i], nc, mp)
-        if len(self.caches) > 1:
+        if len(self.caches) > 1 and not resumed:
             self.turn = 1 - self.turn
             self.warm = True
         return self.events[len(cuts) - 1]
@@ -150,6 +156,7 @@ class InspectorPipeline:
                       torch.empty(cr, dtype=torch.int64, device=dev),
                       torch.empty(cc, dtype=torch.int32, device=dev)) for _ in range(2)]
         self.streams = (torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev))
+        self.state = None
 
     def _sample(self, k, seeds, seed_offsets, first_batch, rng_seed):
         with torch.cuda.stream(self.streams[0]):
@@ -157,8 +164,19 @@ class InspectorPipeline:
                                          rng_seed=rng_seed, first_batch_index=first_batch,
                                          workspace=self.ws_sample, out=self.bufs[k % 2])
 
+    def carry_cache_from(self, start_ids):
+        """From now on every superbatch starts from the cache state the one before it left
+        (``changeset_resume``); ``start_ids`` (device int32 [cap]) is what the cache holds
+        now, line by line.  ``None`` goes back to a fresh prefetch per superbatch."""
+        self.state = start_ids
+
     def _changeset(self, samp):
         with torch.cuda.stream(self.streams[1]):
+            if self.state is not None:
+                cs = api.changeset_resume(self.num_nodes, samp.ids, samp.ids_offsets, self.state,
+                                          workspace=self.ws_changeset)
+                self.state = cs.final_ids
+                return cs
             return api.changeset(self.num_nodes, samp.ids, samp.ids_offsets, self.cap,
                                  workspace=self.ws_changeset)
 

@@ -602,3 +602,86 @@ def test_warm_initialization_leaves_the_same_cache_as_a_cold_one(ginex, case2):
             lines = torch.from_numpy(a_c[held]).long().cuda()
             assert torch.equal(warm.cache.rows[lines], cold.cache.rows[lines]), (cap, k)
         assert reused > 0      # the superbatches do share rows, so the warm path was taken
+
+
+# ---- cache carried from superbatch to superbatch ---------------------------------------------
+
+def check_resumed(res, ref):
+    check_changeset(res, ref)
+    assert np.array_equal(res.final_ids.cpu().numpy(), ref["final_ids"])
+
+
+def test_resumed_changeset_random_small_traces(ginex):
+    rng = np.random.default_rng(51)
+    for trial in range(60):
+        n = int(rng.integers(2, 400))
+        S = int(rng.integers(1, 14))
+        cap = int(rng.integers(1, n + 1))
+        ids, off = random_trace(rng, n, S, int(rng.integers(1, 200)))
+        start = rng.permutation(n)[:cap].astype(np.int32)
+        ref = oracle.changeset_resume(n, ids, off, cap, start)
+        ids_d = dev(ids) if len(ids) else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
+        res = ginex.changeset_resume(n, ids_d, off, dev(start))
+        try:
+            check_resumed(res, ref)
+        except AssertionError:
+            print("failing trial", trial, n, S, cap, flush=True)
+            raise
+    # a start state with a repeated or an out-of-range row is refused before the loop runs
+    ids, off = random_trace(rng, 50, 4, 20)
+    for bad in ([1, 2, 2, 3], [1, 2, 50, 3], [1, -1, 4, 3]):
+        with pytest.raises(ginex.GinexError):
+            ginex.changeset_resume(50, dev(ids), off, dev(np.array(bad, dtype=np.int32)))
+
+
+def test_carried_cache_over_consecutive_superbatches(ginex, case2):
+    from workload.configs import seed_batches, train_nodes
+    c = case2
+    cfg, n = c.cfg, c.cfg.num_nodes
+    S = 6
+    train = train_nodes(n, cfg.train_frac, cfg.seed)
+    feats = c.w.features
+    sb = feats.numpy().view(np.uint8).reshape(n, -1)
+    off, ind = c.off, c.ind
+    for cap in (cfg.cap, 20000):
+        # start: the rows of the highest out-degree nodes, as a static cache would hold
+        start = np.argsort(-np.bincount(ind, minlength=n), kind="stable")[:cap].astype(np.int32)
+        cache = ginex.FeatureCache(feats, cap)
+        cache.init(dev(start))
+        ex = ginex.Executor(cache)
+        state_d, state_h = dev(start), start
+        out = None
+        link_rows = 0
+        for k in range(3):
+            seeds, so = seed_batches(train, cfg.batch, S, cfg.seed, first_batch=k * S)
+            ref_s = oracle.sample_superbatch(off, ind, seeds.numpy(), so.numpy(), cfg.fanout,
+                                             rng_seed=0, first_batch_index=k * S)
+            samp = ginex.sample_superbatch(c.w.offsets, c.w.indices, seeds.cuda(), so.numpy(),
+                                           cfg.fanout, rng_seed=0, first_batch_index=k * S)
+            assert np.array_equal(samp.ids.cpu().numpy(), ref_s["ids"])
+            ids, io = ref_s["ids"], ref_s["ids_offsets"]
+            ref = oracle.changeset_resume(n, ids, io, cap, state_h)
+            cs = ginex.changeset_resume(n, samp.ids, samp.ids_offsets, state_d)
+            check_resumed(cs, ref)
+            longest = int(np.diff(io).max())
+            if out is None or out.shape[0] < longest:
+                out = torch.empty((longest, cfg.feat_dim), dtype=torch.float32, device="cuda")
+            got = {}
+
+            def keep(i, rows):
+                got[i] = out[:rows].clone()
+            ex.run(samp, cs, out, resumed=True, after_gather=keep)
+            torch.cuda.synchronize()
+            for i in range(S):
+                g = got[i].cpu().numpy().view(np.uint8).reshape(got[i].shape[0], -1)
+                assert np.array_equal(g, sb[ids[io[i]:io[i + 1]]]), (cap, k, i)
+            # the cache now holds exactly the final state, line by line, with the right bytes
+            final = ref["final_ids"]
+            addr = cache.addr.cpu().numpy()
+            assert np.array_equal(np.sort(np.nonzero(addr >= 0)[0]), np.sort(final))
+            assert np.array_equal(addr[final], np.arange(cap))
+            rows = cache.rows.cpu().numpy().view(np.uint8).reshape(cap, -1)
+            assert np.array_equal(rows, sb[final])
+            link_rows += int(ref["miss_count"].sum())
+            state_d, state_h = cs.final_ids, final
+        assert link_rows > 0
