@@ -253,6 +253,39 @@ def pipeline_leg(ginex, w, K):
         out[key + "_ms_per_superbatch"] = t * 1e3 / K
         out[key + "_edges_per_s"] = edges[0] / t
     out["warm_init_rows_found_in_previous_cache"] = reuse[0] / max(reuse[1], 1)
+
+    # The cache carried from superbatch to superbatch: no initialization at all, every
+    # superbatch starts from what the one before left (ginex_changeset_resume); only rows
+    # that are not resident any more cross the host link, as misses of the gathers.
+    # K more superbatches first bring the cache to its steady state.
+    more = []
+    for k in range(K, 2 * K):
+        seeds, so = seed_batches(train, cfg.batch, cfg.S, cfg.seed, first_batch=k * cfg.S)
+        more.append((seeds.cuda(), so.numpy(), k * cfg.S))
+    del executor
+    start = torch.argsort(torch.bincount(w.indices, minlength=cfg.num_nodes),
+                          descending=True)[:cfg.cap].to(torch.int32).contiguous()
+    cache.init(start)
+    carried = ginex.Executor(cache)
+    pipe.carry_cache_from(start)
+    stats = [0, 0, 0]
+
+    def execute_carried(k, samp, cs):
+        carried.run(samp, cs, batch_input, resumed=True)
+        torch.cuda.current_stream().synchronize()
+        stats[0] += int(samp.totals[2])
+        stats[1] += int(cs.miss_count.sum())
+        stats[2] += int(samp.totals[0])
+
+    pipe.run_with_executor(sbs, execute_carried, overlap=True)          # towards steady state
+    for key, overlap in (("whole_path_carried_cache_sequential", False),
+                         ("whole_path_carried_cache_overlapped", True)):
+        stats[:] = [0, 0, 0]
+        t = pipe.run_with_executor(more, execute_carried, overlap=overlap)
+        out[key + "_ms_per_superbatch"] = t * 1e3 / K
+        out[key + "_edges_per_s"] = stats[0] / t
+        out[key + "_miss_ratio"] = stats[1] / max(stats[2], 1)
+    pipe.carry_cache_from(None)
     return out
 
 

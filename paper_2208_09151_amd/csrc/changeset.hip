@@ -62,6 +62,8 @@ struct State {
   int32_t S;
   int64_t max_change;     // entries of out_slot / in_id / in_next
   int32_t lru;            // 0: Belady keys (next accessed iteration), 1: LRU keys
+  int32_t dead_scatter;   // evictions among the dead residents are found from the id bitmap
+                          // (large caches) instead of by a pass over all cache lines
 };
 
 // Iteration that holds flat position p: the largest i with off[i] <= p.  `off` is the
@@ -597,6 +599,43 @@ __device__ void p_evict_flags(const State& st, const Ctrl& c, int64_t vb) {
   if (threadIdx.x == 0) st.evict_tiles[vb] = total;
 }
 
+// Large caches, evictions among the dead residents only (the usual case once a cache is
+// full): the evicted rows are the set bits above T of the standing dead-row bitmap, a short
+// stretch at its upper end, so they are found from there and their lines flagged through
+// the address table, instead of reading the key and id of every cache line.  The flag
+// words are all zero when the phase starts (p_evict_emit clears what it consumes).
+__device__ void p_dead_scatter(const State& st, const Ctrl& c, int64_t words, int64_t vb) {
+  const int64_t t_word = c.T >> 5;
+  const int64_t base = (vb * TB + threadIdx.x) * BITS_WORDS;
+  if (base + BITS_WORDS <= t_word) return;
+#pragma unroll
+  for (int t = 0; t < BITS_WORDS; ++t) {
+    const int64_t w = base + t;
+    if (w >= words || w < t_word) continue;
+    uint32_t bits = st.dead_bits[w];
+    if (w == t_word) bits &= (c.T & 31) == 31 ? 0u : ~((2u << (c.T & 31)) - 1u);
+    while (bits) {
+      const int32_t v = (int32_t)(w * 32 + (__ffs(bits) - 1));
+      bits &= bits - 1;
+      const int32_t line = st.addr[v];   // a dead row is resident, so this is its line
+      if (line >= 0)
+        atomicOr((unsigned long long*)&st.evict_words[line >> 6], 1ull << (line & 63));
+    }
+  }
+}
+
+// Tile totals of flag words that p_dead_scatter has set.
+__device__ void p_evict_count(const State& st, int64_t vb) {
+  __shared__ uint32_t red[TB / WAVE];
+  uint32_t cnt = 0;
+  if (threadIdx.x < WAVE) {
+    const int64_t word_at = vb * WAVE + threadIdx.x;
+    if (word_at * WAVE < st.cap) cnt = (uint32_t)__popcll(st.evict_words[word_at]);
+  }
+  const uint32_t total = block_sum_u32(cnt, red);
+  if (threadIdx.x == 0) st.evict_tiles[vb] = total;
+}
+
 constexpr int IN_ITEMS = 8;
 
 __device__ void p_in_count(const State& st, const Ctrl& c, const Iter& it, int64_t vb) {
@@ -636,6 +675,7 @@ __device__ void p_evict_emit(const State& st, int32_t i, const Outputs& o, int64
   if (tile >= tiles) return;
   const int64_t word_at = tile * WAVE + lane_id();
   uint64_t word = word_at * WAVE < st.cap ? st.evict_words[word_at] : 0;
+  if (st.dead_scatter && word) st.evict_words[word_at] = 0;   // consumed: zero for p_dead_scatter
   const uint32_t mine = (uint32_t)__popcll(word);
   uint32_t at = st.evict_tiles[tile] + wave_inclusive_scan(mine) - mine;
   const int64_t dst = o.cs_offsets[i];
@@ -730,6 +770,11 @@ __global__ __launch_bounds__(BIG) void k_bits_find(State st, int64_t words, int6
   p_bits_find<BIG>(st, c.use_dead ? st.dead_bits : st.bitmap, words, parts);
 }
 
+__global__ __launch_bounds__(TB) void k_dead_scatter(State st, int64_t words) {
+  const Ctrl c = *st.ctrl;
+  if (c.n_change > 0 && c.use_dead) p_dead_scatter(st, c, words, blockIdx.x);
+}
+
 // blocks [0, evict_tiles): evictions per tile; next in_tiles blocks: insertions per tile;
 // the remaining blocks clear the select bitmap
 __global__ __launch_bounds__(TB) void k_tile_count(State st, Iter it, int64_t evict_tiles,
@@ -737,7 +782,10 @@ __global__ __launch_bounds__(TB) void k_tile_count(State st, Iter it, int64_t ev
   const Ctrl c = *st.ctrl;
   const int64_t vb = blockIdx.x;
   if (vb < evict_tiles) {
-    if (c.n_change > 0) p_evict_flags(st, c, vb);
+    if (c.n_change > 0) {
+      if (st.dead_scatter && c.use_dead) p_evict_count(st, vb);
+      else p_evict_flags(st, c, vb);
+    }
   } else if (vb < evict_tiles + in_tiles) {
     if (c.n_change > 0) p_in_count(st, c, it, vb - evict_tiles);
   } else if ((c.mode_res == MODE_SELECT || c.mode_in == MODE_SELECT) && !c.use_dead) {
@@ -902,6 +950,10 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   hipStream_t st = (hipStream_t)stream;
   State& state = w.st;
   state.lru = lru ? 1 : 0;
+  // Worth a tenth launch per iteration only where a pass over the cache lines is long;
+  // GINEX_DEAD_SCATTER=0/1 overrides the choice (both ways give the same lists).
+  const char* scatter_env = getenv("GINEX_DEAD_SCATTER");
+  state.dead_scatter = !lru && (scatter_env ? scatter_env[0] == '1' : cap >= (int64_t(1) << 20));
 
   GINEX_HIP(hipMemcpyAsync(w.d_offsets, ids_offsets, sizeof(int64_t) * (S + 1),
                            hipMemcpyHostToDevice, st));
@@ -1006,6 +1058,8 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   GINEX_HIP(fill_async<uint32_t>(state.ihist, S + 2, 0u, st));
   GINEX_HIP(fill_async<uint32_t>(state.bitmap, w.bit_words, 0u, st));
   GINEX_HIP(fill_async<uint32_t>(state.dead_bits, w.bit_words, 0u, st));
+  if (state.dead_scatter)
+    GINEX_HIP(fill_async<uint64_t>(state.evict_words, w.evict_tiles * WAVE, 0ull, st));
   {
     int64_t blocks = ceil_div(cap, TB * 8);
     if (blocks > 4096) blocks = 4096;
@@ -1059,6 +1113,9 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       hipLaunchKernelGGL(k_bits_count, dim3((unsigned)w.bit_parts), dim3(TB), 0, st, state,
                          w.bit_words);
       hipLaunchKernelGGL(k_bits_find, dim3(1), dim3(BIG), 0, st, state, w.bit_words, w.bit_parts);
+      if (state.dead_scatter)
+        hipLaunchKernelGGL(k_dead_scatter, dim3((unsigned)w.bit_parts), dim3(TB), 0, st, state,
+                           w.bit_words);
       GINEX_LAUNCH_CHECK();
       hipLaunchKernelGGL(k_tile_count, dim3((unsigned)(w.evict_tiles + in_tiles + clear_blocks)),
                          dim3(TB), 0, st, state, it, w.evict_tiles, in_tiles, w.bit_words);

@@ -685,3 +685,31 @@ def test_carried_cache_over_consecutive_superbatches(ginex, case2):
             link_rows += int(ref["miss_count"].sum())
             state_d, state_h = cs.final_ids, final
         assert link_rows > 0
+
+
+@pytest.mark.parametrize("scatter", ["0", "1"])
+def test_both_ways_of_finding_dead_evictions_give_the_same_lists(ginex, case1, case2, scatter,
+                                                                 monkeypatch):
+    """Large caches find the evicted dead rows from the id bitmap, small ones by a pass over
+    the cache lines; GINEX_DEAD_SCATTER forces either way at any size."""
+    monkeypatch.setenv("GINEX_DEAD_SCATTER", scatter)
+    rng = np.random.default_rng(61)
+    for trial in range(40):
+        n = int(rng.integers(2, 400))
+        S = int(rng.integers(1, 14))
+        cap = int(rng.integers(1, n + 1))
+        ids, off = random_trace(rng, n, S, int(rng.integers(1, 200)))
+        ids_d = dev(ids) if len(ids) else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
+        check_changeset(ginex.changeset(n, ids_d, off, cap), oracle.changeset(n, ids, off, cap))
+        start = rng.permutation(n)[:cap].astype(np.int32)
+        check_resumed(ginex.changeset_resume(n, ids_d, off, dev(start)),
+                      oracle.changeset_resume(n, ids, off, cap, start))
+    for c in (case1, case2):
+        ids, io = c.samp["ids"], c.samp["ids_offsets"]
+        distinct = len(np.unique(ids))
+        for cap in (1000, distinct // 16, distinct // 2, distinct - 1):
+            check_changeset(ginex.changeset(c.cfg.num_nodes, dev(ids), io, cap),
+                            oracle.changeset(c.cfg.num_nodes, ids, io, cap))
+        start = np.arange(c.cfg.cap, dtype=np.int32)[::-1].copy()
+        check_resumed(ginex.changeset_resume(c.cfg.num_nodes, dev(ids), io, dev(start)),
+                      oracle.changeset_resume(c.cfg.num_nodes, ids, io, c.cfg.cap, start))
