@@ -10,9 +10,10 @@
  *    nothing.  Workspace sizes come from the matching *_workspace_bytes query called
  *    with the same shape arguments.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All kernels
- *    of a call are enqueued on it.  ginex_cache_init and ginex_gather only enqueue;
- *    ginex_sample_superbatch and ginex_changeset also wait for the stream before they
- *    return, because they hand counts back to the host.
+ *    of a call are enqueued on it.  The executor calls (ginex_cache_init*, ginex_gather,
+ *    ginex_cache_update) only enqueue; ginex_sample_superbatch, ginex_changeset*,
+ *    and ginex_neighbor_cache_build also wait for the stream before they return, because
+ *    they hand counts back to the host.
  *  - Every function returns 0 (GINEX_OK) or a negative GINEX_ERR_* code; the message of
  *    the last failure on the calling thread is returned by ginex_last_error().
  *    Arguments are validated on the host before anything is launched.  On

@@ -26,4 +26,4 @@ int32_t fail(int32_t code, const char* fmt, ...) {
 }  // namespace ginex
 
 extern "C" const char* ginex_last_error(void) { return ginex::g_error; }
-extern "C" int32_t ginex_version(void) { return 100; }
+extern "C" int32_t ginex_version(void) { return 10100; }
