@@ -25,6 +25,7 @@ sys.path.insert(0, ROOT)
 
 METRIC = "sampled edges/s; Belady changeset accesses/s; gather GB/s vs HBM peak"
 HBM_PEAK_GBPS = 8000.0
+HOST_LINK_GBPS = 64.0     # PCIe Gen5 x16, raw
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 
 
@@ -428,6 +429,12 @@ def main():
         "host_link_GBps": miss_per_launch * row_bytes / (g_ms * 1e-3) / 1e9,
     }
     roof["frac"] = roof["achieved"] / roof["peak"]
+    # By wall time the largest kernel of a step is the cache fill, which neither HBM nor the
+    # ALUs bound: every row of C_0 crosses the host link once (PCIe Gen5 x16, 64 GB/s raw).
+    fill_GBps = len(cs.init_ids) * row_bytes / mean["cache_init_s"] / 1e9
+    link_roof = {"kernel": "k_cache_fill", "bound": "host link", "achieved": fill_GBps,
+                 "peak": HOST_LINK_GBPS, "unit": "GB/s", "frac": fill_GBps / HOST_LINK_GBPS,
+                 "avg_launch_ms": mean["cache_init_s"] * 1e3, "rows_per_launch": len(cs.init_ids)}
 
     stages = {
         "sample_edges_per_s": edges / mean["sample_s"],
@@ -507,6 +514,7 @@ def main():
                                f"fanout={list(cfg.fanout)} S={S} cache_rows={cfg.cap}"},
         "stages": stages,
         "roofline": roof,
+        "roofline_cache_fill": link_roof,
     }
     if args.cpu_batches > 0:
         log("timing the CPU oracle on a bounded sample ...")

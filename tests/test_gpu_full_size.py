@@ -6,6 +6,9 @@ iterations.  Configurations 3 and 4 never miss (the rows a superbatch touches fi
 cache), so each workload is also run with a cache a sixteenth of the distinct rows, which
 puts the Belady loop and the slow-tier reads under full-size pressure.
 
+Configuration 3 also carries the rows built after the main path (LRU, resumed changesets,
+neighbour cache) at its full size.
+
 The three tests take about two minutes together (configuration 5, with 3.6 billion edges,
 about one of them); GINEX_SKIP_HEAVY=1 leaves configuration 5 out.
 """
@@ -48,7 +51,7 @@ def release_memory():
         torch._C._host_emptyCache()
 
 
-def run_full(index):
+def run_full(index, extras=False):
     import paper_2208_09151_amd as ginex
     release_memory()
     t = time.time()
@@ -115,12 +118,49 @@ def run_full(index):
         assert np.array_equal(rows, feats[pick])
         say(f"gather parity ok (cap={cap})")
         del cache, cs, rcs, out
+    if extras:
+        widened_rows(ginex, w, res, ref, distinct)
     del w, res, ref, feats
     release_memory()
 
 
+def widened_rows(ginex, w, res, ref, distinct):
+    """The rows built after the main path, at full size: LRU changesets, changesets resumed
+    from a carried cache state, the neighbour cache and sampling through it."""
+    cfg = w.cfg
+    ids, io = ref["ids"], ref["ids_offsets"]
+    cap = max(1, distinct // 16)
+    t = time.time()
+    compare_changeset(ginex.changeset(cfg.num_nodes, res.ids, res.ids_offsets, cap, policy="lru"),
+                      oracle.changeset_lru(cfg.num_nodes, ids, io, cap))
+    say(f"LRU changeset parity ok ({time.time() - t:.1f}s)")
+    for cap in (distinct // 16, 1 << 21):       # the larger one takes the dead-row scatter path
+        t = time.time()
+        start = (np.arange(cap, dtype=np.int64) * 7 % cfg.num_nodes).astype(np.int32)
+        assert len(np.unique(start)) == cap
+        rcs = oracle.changeset_resume(cfg.num_nodes, ids, io, cap, start)
+        cs = ginex.changeset_resume(cfg.num_nodes, res.ids, res.ids_offsets, dev(start))
+        compare_changeset(cs, rcs)
+        assert np.array_equal(cs.final_ids.cpu().numpy(), rcs["final_ids"])
+        say(f"resumed changeset parity ok, cap={cap} ({time.time() - t:.1f}s, "
+            f"{int(rcs['cs_offsets'][-1])} changes)")
+    t = time.time()
+    off, ind = w.offsets.cpu().numpy(), w.indices.cpu().numpy()
+    budget = len(ind) // 10
+    at, ca, cached = oracle.neighbor_cache_build(off, ind, budget)
+    nc = ginex.neighbor_cache_build(w.offsets, w.indices, budget)
+    assert nc.cached_nodes == cached and nc.used_entries == len(ca)
+    assert np.array_equal(nc.address_table.cpu().numpy(), at)
+    assert np.array_equal(nc.cache_array[:nc.used_entries].cpu().numpy(), ca)
+    again = ginex.sample_superbatch(w.offsets, w.indices, w.seeds.cuda(), w.seed_offsets.numpy(),
+                                    cfg.fanout, rng_seed=0, neighbor_cache=nc)
+    assert torch.equal(again.ids, res.ids) and torch.equal(again.adj_col, res.adj_col)
+    assert torch.equal(again.adj_rowptr, res.adj_rowptr)
+    say(f"neighbour cache parity ok: {cached} nodes cached ({time.time() - t:.1f}s)")
+
+
 def test_full_size_config3():
-    run_full(3)
+    run_full(3, extras=True)
 
 
 def test_full_size_config4():
