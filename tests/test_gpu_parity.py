@@ -713,3 +713,20 @@ def test_both_ways_of_finding_dead_evictions_give_the_same_lists(ginex, case1, c
         start = np.arange(c.cfg.cap, dtype=np.int32)[::-1].copy()
         check_resumed(ginex.changeset_resume(c.cfg.num_nodes, dev(ids), io, dev(start)),
                       oracle.changeset_resume(c.cfg.num_nodes, ids, io, c.cfg.cap, start))
+
+
+def test_changeset_at_the_largest_superbatch_the_library_accepts(ginex):
+    """S = 8191 iterations (the documented limit) of a few ids each, under eviction pressure,
+    for both policies and for a resumed cache."""
+    rng = np.random.default_rng(71)
+    n, S, cap = 500, 8191, 40
+    ids, off = random_trace(rng, n, S, 6)
+    ids_d = dev(ids)
+    check_changeset(ginex.changeset(n, ids_d, off, cap), oracle.changeset(n, ids, off, cap))
+    check_changeset(ginex.changeset(n, ids_d, off, cap, policy="lru"),
+                    oracle.changeset_lru(n, ids, off, cap))
+    start = rng.permutation(n)[:cap].astype(np.int32)
+    check_resumed(ginex.changeset_resume(n, ids_d, off, dev(start)),
+                  oracle.changeset_resume(n, ids, off, cap, start))
+    with pytest.raises(ginex.GinexError):
+        ginex.changeset(n, ids_d, np.concatenate([off, off[-1:]]), cap)     # S = 8192
