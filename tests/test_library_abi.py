@@ -98,6 +98,32 @@ def test_precondition_and_workspace_errors_are_reported_before_any_launch():
     assert lib.ginex_cache_init_part(ctypes.byref(c), fake, 2, 5, None) == -1
     assert lib.ginex_cache_init_part(ctypes.byref(c), fake, 3, 2, None) == -1
     assert lib.ginex_gather(ctypes.byref(c), fake, 2, fake, fake, fake, fake, 3, None) == -1
+    # warm initialization: the two caches must front the same slow tier and share no array
+    other = _lib.CacheDesc(0x2000, 4, 64, 0x2000, 10, 0x3000)
+    assert lib.ginex_cache_init_warm(ctypes.byref(c), ctypes.byref(other), fake, 0, 2, None) == -1
+    assert b"same slow tier" in lib.ginex_last_error()
+    assert lib.ginex_cache_init_warm(ctypes.byref(c), ctypes.byref(c), fake, 0, 2, None) == -1
+    assert b"share" in lib.ginex_last_error()
+    # a carried cache needs a start state, and at least one line
+    assert lib.ginex_changeset_resume(100, fake, P(io), 2, 3, None, fake, fake, fake, fake, 100,
+                                      fake, fake, P(tc), fake, 16, None) == -1
+    assert lib.ginex_changeset_resume(100, fake, P(io), 2, 0, fake, fake, fake, fake, fake, 100,
+                                      fake, fake, P(tc), fake, 1 << 40, None) == -1
+    assert b"cap >= 1" in lib.ginex_last_error()
+    # neighbour cache: half a cache in the graph descriptor, missing outputs, small workspace
+    half = _lib.CsrDesc(100, 1000, 0x1000, 0, 0x1000, 0x1000, None)
+    assert lib.ginex_sample_superbatch(
+        ctypes.byref(half), fake, P(so), 2, P(fan), 2, 0, 0, fake, 1000, P(ids_off), P(hops),
+        fake, 1000, fake, 1000, P(ro), P(co), P(tot), fake, 1 << 40, None) == -1
+    assert b"neighbour cache" in lib.ginex_last_error()
+    cn, ue = host(1), host(1)
+    assert lib.ginex_neighbor_cache_build(ctypes.byref(g), 10, None, fake, P(cn), P(ue), fake,
+                                          1 << 40, None) == -1
+    assert lib.ginex_neighbor_cache_build(ctypes.byref(g), -1, fake, fake, P(cn), P(ue), fake,
+                                          1 << 40, None) == -1
+    assert lib.ginex_neighbor_cache_build(ctypes.byref(g), 10, fake, fake, P(cn), P(ue), fake,
+                                          16, None) == -3
+    assert lib.ginex_neighbor_cache_workspace_bytes(0) == 0
     assert lib.ginex_cache_update(ctypes.byref(c), fake, fake, fake, fake, 9, None) == -1
     assert lib.ginex_gather(ctypes.byref(c), fake, 2, ctypes.c_void_p(0x1008), None, None, None,
                             0, None) == -1                                   # out misaligned
