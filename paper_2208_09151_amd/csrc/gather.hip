@@ -16,6 +16,11 @@ constexpr int THREADS = 256;
 constexpr int UNROLL = 4;
 
 // out[p,:] = addr[ids[p]] >= 0 ? rows[addr[ids[p]],:] : slow[ids[p],:]
+// SHIFT >= 0: a row has 2^SHIFT chunks (the usual case), so chunk -> (row, column) is a
+// shift and a mask; SHIFT < 0: any row size, by a 64-bit division, which costs 5 % of the
+// kernel's time on 512-byte rows.  (Non-temporal loads of the rows change nothing;
+// non-temporal stores of the output are worth 8-10 %.)
+template <int SHIFT>
 __global__ __launch_bounds__(THREADS) void k_gather(
     const chunk_t* __restrict__ rows, const int32_t* __restrict__ addr,
     const chunk_t* __restrict__ slow, const int32_t* __restrict__ ids, int64_t n,
@@ -29,8 +34,9 @@ __global__ __launch_bounds__(THREADS) void k_gather(
     for (int u = 0; u < UNROLL; ++u) {
       const int64_t c = c0 + u * span;
       if (c < total) {
-        const int64_t p = c / cpr;
-        const int32_t col = (int32_t)(c - p * cpr);
+        const int64_t p = SHIFT >= 0 ? c >> (SHIFT & 31) : c / cpr;
+        const int32_t col = SHIFT >= 0 ? (int32_t)(c & ((1 << (SHIFT & 31)) - 1))
+                                       : (int32_t)(c - p * cpr);
         const int32_t id = ids[p];
         const int32_t line = addr[id];
         const chunk_t* src = line >= 0 ? rows + (int64_t)line * cpr : slow + (int64_t)id * cpr;
@@ -299,9 +305,23 @@ extern "C" int32_t ginex_gather(const ginex_cache_t* c, const int32_t* ids, int6
   hipStream_t st = (hipStream_t)stream;
   if (n > 0) {
     const int32_t cpr = (int32_t)(c->row_bytes / 16);
-    hipLaunchKernelGGL(k_gather, dim3(grid_for(n * cpr, UNROLL)), dim3(THREADS), 0, st,
-                       (const chunk_t*)c->rows, c->addr, (const chunk_t*)c->slow, ids, n, cpr,
-                       (chunk_t*)out);
+    const dim3 grid(grid_for(n * cpr, UNROLL));
+#define GINEX_GATHER(S)                                                                       \
+  hipLaunchKernelGGL((k_gather<S>), grid, dim3(THREADS), 0, st, (const chunk_t*)c->rows,       \
+                     c->addr, (const chunk_t*)c->slow, ids, n, cpr, (chunk_t*)out)
+    switch (cpr) {      // rows of 16 B .. 4 KB with a power-of-two size
+      case 1: GINEX_GATHER(0); break;
+      case 2: GINEX_GATHER(1); break;
+      case 4: GINEX_GATHER(2); break;
+      case 8: GINEX_GATHER(3); break;
+      case 16: GINEX_GATHER(4); break;
+      case 32: GINEX_GATHER(5); break;
+      case 64: GINEX_GATHER(6); break;
+      case 128: GINEX_GATHER(7); break;
+      case 256: GINEX_GATHER(8); break;
+      default: GINEX_GATHER(-1);
+    }
+#undef GINEX_GATHER
     GINEX_LAUNCH_CHECK();
   }
   return launch_update(c, out, in_ids, out_ids, in_positions, n_change, st);
