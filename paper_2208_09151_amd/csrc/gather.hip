@@ -14,6 +14,10 @@ namespace {
 typedef unsigned int chunk_t __attribute__((ext_vector_type(4)));  // 16 bytes
 constexpr int THREADS = 256;
 constexpr int UNROLL = 4;
+// The gather runs in blocks of one wave: finer to schedule at the end of a launch (37.7 us
+// per 177 k rows of 512 B against 38.3 with 256 threads and 39.9 with 1024); four chunks per
+// thread (1, 2, 6, 8 are 1-5 % slower).
+constexpr int GATHER_THREADS = 64;
 
 // out[p,:] = addr[ids[p]] >= 0 ? rows[addr[ids[p]],:] : slow[ids[p],:]
 // SHIFT >= 0: a row has 2^SHIFT chunks (the usual case), so chunk -> (row, column) is a
@@ -21,28 +25,36 @@ constexpr int UNROLL = 4;
 // kernel's time on 512-byte rows.  (Non-temporal loads of the rows change nothing;
 // non-temporal stores of the output are worth 8-10 %.)
 template <int SHIFT>
-__global__ __launch_bounds__(THREADS) void k_gather(
+__global__ __launch_bounds__(GATHER_THREADS) void k_gather(
     const chunk_t* __restrict__ rows, const int32_t* __restrict__ addr,
     const chunk_t* __restrict__ slow, const int32_t* __restrict__ ids, int64_t n,
     int32_t cpr /*chunks per row*/, chunk_t* __restrict__ out) {
   const int64_t total = n * cpr;
-  const int64_t span = (int64_t)gridDim.x * THREADS;
-  int64_t c0 = (int64_t)blockIdx.x * THREADS + threadIdx.x;
+  const int64_t span = (int64_t)gridDim.x * GATHER_THREADS;
+  int64_t c0 = (int64_t)blockIdx.x * GATHER_THREADS + threadIdx.x;
   for (; c0 < total; c0 += span * UNROLL) {
+    // The three dependent reads (id, address-table entry, row chunk) of the UNROLL chunks
+    // are issued level by level, so that each level's loads are in flight together.  A
+    // chunk beyond the end repeats chunk c0 (in range) and is dropped at the store: no
+    // branch separates the loads, which would make each wait for all earlier ones.
+    int32_t id[UNROLL], col[UNROLL];
+    const chunk_t* src[UNROLL];
     chunk_t v[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-      const int64_t c = c0 + u * span;
-      if (c < total) {
-        const int64_t p = SHIFT >= 0 ? c >> (SHIFT & 31) : c / cpr;
-        const int32_t col = SHIFT >= 0 ? (int32_t)(c & ((1 << (SHIFT & 31)) - 1))
-                                       : (int32_t)(c - p * cpr);
-        const int32_t id = ids[p];
-        const int32_t line = addr[id];
-        const chunk_t* src = line >= 0 ? rows + (int64_t)line * cpr : slow + (int64_t)id * cpr;
-        v[u] = src[col];
-      }
+      int64_t c = c0 + u * span;
+      c = c < total ? c : c0;
+      const int64_t p = SHIFT >= 0 ? c >> (SHIFT & 31) : c / cpr;
+      col[u] = SHIFT >= 0 ? (int32_t)(c & ((1 << (SHIFT & 31)) - 1)) : (int32_t)(c - p * cpr);
+      id[u] = ids[p];
     }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int32_t line = addr[id[u]];
+      src[u] = line >= 0 ? rows + (int64_t)line * cpr : slow + (int64_t)id[u] * cpr;
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) v[u] = src[u][col[u]];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       const int64_t c = c0 + u * span;
@@ -80,7 +92,11 @@ __global__ __launch_bounds__(THREADS) void k_update_addr(
   }
 }
 
-// rows[r,:] = slow[init_ids[r],:]; addr[init_ids[r]] = r, for lines r in [begin, end)
+// rows[r,:] = slow[init_ids[r],:]; addr[init_ids[r]] = r, for lines r in [begin, end).
+// Unlike k_gather this kernel keeps the three dependent reads of a chunk behind one another
+// (one chunk in flight per thread at a time): the host link is saturated either way, and
+// with four times as many link reads in flight per wave a gather running beside the fill
+// took twice as long again and slowed the fill down by 5-30 %.
 __global__ __launch_bounds__(THREADS) void k_cache_fill(
     chunk_t* __restrict__ rows, int32_t* __restrict__ addr, const chunk_t* __restrict__ slow,
     const int32_t* __restrict__ init_ids, int64_t begin, int64_t end, int32_t cpr) {
@@ -305,10 +321,14 @@ extern "C" int32_t ginex_gather(const ginex_cache_t* c, const int32_t* ids, int6
   hipStream_t st = (hipStream_t)stream;
   if (n > 0) {
     const int32_t cpr = (int32_t)(c->row_bytes / 16);
-    const dim3 grid(grid_for(n * cpr, UNROLL));
+    // one pass of the kernel's loop up to 2^24 blocks (8 TB of rows), more passes beyond
+    int64_t blocks = ceil_div(n * cpr, (int64_t)GATHER_THREADS * UNROLL);
+    if (blocks > (1 << 24)) blocks = 1 << 24;
+    const dim3 grid((unsigned)blocks);
 #define GINEX_GATHER(S)                                                                       \
-  hipLaunchKernelGGL((k_gather<S>), grid, dim3(THREADS), 0, st, (const chunk_t*)c->rows,       \
-                     c->addr, (const chunk_t*)c->slow, ids, n, cpr, (chunk_t*)out)
+  hipLaunchKernelGGL((k_gather<S>), grid, dim3(GATHER_THREADS), 0, st,                         \
+                     (const chunk_t*)c->rows, c->addr, (const chunk_t*)c->slow, ids, n, cpr,   \
+                     (chunk_t*)out)
     switch (cpr) {      // rows of 16 B .. 4 KB with a power-of-two size
       case 1: GINEX_GATHER(0); break;
       case 2: GINEX_GATHER(1); break;
