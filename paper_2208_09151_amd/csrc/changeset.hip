@@ -334,27 +334,41 @@ __device__ void p_touch(const State& st, const Iter& it, unsigned long long* mis
   __syncthreads();
   uint32_t misses = 0;
   const int64_t base = vb * (TB * TOUCH_ITEMS);
+  // id, then address-table entry, then the line's state: the reads of one level are issued
+  // for all items before any is used, so that they are in flight together.  An item beyond
+  // the end repeats the block's first item (in range) and is skipped when it is processed.
+  int32_t v[TOUCH_ITEMS], line[TOUCH_ITEMS], nx[TOUCH_ITEMS];
 #pragma unroll
   for (int t = 0; t < TOUCH_ITEMS; ++t) {
-    const int64_t p = base + t * TB + threadIdx.x;
-    if (p < it.n) {
-      const int32_t nx = key_of(it, p);
-      const int32_t line = st.addr[it.ids[p]];
-      if (line >= 0) {
-        // An LRU hit leaves a bucket that is still walked (an older one): take it out of
-        // the count there; counters wrap, the flush below adds them modulo 2^32.  A Belady
-        // hit leaves bucket i, which no later iteration looks at.
-        if (st.lru) atomicSub(&hr[st.res_next[line]], 1u);
-        st.res_next[line] = nx;
-        atomicAdd(&hr[nx], 1u);
-        if (nx == st.S && !st.lru) {   // the row's last access: a dead resident from now on
-          const uint32_t v = (uint32_t)it.ids[p];
-          atomicOr(&st.dead_bits[v >> 5], 1u << (v & 31));
-        }
-      } else {
-        atomicAdd(&hi[nx], 1u);
-        ++misses;
+    int64_t p = base + t * TB + threadIdx.x;
+    p = p < it.n ? p : base;
+    v[t] = it.ids[p];
+    nx[t] = key_of(it, p);
+  }
+#pragma unroll
+  for (int t = 0; t < TOUCH_ITEMS; ++t) line[t] = st.addr[v[t]];
+  int32_t old_key[TOUCH_ITEMS];
+  if (st.lru) {
+#pragma unroll
+    for (int t = 0; t < TOUCH_ITEMS; ++t) old_key[t] = line[t] >= 0 ? st.res_next[line[t]] : 0;
+  }
+#pragma unroll
+  for (int t = 0; t < TOUCH_ITEMS; ++t) {
+    if (base + t * TB + threadIdx.x >= it.n) continue;
+    if (line[t] >= 0) {
+      // An LRU hit leaves a bucket that is still walked (an older one): take it out of
+      // the count there; counters wrap, the flush below adds them modulo 2^32.  A Belady
+      // hit leaves bucket i, which no later iteration looks at.
+      if (st.lru) atomicSub(&hr[old_key[t]], 1u);
+      st.res_next[line[t]] = nx[t];
+      atomicAdd(&hr[nx[t]], 1u);
+      if (nx[t] == st.S && !st.lru) {   // the row's last access: a dead resident from now on
+        const uint32_t u = (uint32_t)v[t];
+        atomicOr(&st.dead_bits[u >> 5], 1u << (u & 31));
       }
+    } else {
+      atomicAdd(&hi[nx[t]], 1u);
+      ++misses;
     }
   }
   const uint32_t total = block_sum_u32(misses, red);
@@ -642,13 +656,20 @@ __device__ void p_in_count(const State& st, const Ctrl& c, const Iter& it, int64
   __shared__ uint32_t red[TB / WAVE];
   const int64_t base = (vb * TB + threadIdx.x) * IN_ITEMS;
   uint32_t cnt = 0;
+  // ids and keys first, then the address-table entries of all items together (an item
+  // beyond the end repeats item 0 of the iteration and is not counted)
+  int32_t v[IN_ITEMS], key[IN_ITEMS], line[IN_ITEMS];
+#pragma unroll
   for (int t = 0; t < IN_ITEMS; ++t) {
-    const int64_t p = base + t;
-    if (p < it.n) {
-      const int32_t v = it.ids[p];
-      cnt += inserts(c, key_of(it, p), v) && st.addr[v] < 0;
-    }
+    const int64_t p = base + t < it.n ? base + t : 0;
+    v[t] = it.ids[p];
+    key[t] = key_of(it, p);
   }
+#pragma unroll
+  for (int t = 0; t < IN_ITEMS; ++t) line[t] = st.addr[v[t]];
+#pragma unroll
+  for (int t = 0; t < IN_ITEMS; ++t)
+    cnt += base + t < it.n && inserts(c, key[t], v[t]) && line[t] < 0;
   const uint32_t total = block_sum_u32(cnt, red);
   if (threadIdx.x == 0) st.in_tiles[vb] = total;
 }
@@ -693,16 +714,21 @@ __device__ void p_in_emit(const State& st, const Ctrl& c, const Iter& it, const 
   __shared__ uint32_t smem[TB / WAVE + 1];
   const int64_t base = (vb * TB + threadIdx.x) * IN_ITEMS;
   uint32_t flags = 0, cnt = 0;
+  int32_t v[IN_ITEMS], key[IN_ITEMS], line[IN_ITEMS];
+#pragma unroll
   for (int t = 0; t < IN_ITEMS; ++t) {
-    const int64_t p = base + t;
-    if (p < it.n) {
-      const int32_t v = it.ids[p];
-      if (inserts(c, key_of(it, p), v) && st.addr[v] < 0) {
-        flags |= 1u << t;
-        ++cnt;
-      }
-    }
+    const int64_t p = base + t < it.n ? base + t : 0;
+    v[t] = it.ids[p];
+    key[t] = key_of(it, p);
   }
+#pragma unroll
+  for (int t = 0; t < IN_ITEMS; ++t) line[t] = st.addr[v[t]];
+#pragma unroll
+  for (int t = 0; t < IN_ITEMS; ++t)
+    if (base + t < it.n && inserts(c, key[t], v[t]) && line[t] < 0) {
+      flags |= 1u << t;
+      ++cnt;
+    }
   uint32_t total;
   uint32_t at = st.in_tiles[vb] + block_exclusive_scan<uint32_t, TB>(cnt, smem, total);
   if (!cnt) return;
