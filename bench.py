@@ -355,7 +355,7 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=4)
-    ap.add_argument("--cpu-batches", type=int, default=6,
+    ap.add_argument("--cpu-batches", type=int, default=40,
                     help="batches of the workload the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--pipeline", type=int, default=0, metavar="K",
                     help="also run K superbatches through the superbatch-level pipeline "
