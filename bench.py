@@ -286,6 +286,10 @@ def pipeline_leg(ginex, w, K):
         out[key + "_ms_per_superbatch"] = t * 1e3 / K
         out[key + "_edges_per_s"] = stats[0] / t
         out[key + "_miss_ratio"] = stats[1] / max(stats[2], 1)
+    stats[:] = [0, 0, 0]
+    t = pipe.run_three_stage(more, execute_carried)
+    out["whole_path_carried_cache_three_stage_ms_per_superbatch"] = t * 1e3 / K
+    out["whole_path_carried_cache_three_stage_edges_per_s"] = stats[0] / t
     pipe.carry_cache_from(None)
     return out
 

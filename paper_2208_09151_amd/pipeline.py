@@ -151,18 +151,19 @@ class InspectorPipeline:
         ws_c = lib.ginex_changeset_workspace_bytes(num_nodes, ci, S, cap)
         self.ws_sample = torch.empty(ws_s, dtype=torch.uint8, device=dev)
         self.ws_changeset = torch.empty(ws_c, dtype=torch.uint8, device=dev)
-        # two sets of sampler outputs: one being filled while the other is consumed
+        # two sets of sampler outputs: one being filled while the other is consumed (a third
+        # one is added by run_three_stage)
         self.bufs = [(torch.empty(ci, dtype=torch.int32, device=dev),
                       torch.empty(cr, dtype=torch.int64, device=dev),
                       torch.empty(cc, dtype=torch.int32, device=dev)) for _ in range(2)]
         self.streams = (torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev))
         self.state = None
 
-    def _sample(self, k, seeds, seed_offsets, first_batch, rng_seed):
+    def _sample(self, k, seeds, seed_offsets, first_batch, rng_seed, nbuf=2):
         with torch.cuda.stream(self.streams[0]):
             return api.sample_superbatch(self.offsets, self.indices, seeds, seed_offsets, self.fanout,
                                          rng_seed=rng_seed, first_batch_index=first_batch,
-                                         workspace=self.ws_sample, out=self.bufs[k % 2])
+                                         workspace=self.ws_sample, out=self.bufs[k % nbuf])
 
     def carry_cache_from(self, start_ids):
         """From now on every superbatch starts from the cache state the one before it left
@@ -230,6 +231,71 @@ class InspectorPipeline:
         """Sampling then changesets of one superbatch on the inspector streams."""
         samp = self._sample(k, seeds, seed_offsets, first_batch, rng_seed)
         return samp, self._changeset(samp)
+
+    def run_three_stage(self, superbatches, execute, rng_seed=0):
+        """Three stages in flight: sampling of superbatch k+2, changesets of k+1 and
+        ``execute(k, samp, cs)`` (on the calling thread), each stage on its own host thread
+        and streams, with three sets of sampler outputs.  Worth it when no stage dominates
+        (a cache carried over: sampling, the changeset loop and the executor are of the same
+        order).  Returns the wall time in seconds."""
+        import queue
+        while len(self.bufs) < 3:
+            self.bufs.append(tuple(torch.empty_like(t) for t in self.bufs[0]))
+        n = len(superbatches)
+        free_bufs = threading.Semaphore(3)
+        sampled, inspected = queue.Queue(), queue.Queue()
+        errors = []
+
+        def sample_all():
+            try:
+                for k in range(n):
+                    free_bufs.acquire()
+                    if errors:
+                        break
+                    sampled.put((k, self._sample(k, *superbatches[k], rng_seed, nbuf=3)))
+            except BaseException as e:      # re-raised on the calling thread
+                errors.append(e)
+            finally:
+                sampled.put(None)
+
+        def inspect_all():
+            try:
+                while True:
+                    item = sampled.get()
+                    if item is None:
+                        break
+                    k, samp = item
+                    inspected.put((k, samp, self._changeset(samp)))
+            except BaseException as e:
+                errors.append(e)
+            finally:
+                inspected.put(None)
+
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        threads = [threading.Thread(target=sample_all), threading.Thread(target=inspect_all)]
+        for th in threads:
+            th.start()
+        try:
+            while True:
+                item = inspected.get()
+                if item is None:
+                    break
+                execute(*item)
+                free_bufs.release()
+        except BaseException as e:
+            errors.append(e)
+        finally:
+            for _ in range(n + 3):          # let a sampler that waits for a buffer run out
+                free_bufs.release()
+            # drain so that neither producer blocks (the queues are unbounded; this only
+            # matters after an error on this thread)
+            for th in threads:
+                th.join()
+        if errors:
+            raise errors[0]
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
 
     def run_with_executor(self, superbatches, execute, rng_seed=0, overlap=True):
         """Two-stage pipeline over superbatches: ``execute(k, samp, cs)`` (cache init,

@@ -404,6 +404,25 @@ def test_executor_under_next_inspector_gathers_the_right_bytes(ginex, case2):
         del done[:]
         pipe.run_with_executor(sbs, execute, overlap=overlap)
         assert done == [0, 1, 2]
+    # three stages in flight (sampling of k+2, changesets of k+1, executor of k), five
+    # superbatches so that every buffer set is reused
+    for k in range(3, 5):
+        seeds, so = seed_batches(train, cfg.batch, S, cfg.seed, first_batch=k * S)
+        sbs.append((seeds.cuda(), so.numpy(), k * S))
+        refs.append(oracle.sample_superbatch(c.off, c.ind, seeds.numpy(), so.numpy(), cfg.fanout,
+                                             rng_seed=0, first_batch_index=k * S))
+    del done[:]
+    pipe.run_three_stage(sbs, execute)
+    assert done == [0, 1, 2, 3, 4]
+
+    # an error in a stage reaches the caller and leaves no thread behind
+    def failing(k, samp, cs):
+        raise RuntimeError("executor failed")
+    with pytest.raises(RuntimeError, match="executor failed"):
+        pipe.run_three_stage(sbs, failing)
+    del done[:]
+    pipe.run_three_stage(sbs[:2], execute)
+    assert done == [0, 1]
 
 
 # ---- LRU changesets through the same kernels (Section 2.3) -------------------------------
