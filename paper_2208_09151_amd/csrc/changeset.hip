@@ -15,6 +15,8 @@
 //   j* does the id order matter, and there the k-th smallest id is found by setting the
 //   members' bits in a bitmap over node ids and locating the k-th set bit.
 //   Evicted lines and inserted positions are then compacted in line / position order.
+//   The same loop serves the LRU policy (other keys) and a superbatch that resumes from the
+//   cache state of the previous one (C_0 given instead of computed).
 #include <cstdlib>
 #include <vector>
 
@@ -269,7 +271,7 @@ __global__ __launch_bounds__(TB) void k_copy_init(const uint64_t* __restrict__ h
 //
 // Every phase of an iteration is a device function over "virtual blocks" of TB threads; the
 // kernels below pack phases that do not depend on each other into one launch (nine
-// launches per iteration).  Two ways of saving launches were measured and dropped: a single
+// launches per iteration, ten with k_dead_scatter on large caches).  Two ways of saving launches were measured and dropped: a single
 // cooperative kernel with grid.sync() between the phases (about 0.1 ms per barrier on 1024
 // blocks, twelve times slower overall), and running the single-block phases in the last
 // block to finish of the launch before them (the device-wide fence every block then needs

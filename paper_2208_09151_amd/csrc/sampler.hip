@@ -98,8 +98,10 @@ __device__ __forceinline__ uint32_t table_value(const uint64_t* t, uint32_t h) {
 // Which (batch, tile) a block works on.  Grids are one-dimensional and the hardware deals
 // consecutive workgroups round-robin to the 8 XCDs, each with its own L2; block n therefore
 // takes a tile of a batch whose index is congruent to n modulo 8, so that all tiles of a
-// batch, and with them the batch's hash table, stay in one XCD's L2 instead of being
-// fetched by all eight.  (Only locality depends on the dealing order, not correctness.)
+// batch, and with them the batch's lists, candidates and hash table, stay in one XCD's L2
+// instead of being fetched by all eight.  (Only locality depends on the dealing order, not
+// correctness.  The table's inserts gain nothing from it: a device-scope atomic is carried
+// out on the memory side of the fabric whatever the L2 holds; the plain reads do.)
 constexpr int XCDS = 8;
 
 struct Where {
