@@ -749,3 +749,53 @@ def test_changeset_at_the_largest_superbatch_the_library_accepts(ginex):
                   oracle.changeset_resume(n, ids, off, cap, start))
     with pytest.raises(ginex.GinexError):
         ginex.changeset(n, ids_d, np.concatenate([off, off[-1:]]), cap)     # S = 8192
+
+
+def structured_traces():
+    """Traces built to sit on the tie rules and the mode switches of the threshold walk."""
+    rng = np.random.default_rng(81)
+    n = 600
+    out = []
+    same = rng.permutation(n)[:150]
+    out.append(("every iteration the same ids", [same] * 9))
+    out.append(("disjoint iterations", [np.arange(i * 60, (i + 1) * 60) for i in range(10)]))
+    out.append(("descending ids, shifted by one each iteration",
+                [np.arange(200 + i, i, -1) for i in range(12)]))
+    out.append(("one huge iteration among tiny ones",
+                [rng.permutation(n)[:5], rng.permutation(n)[:590], rng.permutation(n)[:3],
+                 rng.permutation(n)[:590], rng.permutation(n)[:1]]))
+    out.append(("two alternating sets", [np.arange(0, 300), np.arange(300, 600)] * 5))
+    out.append(("a hot core plus a cold stream",
+                [np.concatenate([np.arange(40), 40 + (np.arange(50) + 50 * i) % 560])
+                 for i in range(14)]))
+    out.append(("empty iterations in between",
+                [rng.permutation(n)[:80], np.zeros(0, dtype=np.int64), rng.permutation(n)[:80],
+                 np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64), rng.permutation(n)[:80]]))
+    return n, out
+
+
+@pytest.mark.parametrize("scatter", ["0", "1"])
+def test_changesets_on_structured_traces(ginex, scatter, monkeypatch):
+    monkeypatch.setenv("GINEX_DEAD_SCATTER", scatter)
+    n, traces = structured_traces()
+    rng = np.random.default_rng(82)
+    for name, tr in traces:
+        off = np.cumsum([0] + [len(x) for x in tr]).astype(np.int64)
+        ids = np.concatenate(tr).astype(np.int32)
+        ids_d = dev(ids)
+        distinct = len(np.unique(ids))
+        for cap in sorted({1, 2, 39, 40, 41, 59, 60, 61, 150, distinct - 1, distinct, n}):
+            if cap < 1:
+                continue
+            try:
+                check_changeset(ginex.changeset(n, ids_d, off, cap), oracle.changeset(n, ids, off, cap))
+                check_changeset(ginex.changeset(n, ids_d, off, cap, policy="lru"),
+                                oracle.changeset_lru(n, ids, off, cap))
+                for start in (np.arange(cap), np.arange(n - 1, n - 1 - cap, -1),
+                              rng.permutation(n)[:cap]):
+                    start = start.astype(np.int32)
+                    check_resumed(ginex.changeset_resume(n, ids_d, off, dev(start)),
+                                  oracle.changeset_resume(n, ids, off, cap, start))
+            except AssertionError:
+                print("failing case:", name, "cap", cap, flush=True)
+                raise
