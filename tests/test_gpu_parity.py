@@ -799,3 +799,45 @@ def test_changesets_on_structured_traces(ginex, scatter, monkeypatch):
             except AssertionError:
                 print("failing case:", name, "cap", cap, flush=True)
                 raise
+
+
+def csr_from_rows(rows, n, offsets_64):
+    off = np.cumsum([0] + [len(rows.get(v, [])) for v in range(n)])
+    ind = np.array([u for v in range(n) for u in rows.get(v, [])], dtype=np.int32)
+    return off.astype(np.int64 if offsets_64 else np.int32), ind
+
+
+@pytest.mark.parametrize("offsets_64", [False, True])
+def test_sampler_on_structured_graphs(ginex, offsets_64):
+    """A hub, a chain, rows of exactly k-1, k and k+1 neighbours, rows of identical neighbours,
+    self loops and isolated seeds, with and without a neighbour cache."""
+    n = 2000
+    rng = np.random.default_rng(91)
+    rows = {0: list(range(1, n))}                                  # hub: everyone
+    for v in range(1, 300):
+        rows[v] = [v + 1]                                          # chain
+    for v, d in zip(range(300, 330), [9, 10, 11] * 10):
+        rows[v] = rng.integers(0, n, size=d).tolist()              # around the fanout
+    for v in range(330, 360):
+        rows[v] = [7] * 40                                         # forty times the same
+    for v in range(360, 400):
+        rows[v] = [v, v, 0, v]                                     # self loops and the hub
+    for v in range(400, 1200):
+        rows[v] = rng.integers(0, n, size=int(rng.integers(0, 60))).tolist()
+    off, ind = csr_from_rows(rows, n, offsets_64)
+    batches = [np.array([0]), np.array([1, 2, 3]), np.arange(300, 400), np.arange(1200, 1300),
+               rng.permutation(n)[:500], np.array([1999, 0, 330])]
+    seeds = np.concatenate(batches).astype(np.int32)
+    so = np.cumsum([0] + [len(b) for b in batches])
+    off_d, ind_d = torch.from_numpy(off).cuda(), torch.from_numpy(ind).cuda()
+    for fanout in ((10, 10, 10), (3, 1), (64, 2), (11,)):
+        ref = oracle.sample_superbatch(off, ind, seeds, so, fanout, rng_seed=5, first_batch_index=3)
+        res = ginex.sample_superbatch(off_d, ind_d, dev(seeds), so, fanout, rng_seed=5,
+                                      first_batch_index=3)
+        check_sample(res, ref, len(batches), len(fanout))
+        for budget in (50, len(ind) // 3, len(ind) + n):
+            nc = ginex.neighbor_cache_build(off_d, ind_d, budget)
+            check_neighbor_cache(nc, oracle.neighbor_cache_build(off, ind, budget))
+            res = ginex.sample_superbatch(off_d, ind_d, dev(seeds), so, fanout, rng_seed=5,
+                                          first_batch_index=3, neighbor_cache=nc)
+            check_sample(res, ref, len(batches), len(fanout))
