@@ -120,7 +120,8 @@ int32_t ginex_sample_superbatch(
  *   cache_array   (device, [budget])
  *   cached_nodes, used_entries (host): number of records and of cache_array entries used
  * g->offsets and g->indices may be device or host-pinned memory; g's nc_* fields are
- * ignored.  The call waits for the stream before it returns.
+ * ignored.  An entry of indices outside [0, num_nodes) returns GINEX_ERR_INPUT (offsets are
+ * trusted).  The call waits for the stream before it returns.
  * ------------------------------------------------------------------------------- */
 size_t ginex_neighbor_cache_workspace_bytes(int64_t num_nodes);
 

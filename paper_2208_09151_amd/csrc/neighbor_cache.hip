@@ -22,12 +22,17 @@ __device__ __forceinline__ uint64_t sort_key(uint32_t out_degree, int64_t in_deg
   return ~ratio;
 }
 
+// Entries outside [0, num_nodes) are counted in *bad and skipped.
 __global__ __launch_bounds__(TB) void k_out_degree(const int32_t* __restrict__ indices,
-                                                   int64_t num_edges,
-                                                   uint32_t* __restrict__ out_degree) {
+                                                   int64_t num_edges, int64_t num_nodes,
+                                                   uint32_t* __restrict__ out_degree,
+                                                   unsigned long long* __restrict__ bad) {
   const int64_t span = (int64_t)gridDim.x * TB;
-  for (int64_t e = (int64_t)blockIdx.x * TB + threadIdx.x; e < num_edges; e += span)
-    atomicAdd(&out_degree[indices[e]], 1u);
+  for (int64_t e = (int64_t)blockIdx.x * TB + threadIdx.x; e < num_edges; e += span) {
+    const int32_t v = indices[e];
+    if ((uint32_t)v < (uint64_t)num_nodes) atomicAdd(&out_degree[v], 1u);
+    else atomicAdd(bad, 1ull);
+  }
 }
 
 // items[v] = (low half of the key << 32) | v: sorted first on the low half ...
@@ -146,7 +151,7 @@ Workspace carve(void* base, int64_t num_nodes) {
   w.cost = a.take<int64_t>(num_nodes);
   w.scan_scratch = a.take<int64_t>(scan_scratch_elems(num_nodes));
   w.hist = a.take<uint32_t>(radix_plan(num_nodes).hist_elems);
-  w.counters = a.take<unsigned long long>(3);
+  w.counters = a.take<unsigned long long>(4);
   w.bytes = (a.used + 255) & ~size_t(255);
   return w;
 }
@@ -190,12 +195,12 @@ extern "C" int32_t ginex_neighbor_cache_build(const ginex_csr_t* g, int64_t budg
   const unsigned node_blocks = (unsigned)ceil_div(n, TB);
 
   GINEX_HIP(fill_async<uint32_t>(w.out_degree, n, 0u, st));
-  GINEX_HIP(fill_async<unsigned long long>(w.counters, 3, 0ull, st));
+  GINEX_HIP(fill_async<unsigned long long>(w.counters, 4, 0ull, st));
   if (g->num_edges > 0) {
     int64_t blocks = ceil_div(g->num_edges, (int64_t)TB * 16);
     if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(k_out_degree, dim3((unsigned)blocks), dim3(TB), 0, st, g->indices,
-                       g->num_edges, w.out_degree);
+                       g->num_edges, n, w.out_degree, w.counters + 3);
     GINEX_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(k_items_low, dim3(node_blocks), dim3(TB), 0, st, g->offsets, off64,
@@ -216,9 +221,12 @@ extern "C" int32_t ginex_neighbor_cache_build(const ginex_csr_t* g, int64_t budg
   hipLaunchKernelGGL(k_place, dim3(node_blocks), dim3(TB), 0, st, ranked, w.cost, g->offsets, off64,
                      n, budget, address_table, cache_array, w.counters);
   GINEX_LAUNCH_CHECK();
-  unsigned long long counts[3] = {0, 0, 0};
+  unsigned long long counts[4] = {0, 0, 0, 0};
   GINEX_HIP(hipMemcpyAsync(counts, w.counters, sizeof(counts), hipMemcpyDeviceToHost, st));
   GINEX_HIP(hipStreamSynchronize(st));
+  if (counts[3])
+    return fail(GINEX_ERR_INPUT, "%s: %llu entries of indices outside [0, %lld)", who, counts[3],
+                (long long)n);
   *cached_nodes = (int64_t)counts[0];
   *used_entries = (int64_t)counts[1];
   if (counts[0] > 0) {

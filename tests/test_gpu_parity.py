@@ -506,6 +506,18 @@ def test_neighbor_cache_build_matches_oracle_on_small_graphs(ginex, offsets_64):
                 raise
 
 
+def test_neighbor_cache_build_rejects_indices_out_of_range(ginex):
+    off, ind = small_graph(500, 4000, seed=3)
+    bad = ind.clone()
+    bad[17] = 500
+    with pytest.raises(ginex.GinexError, match="outside"):
+        ginex.neighbor_cache_build(off.cuda(), bad.cuda(), 1000)
+    bad[17] = -3
+    with pytest.raises(ginex.GinexError, match="outside"):
+        ginex.neighbor_cache_build(off.cuda(), bad.cuda(), 1000)
+    ginex.neighbor_cache_build(off.cuda(), ind.cuda(), 1000)
+
+
 @pytest.mark.parametrize("which", ["case1", "case2"])
 def test_neighbor_cache_is_transparent_to_the_sampler(ginex, which, request):
     c = request.getfixturevalue(which)
