@@ -89,9 +89,10 @@ typedef struct ginex_csr {
  *   totals (host, [3]): number of ids, of rowptr entries and of col entries (= sampled
  *   edges) produced, or required on GINEX_ERR_CAPACITY.
  * Limits: 1 <= H <= GINEX_MAX_HOPS, 1 <= fanout[h] <= GINEX_MAX_FANOUT, and a batch's
- * list must stay below 2^30 entries.  Seeds must lie in [0, num_nodes): unchecked by
- * default, checked on the device first (GINEX_ERR_INPUT) when GINEX_VALIDATE=1 is set in
- * the environment.  The CSR itself is trusted.
+ * list must stay below 2^30 entries.  Seeds must lie in [0, num_nodes) and the CSR must be
+ * well formed (offsets from 0 to num_edges without a decrease, indices in range): unchecked
+ * by default, checked on the device first (GINEX_ERR_INPUT) when GINEX_VALIDATE=1 is set in
+ * the environment.
  * ------------------------------------------------------------------------------- */
 size_t ginex_sample_workspace_bytes(int64_t num_nodes, int32_t S, int64_t max_batch,
                                     const int32_t* fanout /*host [H]*/, int32_t H);

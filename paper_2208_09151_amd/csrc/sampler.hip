@@ -472,6 +472,26 @@ __global__ __launch_bounds__(TB) void k_validate_seeds(const int32_t* __restrict
   if (j < n && (uint32_t)seeds[j] >= (uint64_t)num_nodes) atomicAdd(bad, 1ull);
 }
 
+// Precondition check (only when asked for): offsets start at 0, never decrease and end at
+// num_edges; every entry of indices inside [0, num_nodes).
+template <typename OffT>
+__global__ __launch_bounds__(TB) void k_validate_csr(const OffT* __restrict__ offsets,
+                                                     const int32_t* __restrict__ indices,
+                                                     int64_t num_nodes, int64_t num_edges,
+                                                     unsigned long long* __restrict__ bad) {
+  const int64_t span = (int64_t)gridDim.x * TB;
+  unsigned long long mine = 0;
+  for (int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x; j < num_nodes || j < num_edges;
+       j += span) {
+    if (j < num_nodes) {
+      mine += (int64_t)offsets[j] > (int64_t)offsets[j + 1];
+      if (j == 0) mine += offsets[0] != 0 || (int64_t)offsets[num_nodes] != num_edges;
+    }
+    if (j < num_edges) mine += (uint32_t)indices[j] >= (uint64_t)num_nodes;
+  }
+  if (mine) atomicAdd(bad, mine);
+}
+
 __global__ void k_seed_counts(const int64_t* __restrict__ seed_off, int S, int32_t* nfront,
                               int32_t* nlist) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -680,6 +700,20 @@ extern "C" int32_t ginex_sample_superbatch(
     GINEX_HIP(hipStreamSynchronize(st));
     if (bad)
       return fail(GINEX_ERR_INPUT, "%s: %llu seeds outside [0, %lld)", who, bad,
+                  (long long)g->num_nodes);
+    GINEX_HIP(fill_async<unsigned long long>(d_bad, 1, 0ull, st));
+    if (g->offsets_64)
+      hipLaunchKernelGGL(k_validate_csr<int64_t>, dim3(4096), dim3(TB), 0, st,
+                         (const int64_t*)g->offsets, g->indices, g->num_nodes, g->num_edges, d_bad);
+    else
+      hipLaunchKernelGGL(k_validate_csr<int32_t>, dim3(4096), dim3(TB), 0, st,
+                         (const int32_t*)g->offsets, g->indices, g->num_nodes, g->num_edges, d_bad);
+    GINEX_LAUNCH_CHECK();
+    GINEX_HIP(hipMemcpyAsync(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost, st));
+    GINEX_HIP(hipStreamSynchronize(st));
+    if (bad)
+      return fail(GINEX_ERR_INPUT, "%s: the CSR breaks %llu of its invariants (offsets from 0 to "
+                  "num_edges without a decrease, indices inside [0, %lld))", who, bad,
                   (long long)g->num_nodes);
   }
   hipLaunchKernelGGL(k_seed_counts, dim3((unsigned)ceil_div(S, TB)), dim3(TB), 0, st, w.seed_off, S,

@@ -340,6 +340,20 @@ def test_validation_mode_rejects_bad_traces(ginex, monkeypatch):
         ginex.sample_superbatch(off_g.cuda(), ind_g.cuda(), dev(np.array([1, 300], dtype=np.int32)),
                                 [0, 2], (3,))
     assert e.value.code == -4 and "seeds outside" in str(e.value)
+    # a broken CSR: an index out of range, offsets that decrease, offsets that do not end at E
+    good_seeds = dev(np.array([1, 2], dtype=np.int32))
+    ginex.sample_superbatch(off_g.cuda(), ind_g.cuda(), good_seeds, [0, 2], (3,))
+    for breakage in ("index", "decrease", "end"):
+        o, i = off_g.clone(), ind_g.clone()
+        if breakage == "index":
+            i[5] = 300
+        elif breakage == "decrease":
+            o[10] = o[11] + 1
+        else:
+            o[-1] += 1
+        with pytest.raises(ginex.GinexError) as e:
+            ginex.sample_superbatch(o.cuda(), i.cuda(), good_seeds, [0, 2], (3,))
+        assert e.value.code == -4 and "CSR" in str(e.value), breakage
     for bad in ([3, 3, 2, 0, 3, 1], [3, 4, 2, 0, 9, 1]):     # a repeat / an id >= num_nodes
         with pytest.raises(ginex.GinexError) as e:
             ginex.changeset(5, dev(np.array(bad, dtype=np.int32)), off, 2)
