@@ -867,3 +867,40 @@ def test_sampler_on_structured_graphs(ginex, offsets_64):
             res = ginex.sample_superbatch(off_d, ind_d, dev(seeds), so, fanout, rng_seed=5,
                                           first_batch_index=3, neighbor_cache=nc)
             check_sample(res, ref, len(batches), len(fanout))
+
+
+def test_sampler_degenerate_shapes(ginex):
+    """Eight hops (the limit), a superbatch of one batch, a superbatch of empty batches only,
+    seeds without neighbours, and a list that saturates at the whole graph."""
+    off, ind = small_graph(300, 6000, seed=9)
+    o, i = off.numpy(), ind.numpy()
+    od, idv = off.cuda(), ind.cuda()
+    empty = torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
+    cases = [
+        ("eight hops", np.array([5, 9, 200], dtype=np.int32), [0, 3], (2,) * 8),
+        ("one batch", np.arange(40, dtype=np.int32), [0, 40], (10, 10)),
+        ("only empty batches", np.zeros(0, dtype=np.int32), [0, 0, 0, 0], (10, 10, 10)),
+        ("the list reaches every node", np.arange(300, dtype=np.int32), [0, 150, 300], (64, 64, 64)),
+    ]
+    for name, seeds, so, fanout in cases:
+        ref = oracle.sample_superbatch(o, i, seeds, so, fanout, rng_seed=2)
+        res = ginex.sample_superbatch(od, idv, dev(seeds) if len(seeds) else empty, so, fanout,
+                                      rng_seed=2)
+        try:
+            check_sample(res, ref, len(so) - 1, len(fanout))
+        except AssertionError:
+            print("failing case:", name, flush=True)
+            raise
+        # the changeset of whatever came out, for a cache of a quarter of it
+        cap = max(1, len(np.unique(ref["ids"])) // 4) if len(ref["ids"]) else 3
+        check_changeset(ginex.changeset(300, res.ids if len(ref["ids"]) else empty,
+                                        res.ids_offsets, cap),
+                        oracle.changeset(300, ref["ids"], ref["ids_offsets"], cap))
+    # a graph without any edge: every list is its seeds
+    n = 50
+    z = torch.zeros(n + 1, dtype=torch.int32)
+    seeds = np.array([3, 4, 4, 7], dtype=np.int32)
+    ref = oracle.sample_superbatch(z.numpy(), np.zeros(0, dtype=np.int32), seeds, [0, 4], (10, 10))
+    res = ginex.sample_superbatch(z.cuda(), empty, dev(seeds), [0, 4], (10, 10))
+    check_sample(res, ref, 1, 2)
+    assert list(res.ids.cpu().numpy()) == [3, 4, 7]
