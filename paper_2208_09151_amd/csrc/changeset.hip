@@ -620,14 +620,11 @@ __device__ void p_evict_flags(const State& st, const Ctrl& c, int64_t vb) {
 // stretch at its upper end, so they are found from there and their lines flagged through
 // the address table, instead of reading the key and id of every cache line.  The flag
 // words are all zero when the phase starts (p_evict_emit clears what it consumes).
-__device__ void p_dead_scatter(const State& st, const Ctrl& c, int64_t words, int64_t vb) {
+__device__ void p_dead_scatter(const State& st, const Ctrl& c, int64_t words, int64_t vb,
+                               int64_t vblocks) {
+  // the stretch above T is short as a rule, so a small grid strides over it from T's word on
   const int64_t t_word = c.T >> 5;
-  const int64_t base = (vb * TB + threadIdx.x) * BITS_WORDS;
-  if (base + BITS_WORDS <= t_word) return;
-#pragma unroll
-  for (int t = 0; t < BITS_WORDS; ++t) {
-    const int64_t w = base + t;
-    if (w >= words || w < t_word) continue;
+  for (int64_t w = t_word + vb * TB + threadIdx.x; w < words; w += vblocks * TB) {
     uint32_t bits = st.dead_bits[w];
     if (w == t_word) bits &= (c.T & 31) == 31 ? 0u : ~((2u << (c.T & 31)) - 1u);
     while (bits) {
@@ -800,7 +797,7 @@ __global__ __launch_bounds__(BIG) void k_bits_find(State st, int64_t words, int6
 
 __global__ __launch_bounds__(TB) void k_dead_scatter(State st, int64_t words) {
   const Ctrl c = *st.ctrl;
-  if (c.n_change > 0 && c.use_dead) p_dead_scatter(st, c, words, blockIdx.x);
+  if (c.n_change > 0 && c.use_dead) p_dead_scatter(st, c, words, blockIdx.x, gridDim.x);
 }
 
 // blocks [0, evict_tiles): evictions per tile; next in_tiles blocks: insertions per tile;
@@ -1142,8 +1139,8 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                          w.bit_words);
       hipLaunchKernelGGL(k_bits_find, dim3(1), dim3(BIG), 0, st, state, w.bit_words, w.bit_parts);
       if (state.dead_scatter)
-        hipLaunchKernelGGL(k_dead_scatter, dim3((unsigned)w.bit_parts), dim3(TB), 0, st, state,
-                           w.bit_words);
+        hipLaunchKernelGGL(k_dead_scatter, dim3((unsigned)(w.bit_parts < 64 ? w.bit_parts : 64)),
+                           dim3(TB), 0, st, state, w.bit_words);
       GINEX_LAUNCH_CHECK();
       hipLaunchKernelGGL(k_tile_count, dim3((unsigned)(w.evict_tiles + in_tiles + clear_blocks)),
                          dim3(TB), 0, st, state, it, w.evict_tiles, in_tiles, w.bit_words);
