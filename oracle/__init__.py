@@ -43,6 +43,7 @@ def lib():
                                             C.c_int64, C.c_int32, C.c_void_p]
         _lib.oracle_lru_misses.restype = C.c_int64
         _lib.oracle_static_misses.restype = C.c_int64
+        _lib.oracle_static_select.restype = C.c_int64
         _lib.oracle_gather_update.restype = C.c_int64
     return _lib
 
@@ -256,6 +257,16 @@ def lru_misses(num_nodes, ids, ids_offsets, cap, init_ids):
     return int(lib().oracle_lru_misses(
         C.c_int64(num_nodes), _p(ids), _p(ids_offsets), C.c_int32(len(ids_offsets) - 1),
         C.c_int64(cap), _p(init_ids), C.c_int64(len(init_ids))))
+
+
+def static_select(num_nodes, indices, cap):
+    """The ``cap`` nodes of highest out-degree (occurrences in ``indices``), larger degree
+    first, smaller id first among equals."""
+    indices = _i32(indices)
+    out = np.zeros(max(min(cap, num_nodes), 1), dtype=np.int32)
+    n = int(lib().oracle_static_select(C.c_int64(num_nodes), _p(indices),
+                                       C.c_int64(len(indices)), C.c_int64(cap), _p(out)))
+    return out[:n].copy()
 
 
 def static_misses(num_nodes, ids, members):

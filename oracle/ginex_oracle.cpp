@@ -23,6 +23,11 @@
 //   neighbour cache        the layout values the paper states for its figure, an exact
 //                          rational ranking in Python, lookup == CSR row for every cached
 //                          node, sampling through the cache == sampling without it
+//   static_select          star / ladder / all-equal graphs whose ranking is known in closed
+//                          form, "no unselected node has a larger out-degree" against a
+//                          library histogram, the order inside ties
+//   static_misses          a hand-counted trace, total - sum of the members' access counts
+//                          against a library histogram, the empty and the complete cache
 //   gather / cache replay  the worked ten-node example of the paper, out[p] == slow[ids[p]]
 //
 // Build: g++ -O2 -std=c++17 -shared -fPIC ginex_oracle.cpp -o libginex_oracle.so
@@ -720,6 +725,27 @@ int64_t oracle_lru_misses(int64_t num_nodes, const int32_t* ids, const int64_t* 
     }
   }
   return misses;
+}
+
+// Content of a static cache (Section 2.3 "Challenge 1": the policy of the
+// systems the paper compares with keeps the nodes of highest out-degree in
+// memory for the whole run).  Rows of the CSR are in-neighbour lists, so a
+// node's out-degree is the number of times it occurs in `indices`.  The cache
+// takes the `cap` nodes of highest out-degree; among equal out-degrees the
+// smaller id comes first (the paper does not say).  out_ids[r] = node of rank r.
+// Returns how many were written: min(cap, num_nodes).
+int64_t oracle_static_select(int64_t num_nodes, const int32_t* indices, int64_t num_edges,
+                             int64_t cap, int32_t* out_ids) {
+  std::vector<int64_t> out_degree(num_nodes, 0);
+  for (int64_t e = 0; e < num_edges; ++e) ++out_degree[indices[e]];
+  std::vector<int32_t> order(num_nodes);
+  for (int64_t v = 0; v < num_nodes; ++v) order[v] = (int32_t)v;
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+    return out_degree[a] > out_degree[b];   // stable: equal degrees stay in id order
+  });
+  const int64_t count = cap < num_nodes ? cap : num_nodes;
+  for (int64_t r = 0; r < count; ++r) out_ids[r] = order[r];
+  return count < 0 ? 0 : count;
 }
 
 // Miss count of a cache whose content never changes (the static policies the
