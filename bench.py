@@ -264,8 +264,7 @@ def pipeline_leg(ginex, w, K):
         seeds, so = seed_batches(train, cfg.batch, cfg.S, cfg.seed, first_batch=k * cfg.S)
         more.append((seeds.cuda(), so.numpy(), k * cfg.S))
     del executor
-    start = torch.argsort(torch.bincount(w.indices, minlength=cfg.num_nodes),
-                          descending=True)[:cfg.cap].to(torch.int32).contiguous()
+    start = ginex.static_select(cfg.num_nodes, w.indices, cfg.cap)
     cache.init(start)
     carried = ginex.Executor(cache)
     pipe.carry_cache_from(start)

@@ -256,6 +256,31 @@ int32_t ginex_cache_update(const ginex_cache_t* c /*host struct*/, const void* o
                            const int32_t* in_ids, const int32_t* out_ids,
                            const int32_t* in_positions, int64_t n_change, void* stream);
 
+/* ---------------------------------------------------------------------------------
+ * Static cache policy (Section 2.3 "Challenge 1": the policy the paper compares Belady's
+ * with keeps the nodes of highest out-degree in memory and never replaces them; Figure
+ * "miss ratio over cache size").  With CSR rows holding in-neighbours, a node's out-degree
+ * is the number of times it occurs in g->indices (device or host-pinned memory; g->offsets
+ * and the nc_* fields are not read).  static_ids[r] (device, [min(cap, num_nodes)]) receives
+ * the node of rank r: larger out-degree first, smaller id first among equal out-degrees.
+ * count (host) receives min(cap, num_nodes).  An entry of indices outside [0, num_nodes)
+ * returns GINEX_ERR_INPUT.  The call waits for the stream before it returns.
+ * A static run is ginex_cache_init(static_ids) followed by ginex_gather calls with
+ * n_change = 0.
+ * ------------------------------------------------------------------------------- */
+size_t ginex_static_select_workspace_bytes(int64_t num_nodes);
+
+int32_t ginex_static_select(const ginex_csr_t* g /*host struct*/, int64_t cap,
+                            int32_t* static_ids, int64_t* count /*host*/,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/* Misses of one iteration against the cache as it stands (Section 3.3: an id whose
+ * address-table entry is -1 is read from the slow tier): adds |{p : addr[ids[p]] < 0}| to
+ * *misses (device, 8-byte aligned; the caller zeroes it).  For policies whose changesets do
+ * not carry miss counts (the static cache).  Only enqueues. */
+int32_t ginex_cache_count_misses(const ginex_cache_t* c /*host struct*/, const int32_t* ids,
+                                 int64_t n, int64_t* misses, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

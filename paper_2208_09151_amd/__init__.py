@@ -7,6 +7,6 @@ There is no CPU fallback: without the built library, or without a GPU, calls rai
 """
 from .api import (GinexError, FeatureCache, SampleResult, ChangesetResult,  # noqa: F401
                   NeighborCache, neighbor_cache_build, sample_superbatch, changeset,
-                  changeset_resume,
+                  changeset_resume, static_select,
                   library_path, version)
 from .pipeline import Executor, InspectorPipeline  # noqa: F401

@@ -40,18 +40,41 @@ SIGNATURES = {
     "ginex_cache_init_warm": (i32, [C.POINTER(CacheDesc), C.POINTER(CacheDesc), vp, i64, i64, vp]),
     "ginex_gather": (i32, [C.POINTER(CacheDesc), vp, i64, vp, vp, vp, vp, i64, vp]),
     "ginex_cache_update": (i32, [C.POINTER(CacheDesc), vp, vp, vp, vp, i64, vp]),
+    "ginex_static_select_workspace_bytes": (sz, [i64]),
+    "ginex_static_select": (i32, [C.POINTER(CsrDesc), i64, vp, vp, vp, sz, vp]),
+    "ginex_cache_count_misses": (i32, [C.POINTER(CacheDesc), vp, i64, vp, vp]),
 }
 
 _lib = None
 
 
+def stale() -> bool:
+    """True if the library is missing or older than any of its sources."""
+    if not os.path.exists(LIB_PATH):
+        return True
+    built = os.path.getmtime(LIB_PATH)
+    csrc = os.path.join(_PKG, "csrc")
+    sources = [os.path.join(csrc, f) for f in os.listdir(csrc)
+               if f.endswith((".hip", ".hpp", ".cpp"))]
+    sources.append(os.path.join(os.path.dirname(_PKG), "include", "ginex.h"))
+    return any(os.path.getmtime(s) > built for s in sources if os.path.exists(s))
+
+
 def load():
-    """Loads the built library; builds it first only if it has never been built."""
+    """Loads the built library.  A library that is missing, or older than one of its sources
+    (csrc/*, include/ginex.h), is rebuilt first where the compiler is installed; where it is
+    not, a stale library is an error rather than a silent run of old kernels."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            from .build import build
-            build()
+        if stale():
+            from .build import HIPCC, build
+            if os.path.exists(HIPCC):
+                build()
+            elif os.path.exists(LIB_PATH):
+                raise RuntimeError(f"{LIB_PATH} is older than its sources and {HIPCC} is not "
+                                   "installed here: rebuild with python -m paper_2208_09151_amd.build")
+            else:
+                raise RuntimeError(f"{LIB_PATH} has not been built and {HIPCC} is not installed")
         lib = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)     # AttributeError if the library lacks a declared symbol

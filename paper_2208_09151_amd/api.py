@@ -131,6 +131,23 @@ def neighbor_cache_build(offsets, indices, budget, device="cuda"):
     return NeighborCache(address_table, cache_array, int(cached[0]), int(used[0]))
 
 
+def static_select(num_nodes, indices, cap, device="cuda"):
+    """ginex_static_select: the ``cap`` nodes of highest out-degree (occurrences in
+    ``indices``, device or pinned host int32), as a device int32 tensor in rank order."""
+    lib = _lib.load()
+    _readable(indices, torch.int32)
+    need = lib.ginex_static_select_workspace_bytes(num_nodes)
+    if need == 0:
+        raise GinexError(-1, lib.ginex_last_error().decode())
+    ws = torch.empty(need, dtype=torch.uint8, device=device)
+    out = torch.empty(max(min(cap, num_nodes), 1), dtype=torch.int32, device=device)
+    count = np.zeros(1, dtype=np.int64)
+    g = CsrDesc(num_nodes, indices.numel(), None, 0, indices.data_ptr(), None, None)
+    _check(lib.ginex_static_select(C.byref(g), cap, _ptr(out), _np_ptr(count), _ptr(ws),
+                                   ws.numel(), _stream()))
+    return out[:int(count[0])]
+
+
 def sample_superbatch(offsets, indices, seeds, seed_offsets, fanout, rng_seed=0,
                       first_batch_index=0, with_adj=True, workspace=None, out=None,
                       neighbor_cache=None):
@@ -330,6 +347,14 @@ class FeatureCache:
                           stream_ptr)
         if rc:
             _check(rc)
+
+    def count_misses(self, ids, counter: torch.Tensor):
+        """ginex_cache_count_misses: adds the number of ``ids`` not resident right now to
+        ``counter`` (device int64, one element, zeroed by the caller)."""
+        _dev(ids, torch.int32)
+        _dev(counter, torch.int64)
+        _check(_lib.load().ginex_cache_count_misses(C.byref(self._desc), _ptr(ids), ids.numel(),
+                                                    _ptr(counter), _stream()))
 
     def update(self, out, in_ids, out_ids, in_positions):
         """The cache update alone, for a gather that was issued without a changeset."""

@@ -15,8 +15,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libginex.so")
-CALIB = os.path.join(PKG, "calib_copy")
-SOURCES = ["core.cpp", "gather.hip", "sampler.hip", "changeset.hip", "neighbor_cache.hip"]
+SOURCES = ["core.cpp", "gather.hip", "sampler.hip", "changeset.hip", "neighbor_cache.hip",
+           "static_policy.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -42,13 +42,8 @@ def build(verbose: bool = False) -> str:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
     subprocess.check_call(cmd)
-    # stand-alone calibration program for the HBM traffic counters (see calib_copy.hip)
-    r = subprocess.run([HIPCC, "-O3", "--offload-arch=gfx950", os.path.join(CSRC, "calib_copy.hip"),
-                        "-o", CALIB], capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed on calib_copy.hip:\n" + r.stderr)
     if verbose:
-        print("built", LIB, "and", CALIB)
+        print("built", LIB)
     return LIB
 
 

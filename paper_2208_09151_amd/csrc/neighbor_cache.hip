@@ -22,19 +22,6 @@ __device__ __forceinline__ uint64_t sort_key(uint32_t out_degree, int64_t in_deg
   return ~ratio;
 }
 
-// Entries outside [0, num_nodes) are counted in *bad and skipped.
-__global__ __launch_bounds__(TB) void k_out_degree(const int32_t* __restrict__ indices,
-                                                   int64_t num_edges, int64_t num_nodes,
-                                                   uint32_t* __restrict__ out_degree,
-                                                   unsigned long long* __restrict__ bad) {
-  const int64_t span = (int64_t)gridDim.x * TB;
-  for (int64_t e = (int64_t)blockIdx.x * TB + threadIdx.x; e < num_edges; e += span) {
-    const int32_t v = indices[e];
-    if ((uint32_t)v < (uint64_t)num_nodes) atomicAdd(&out_degree[v], 1u);
-    else atomicAdd(bad, 1ull);
-  }
-}
-
 // items[v] = (low half of the key << 32) | v: sorted first on the low half ...
 __global__ __launch_bounds__(TB) void k_items_low(const void* __restrict__ offsets, int off64,
                                                   const uint32_t* __restrict__ out_degree,
@@ -196,13 +183,7 @@ extern "C" int32_t ginex_neighbor_cache_build(const ginex_csr_t* g, int64_t budg
 
   GINEX_HIP(fill_async<uint32_t>(w.out_degree, n, 0u, st));
   GINEX_HIP(fill_async<unsigned long long>(w.counters, 4, 0ull, st));
-  if (g->num_edges > 0) {
-    int64_t blocks = ceil_div(g->num_edges, (int64_t)TB * 16);
-    if (blocks > 16384) blocks = 16384;
-    hipLaunchKernelGGL(k_out_degree, dim3((unsigned)blocks), dim3(TB), 0, st, g->indices,
-                       g->num_edges, n, w.out_degree, w.counters + 3);
-    GINEX_LAUNCH_CHECK();
-  }
+  GINEX_HIP(occurrences_async(g->indices, g->num_edges, n, w.out_degree, w.counters + 3, st));
   hipLaunchKernelGGL(k_items_low, dim3(node_blocks), dim3(TB), 0, st, g->offsets, off64,
                      w.out_degree, n, w.items_a);
   GINEX_LAUNCH_CHECK();

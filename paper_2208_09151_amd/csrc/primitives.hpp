@@ -77,6 +77,33 @@ inline hipError_t exclusive_scan_inplace(T* data, int64_t n, T* scratch, hipStre
 }
 
 // ---------------------------------------------------------------------------------
+// Occurrence histogram: count[v] += number of times v occurs in values[0..n).  With the CSR
+// rows holding in-neighbours this is the out-degree of every node.  Entries outside
+// [0, bins) are counted in *bad and skipped.  `values` may live in host-pinned memory.
+// ---------------------------------------------------------------------------------
+static __global__ __launch_bounds__(256) void k_occurrences(const int32_t* __restrict__ values,
+                                                            int64_t n, int64_t bins,
+                                                            uint32_t* __restrict__ count,
+                                                            unsigned long long* __restrict__ bad) {
+  const int64_t span = (int64_t)gridDim.x * 256;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += span) {
+    const int32_t v = values[e];
+    if ((uint32_t)v < (uint64_t)bins) atomicAdd(&count[v], 1u);
+    else atomicAdd(bad, 1ull);
+  }
+}
+
+inline hipError_t occurrences_async(const int32_t* values, int64_t n, int64_t bins, uint32_t* count,
+                                    unsigned long long* bad, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = ceil_div(n, (int64_t)256 * 16);
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(k_occurrences, dim3((unsigned)blocks), dim3(256), 0, st, values, n, bins, count,
+                     bad);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
 // Stable LSD radix sort of uint64 words on bits [bit_lo, bit_hi), 8 bits per pass.
 // Each pass: (1) per-tile digit histogram, (2) exclusive scan of the digit-major
 // histogram, (3) scatter.  In the scatter a wave owns a contiguous run of its tile and

@@ -904,3 +904,65 @@ def test_sampler_degenerate_shapes(ginex):
     res = ginex.sample_superbatch(z.cuda(), empty, dev(seeds), [0, 4], (10, 10))
     check_sample(res, ref, 1, 2)
     assert list(res.ids.cpu().numpy()) == [3, 4, 7]
+
+
+# ---- static highest-out-degree cache (Section 2.3) ------------------------------------
+
+def test_static_select_matches_oracle_on_small_and_structured_graphs(ginex):
+    rng = np.random.default_rng(11)
+    graphs = []
+    for n, e in ((1, 0), (1, 5), (9, 0), (300, 6000), (5000, 40000), (70000, 900000)):
+        graphs.append((n, rng.integers(0, n, size=e).astype(np.int32)))
+    graphs.append((9, np.full(9, 5, dtype=np.int32)))                              # star
+    graphs.append((40, np.concatenate([np.full(v, v, np.int32) for v in range(40)])))  # ladder
+    graphs.append((1000, np.arange(1000, dtype=np.int32)[::-1].copy()))            # all tie
+    hub = np.concatenate([np.zeros(300000, np.int32) + 77, rng.integers(0, 500, 2000).astype(np.int32)])
+    graphs.append((500, hub))                                                       # 19-bit degree
+    for n, ind in graphs:
+        ind_d = dev(ind) if len(ind) else torch.zeros(0, dtype=torch.int32, device="cuda")
+        for cap in sorted({0, 1, n // 3, n, n + 7}):
+            got = ginex.static_select(n, ind_d, cap).cpu().numpy()
+            want = oracle.static_select(n, ind, cap)
+            assert np.array_equal(got, want), (n, len(ind), cap)
+    with pytest.raises(ginex.GinexError) as err:
+        ginex.static_select(10, dev(np.array([1, 2, 10], dtype=np.int32)), 3)
+    assert err.value.code == -4
+
+
+@pytest.mark.parametrize("which", ["case1", "case2"])
+def test_static_cache_through_the_executor(ginex, which, request):
+    c = request.getfixturevalue(which)
+    n, cap = c.cfg.num_nodes, c.cfg.cap
+    sel = ginex.static_select(n, c.w.indices, cap)
+    want_sel = oracle.static_select(n, c.ind, cap)
+    assert np.array_equal(sel.cpu().numpy(), want_sel)
+    # the indices may also sit in pinned host memory
+    pinned = torch.empty(c.w.indices.numel(), dtype=torch.int32, pin_memory=True)
+    pinned.copy_(c.w.indices)
+    assert torch.equal(ginex.static_select(n, pinned, cap), sel)
+    slow = c.w.features
+    sb = slow.numpy().view(np.uint8).reshape(slow.shape[0], -1)
+    cache = ginex.FeatureCache(slow, cap)
+    cache.init(sel)
+    ref = oracle.Cache(slow.numpy(), cap)
+    ref.init(want_sel)
+    assert np.array_equal(cache.addr.cpu().numpy(), ref.addr)
+    ids_d = dev(c.samp["ids"])
+    io = c.samp["ids_offsets"]
+    counter = torch.zeros(1, dtype=torch.int64, device="cuda")
+    none = np.zeros(0, dtype=np.int32)
+    hits = 0
+    for i in range(c.cfg.S):
+        ids_i = c.samp["ids"][io[i]:io[i + 1]]
+        cache.count_misses(ids_d[io[i]:io[i + 1]], counter)
+        out = cache.gather(ids_d[io[i]:io[i + 1]])
+        got = out.cpu().numpy().view(np.uint8).reshape(out.shape[0], -1)
+        want, h = ref.gather_update(ids_i, none, none, none)
+        hits += h
+        assert np.array_equal(got, want), i
+        assert np.array_equal(got, sb[ids_i]), i
+    misses = int(counter.item())
+    assert misses == len(c.samp["ids"]) - hits
+    assert misses == oracle.static_misses(n, c.samp["ids"], want_sel)
+    assert np.array_equal(cache.addr.cpu().numpy(), ref.addr)          # a static cache never changes
+    assert misses >= int(c.cs["miss_count"].sum())                      # Belady is the lower bound

@@ -18,7 +18,7 @@ def test_every_declared_symbol_is_exported_and_bound():
     from paper_2208_09151_amd import _lib
     lib = _lib.load()
     names = declared_symbols()
-    assert len(names) == 15
+    assert len(names) == 18
     assert sorted(_lib.SIGNATURES) == names
     for n in names:
         assert getattr(lib, n) is not None
@@ -125,5 +125,15 @@ def test_precondition_and_workspace_errors_are_reported_before_any_launch():
                                           16, None) == -3
     assert lib.ginex_neighbor_cache_workspace_bytes(0) == 0
     assert lib.ginex_cache_update(ctypes.byref(c), fake, fake, fake, fake, 9, None) == -1
+    # static policy: descriptor, outputs and workspace are checked on the host
+    assert lib.ginex_static_select_workspace_bytes(0) == 0
+    assert lib.ginex_static_select_workspace_bytes(1000) > 2 * 8 * 1000
+    assert lib.ginex_static_select(None, 3, fake, P(cn), fake, 1 << 40, None) == -1
+    assert lib.ginex_static_select(ctypes.byref(g), 3, None, P(cn), fake, 1 << 40, None) == -1
+    assert lib.ginex_static_select(ctypes.byref(g), -1, fake, P(cn), fake, 1 << 40, None) == -1
+    assert lib.ginex_static_select(ctypes.byref(g), 3, fake, P(cn), fake, 16, None) == -3
+    assert lib.ginex_cache_count_misses(None, fake, 3, fake, None) == -1
+    assert lib.ginex_cache_count_misses(ctypes.byref(c), None, 3, fake, None) == -1
+    assert lib.ginex_cache_count_misses(ctypes.byref(c), fake, 3, None, None) == -1
     assert lib.ginex_gather(ctypes.byref(c), fake, 2, ctypes.c_void_p(0x1008), None, None, None,
                             0, None) == -1                                   # out misaligned
