@@ -181,6 +181,26 @@ int32_t ginex_changeset_lru(
     int64_t* total_changes /*host*/, int64_t* init_ready /*host [S] or NULL*/,
     void* ws, size_t ws_bytes, void* stream);
 
+/* ginex_changeset for callers that cannot allocate device memory or hand over a workspace
+ * (code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the same arguments, outputs, order and limits, without `ws`.  The scratch
+ * memory is an array of GINEX_NOALLOC_SCRATCH_BYTES built into the library, one copy per GPU,
+ * held until the process ends; the call allocates nothing on the device and frees nothing.
+ * A shape whose ginex_changeset_workspace_bytes figure exceeds that size is rejected with
+ * GINEX_ERR_WORKSPACE before anything is launched.  All calls on one GPU share the array:
+ * calls that overlap in time on the same GPU (other streams, other threads) race; one after
+ * the other they are independent, the array needs no clearing by the caller. */
+#define GINEX_NOALLOC_SCRATCH_BYTES (64ll << 20)
+
+int32_t ginex_changeset_noalloc(
+    int64_t num_nodes, const int32_t* ids, const int64_t* ids_offsets /*host [S+1]*/,
+    int32_t S, int64_t cap,
+    int32_t* init_ids /*[cap]*/, int64_t* init_count /*host*/,
+    int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
+    int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
+    int64_t* total_changes /*host*/, int64_t* init_ready /*host [S] or NULL*/,
+    void* stream);
+
 /* Belady changesets of a superbatch that starts from the cache the previous superbatch left
  * behind (an extension: the paper prefetches a fresh C_0 for every superbatch, Section 3.1,
  * which costs one slow-tier read per distinct row per superbatch; carried over, only rows

@@ -31,6 +31,8 @@ SIGNATURES = {
     "ginex_changeset_workspace_bytes": (sz, [i64, i64, i32, i64]),
     "ginex_changeset": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp,
                               vp, sz, vp]),
+    "ginex_changeset_noalloc": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp,
+                                      vp]),
     "ginex_changeset_lru": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp,
                                   vp, sz, vp]),
     "ginex_changeset_resume": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp,

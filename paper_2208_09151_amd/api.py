@@ -211,22 +211,29 @@ class ChangesetResult:
     final_ids: torch.Tensor = None  # resumed superbatches: row of every line after the last iteration
 
 
-def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady"):
+def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady",
+              builtin_scratch=False):
     """ginex_changeset (``policy="belady"``) or ginex_changeset_lru (``policy="lru"``).
-    ``ids`` is a device int32 tensor, ``ids_offsets`` a host array."""
+    ``ids`` is a device int32 tensor, ``ids_offsets`` a host array.  ``builtin_scratch``:
+    ginex_changeset_noalloc, which takes no workspace (small shapes only); the outputs are
+    still allocated here, by the caller."""
     lib = _lib.load()
     if policy not in ("belady", "lru"):
         raise ValueError(f"unknown policy {policy!r}")
+    if builtin_scratch and policy != "belady":
+        raise ValueError("the allocation-free entry point exists for Belady changesets only")
     entry = lib.ginex_changeset if policy == "belady" else lib.ginex_changeset_lru
     _dev(ids, torch.int32)
     io = np.ascontiguousarray(np.asarray(ids_offsets), dtype=np.int64)
     S = len(io) - 1
     total = int(io[-1]) if S >= 0 else 0
     dev = ids.device
-    need = lib.ginex_changeset_workspace_bytes(num_nodes, total, S, cap)
-    if need == 0:
-        raise GinexError(-1, lib.ginex_last_error().decode())
-    ws = workspace if workspace is not None and workspace.numel() >= need else _workspace(need, dev)
+    if not builtin_scratch:
+        need = lib.ginex_changeset_workspace_bytes(num_nodes, total, S, cap)
+        if need == 0:
+            raise GinexError(-1, lib.ginex_last_error().decode())
+        ws = workspace if workspace is not None and workspace.numel() >= need \
+            else _workspace(need, dev)
     init_ids = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
     cs_cap = max(total, 1)
     in_ids = torch.empty(cs_cap, dtype=torch.int32, device=dev)
@@ -237,9 +244,16 @@ def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady")
     init_count = np.zeros(1, dtype=np.int64)
     total_changes = np.zeros(1, dtype=np.int64)
     init_ready = np.zeros(max(S, 1), dtype=np.int64)
-    rc = entry(num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(init_ids), _np_ptr(init_count),
-               _ptr(in_ids), _ptr(out_ids), _ptr(in_pos), cs_cap, _ptr(cs_off), _ptr(miss),
-               _np_ptr(total_changes), _np_ptr(init_ready), _ptr(ws), ws.numel(), _stream())
+    if builtin_scratch:
+        rc = lib.ginex_changeset_noalloc(
+            num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(init_ids), _np_ptr(init_count),
+            _ptr(in_ids), _ptr(out_ids), _ptr(in_pos), cs_cap, _ptr(cs_off), _ptr(miss),
+            _np_ptr(total_changes), _np_ptr(init_ready), _stream())
+    else:
+        rc = entry(num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(init_ids),
+                   _np_ptr(init_count), _ptr(in_ids), _ptr(out_ids), _ptr(in_pos), cs_cap,
+                   _ptr(cs_off), _ptr(miss), _np_ptr(total_changes), _np_ptr(init_ready),
+                   _ptr(ws), ws.numel(), _stream())
     _check(rc)
     n = int(total_changes[0])
     return ChangesetResult(init_ids[:int(init_count[0])], in_ids[:n], out_ids[:n], in_pos[:n],

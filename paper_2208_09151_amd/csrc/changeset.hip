@@ -18,7 +18,7 @@
 //   The same loop serves the LRU policy (other keys) and a superbatch that resumes from the
 //   cache state of the previous one (C_0 given instead of computed).
 #include <cstdlib>
-#include <vector>
+#include <mutex>
 
 #include "common.hpp"
 #include "primitives.hpp"
@@ -259,6 +259,13 @@ __global__ __launch_bounds__(TB) void k_init_state_resume(const int32_t* __restr
   __syncthreads();
   for (int j = threadIdx.x; j <= st.S; j += TB)
     if (lds_hist[j]) atomicAdd(&st.rhist[j], lds_hist[j]);
+}
+
+// miss_count[i] = |ids_i| (a cache without lines: every access misses)
+__global__ __launch_bounds__(TB) void k_iteration_lengths(const int64_t* __restrict__ off, int32_t S,
+                                                          int64_t* __restrict__ miss_count) {
+  const int32_t i = blockIdx.x * TB + threadIdx.x;
+  if (i < S) miss_count[i] = off[i + 1] - off[i];
 }
 
 __global__ __launch_bounds__(TB) void k_copy_init(const uint64_t* __restrict__ heads, int64_t count,
@@ -1061,13 +1068,9 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       GINEX_LAUNCH_CHECK();
     }
     if (cap == 0) {
-      // miss_count[i] = |ids_i|
-      std::vector<int64_t> tmp(S);
-      for (int32_t i = 0; i < S; ++i) tmp[i] = ids_offsets[i + 1] - ids_offsets[i];
-      GINEX_HIP(hipMemcpyAsync(miss_count, tmp.data(), sizeof(int64_t) * S, hipMemcpyHostToDevice,
-                               st));
-      GINEX_HIP(hipStreamSynchronize(st));
-      return GINEX_OK;
+      hipLaunchKernelGGL(k_iteration_lengths, dim3((unsigned)ceil_div(S, TB)), dim3(TB), 0, st,
+                         w.d_offsets, S, miss_count);
+      GINEX_LAUNCH_CHECK();
     }
     GINEX_HIP(hipStreamSynchronize(st));
     return GINEX_OK;
@@ -1210,4 +1213,66 @@ extern "C" int32_t ginex_changeset_lru(int64_t num_nodes, const int32_t* ids,
                        init_count, in_ids, out_ids, in_positions, cs_capacity, cs_offsets,
                        miss_count, total_changes, init_ready, nullptr, nullptr, ws, ws_bytes,
                        stream);
+}
+
+// ---- the variant that allocates nothing ------------------------------------------------
+//
+// The workspace of ginex_changeset_noalloc is a static device array.  Every GPU the library
+// runs on holds its own copy at its own address until the process ends; in host code the
+// array's name is only a stand-in for the symbol, so the device address is looked up once per
+// device (with that device current) and that pointer is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[GINEX_NOALLOC_SCRATCH_BYTES];
+
+namespace ginex {
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+int32_t scratch_for_current_device(const char* who, void** out) {
+  int device = -1;
+  GINEX_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= MAX_DEVICES)
+    return fail(GINEX_ERR_HIP, "%s: device index %d outside [0, %d)", who, device, MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    GINEX_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(GINEX_ERR_HIP, "%s: the scratch array has no device address", who);
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return GINEX_OK;
+}
+
+}  // namespace
+}  // namespace ginex
+
+extern "C" int32_t ginex_changeset_noalloc(int64_t num_nodes, const int32_t* ids,
+                                           const int64_t* ids_offsets, int32_t S, int64_t cap,
+                                           int32_t* init_ids, int64_t* init_count,
+                                           int32_t* in_ids, int32_t* out_ids,
+                                           int32_t* in_positions, int64_t cs_capacity,
+                                           int64_t* cs_offsets, int64_t* miss_count,
+                                           int64_t* total_changes, int64_t* init_ready,
+                                           void* stream) {
+  const char* who = "ginex_changeset_noalloc";
+  if (!ids_offsets) return fail(GINEX_ERR_ARG, "%s: ids_offsets is null", who);
+  const int64_t total = S >= 1 ? ids_offsets[S] : 0;
+  if (int32_t rc = check_shape(num_nodes, total, S, cap, who)) return rc;
+  const int64_t bound = total < num_nodes ? total : num_nodes;
+  const size_t need = carve(nullptr, num_nodes, total, S, cap, bound).bytes;
+  if (need > (size_t)GINEX_NOALLOC_SCRATCH_BYTES)
+    return fail(GINEX_ERR_WORKSPACE,
+                "%s: this shape (num_nodes=%lld, %lld ids, S=%d, cap=%lld) needs %zu bytes of "
+                "scratch, the built-in array holds %zu: use ginex_changeset with a workspace", who,
+                (long long)num_nodes, (long long)total, S, (long long)cap, need,
+                (size_t)GINEX_NOALLOC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  if (int32_t rc = scratch_for_current_device(who, &ws)) return rc;
+  return changeset_run(who, false, num_nodes, ids, ids_offsets, S, cap, init_ids, init_count,
+                       in_ids, out_ids, in_positions, cs_capacity, cs_offsets, miss_count,
+                       total_changes, init_ready, nullptr, nullptr, ws,
+                       (size_t)GINEX_NOALLOC_SCRATCH_BYTES, stream);
 }

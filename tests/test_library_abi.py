@@ -18,7 +18,7 @@ def test_every_declared_symbol_is_exported_and_bound():
     from paper_2208_09151_amd import _lib
     lib = _lib.load()
     names = declared_symbols()
-    assert len(names) == 18
+    assert len(names) == 19
     assert sorted(_lib.SIGNATURES) == names
     for n in names:
         assert getattr(lib, n) is not None
