@@ -142,6 +142,12 @@ int32_t ginex_neighbor_cache_build(const ginex_csr_t* g /*host struct*/, int64_t
  *   those positions, out_ids = C_i\C_{i+1} ordered by cache line; in_ids[j] takes the
  *   line of out_ids[j].  Records of iteration i occupy [cs_offsets[i], cs_offsets[i+1]).
  *   miss_count[i] = |ids_i \ C_i|.
+ *   src_line (device, [ids_offsets[S]], may be NULL): for every access p of iteration i, the
+ *   cache line that holds ids[p] in C_i, or -1 if the row is not resident then.  It is what
+ *   the address table of Section 3.3 would return at gather time, resolved ahead of time, so
+ *   that the executor's gather (ginex_gather_lines) reads it sequentially instead of probing
+ *   the table; it holds for an executor that loads C_0 line by line and applies every
+ *   changeset in order.
  * init_count and total_changes are host outputs.  cs_capacity >= total_changes is
  * required (ids_offsets[S] always suffices).
  * init_ready (host, [S], may be NULL): init_ready[i] = number of rows of C_0 first accessed
@@ -163,6 +169,7 @@ int32_t ginex_changeset(
     int32_t* init_ids /*[cap]*/, int64_t* init_count /*host*/,
     int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
     int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
+    int32_t* src_line /*[total ids] or NULL*/,
     int64_t* total_changes /*host*/, int64_t* init_ready /*host [S] or NULL*/,
     void* ws, size_t ws_bytes, void* stream);
 
@@ -178,6 +185,7 @@ int32_t ginex_changeset_lru(
     int32_t* init_ids /*[cap]*/, int64_t* init_count /*host*/,
     int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
     int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
+    int32_t* src_line /*[total ids] or NULL*/,
     int64_t* total_changes /*host*/, int64_t* init_ready /*host [S] or NULL*/,
     void* ws, size_t ws_bytes, void* stream);
 
@@ -198,6 +206,7 @@ int32_t ginex_changeset_noalloc(
     int32_t* init_ids /*[cap]*/, int64_t* init_count /*host*/,
     int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
     int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
+    int32_t* src_line /*[total ids] or NULL*/,
     int64_t* total_changes /*host*/, int64_t* init_ready /*host [S] or NULL*/,
     void* stream);
 
@@ -216,6 +225,7 @@ int32_t ginex_changeset_resume(
     int32_t S, int64_t cap, const int32_t* start_ids /*[cap]*/, int32_t* final_ids /*[cap]*/,
     int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
     int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
+    int32_t* src_line /*[total ids] or NULL*/,
     int64_t* total_changes /*host*/,
     void* ws, size_t ws_bytes, void* stream);
 
@@ -267,6 +277,18 @@ int32_t ginex_cache_init_warm(const ginex_cache_t* c /*host struct*/,
 int32_t ginex_gather(const ginex_cache_t* c /*host struct*/, const int32_t* ids, int64_t n,
                      void* out, const int32_t* in_ids, const int32_t* out_ids,
                      const int32_t* in_positions, int64_t n_change, void* stream);
+
+/* The same iteration with the address-table lookups resolved ahead of time: src_line[p]
+ * (device, [n]) is the cache line of ids[p], or -1 for a row to be read from the slow tier
+ * (the src_line output of ginex_changeset* for this iteration).  The gather reads src_line
+ * and ids sequentially and never probes the address table; the update is the one of
+ * ginex_gather and keeps the address table current, so the two calls may be mixed.  The
+ * gathered bytes equal those of ginex_gather provided src_line describes the cache as it
+ * stands (checked by the caller's bookkeeping, not by the kernel). */
+int32_t ginex_gather_lines(const ginex_cache_t* c /*host struct*/, const int32_t* ids,
+                           const int32_t* src_line, int64_t n, void* out,
+                           const int32_t* in_ids, const int32_t* out_ids,
+                           const int32_t* in_positions, int64_t n_change, void* stream);
 
 /* The cache update of one iteration on its own (Section 3.1 "Main Loop": the step between
  * gather and transfer; Section 3.3 "Feature Cache Update"): exactly the second half of

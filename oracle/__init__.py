@@ -275,6 +275,20 @@ def static_misses(num_nodes, ids, members):
                                           _p(members), C.c_int64(len(members))))
 
 
+def resolve_lines(num_nodes, ids, ids_offsets, init_ids, in_ids, out_ids, cs_offsets):
+    """Address-table lookup result (cache line or -1) of every access, the table being set up
+    from ``init_ids`` and patched with each iteration's update after that iteration's
+    lookups."""
+    ids, ids_offsets, init_ids = _i32(ids), _i64(ids_offsets), _i32(init_ids)
+    in_ids, out_ids, cs_offsets = _i32(in_ids), _i32(out_ids), _i64(cs_offsets)
+    lines = np.zeros(max(len(ids), 1), dtype=np.int32)
+    lib().oracle_resolve_lines(C.c_int64(num_nodes), _p(ids), _p(ids_offsets),
+                               C.c_int32(len(ids_offsets) - 1), _p(init_ids),
+                               C.c_int64(len(init_ids)), _p(in_ids), _p(out_ids), _p(cs_offsets),
+                               _p(lines))
+    return lines[:len(ids)]
+
+
 def _bytes2d(a):
     a = np.ascontiguousarray(a)
     return a.view(np.uint8).reshape(a.shape[0], -1)

@@ -29,6 +29,8 @@
 //   static_misses          a hand-counted trace, total - sum of the members' access counts
 //                          against a library histogram, the empty and the complete cache
 //   gather / cache replay  the worked ten-node example of the paper, out[p] == slow[ids[p]]
+//   resolve_lines          the same example, the address table of the cache replay before
+//                          every iteration, hit counts
 //
 // Build: g++ -O2 -std=c++17 -shared -fPIC ginex_oracle.cpp -o libginex_oracle.so
 
@@ -799,6 +801,28 @@ int64_t oracle_gather_update(uint8_t* cache, int32_t* address_table, const uint8
 
 // Feature cache initialization (Section 3.1): load the rows named in `init`
 // and build the address table.
+// What the address table returns for every access of a superbatch (Section 3.3 "Feature
+// Cache Structure": the entry of a node is its cache line, or -1): the table is set up
+// from `init` (line r holds init_ids[r]) and, after the lookups of iteration i, patched
+// with update_i exactly as the cache update does (in_ids[j] inherits the line of
+// out_ids[j]).  No rows are moved; lines[p] is the lookup result for access p.
+void oracle_resolve_lines(int64_t num_nodes, const int32_t* ids, const int64_t* ids_offsets,
+                          int32_t S, const int32_t* init_ids, int64_t init_count,
+                          const int32_t* in_ids, const int32_t* out_ids,
+                          const int64_t* cs_offsets, int32_t* lines) {
+  std::vector<int32_t> address_table(num_nodes, -1);
+  for (int64_t r = 0; r < init_count; ++r) address_table[init_ids[r]] = (int32_t)r;
+  for (int32_t i = 0; i < S; ++i) {
+    for (int64_t p = ids_offsets[i]; p < ids_offsets[i + 1]; ++p)
+      lines[p] = address_table[ids[p]];
+    for (int64_t j = cs_offsets[i]; j < cs_offsets[i + 1]; ++j) {
+      const int32_t line = address_table[out_ids[j]];
+      address_table[out_ids[j]] = -1;
+      address_table[in_ids[j]] = line;
+    }
+  }
+}
+
 void oracle_cache_init(uint8_t* cache, int32_t* address_table, int64_t num_nodes,
                        const uint8_t* slow, int64_t row_bytes, const int32_t* init_ids,
                        int64_t init_count) {

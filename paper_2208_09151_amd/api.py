@@ -209,14 +209,15 @@ class ChangesetResult:
     miss_count: np.ndarray      # [S] host
     init_ready: np.ndarray = None   # [S] host: rows of C_0 first accessed in iterations 0..i
     final_ids: torch.Tensor = None  # resumed superbatches: row of every line after the last iteration
+    src_line: torch.Tensor = None   # int32 device [total ids]: cache line of every access, -1 = miss
 
 
 def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady",
-              builtin_scratch=False):
+              builtin_scratch=False, with_lines=True):
     """ginex_changeset (``policy="belady"``) or ginex_changeset_lru (``policy="lru"``).
     ``ids`` is a device int32 tensor, ``ids_offsets`` a host array.  ``builtin_scratch``:
     ginex_changeset_noalloc, which takes no workspace (small shapes only); the outputs are
-    still allocated here, by the caller."""
+    still allocated here, by the caller.  ``with_lines``: also ask for ``src_line``."""
     lib = _lib.load()
     if policy not in ("belady", "lru"):
         raise ValueError(f"unknown policy {policy!r}")
@@ -244,23 +245,25 @@ def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady",
     init_count = np.zeros(1, dtype=np.int64)
     total_changes = np.zeros(1, dtype=np.int64)
     init_ready = np.zeros(max(S, 1), dtype=np.int64)
+    lines = torch.empty(cs_cap, dtype=torch.int32, device=dev) if with_lines else None
     if builtin_scratch:
         rc = lib.ginex_changeset_noalloc(
             num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(init_ids), _np_ptr(init_count),
             _ptr(in_ids), _ptr(out_ids), _ptr(in_pos), cs_cap, _ptr(cs_off), _ptr(miss),
-            _np_ptr(total_changes), _np_ptr(init_ready), _stream())
+            _ptr(lines), _np_ptr(total_changes), _np_ptr(init_ready), _stream())
     else:
         rc = entry(num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(init_ids),
                    _np_ptr(init_count), _ptr(in_ids), _ptr(out_ids), _ptr(in_pos), cs_cap,
-                   _ptr(cs_off), _ptr(miss), _np_ptr(total_changes), _np_ptr(init_ready),
-                   _ptr(ws), ws.numel(), _stream())
+                   _ptr(cs_off), _ptr(miss), _ptr(lines), _np_ptr(total_changes),
+                   _np_ptr(init_ready), _ptr(ws), ws.numel(), _stream())
     _check(rc)
     n = int(total_changes[0])
     return ChangesetResult(init_ids[:int(init_count[0])], in_ids[:n], out_ids[:n], in_pos[:n],
-                           cs_off.cpu().numpy(), miss[:S].cpu().numpy(), init_ready[:S])
+                           cs_off.cpu().numpy(), miss[:S].cpu().numpy(), init_ready[:S],
+                           src_line=lines[:total] if with_lines else None)
 
 
-def changeset_resume(num_nodes, ids, ids_offsets, start_ids, workspace=None):
+def changeset_resume(num_nodes, ids, ids_offsets, start_ids, workspace=None, with_lines=True):
     """ginex_changeset_resume: Belady changesets from the cache state ``start_ids`` (device
     int32 [cap], line r holds start_ids[r]).  ``init_ids`` of the result echoes the start state,
     ``final_ids`` is the start state of the next superbatch."""
@@ -284,14 +287,16 @@ def changeset_resume(num_nodes, ids, ids_offsets, start_ids, workspace=None):
     cs_off = torch.empty(S + 1, dtype=torch.int64, device=dev)
     miss = torch.empty(max(S, 1), dtype=torch.int64, device=dev)
     total_changes = np.zeros(1, dtype=np.int64)
+    lines = torch.empty(cs_cap, dtype=torch.int32, device=dev) if with_lines else None
     rc = lib.ginex_changeset_resume(num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(start_ids),
                                     _ptr(final_ids), _ptr(in_ids), _ptr(out_ids), _ptr(in_pos),
-                                    cs_cap, _ptr(cs_off), _ptr(miss), _np_ptr(total_changes),
-                                    _ptr(ws), ws.numel(), _stream())
+                                    cs_cap, _ptr(cs_off), _ptr(miss), _ptr(lines),
+                                    _np_ptr(total_changes), _ptr(ws), ws.numel(), _stream())
     _check(rc)
     n = int(total_changes[0])
     return ChangesetResult(start_ids, in_ids[:n], out_ids[:n], in_pos[:n], cs_off.cpu().numpy(),
-                           miss[:S].cpu().numpy(), np.full(S, cap, dtype=np.int64), final_ids)
+                           miss[:S].cpu().numpy(), np.full(S, cap, dtype=np.int64), final_ids,
+                           src_line=lines[:total] if with_lines else None)
 
 
 class FeatureCache:
@@ -312,6 +317,7 @@ class FeatureCache:
                                self.num_nodes, slow.data_ptr())
         self._desc_ref = C.byref(self._desc)
         self._gather = _lib.load().ginex_gather
+        self._gather_lines = _lib.load().ginex_gather_lines
         self._update = _lib.load().ginex_cache_update
         self._init_part = _lib.load().ginex_cache_init_part
         self._init_warm = _lib.load().ginex_cache_init_warm
@@ -334,23 +340,38 @@ class FeatureCache:
         if rc:
             _check(rc)
 
-    def gather(self, ids, out=None, in_ids=None, out_ids=None, in_positions=None):
-        """One executor iteration: gather the rows of ``ids`` then apply the changeset."""
+    def gather(self, ids, out=None, in_ids=None, out_ids=None, in_positions=None, src_line=None):
+        """One executor iteration: gather the rows of ``ids`` then apply the changeset.  With
+        ``src_line`` (the slice of ``ChangesetResult.src_line`` for this iteration) the gather
+        is ginex_gather_lines and does not probe the address table."""
         _dev(ids, torch.int32)
         n = ids.numel()
         if out is None:
             out = torch.empty((n, self.slow.shape[1]), dtype=self.slow.dtype,
                               device=self.rows.device)
         nc = in_ids.numel() if in_ids is not None else 0
-        _check(_lib.load().ginex_gather(C.byref(self._desc), _ptr(ids), n, _ptr(out),
-                                        _ptr(in_ids) if nc else None,
-                                        _ptr(out_ids) if nc else None,
-                                        _ptr(in_positions) if nc else None, nc, _stream()))
+        lists = (_ptr(in_ids) if nc else None, _ptr(out_ids) if nc else None,
+                 _ptr(in_positions) if nc else None, nc, _stream())
+        if src_line is not None:
+            _dev(src_line, torch.int32)
+            if src_line.numel() != n:
+                raise ValueError("src_line must have one entry per id")
+            _check(self._gather_lines(C.byref(self._desc), _ptr(ids), _ptr(src_line), n, _ptr(out),
+                                      *lists))
+        else:
+            _check(self._gather(C.byref(self._desc), _ptr(ids), n, _ptr(out), *lists))
         return out
 
     def gather_raw(self, ids_ptr: int, n: int, out_ptr: int, stream_ptr: int):
         """ginex_gather with an empty changeset, on raw device addresses (for tight loops)."""
         rc = self._gather(self._desc_ref, ids_ptr, n, out_ptr, None, None, None, 0, stream_ptr)
+        if rc:
+            _check(rc)
+
+    def gather_lines_raw(self, ids_ptr: int, lines_ptr: int, n: int, out_ptr: int, stream_ptr: int):
+        """ginex_gather_lines with an empty changeset, on raw device addresses."""
+        rc = self._gather_lines(self._desc_ref, ids_ptr, lines_ptr, n, out_ptr, None, None, None, 0,
+                                stream_ptr)
         if rc:
             _check(rc)
 

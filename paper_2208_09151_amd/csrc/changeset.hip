@@ -261,6 +261,34 @@ __global__ __launch_bounds__(TB) void k_init_state_resume(const int32_t* __restr
     if (lds_hist[j]) atomicAdd(&st.rhist[j], lds_hist[j]);
 }
 
+// addr[node of rank r] = r for the first `count` heads (C_0 when everything fits)
+__global__ __launch_bounds__(TB) void k_scatter_rank(const uint64_t* __restrict__ heads,
+                                                     int64_t count, int32_t* __restrict__ addr) {
+  const int64_t r = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (r < count) addr[heads[r] & 0xFFFFFFFFu] = (int32_t)r;
+}
+
+// src_line[p] = addr[ids[p]]: every accessed row is resident, nothing ever changes
+__global__ __launch_bounds__(TB) void k_lookup_lines(const int32_t* __restrict__ ids, int64_t n,
+                                                     const int32_t* __restrict__ addr,
+                                                     int32_t* __restrict__ src_line) {
+  constexpr int ITEMS = 4;
+  const int64_t base = (int64_t)blockIdx.x * (TB * ITEMS) + threadIdx.x;
+  int32_t v[ITEMS];
+#pragma unroll
+  for (int t = 0; t < ITEMS; ++t) {
+    const int64_t p = base + t * TB;
+    v[t] = ids[p < n ? p : 0];
+  }
+#pragma unroll
+  for (int t = 0; t < ITEMS; ++t) v[t] = addr[v[t]];
+#pragma unroll
+  for (int t = 0; t < ITEMS; ++t) {
+    const int64_t p = base + t * TB;
+    if (p < n) src_line[p] = v[t];
+  }
+}
+
 // miss_count[i] = |ids_i| (a cache without lines: every access misses)
 __global__ __launch_bounds__(TB) void k_iteration_lengths(const int64_t* __restrict__ off, int32_t S,
                                                           int64_t* __restrict__ miss_count) {
@@ -307,6 +335,7 @@ struct Iter {           // what a phase needs to know about the running iteratio
   int32_t key;          // >= 0: every access of the iteration takes this key (LRU: S-1-i,
                         // smaller = used more recently); < 0: the key is next[p]
   int32_t lo_bin;       // smallest bucket a candidate of this iteration can fall into
+  int32_t* src_line;    // out (may be null): cache line of each access in C_i, -1 for a miss
 };
 
 __device__ __forceinline__ int32_t key_of(const Iter& it, int64_t p) {
@@ -356,6 +385,13 @@ __device__ void p_touch(const State& st, const Iter& it, unsigned long long* mis
   }
 #pragma unroll
   for (int t = 0; t < TOUCH_ITEMS; ++t) line[t] = st.addr[v[t]];
+  if (it.src_line) {   // what the executor's gather will find: the state is C_i here
+#pragma unroll
+    for (int t = 0; t < TOUCH_ITEMS; ++t) {
+      const int64_t p = base + t * TB + threadIdx.x;
+      if (p < it.n) it.src_line[p] = line[t];
+    }
+  }
   int32_t old_key[TOUCH_ITEMS];
   if (st.lru) {
 #pragma unroll
@@ -949,9 +985,9 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                       const int64_t* ids_offsets, int32_t S, int64_t cap, int32_t* init_ids,
                       int64_t* init_count, int32_t* in_ids, int32_t* out_ids,
                       int32_t* in_positions, int64_t cs_capacity, int64_t* cs_offsets,
-                      int64_t* miss_count, int64_t* total_changes, int64_t* init_ready,
-                      const int32_t* start_ids, int32_t* final_ids, void* ws, size_t ws_bytes,
-                      void* stream) {
+                      int64_t* miss_count, int32_t* src_line, int64_t* total_changes,
+                      int64_t* init_ready, const int32_t* start_ids, int32_t* final_ids, void* ws,
+                      size_t ws_bytes, void* stream) {
   if (!ids_offsets || !init_count || !cs_offsets || !miss_count || !total_changes || !ws)
     return fail(GINEX_ERR_ARG, "%s: a required pointer is null", who);
   if (S >= 1 && ids_offsets[0] != 0)
@@ -1071,6 +1107,14 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       hipLaunchKernelGGL(k_iteration_lengths, dim3((unsigned)ceil_div(S, TB)), dim3(TB), 0, st,
                          w.d_offsets, S, miss_count);
       GINEX_LAUNCH_CHECK();
+      if (src_line) GINEX_HIP(fill_async<int32_t>(src_line, total, -1, st));
+    } else if (src_line) {
+      // every accessed row sits in the line of its rank for the whole superbatch
+      hipLaunchKernelGGL(k_scatter_rank, dim3((unsigned)ceil_div(n_init, TB)), dim3(TB), 0, st,
+                         heads, n_init, state.addr);
+      hipLaunchKernelGGL(k_lookup_lines, dim3((unsigned)ceil_div(total, TB * 4)), dim3(TB), 0, st,
+                         ids, total, state.addr, src_line);
+      GINEX_LAUNCH_CHECK();
     }
     GINEX_HIP(hipStreamSynchronize(st));
     return GINEX_OK;
@@ -1127,6 +1171,7 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       it.i = i;
       it.key = lru ? S - 1 - i : -1;
       it.lo_bin = lru ? S - 1 - i : i + 1;
+      it.src_line = src_line ? src_line + lo : nullptr;
       if (it.n > 0) {
         hipLaunchKernelGGL(k_touch, dim3((unsigned)ceil_div(it.n, TB * TOUCH_ITEMS)), dim3(TB),
                            touch_lds, st, state, it, (unsigned long long*)(miss_count + i));
@@ -1175,13 +1220,13 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
                                    const int64_t* ids_offsets, int32_t S, int64_t cap,
                                    int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
                                    int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
-                                   int64_t* cs_offsets, int64_t* miss_count,
+                                   int64_t* cs_offsets, int64_t* miss_count, int32_t* src_line,
                                    int64_t* total_changes, int64_t* init_ready, void* ws,
                                    size_t ws_bytes, void* stream) {
   return changeset_run("ginex_changeset", false, num_nodes, ids, ids_offsets, S, cap, init_ids,
                        init_count, in_ids, out_ids, in_positions, cs_capacity, cs_offsets,
-                       miss_count, total_changes, init_ready, nullptr, nullptr, ws, ws_bytes,
-                       stream);
+                       miss_count, src_line, total_changes, init_ready, nullptr, nullptr, ws,
+                       ws_bytes, stream);
 }
 
 extern "C" int32_t ginex_changeset_resume(int64_t num_nodes, const int32_t* ids,
@@ -1190,15 +1235,15 @@ extern "C" int32_t ginex_changeset_resume(int64_t num_nodes, const int32_t* ids,
                                           int32_t* in_ids, int32_t* out_ids,
                                           int32_t* in_positions, int64_t cs_capacity,
                                           int64_t* cs_offsets, int64_t* miss_count,
-                                          int64_t* total_changes, void* ws, size_t ws_bytes,
-                                          void* stream) {
+                                          int32_t* src_line, int64_t* total_changes, void* ws,
+                                          size_t ws_bytes, void* stream) {
   if (!start_ids)
     return fail(GINEX_ERR_ARG, "ginex_changeset_resume: start_ids is null");
   int64_t init_count = 0;
   return changeset_run("ginex_changeset_resume", false, num_nodes, ids, ids_offsets, S, cap,
                        nullptr, &init_count, in_ids, out_ids, in_positions, cs_capacity,
-                       cs_offsets, miss_count, total_changes, nullptr, start_ids, final_ids, ws,
-                       ws_bytes, stream);
+                       cs_offsets, miss_count, src_line, total_changes, nullptr, start_ids,
+                       final_ids, ws, ws_bytes, stream);
 }
 
 extern "C" int32_t ginex_changeset_lru(int64_t num_nodes, const int32_t* ids,
@@ -1206,13 +1251,13 @@ extern "C" int32_t ginex_changeset_lru(int64_t num_nodes, const int32_t* ids,
                                        int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
                                        int32_t* out_ids, int32_t* in_positions,
                                        int64_t cs_capacity, int64_t* cs_offsets,
-                                       int64_t* miss_count, int64_t* total_changes,
-                                       int64_t* init_ready, void* ws, size_t ws_bytes,
-                                       void* stream) {
+                                       int64_t* miss_count, int32_t* src_line,
+                                       int64_t* total_changes, int64_t* init_ready, void* ws,
+                                       size_t ws_bytes, void* stream) {
   return changeset_run("ginex_changeset_lru", true, num_nodes, ids, ids_offsets, S, cap, init_ids,
                        init_count, in_ids, out_ids, in_positions, cs_capacity, cs_offsets,
-                       miss_count, total_changes, init_ready, nullptr, nullptr, ws, ws_bytes,
-                       stream);
+                       miss_count, src_line, total_changes, init_ready, nullptr, nullptr, ws,
+                       ws_bytes, stream);
 }
 
 // ---- the variant that allocates nothing ------------------------------------------------
@@ -1255,8 +1300,8 @@ extern "C" int32_t ginex_changeset_noalloc(int64_t num_nodes, const int32_t* ids
                                            int32_t* in_ids, int32_t* out_ids,
                                            int32_t* in_positions, int64_t cs_capacity,
                                            int64_t* cs_offsets, int64_t* miss_count,
-                                           int64_t* total_changes, int64_t* init_ready,
-                                           void* stream) {
+                                           int32_t* src_line, int64_t* total_changes,
+                                           int64_t* init_ready, void* stream) {
   const char* who = "ginex_changeset_noalloc";
   if (!ids_offsets) return fail(GINEX_ERR_ARG, "%s: ids_offsets is null", who);
   const int64_t total = S >= 1 ? ids_offsets[S] : 0;
@@ -1273,6 +1318,6 @@ extern "C" int32_t ginex_changeset_noalloc(int64_t num_nodes, const int32_t* ids
   if (int32_t rc = scratch_for_current_device(who, &ws)) return rc;
   return changeset_run(who, false, num_nodes, ids, ids_offsets, S, cap, init_ids, init_count,
                        in_ids, out_ids, in_positions, cs_capacity, cs_offsets, miss_count,
-                       total_changes, init_ready, nullptr, nullptr, ws,
+                       src_line, total_changes, init_ready, nullptr, nullptr, ws,
                        (size_t)GINEX_NOALLOC_SCRATCH_BYTES, stream);
 }

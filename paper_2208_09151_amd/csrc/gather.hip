@@ -63,6 +63,44 @@ __global__ __launch_bounds__(GATHER_THREADS) void k_gather(
   }
 }
 
+// The same copy with the source of every row resolved ahead of time: lines[p] is the cache
+// line of ids[p] or -1 (slow tier).  Both arrays are read in output order, so the random
+// 4-byte probe of the address table (a 128-byte line fetched per row) and one level of the
+// dependent load chain are gone: what is left per row is R bytes in, R bytes out and 8 bytes
+// of sequential index data.
+template <int SHIFT>
+__global__ __launch_bounds__(GATHER_THREADS) void k_gather_lines(
+    const chunk_t* __restrict__ rows, const chunk_t* __restrict__ slow,
+    const int32_t* __restrict__ ids, const int32_t* __restrict__ lines, int64_t n,
+    int32_t cpr /*chunks per row*/, chunk_t* __restrict__ out) {
+  const int64_t total = n * cpr;
+  const int64_t span = (int64_t)gridDim.x * GATHER_THREADS;
+  int64_t c0 = (int64_t)blockIdx.x * GATHER_THREADS + threadIdx.x;
+  for (; c0 < total; c0 += span * UNROLL) {
+    int32_t id[UNROLL], line[UNROLL], col[UNROLL];
+    chunk_t v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      int64_t c = c0 + u * span;
+      c = c < total ? c : c0;
+      const int64_t p = SHIFT >= 0 ? c >> (SHIFT & 31) : c / cpr;
+      col[u] = SHIFT >= 0 ? (int32_t)(c & ((1 << (SHIFT & 31)) - 1)) : (int32_t)(c - p * cpr);
+      id[u] = ids[p];
+      line[u] = lines[p];
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const chunk_t* src = line[u] >= 0 ? rows + (int64_t)line[u] * cpr : slow + (int64_t)id[u] * cpr;
+      v[u] = src[col[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int64_t c = c0 + u * span;
+      if (c < total) __builtin_nontemporal_store(v[u], out + c);
+    }
+  }
+}
+
 // line = addr[out_ids[j]]; rows[line,:] = out[in_positions[j],:].  The address table is
 // patched by a second kernel so that every line is resolved before any entry changes
 // (in_ids and out_ids are disjoint, but keeping the phases apart costs nothing).
@@ -308,16 +346,20 @@ extern "C" int32_t ginex_cache_update(const ginex_cache_t* c, const void* out,
   return launch_update(c, out, in_ids, out_ids, in_positions, n_change, (hipStream_t)stream);
 }
 
-extern "C" int32_t ginex_gather(const ginex_cache_t* c, const int32_t* ids, int64_t n, void* out,
-                                const int32_t* in_ids, const int32_t* out_ids,
-                                const int32_t* in_positions, int64_t n_change, void* stream) {
-  if (int32_t rc = check_cache(c, "ginex_gather")) return rc;
+namespace ginex {
+namespace {
+
+// lines == nullptr: the gather probes the address table itself
+int32_t gather_run(const char* who, const ginex_cache_t* c, const int32_t* ids,
+                   const int32_t* lines, int64_t n, void* out, const int32_t* in_ids,
+                   const int32_t* out_ids, const int32_t* in_positions, int64_t n_change,
+                   void* stream) {
+  if (int32_t rc = check_cache(c, who)) return rc;
   if (n < 0 || n_change > n)
-    return fail(GINEX_ERR_ARG, "ginex_gather: n=%lld n_change=%lld inconsistent", (long long)n,
+    return fail(GINEX_ERR_ARG, "%s: n=%lld n_change=%lld inconsistent", who, (long long)n,
                 (long long)n_change);
-  if (n > 0 && (!ids || !out)) return fail(GINEX_ERR_ARG, "ginex_gather: ids/out is null");
-  if (int32_t rc = check_update(c, out, in_ids, out_ids, in_positions, n_change, "ginex_gather"))
-    return rc;
+  if (n > 0 && (!ids || !out)) return fail(GINEX_ERR_ARG, "%s: ids/out is null", who);
+  if (int32_t rc = check_update(c, out, in_ids, out_ids, in_positions, n_change, who)) return rc;
   hipStream_t st = (hipStream_t)stream;
   if (n > 0) {
     const int32_t cpr = (int32_t)(c->row_bytes / 16);
@@ -326,9 +368,16 @@ extern "C" int32_t ginex_gather(const ginex_cache_t* c, const int32_t* ids, int6
     if (blocks > (1 << 24)) blocks = 1 << 24;
     const dim3 grid((unsigned)blocks);
 #define GINEX_GATHER(S)                                                                       \
-  hipLaunchKernelGGL((k_gather<S>), grid, dim3(GATHER_THREADS), 0, st,                         \
-                     (const chunk_t*)c->rows, c->addr, (const chunk_t*)c->slow, ids, n, cpr,   \
-                     (chunk_t*)out)
+  do {                                                                                        \
+    if (lines)                                                                                \
+      hipLaunchKernelGGL((k_gather_lines<S>), grid, dim3(GATHER_THREADS), 0, st,               \
+                         (const chunk_t*)c->rows, (const chunk_t*)c->slow, ids, lines, n, cpr, \
+                         (chunk_t*)out);                                                      \
+    else                                                                                      \
+      hipLaunchKernelGGL((k_gather<S>), grid, dim3(GATHER_THREADS), 0, st,                     \
+                         (const chunk_t*)c->rows, c->addr, (const chunk_t*)c->slow, ids, n,    \
+                         cpr, (chunk_t*)out);                                                 \
+  } while (0)
     switch (cpr) {      // rows of 16 B .. 4 KB with a power-of-two size
       case 1: GINEX_GATHER(0); break;
       case 2: GINEX_GATHER(1); break;
@@ -345,4 +394,24 @@ extern "C" int32_t ginex_gather(const ginex_cache_t* c, const int32_t* ids, int6
     GINEX_LAUNCH_CHECK();
   }
   return launch_update(c, out, in_ids, out_ids, in_positions, n_change, st);
+}
+
+}  // namespace
+}  // namespace ginex
+
+extern "C" int32_t ginex_gather(const ginex_cache_t* c, const int32_t* ids, int64_t n, void* out,
+                                const int32_t* in_ids, const int32_t* out_ids,
+                                const int32_t* in_positions, int64_t n_change, void* stream) {
+  return gather_run("ginex_gather", c, ids, nullptr, n, out, in_ids, out_ids, in_positions,
+                    n_change, stream);
+}
+
+extern "C" int32_t ginex_gather_lines(const ginex_cache_t* c, const int32_t* ids,
+                                      const int32_t* src_line, int64_t n, void* out,
+                                      const int32_t* in_ids, const int32_t* out_ids,
+                                      const int32_t* in_positions, int64_t n_change,
+                                      void* stream) {
+  if (n > 0 && !src_line) return fail(GINEX_ERR_ARG, "ginex_gather_lines: src_line is null");
+  return gather_run("ginex_gather_lines", c, ids, src_line, n, out, in_ids, out_ids, in_positions,
+                    n_change, stream);
 }

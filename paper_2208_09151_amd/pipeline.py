@@ -61,13 +61,15 @@ class Executor:
         return self.events[k]
 
     def run(self, samp, cs, out, streamed=True, before_gather=None, after_gather=None,
-            resumed=False):
+            resumed=False, use_lines=True):
         """``out``: device buffer [>= longest iteration, feat_dim] that receives every batch
         input in turn; ``before_gather(i)`` / ``after_gather(i, n)`` are called right before
         and after the gather kernel of iteration i is enqueued (timing events; the consumer
         enqueues its own work on the current stream in ``after_gather``).  With ``resumed``
         the cache already holds ``cs.init_ids`` line by line (the changesets come from
         ``changeset_resume`` on the state the last superbatch left) and nothing is loaded.
+        With ``use_lines`` (and ``cs.src_line`` present) the gathers take their cache lines from
+        the changeset stage instead of probing the address table.
         Returns the event that marks the end of the initialization."""
         cache = self.caches[self.turn]
         prev = self.caches[self.turn - 1] if self.warm and len(self.caches) > 1 else None
@@ -86,6 +88,7 @@ class Executor:
         ids_base, out_ptr = samp.ids.data_ptr(), out.data_ptr()
         bases = (cs.in_ids.data_ptr(), cs.out_ids.data_ptr(), cs.in_positions.data_ptr())
         init_ptr = cs.init_ids.data_ptr()
+        lines_base = cs.src_line.data_ptr() if use_lines and cs.src_line is not None else 0
         wait_for = None
         if resumed:
             self._event(0).record(main)
@@ -125,7 +128,10 @@ class Executor:
             n = io[i + 1] - io[i]
             if before_gather is not None:
                 before_gather(i)
-            cache.gather_raw(ids_base + 4 * io[i], n, out_ptr, mp)
+            if lines_base:
+                cache.gather_lines_raw(ids_base + 4 * io[i], lines_base + 4 * io[i], n, out_ptr, mp)
+            else:
+                cache.gather_raw(ids_base + 4 * io[i], n, out_ptr, mp)
             if after_gather is not None:
                 after_gather(i, n)
             nc = co[i + 1] - co[i]

@@ -1,8 +1,10 @@
 """Full-size parity: configurations 3, 4 and 5 in the launch configuration bench.py times.
 
 The oracle runs the whole superbatch itself (sampling, then changesets on ITS ids), and the
-GPU outputs are compared element by element; gathered bytes are compared on a spread of
-iterations.  Configurations 3 and 4 never miss (the rows a superbatch touches fit in the
+GPU outputs are compared element by element: sampled ids and adjacency, every changeset
+list, the resolved cache line of every access, the gathered bytes of EVERY iteration
+(configurations 3 and 4; every eighth iteration on configuration 5, whose 200 iterations
+gather 156 GB) and every resident cache line at the end.  Configurations 3 and 4 never miss (the rows a superbatch touches fit in the
 cache), so each workload is also run with a cache a sixteenth of the distinct rows, which
 puts the Belady loop and the slow-tier reads under full-size pressure.
 
@@ -51,7 +53,7 @@ def release_memory():
         torch._C._host_emptyCache()
 
 
-def run_full(index, extras=False):
+def run_full(index, extras=False, every=1):
     import paper_2208_09151_amd as ginex
     release_memory()
     t = time.time()
@@ -95,29 +97,46 @@ def run_full(index, extras=False):
             f"{int(rcs['miss_count'].sum())} misses, {int(rcs['cs_offsets'][-1])} changes")
         cs = ginex.changeset(cfg.num_nodes, res.ids, res.ids_offsets, cap)
         compare_changeset(cs, rcs)
-        say("changeset parity ok")
+        want_lines = oracle.resolve_lines(cfg.num_nodes, ids, io, rcs["init_ids"], rcs["in_ids"],
+                                          rcs["out_ids"], rcs["cs_offsets"])
+        assert np.array_equal(cs.src_line.cpu().numpy(), want_lines)
+        del want_lines
+        say("changeset parity ok (lists and resolved lines)")
         cache = ginex.FeatureCache(w.features, cap)
         cache.init(cs.init_ids)
         co = cs.cs_offsets
-        check = set(np.linspace(0, S - 1, 5).astype(int).tolist())
-        out = None
+        longest = int(np.diff(io).max())
+        out = torch.empty((longest, cfg.feat_dim), dtype=torch.float32, device="cuda")
+        t = time.time()
+        compared = 0
         for i in range(S):
             sl = slice(co[i], co[i + 1])
-            out = cache.gather(res.ids[io[i]:io[i + 1]], None, cs.in_ids[sl], cs.out_ids[sl],
-                               cs.in_positions[sl])
-            if i in check:
-                want = oracle.gather(feats, ids[io[i]:io[i + 1]])
-                got = out.cpu().numpy().view(np.uint8).reshape(out.shape[0], -1)
-                assert np.array_equal(got, want), i
-        # the final cache content: every resident line holds its node's row
+            a, b = io[i], io[i + 1]
+            # even iterations probe the address table, odd ones take the resolved lines
+            got = cache.gather(res.ids[a:b], out[:b - a], cs.in_ids[sl], cs.out_ids[sl],
+                               cs.in_positions[sl], src_line=cs.src_line[a:b] if i % 2 else None)
+            if i % every == 0 or i == S - 1:
+                want = torch.from_numpy(oracle.gather(feats, ids[a:b])).cuda()
+                assert torch.equal(got.view(torch.uint8).reshape(b - a, -1), want), i
+                compared += 1
+                del want
+            if i % 25 == 0:
+                say(f"  iteration {i} of {S} gathered and compared")
+        say(f"{compared} of {S} iterations compared byte by byte in {time.time() - t:.1f}s")
+        # the final cache content: EVERY resident line holds its node's row
         addr = cache.addr.cpu().numpy()
         resident = np.nonzero(addr >= 0)[0]
         assert len(resident) == len(cs.init_ids)
-        pick = resident[:: max(1, len(resident) // 200000)]
-        rows = cache.rows[torch.from_numpy(addr[pick]).long().cuda()].cpu().numpy()
-        assert np.array_equal(rows, feats[pick])
-        say(f"gather parity ok (cap={cap})")
-        del cache, cs, rcs, out
+        rows8 = cache.rows.view(torch.uint8).reshape(cache.rows.shape[0], -1)
+        step = 1 << 20
+        for lo in range(0, len(resident), step):
+            part = resident[lo:lo + step]
+            want = torch.from_numpy(oracle.gather(feats, part)).cuda()
+            got = rows8[torch.from_numpy(addr[part]).long().cuda()]
+            assert torch.equal(got, want), lo
+            del want, got
+        say(f"gather parity ok (cap={cap}): all {len(resident)} resident lines hold their rows")
+        del cache, cs, rcs, out, rows8
     if extras:
         widened_rows(ginex, w, res, ref, distinct)
     del w, res, ref, feats
@@ -171,4 +190,4 @@ def test_full_size_config4():
 @pytest.mark.skipif(os.environ.get("GINEX_SKIP_HEAVY") == "1",
                     reason="GINEX_SKIP_HEAVY=1: configuration 5 (about a minute) skipped")
 def test_full_size_config5():
-    run_full(5)
+    run_full(5, every=8)

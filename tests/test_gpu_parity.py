@@ -89,7 +89,15 @@ def test_sampler_matches_oracle(ginex, which, request):
     assert np.array_equal(res.adj_col_offsets, no_adj.adj_col_offsets)
 
 
-def check_changeset(res, ref):
+def check_changeset(res, ref, trace=None):
+    """``trace`` = (num_nodes, ids, ids_offsets): also compares the resolved cache line of
+    every access with the oracle's address-table replay of ITS lists."""
+    if trace is not None:
+        n, ids, off = trace
+        want = oracle.resolve_lines(n, ids, off, ref["init_ids"], ref["in_ids"], ref["out_ids"],
+                                    ref["cs_offsets"])
+        assert res.src_line is not None and res.src_line.numel() == len(ids)
+        assert np.array_equal(res.src_line.cpu().numpy(), want)
     assert np.array_equal(res.miss_count, ref["miss_count"])
     assert np.array_equal(res.cs_offsets, ref["cs_offsets"])
     assert np.array_equal(res.init_ids.cpu().numpy(), ref["init_ids"])
@@ -101,12 +109,18 @@ def check_changeset(res, ref):
 @pytest.mark.parametrize("which", ["case1", "case2"])
 def test_changeset_matches_oracle(ginex, which, request):
     c = request.getfixturevalue(which)
+    trace = (c.cfg.num_nodes, c.samp["ids"], c.samp["ids_offsets"])
     res = ginex.changeset(c.cfg.num_nodes, dev(c.samp["ids"]), c.samp["ids_offsets"], c.cfg.cap)
-    check_changeset(res, c.cs)
+    check_changeset(res, c.cs, trace)
     # a small cache puts every iteration under pressure
     ref = oracle.changeset(c.cfg.num_nodes, c.samp["ids"], c.samp["ids_offsets"], 1000)
     check_changeset(ginex.changeset(c.cfg.num_nodes, dev(c.samp["ids"]),
-                                    c.samp["ids_offsets"], 1000), ref)
+                                    c.samp["ids_offsets"], 1000), ref, trace)
+    # the lists do not depend on whether the lines are asked for
+    bare = ginex.changeset(c.cfg.num_nodes, dev(c.samp["ids"]), c.samp["ids_offsets"], 1000,
+                           with_lines=False)
+    assert bare.src_line is None
+    check_changeset(bare, ref)
 
 
 @pytest.mark.parametrize("which", ["case1", "case2"])
@@ -229,7 +243,7 @@ def test_changeset_random_small_traces(ginex):
         ids_d = dev(ids) if len(ids) else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
         res = ginex.changeset(n, ids_d, off, cap)
         try:
-            check_changeset(res, ref)
+            check_changeset(res, ref, (n, ids, off))
         except AssertionError:
             print("failing trial", trial, n, S, cap, flush=True)
             raise
@@ -242,7 +256,7 @@ def test_changeset_degenerate_capacities(ginex, case1):
     for cap in (0, 1, 7, distinct - 1, distinct, distinct + 5):
         ref = oracle.changeset(c.cfg.num_nodes, ids, io, cap)
         res = ginex.changeset(c.cfg.num_nodes, dev(ids), io, cap)
-        check_changeset(res, ref)
+        check_changeset(res, ref, (c.cfg.num_nodes, ids, io))
     # one iteration only, and a trace whose ties all fall into one bucket
     one = oracle.changeset(c.cfg.num_nodes, ids[:io[1]], io[:2], 100)
     check_changeset(ginex.changeset(c.cfg.num_nodes, dev(ids[:io[1]]), io[:2], 100), one)
@@ -452,7 +466,7 @@ def test_lru_changeset_random_small_traces(ginex):
         ids_d = dev(ids) if len(ids) else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
         res = ginex.changeset(n, ids_d, off, cap, policy="lru")
         try:
-            check_changeset(res, ref)
+            check_changeset(res, ref, (n, ids, off))
         except AssertionError:
             print("failing trial", trial, n, S, cap, flush=True)
             raise
@@ -470,7 +484,7 @@ def test_lru_changeset_matches_oracle_and_feeds_the_executor(ginex, which, reque
     for cap in (1, 1000, c.cfg.cap, longest + 1, distinct // 2, distinct - 1, distinct):
         ref = oracle.changeset_lru(n, ids, io, cap)
         res = ginex.changeset(n, ids_d, io, cap, policy="lru")
-        check_changeset(res, ref)
+        check_changeset(res, ref, (n, ids, io))
         bel = ginex.changeset(n, ids_d, io, cap)
         assert bel.miss_count.sum() <= res.miss_count.sum()
     # the executor runs an LRU changeset like any other
@@ -482,7 +496,8 @@ def test_lru_changeset_matches_oracle_and_feeds_the_executor(ginex, which, reque
     for i in range(S):
         sl = slice(co[i], co[i + 1])
         out = cache.gather(ids_d[io[i]:io[i + 1]], None, res.in_ids[sl], res.out_ids[sl],
-                           res.in_positions[sl])
+                           res.in_positions[sl],
+                           src_line=res.src_line[io[i]:io[i + 1]] if i % 2 else None)
         if i % 7 == 0 or i == S - 1:
             got = out.cpu().numpy().view(np.uint8).reshape(out.shape[0], -1)
             assert np.array_equal(got, sb[ids[io[i]:io[i + 1]]]), i
@@ -651,8 +666,8 @@ def test_warm_initialization_leaves_the_same_cache_as_a_cold_one(ginex, case2):
 
 # ---- cache carried from superbatch to superbatch ---------------------------------------------
 
-def check_resumed(res, ref):
-    check_changeset(res, ref)
+def check_resumed(res, ref, trace=None):
+    check_changeset(res, ref, trace)
     assert np.array_equal(res.final_ids.cpu().numpy(), ref["final_ids"])
 
 
@@ -668,7 +683,7 @@ def test_resumed_changeset_random_small_traces(ginex):
         ids_d = dev(ids) if len(ids) else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
         res = ginex.changeset_resume(n, ids_d, off, dev(start))
         try:
-            check_resumed(res, ref)
+            check_resumed(res, ref, (n, ids, off))
         except AssertionError:
             print("failing trial", trial, n, S, cap, flush=True)
             raise
@@ -707,7 +722,7 @@ def test_carried_cache_over_consecutive_superbatches(ginex, case2):
             ids, io = ref_s["ids"], ref_s["ids_offsets"]
             ref = oracle.changeset_resume(n, ids, io, cap, state_h)
             cs = ginex.changeset_resume(n, samp.ids, samp.ids_offsets, state_d)
-            check_resumed(cs, ref)
+            check_resumed(cs, ref, (n, ids, io))
             longest = int(np.diff(io).max())
             if out is None or out.shape[0] < longest:
                 out = torch.empty((longest, cfg.feat_dim), dtype=torch.float32, device="cuda")
@@ -754,10 +769,12 @@ def test_both_ways_of_finding_dead_evictions_give_the_same_lists(ginex, case1, c
         distinct = len(np.unique(ids))
         for cap in (1000, distinct // 16, distinct // 2, distinct - 1):
             check_changeset(ginex.changeset(c.cfg.num_nodes, dev(ids), io, cap),
-                            oracle.changeset(c.cfg.num_nodes, ids, io, cap))
+                            oracle.changeset(c.cfg.num_nodes, ids, io, cap),
+                            (c.cfg.num_nodes, ids, io))
         start = np.arange(c.cfg.cap, dtype=np.int32)[::-1].copy()
         check_resumed(ginex.changeset_resume(c.cfg.num_nodes, dev(ids), io, dev(start)),
-                      oracle.changeset_resume(c.cfg.num_nodes, ids, io, c.cfg.cap, start))
+                      oracle.changeset_resume(c.cfg.num_nodes, ids, io, c.cfg.cap, start),
+                      (c.cfg.num_nodes, ids, io))
 
 
 def test_changeset_at_the_largest_superbatch_the_library_accepts(ginex):
@@ -767,12 +784,13 @@ def test_changeset_at_the_largest_superbatch_the_library_accepts(ginex):
     n, S, cap = 500, 8191, 40
     ids, off = random_trace(rng, n, S, 6)
     ids_d = dev(ids)
-    check_changeset(ginex.changeset(n, ids_d, off, cap), oracle.changeset(n, ids, off, cap))
+    check_changeset(ginex.changeset(n, ids_d, off, cap), oracle.changeset(n, ids, off, cap),
+                    (n, ids, off))
     check_changeset(ginex.changeset(n, ids_d, off, cap, policy="lru"),
-                    oracle.changeset_lru(n, ids, off, cap))
+                    oracle.changeset_lru(n, ids, off, cap), (n, ids, off))
     start = rng.permutation(n)[:cap].astype(np.int32)
     check_resumed(ginex.changeset_resume(n, ids_d, off, dev(start)),
-                  oracle.changeset_resume(n, ids, off, cap, start))
+                  oracle.changeset_resume(n, ids, off, cap, start), (n, ids, off))
     with pytest.raises(ginex.GinexError):
         ginex.changeset(n, ids_d, np.concatenate([off, off[-1:]]), cap)     # S = 8192
 
@@ -814,14 +832,15 @@ def test_changesets_on_structured_traces(ginex, scatter, monkeypatch):
             if cap < 1:
                 continue
             try:
-                check_changeset(ginex.changeset(n, ids_d, off, cap), oracle.changeset(n, ids, off, cap))
+                check_changeset(ginex.changeset(n, ids_d, off, cap), oracle.changeset(n, ids, off, cap),
+                                (n, ids, off))
                 check_changeset(ginex.changeset(n, ids_d, off, cap, policy="lru"),
-                                oracle.changeset_lru(n, ids, off, cap))
+                                oracle.changeset_lru(n, ids, off, cap), (n, ids, off))
                 for start in (np.arange(cap), np.arange(n - 1, n - 1 - cap, -1),
                               rng.permutation(n)[:cap]):
                     start = start.astype(np.int32)
                     check_resumed(ginex.changeset_resume(n, ids_d, off, dev(start)),
-                                  oracle.changeset_resume(n, ids, off, cap, start))
+                                  oracle.changeset_resume(n, ids, off, cap, start), (n, ids, off))
             except AssertionError:
                 print("failing case:", name, "cap", cap, flush=True)
                 raise
@@ -966,3 +985,61 @@ def test_static_cache_through_the_executor(ginex, which, request):
     assert misses == oracle.static_misses(n, c.samp["ids"], want_sel)
     assert np.array_equal(cache.addr.cpu().numpy(), ref.addr)          # a static cache never changes
     assert misses >= int(c.cs["miss_count"].sum())                      # Belady is the lower bound
+
+
+# ---- gather through the lines resolved by the changeset stage ---------------------------
+
+@pytest.mark.parametrize("which", ["case1", "case2"])
+def test_gather_through_resolved_lines_matches_oracle(ginex, which, request):
+    """ginex_gather_lines on every iteration: bytes equal to the oracle's gather, address
+    table and cache rows equal to the oracle's replay, for a cache under pressure, the
+    configured cache, a cache that holds everything and no cache at all."""
+    c = request.getfixturevalue(which)
+    n, S = c.cfg.num_nodes, c.cfg.S
+    ids, io = c.samp["ids"], c.samp["ids_offsets"]
+    ids_d = dev(ids)
+    slow = c.w.features
+    distinct = len(np.unique(ids))
+    for cap in (max(1, distinct // 16), c.cfg.cap, distinct + 3, 0):
+        ref_cs = oracle.changeset(n, ids, io, cap)
+        cs = ginex.changeset(n, ids_d, io, cap)
+        check_changeset(cs, ref_cs, (n, ids, io))
+        cache = ginex.FeatureCache(slow, cap)
+        cache.init(cs.init_ids)
+        ref = oracle.Cache(slow.numpy(), cap)
+        ref.init(ref_cs["init_ids"])
+        co = cs.cs_offsets
+        for i in range(S):
+            sl = slice(co[i], co[i + 1])
+            a, b = io[i], io[i + 1]
+            out = cache.gather(ids_d[a:b], None, cs.in_ids[sl], cs.out_ids[sl], cs.in_positions[sl],
+                               src_line=cs.src_line[a:b])
+            want, _ = ref.gather_update(ids[a:b], ref_cs["in_ids"][sl], ref_cs["out_ids"][sl],
+                                        ref_cs["in_positions"][sl])
+            got = out.cpu().numpy().view(np.uint8).reshape(out.shape[0], -1)
+            assert np.array_equal(got, want), (cap, i)
+            assert np.array_equal(got, oracle.gather(slow.numpy(), ids[a:b])), (cap, i)
+        assert np.array_equal(cache.addr.cpu().numpy(), ref.addr), cap
+        if cap:
+            rows = cache.rows.cpu().numpy().view(np.uint8).reshape(cache.rows.shape[0], -1)
+            used = len(ref_cs["init_ids"])
+            assert np.array_equal(rows[:used], ref.rows[:used]), cap
+
+
+@pytest.mark.parametrize("row_bytes", [16, 48, 512, 3072])
+def test_gather_lines_row_sizes(ginex, row_bytes):
+    rng = np.random.default_rng(row_bytes)
+    n, cap = 5000, 700
+    slow = torch.from_numpy(rng.integers(0, 2 ** 31, size=(n, row_bytes // 4)).astype(np.int32)).pin_memory()
+    cache = ginex.FeatureCache(slow, cap)
+    init = rng.permutation(n)[:cap].astype(np.int32)
+    cache.init(dev(init))
+    line_of = np.full(n, -1, dtype=np.int32)
+    line_of[init] = np.arange(cap, dtype=np.int32)
+    for count in (0, 1, 63, 64, 65, 1000, 4097):
+        ids = rng.integers(0, n, size=count).astype(np.int32)
+        ids_d = dev(ids) if count else torch.zeros(0, dtype=torch.int32, device="cuda")
+        lines = dev(line_of[ids]) if count else torch.zeros(0, dtype=torch.int32, device="cuda")
+        out = cache.gather(ids_d, src_line=lines)
+        assert np.array_equal(out.cpu().numpy().view(np.uint8).reshape(count, row_bytes),
+                              oracle.gather(slow.numpy(), ids))

@@ -64,3 +64,33 @@ def test_gather_is_row_selection_and_cache_stays_coherent():
         res = np.nonzero(c.addr >= 0)[0]
         assert len(res) <= w.cfg.cap
         assert np.array_equal(c.rows[c.addr[res]], sb[res])    # every cached row is right
+
+
+def test_resolved_lines_on_the_worked_example_and_against_the_cache_replay():
+    ex = load_example()
+    n = ex["num_nodes"][0]
+    # one iteration, then the same ids once more: after the update 2 and 5 sit in the lines
+    # of 0 and 6, and 0 is gone
+    ids = ex["ids"] + ex["ids"]
+    lines = oracle.resolve_lines(n, ids, [0, 4, 8], ex["cached"], ex["in_ids"], ex["out_ids"],
+                                 [0, 2, 2])
+    assert lines[:4].tolist() == ex["src_line"]
+    assert lines[4:].tolist() == [-1, 0, 4, 3]
+    # on a sampled workload: equal to the address table of the full cache replay, iteration
+    # by iteration, and consistent with the miss counts
+    w = make_workload(1)
+    r = oracle.sample_superbatch(w.offsets.numpy(), w.indices.numpy(), w.seeds.numpy(),
+                                 w.seed_offsets.numpy(), w.cfg.fanout)
+    for cap in (w.cfg.cap, 300, 10 ** 6, 0):
+        cs = oracle.changeset(w.cfg.num_nodes, r["ids"], r["ids_offsets"], cap)
+        lines = oracle.resolve_lines(w.cfg.num_nodes, r["ids"], r["ids_offsets"], cs["init_ids"],
+                                     cs["in_ids"], cs["out_ids"], cs["cs_offsets"])
+        c = oracle.Cache(w.features.numpy(), cap)
+        c.init(cs["init_ids"])
+        for i in range(w.cfg.S):
+            a, b = r["ids_offsets"][i], r["ids_offsets"][i + 1]
+            lo, hi = cs["cs_offsets"][i], cs["cs_offsets"][i + 1]
+            assert np.array_equal(lines[a:b], c.addr[r["ids"][a:b]])
+            assert int((lines[a:b] < 0).sum()) == cs["miss_count"][i]
+            c.gather_update(r["ids"][a:b], cs["in_ids"][lo:hi], cs["out_ids"][lo:hi],
+                            cs["in_positions"][lo:hi])
