@@ -13,8 +13,9 @@
 //   S-i distinct values, so a histogram per next iteration (kept incrementally for the
 //   residents, rebuilt for the incoming rows) finds the threshold bucket j*; only inside
 //   j* does the id order matter, and there the k-th smallest id is found by setting the
-//   members' bits in a bitmap over node ids and locating the k-th set bit.
-//   Evicted lines and inserted positions are then compacted in line / position order.
+//   members' bits in a bitmap over node ids and locating the k-th set bit through per-part
+//   counts.  Evicted lines and inserted positions are then compacted in line / position
+//   order and paired.
 //   The same loop serves the LRU policy (other keys) and a superbatch that resumes from the
 //   cache state of the previous one (C_0 given instead of computed).
 #include <cstdlib>
@@ -29,7 +30,8 @@ namespace {
 constexpr int TB = 256;
 constexpr int BIG = 1024;          // threads of the single-block kernels
 constexpr int TOUCH_ITEMS = 8;     // accesses per thread in the touch kernel
-constexpr int BITS_WORDS = 8;      // bitmap words per thread in the select kernels
+constexpr int PART_SHIFT = 16;     // a part of a bitmap covers 2^16 node ids ...
+constexpr int PART_WORDS = 1 << (PART_SHIFT - 5);   // ... in 2048 words
 
 enum { MODE_NONE = 0, MODE_ALL = 1, MODE_SELECT = 2 };
 
@@ -50,19 +52,20 @@ struct State {
   int32_t* addr;        // [N] line of a node or -1
   uint32_t* rhist;      // [S+1] residents per next iteration
   uint32_t* ihist;      // [S+1] incoming rows of the running iteration per next iteration
-  uint32_t* bitmap;     // [ceil(N/32)] select scratch, all zero between iterations
-  uint32_t* dead_bits;  // [ceil(N/32)] residents that are never accessed again, kept up to date
-  uint32_t* bit_part;   // popcount of each block of bitmap words
+  uint32_t* bitmap;     // [words] select scratch, all zero between iterations
+  uint32_t* sel_part;   // [parts] its set bits per part, all zero between iterations
+  uint32_t* dead_bits;  // [words] residents that are never accessed again, kept up to date
+  uint32_t* dead_part;  // [parts] its set bits per part, kept up to date
   Ctrl* ctrl;
   uint64_t* evict_words;  // bit l%64 of word l/64: line l is evicted in this iteration
-  uint32_t* evict_tiles;  // evictions per tile of EVICT_TILE lines, then their scanned bases
-  uint32_t* in_tiles;     // the same by position in ids_i
-  int32_t* out_slot;      // line of the t-th eviction
-  int32_t* in_id;         // node of the t-th insertion
-  int32_t* in_next;       // its next accessed iteration
+  uint32_t* evict_tiles;  // evictions per tile of EVICT_TILE lines
+  uint32_t* in_tiles;     // insertions per tile of positions in ids_i
+  int32_t* acc_line;      // [longest iteration] line of each access of the running iteration, -1 = miss
+  uint64_t* pair;         // [max_change] meeting point of the t-th eviction and the t-th insertion
   int64_t cap, num_nodes;
+  int64_t words, parts;   // of the two bitmaps
   int32_t S;
-  int64_t max_change;     // entries of out_slot / in_id / in_next
+  int64_t max_change;     // entries of pair
   int32_t lru;            // 0: Belady keys (next accessed iteration), 1: LRU keys
   int32_t dead_scatter;   // evictions among the dead residents are found from the id bitmap
                           // (large caches) instead of by a pass over all cache lines
@@ -304,13 +307,30 @@ __global__ __launch_bounds__(TB) void k_copy_init(const uint64_t* __restrict__ h
 
 // ---- part 3 -----------------------------------------------------------------------
 //
-// Every phase of an iteration is a device function over "virtual blocks" of TB threads; the
-// kernels below pack phases that do not depend on each other into one launch (nine
-// launches per iteration, ten with k_dead_scatter on large caches).  Two ways of saving launches were measured and dropped: a single
-// cooperative kernel with grid.sync() between the phases (about 0.1 ms per barrier on 1024
-// blocks, twelve times slower overall), and running the single-block phases in the last
-// block to finish of the launch before them (the device-wide fence every block then needs
-// writes back and invalidates L2 on this multi-XCD part: three to four times slower).
+// One iteration of the recurrence is six dependent launches:
+//   k_touch      hits get their new key, hits and misses are histogrammed by key, the line of
+//                every access (or -1) is kept for the later phases and for the executor
+//   k_threshold  one block: walks the histograms down from "never", fixes the threshold
+//                bucket j*, what happens inside it and the size of the changeset; when the
+//                evictions fall among the dead residents (the usual case of a large cache)
+//                it also finds the id threshold T, from part counts of the standing dead-row
+//                bitmap that are kept up to date wherever a bit changes
+//   k_mark       otherwise: the members of the selected class of bucket j* set their bit in a
+//                scratch bitmap over node ids and count themselves per part; or, dead
+//                residents of a large cache: the bits above T are turned into line flags
+//   k_find       one block: T = the keep-th set bit, from the part counts
+//   k_flags      eviction flags per cache line and insertion counts per tile of accesses;
+//                the scratch bitmap is cleared by the members that set it
+//   k_emit       both lists in their order (every block sums the tile counts in front of it:
+//                no scan launch), and the cache state of C_{i+1}: the t-th insertion takes
+//                the line of the t-th eviction, the two sides meeting in one 64-bit word per
+//                t that the second to arrive completes
+// No phase makes a pass over a whole bitmap or scans all tiles in one block: the cost of an
+// iteration follows its accesses and, unless the dead-row path applies, the cache lines.
+// Measured and dropped earlier: a single cooperative kernel with grid.sync() between the
+// phases (about 0.1 ms per barrier on 1024 blocks), and running the single-block phases in
+// the last block to finish of the launch before them with a device-wide fence per block
+// (writes back and invalidates L2 on this multi-XCD part: three to four times slower).
 
 // ready[i] = number of prefetched rows whose first access lies in iterations 0..i: the
 // prefix of C_0 (it is ordered by first access) that iteration i can touch.
@@ -361,17 +381,22 @@ __device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* red) {
   return s;
 }
 
-// Refresh the keys of the hits, histogram hits and misses by next iteration.
-// lds: 2*(S+1) counters.  One virtual block covers TB*TOUCH_ITEMS accesses.
-__device__ void p_touch(const State& st, const Iter& it, unsigned long long* miss_out,
-                        uint32_t* lds, int64_t vb) {
+__device__ __forceinline__ void dead_bit_set(const State& st, uint32_t v) {
+  atomicOr(&st.dead_bits[v >> 5], 1u << (v & 31));
+  atomicAdd(&st.dead_part[v >> PART_SHIFT], 1u);
+}
+
+// Refresh the keys of the hits, histogram hits and misses by key, keep every access's line.
+// lds: 2*(S+1) counters.  One block covers TB*TOUCH_ITEMS accesses.
+__global__ __launch_bounds__(TB) void k_touch(State st, Iter it, unsigned long long* miss_out) {
+  extern __shared__ uint32_t lds[];
   __shared__ uint32_t red[TB / WAVE];
   uint32_t* hr = lds;
   uint32_t* hi = lds + st.S + 1;
   for (int j = threadIdx.x; j < 2 * (st.S + 1); j += TB) lds[j] = 0;
   __syncthreads();
   uint32_t misses = 0;
-  const int64_t base = vb * (TB * TOUCH_ITEMS);
+  const int64_t base = (int64_t)blockIdx.x * (TB * TOUCH_ITEMS);
   // id, then address-table entry, then the line's state: the reads of one level are issued
   // for all items before any is used, so that they are in flight together.  An item beyond
   // the end repeats the block's first item (in range) and is skipped when it is processed.
@@ -385,11 +410,12 @@ __device__ void p_touch(const State& st, const Iter& it, unsigned long long* mis
   }
 #pragma unroll
   for (int t = 0; t < TOUCH_ITEMS; ++t) line[t] = st.addr[v[t]];
-  if (it.src_line) {   // what the executor's gather will find: the state is C_i here
 #pragma unroll
-    for (int t = 0; t < TOUCH_ITEMS; ++t) {
-      const int64_t p = base + t * TB + threadIdx.x;
-      if (p < it.n) it.src_line[p] = line[t];
+  for (int t = 0; t < TOUCH_ITEMS; ++t) {
+    const int64_t p = base + t * TB + threadIdx.x;
+    if (p < it.n) {
+      st.acc_line[p] = line[t];
+      if (it.src_line) it.src_line[p] = line[t];   // the state is C_i here
     }
   }
   int32_t old_key[TOUCH_ITEMS];
@@ -407,10 +433,8 @@ __device__ void p_touch(const State& st, const Iter& it, unsigned long long* mis
       if (st.lru) atomicSub(&hr[old_key[t]], 1u);
       st.res_next[line[t]] = nx[t];
       atomicAdd(&hr[nx[t]], 1u);
-      if (nx[t] == st.S && !st.lru) {   // the row's last access: a dead resident from now on
-        const uint32_t u = (uint32_t)v[t];
-        atomicOr(&st.dead_bits[u >> 5], 1u << (u & 31));
-      }
+      // the row's last access: a dead resident from now on
+      if (nx[t] == st.S && !st.lru) dead_bit_set(st, (uint32_t)v[t]);
     } else {
       atomicAdd(&hi[nx[t]], 1u);
       ++misses;
@@ -422,7 +446,6 @@ __device__ void p_touch(const State& st, const Iter& it, unsigned long long* mis
     if (hi[j]) atomicAdd(&st.ihist[j], hi[j]);
   }
   if (threadIdx.x == 0 && total) atomicAdd(miss_out, (unsigned long long)total);
-  __syncthreads();
 }
 
 // One block of NT threads.  Walks the buckets from "never" downwards until as many
@@ -516,65 +539,28 @@ __device__ void p_threshold(const State& st, int32_t i, int32_t lo_bin, const in
   __syncthreads();
 }
 
-constexpr int MARK_ITEMS = 8;   // lines / accesses per thread in the mark phases
-
-// Set the bit of every member of the selected class in bucket j*.
-__device__ void p_mark_residents(const State& st, const Ctrl& c, int64_t vb) {
-  const int64_t base = vb * (TB * MARK_ITEMS);
-#pragma unroll
-  for (int t = 0; t < MARK_ITEMS; ++t) {
-    const int64_t s = base + t * TB + threadIdx.x;
-    if (s < st.cap && st.res_next[s] == c.jstar) {
-      const uint32_t v = (uint32_t)st.res_id[s];
-      atomicOr(&st.bitmap[v >> 5], 1u << (v & 31));
-    }
-  }
-}
-
-__device__ void p_mark_incoming(const State& st, const Ctrl& c, const Iter& it, int64_t vb) {
-  const int64_t base = vb * (TB * MARK_ITEMS);
-#pragma unroll
-  for (int t = 0; t < MARK_ITEMS; ++t) {
-    const int64_t p = base + t * TB + threadIdx.x;
-    if (p < it.n && key_of(it, p) == c.jstar) {
-      const uint32_t v = (uint32_t)it.ids[p];
-      if (st.addr[v] < 0) atomicOr(&st.bitmap[v >> 5], 1u << (v & 31));
-    }
-  }
-}
-
-// popcount of one part (TB*BITS_WORDS words) of the bitmap
-__device__ void p_bits_count(const State& st, const uint32_t* __restrict__ bits, int64_t words,
-                             int64_t vb) {
-  __shared__ uint32_t red[TB / WAVE];
-  const int64_t base = (vb * TB + threadIdx.x) * BITS_WORDS;
-  uint32_t cnt = 0;
-#pragma unroll
-  for (int t = 0; t < BITS_WORDS; ++t)
-    if (base + t < words) cnt += __popc(bits[base + t]);
-  const uint32_t total = block_sum_u32(cnt, red);
-  if (threadIdx.x == 0) st.bit_part[vb] = total;
-}
-
-// One block of NT threads: T = the id whose bit is the keep-th set bit of the bitmap.
+// One block of NT threads: T = the id whose bit is the keep-th set bit of `bits`, found
+// through `part` (set bits per PART_WORDS words).  With `trim`, the part counts are rewritten
+// to what remains once every bit above T is cleared (the dead rows above T are evicted).
 template <int NT>
-__device__ void p_bits_find(const State& st, const uint32_t* __restrict__ bits, int64_t words,
-                            int64_t parts) {
+__device__ void p_bits_find(const State& st, const uint32_t* __restrict__ bits,
+                            uint32_t* __restrict__ part, bool trim) {
   Ctrl* c = st.ctrl;
   __shared__ int64_t smem[NT / WAVE + 1];
   __shared__ int64_t s_part, s_before;
   const int64_t keep = c->keep;
+  const int64_t parts = st.parts, words = st.words;
   // 1. the part that holds the keep-th set bit
   const int64_t per = (parts + NT - 1) / NT;
   const int64_t q0 = threadIdx.x * per;
   int64_t mine = 0;
-  for (int64_t q = q0; q < q0 + per && q < parts; ++q) mine += st.bit_part[q];
+  for (int64_t q = q0; q < q0 + per && q < parts; ++q) mine += part[q];
   int64_t total;
   int64_t before = block_exclusive_scan<int64_t, NT>(mine, smem, total);
   if (threadIdx.x == 0) s_part = -1;
   __syncthreads();
   for (int64_t q = q0; q < q0 + per && q < parts; ++q) {
-    const int64_t cnt = st.bit_part[q];
+    const int64_t cnt = part[q];
     if (before < keep && before + cnt >= keep) {
       s_part = q;
       s_before = before;
@@ -583,9 +569,14 @@ __device__ void p_bits_find(const State& st, const uint32_t* __restrict__ bits, 
   }
   __syncthreads();
   if (s_part < 0) return;  // fewer set bits than asked for: cannot happen, T stays -1
+  if (trim) {
+    for (int64_t q = q0; q < q0 + per && q < parts; ++q)
+      if (q > s_part) part[q] = 0;
+      else if (q == s_part) part[q] = (uint32_t)(keep - s_before);
+  }
   // 2. the word inside that part, then the bit inside the word
-  constexpr int WPT = TB * BITS_WORDS / NT;
-  const int64_t w0 = s_part * (TB * BITS_WORDS) + (int64_t)threadIdx.x * WPT;
+  constexpr int WPT = PART_WORDS / NT;
+  const int64_t w0 = s_part * PART_WORDS + (int64_t)threadIdx.x * WPT;
   int64_t cntw = 0;
   for (int t = 0; t < WPT; ++t)
     if (w0 + t < words) cntw += __popc(bits[w0 + t]);
@@ -610,12 +601,88 @@ __device__ void p_bits_find(const State& st, const uint32_t* __restrict__ bits, 
   __syncthreads();
 }
 
-__device__ void p_bits_clear(const State& st, int64_t words, int64_t vb) {
-  const int64_t base = vb * (TB * BITS_WORDS);
+__global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i, int32_t lo_bin, Outputs o,
+                                                   int64_t evict_tiles) {
+  p_threshold<BIG>(st, i, lo_bin, o.miss_count, o.cs_offsets);
+  const Ctrl c = *st.ctrl;   // written by this block, in front of the barrier that ends p_threshold
+  if (c.use_dead) {
+    p_bits_find<BIG>(st, st.dead_bits, st.dead_part, true);
+    if (st.dead_scatter)     // the scatter counts evictions per tile with atomics
+      for (int64_t q = threadIdx.x; q < evict_tiles; q += BIG) st.evict_tiles[q] = 0;
+  }
+}
+
+__global__ __launch_bounds__(BIG) void k_find(State st) {
+  const Ctrl c = *st.ctrl;
+  if (c.use_dead || (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT)) return;
+  p_bits_find<BIG>(st, st.bitmap, st.sel_part, false);
+}
+
+constexpr int MARK_ITEMS = 8;   // lines / accesses per thread in the mark phases
+constexpr int EVICT_TILE = WAVE * WAVE;   // cache lines per tile: 64 flag words of 64 lines
+
+__device__ __forceinline__ void select_bit_set(const State& st, uint32_t v) {
+  const uint32_t bit = 1u << (v & 31);
+  if (!(atomicOr(&st.bitmap[v >> 5], bit) & bit)) atomicAdd(&st.sel_part[v >> PART_SHIFT], 1u);
+}
+
+// Set the bit of every member of the selected class in bucket j*.
+__device__ void p_mark_residents(const State& st, const Ctrl& c, int64_t vb) {
+  const int64_t base = vb * (TB * MARK_ITEMS);
 #pragma unroll
-  for (int t = 0; t < BITS_WORDS; ++t) {
-    const int64_t w = base + t * TB + threadIdx.x;
-    if (w < words) st.bitmap[w] = 0;
+  for (int t = 0; t < MARK_ITEMS; ++t) {
+    const int64_t s = base + t * TB + threadIdx.x;
+    if (s < st.cap && st.res_next[s] == c.jstar) select_bit_set(st, (uint32_t)st.res_id[s]);
+  }
+}
+
+__device__ void p_mark_incoming(const State& st, const Ctrl& c, const Iter& it, int64_t vb) {
+  const int64_t base = vb * (TB * MARK_ITEMS);
+#pragma unroll
+  for (int t = 0; t < MARK_ITEMS; ++t) {
+    const int64_t p = base + t * TB + threadIdx.x;
+    if (p < it.n && st.acc_line[p] < 0 && key_of(it, p) == c.jstar)
+      select_bit_set(st, (uint32_t)it.ids[p]);
+  }
+}
+
+// Large caches, evictions among the dead residents only (the usual case once a cache is
+// full): the evicted rows are the set bits above T of the standing dead-row bitmap, a short
+// stretch at its upper end, so they are found from there and their lines flagged through
+// the address table, instead of reading the key and id of every cache line.  The flag
+// words are all zero when the phase starts (the emit phase clears what it consumes), the
+// tile counts were zeroed by k_threshold; the bits above T leave the bitmap here.
+__device__ void p_dead_scatter(const State& st, const Ctrl& c, int64_t vb, int64_t vblocks) {
+  // the stretch above T is short as a rule, so a small grid strides over it from T's word on
+  const int64_t t_word = c.T >> 5;
+  for (int64_t w = t_word + vb * TB + threadIdx.x; w < st.words; w += vblocks * TB) {
+    const uint32_t all = st.dead_bits[w];
+    uint32_t bits = all;
+    if (w == t_word) bits &= (c.T & 31) == 31 ? 0u : ~((2u << (c.T & 31)) - 1u);
+    if (!bits) continue;
+    st.dead_bits[w] = all & ~bits;
+    while (bits) {
+      const int32_t v = (int32_t)(w * 32 + (__ffs(bits) - 1));
+      bits &= bits - 1;
+      const int32_t line = st.addr[v];   // a dead row is resident, so this is its line
+      if (line >= 0) {
+        atomicOr((unsigned long long*)&st.evict_words[line >> 6], 1ull << (line & 63));
+        atomicAdd(&st.evict_tiles[line / EVICT_TILE], 1u);
+      }
+    }
+  }
+}
+
+// blocks [0, res_blocks): residents, the next in_blocks blocks: incoming rows; only one
+// class is selected.  The dead-row scatter uses the whole grid.
+__global__ __launch_bounds__(TB) void k_mark(State st, Iter it, int64_t res_blocks) {
+  const Ctrl c = *st.ctrl;
+  if (c.use_dead) {
+    if (st.dead_scatter && c.n_change > 0) p_dead_scatter(st, c, blockIdx.x, gridDim.x);
+  } else if ((int64_t)blockIdx.x < res_blocks) {
+    if (c.mode_res == MODE_SELECT) p_mark_residents(st, c, blockIdx.x);
+  } else if (c.mode_in == MODE_SELECT) {
+    p_mark_incoming(st, c, it, blockIdx.x - res_blocks);
   }
 }
 
@@ -628,26 +695,33 @@ __device__ __forceinline__ bool inserts(const Ctrl& c, int32_t next, int32_t id)
          (next == c.jstar && (c.mode_in == MODE_ALL || (c.mode_in == MODE_SELECT && id <= c.T)));
 }
 
-__device__ __forceinline__ bool line_evicted(const State& st, const Ctrl& c, int64_t s) {
-  const int32_t next = st.res_next[s];
-  if (next < c.jstar) return false;   // the common case needs no look at the node id
-  return evicts(c, next, st.res_id[s]);
-}
-
-constexpr int EVICT_TILE = WAVE * WAVE;   // cache lines per tile: 64 flag words of 64 lines
-
 // Eviction flags of one tile of cache lines.  A wave reads 64 consecutive lines at a time
 // (coalesced) and its ballot is a 64-bit flag word; the four waves of the block share the
-// tile's 64 words.  The tile's total goes to evict_tiles.
+// tile's 64 words.  The tile's total goes to evict_tiles.  Residents that marked themselves
+// for the select take their word of the scratch bitmap back to zero.
 __device__ void p_evict_flags(const State& st, const Ctrl& c, int64_t vb) {
   __shared__ uint32_t red[TB / WAVE];
   constexpr int PER_WAVE = WAVE / (TB / WAVE);
   const int64_t first_word = vb * WAVE + (threadIdx.x / WAVE) * PER_WAVE;
-  uint32_t cnt = 0;
-#pragma unroll 4
+  const bool unmark = c.mode_res == MODE_SELECT && !c.use_dead;
+  // all keys of the wave's 16 x 64 lines first, so that the loads are in flight together;
+  // a line beyond the end repeats line 0 and is masked out below
+  int32_t next[PER_WAVE];
+#pragma unroll
   for (int g = 0; g < PER_WAVE; ++g) {
     const int64_t line = (first_word + g) * WAVE + lane_id();
-    const bool out = line < st.cap && line_evicted(st, c, line);
+    next[g] = st.res_next[line < st.cap ? line : 0];
+  }
+  uint32_t cnt = 0;
+#pragma unroll
+  for (int g = 0; g < PER_WAVE; ++g) {
+    const int64_t line = (first_word + g) * WAVE + lane_id();
+    bool out = false;
+    if (line < st.cap && next[g] >= c.jstar) {   // the common case needs no look at the node id
+      const int32_t id = st.res_id[line];
+      out = evicts(c, next[g], id);
+      if (unmark && next[g] == c.jstar) st.bitmap[(uint32_t)id >> 5] = 0;
+    }
     const uint64_t word = __ballot(out);
     if ((first_word + g) * WAVE < st.cap && lane_id() == 0) {
       st.evict_words[first_word + g] = word;
@@ -658,225 +732,227 @@ __device__ void p_evict_flags(const State& st, const Ctrl& c, int64_t vb) {
   if (threadIdx.x == 0) st.evict_tiles[vb] = total;
 }
 
-// Large caches, evictions among the dead residents only (the usual case once a cache is
-// full): the evicted rows are the set bits above T of the standing dead-row bitmap, a short
-// stretch at its upper end, so they are found from there and their lines flagged through
-// the address table, instead of reading the key and id of every cache line.  The flag
-// words are all zero when the phase starts (p_evict_emit clears what it consumes).
-__device__ void p_dead_scatter(const State& st, const Ctrl& c, int64_t words, int64_t vb,
-                               int64_t vblocks) {
-  // the stretch above T is short as a rule, so a small grid strides over it from T's word on
-  const int64_t t_word = c.T >> 5;
-  for (int64_t w = t_word + vb * TB + threadIdx.x; w < words; w += vblocks * TB) {
-    uint32_t bits = st.dead_bits[w];
-    if (w == t_word) bits &= (c.T & 31) == 31 ? 0u : ~((2u << (c.T & 31)) - 1u);
-    while (bits) {
-      const int32_t v = (int32_t)(w * 32 + (__ffs(bits) - 1));
-      bits &= bits - 1;
-      const int32_t line = st.addr[v];   // a dead row is resident, so this is its line
-      if (line >= 0)
-        atomicOr((unsigned long long*)&st.evict_words[line >> 6], 1ull << (line & 63));
-    }
-  }
-}
-
-// Tile totals of flag words that p_dead_scatter has set.
-__device__ void p_evict_count(const State& st, int64_t vb) {
-  __shared__ uint32_t red[TB / WAVE];
-  uint32_t cnt = 0;
-  if (threadIdx.x < WAVE) {
-    const int64_t word_at = vb * WAVE + threadIdx.x;
-    if (word_at * WAVE < st.cap) cnt = (uint32_t)__popcll(st.evict_words[word_at]);
-  }
-  const uint32_t total = block_sum_u32(cnt, red);
-  if (threadIdx.x == 0) st.evict_tiles[vb] = total;
-}
-
 constexpr int IN_ITEMS = 8;
 
+// Insertions per tile of TB*IN_ITEMS accesses; incoming rows that marked themselves for the
+// select take their word of the scratch bitmap back to zero.
 __device__ void p_in_count(const State& st, const Ctrl& c, const Iter& it, int64_t vb) {
   __shared__ uint32_t red[TB / WAVE];
   const int64_t base = (vb * TB + threadIdx.x) * IN_ITEMS;
-  uint32_t cnt = 0;
-  // ids and keys first, then the address-table entries of all items together (an item
-  // beyond the end repeats item 0 of the iteration and is not counted)
-  int32_t v[IN_ITEMS], key[IN_ITEMS], line[IN_ITEMS];
+  const bool unmark = c.mode_in == MODE_SELECT;
+  // line, key and id of all items first (an item beyond the end repeats item 0 of the
+  // iteration and is not counted)
+  int32_t line[IN_ITEMS], key[IN_ITEMS], v[IN_ITEMS];
 #pragma unroll
   for (int t = 0; t < IN_ITEMS; ++t) {
     const int64_t p = base + t < it.n ? base + t : 0;
-    v[t] = it.ids[p];
+    line[t] = st.acc_line[p];
     key[t] = key_of(it, p);
+    v[t] = it.ids[p];
   }
-#pragma unroll
-  for (int t = 0; t < IN_ITEMS; ++t) line[t] = st.addr[v[t]];
+  uint32_t cnt = 0;
 #pragma unroll
   for (int t = 0; t < IN_ITEMS; ++t)
-    cnt += base + t < it.n && inserts(c, key[t], v[t]) && line[t] < 0;
+    if (base + t < it.n && line[t] < 0 && key[t] <= c.jstar) {
+      cnt += inserts(c, key[t], v[t]);
+      if (unmark && key[t] == c.jstar) st.bitmap[(uint32_t)v[t] >> 5] = 0;
+    }
   const uint32_t total = block_sum_u32(cnt, red);
   if (threadIdx.x == 0) st.in_tiles[vb] = total;
 }
 
-// One block of NT threads: exclusive scan of n counters in place.
-template <int NT>
-__device__ void p_scan_counts(uint32_t* data, int64_t n) {
-  __shared__ uint32_t smem[NT / WAVE + 1];
-  uint32_t carry = 0;
-  for (int64_t base = 0; base < n; base += NT) {
-    const int64_t j = base + threadIdx.x;
-    const uint32_t v = j < n ? data[j] : 0;
-    uint32_t total;
-    const uint32_t ex = block_exclusive_scan<uint32_t, NT>(v, smem, total);
-    if (j < n) data[j] = carry + ex;
-    carry += total;
+// blocks [0, evict_tiles): eviction flags and counts per tile (not when the dead-row scatter
+// has produced them); the next in_tiles blocks: insertions per tile; one more block takes the
+// part counts of the scratch bitmap back to zero.
+__global__ __launch_bounds__(TB) void k_flags(State st, Iter it, int64_t evict_tiles,
+                                              int64_t in_tiles) {
+  const Ctrl c = *st.ctrl;
+  const int64_t vb = blockIdx.x;
+  const bool selected = !c.use_dead && (c.mode_res == MODE_SELECT || c.mode_in == MODE_SELECT);
+  if (vb < evict_tiles) {
+    if ((c.n_change > 0 || selected) && !(st.dead_scatter && c.use_dead)) p_evict_flags(st, c, vb);
+  } else if (vb < evict_tiles + in_tiles) {
+    if (c.n_change > 0 || selected) p_in_count(st, c, it, vb - evict_tiles);
+  } else if (selected) {
+    for (int64_t q = threadIdx.x; q < st.parts; q += TB) st.sel_part[q] = 0;
   }
 }
 
-// One thread per flag word, one wave per tile: the evicted lines in line order.
-__device__ void p_evict_emit(const State& st, int32_t i, const Outputs& o, int64_t vb,
-                             int64_t tiles) {
-  const int64_t tile = vb * (TB / WAVE) + threadIdx.x / WAVE;
-  if (tile >= tiles) return;
+// ---- the last phase: lists and the state of C_{i+1} ----------------------------------------
+//
+// The t-th insertion takes the line of the t-th eviction.  The two sides compute their ranks
+// independently; they meet in pair[t], one 64-bit word (iteration tag, side, line or
+// position) that each side swaps in atomically: the side that finds the other's word there
+// knows line and position and writes the line's new state.  Everything that crosses from one
+// block to another travels inside that word, so no fence is needed; the state arrays are
+// read by the next launch.
+constexpr uint64_t PAIR_EVICT = 1ull << 39;
+
+__device__ __forceinline__ uint64_t pair_tag(int32_t i) { return (uint64_t)(i + 1) << 40; }
+
+__device__ __forceinline__ void finish_line(const State& st, int32_t line, int32_t v, int32_t key) {
+  st.res_id[line] = v;
+  st.res_next[line] = key;
+  st.addr[v] = line;
+}
+
+// Sum of counts[0 .. n) by the whole block.
+__device__ __forceinline__ uint32_t block_prefix_of(const uint32_t* __restrict__ counts, int64_t n,
+                                                    uint32_t* red) {
+  uint32_t s = 0;
+  for (int64_t q = threadIdx.x; q < n; q += TB) s += counts[q];
+  return block_sum_u32(s, red);
+}
+
+__device__ __forceinline__ uint64_t shfl_u64(uint64_t v, int src) {
+  const uint32_t lo = __shfl((uint32_t)v, src, WAVE);
+  const uint32_t hi = __shfl((uint32_t)(v >> 32), src, WAVE);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// One wave per tile of 64 flag words: the evicted lines in line order.  The tile's set bits
+// are dealt to the lanes round-robin by rank (lane l takes the l-th, (l+64)-th ... set bit,
+// located through the wave's running popcounts), so that the chain of dependent memory
+// operations behind every eviction is as long for a clustered tile as for an even one.
+__device__ void p_evict_emit(const State& st, const Ctrl& c, const Iter& it, const Outputs& o,
+                             int64_t vb, int64_t tiles) {
+  __shared__ uint32_t red[TB / WAVE];
+  constexpr int TPB = TB / WAVE;                 // tiles per block
+  const int64_t first_tile = vb * TPB;
+  const int w = threadIdx.x / WAVE;
+  const int64_t tile = first_tile + w;
+  // the block's own tiles first: most blocks of a large cache have nothing to emit
+  uint32_t own[TPB];
+  uint32_t any = 0;
+#pragma unroll
+  for (int k = 0; k < TPB; ++k) {
+    own[k] = first_tile + k < tiles ? st.evict_tiles[first_tile + k] : 0;
+    any |= own[k];
+  }
+  if (!any) return;                              // uniform over the block
   const int64_t word_at = tile * WAVE + lane_id();
-  uint64_t word = word_at * WAVE < st.cap ? st.evict_words[word_at] : 0;
-  if (st.dead_scatter && word) st.evict_words[word_at] = 0;   // consumed: zero for p_dead_scatter
+  const uint64_t word = tile < tiles && word_at * WAVE < st.cap ? st.evict_words[word_at] : 0;
+  uint32_t tile_base = block_prefix_of(st.evict_tiles, first_tile, red);
+#pragma unroll
+  for (int k = 0; k < TPB; ++k)
+    if (k < w) tile_base += own[k];
+  if (tile >= tiles) return;                     // uniform over the wave
+  const bool scattered = st.dead_scatter && c.use_dead;
+  if (st.dead_scatter && word) st.evict_words[word_at] = 0;   // consumed: zero for the next scatter
   const uint32_t mine = (uint32_t)__popcll(word);
-  uint32_t at = st.evict_tiles[tile] + wave_inclusive_scan(mine) - mine;
-  const int64_t dst = o.cs_offsets[i];
-  while (word) {
-    const int64_t line = word_at * WAVE + (__ffsll((unsigned long long)word) - 1);
-    word &= word - 1;
-    if (at < st.max_change) st.out_slot[at] = (int32_t)line;
-    if (dst + at < o.cs_capacity) o.out_ids[dst + at] = st.res_id[line];
-    ++at;
+  const uint32_t incl = wave_inclusive_scan(mine);
+  const uint32_t total = __shfl(incl, WAVE - 1, WAVE);
+  const int64_t dst = o.cs_offsets[it.i];
+  const uint64_t tag = pair_tag(it.i);
+  for (uint32_t k0 = 0; k0 < total; k0 += WAVE) {        // uniform trip count: shuffles inside
+    const uint32_t k = k0 + lane_id();
+    int lo = 0, hi = WAVE - 1;                   // the first word whose running count exceeds k
+#pragma unroll
+    for (int step = 0; step < 6; ++step) {
+      const int mid = (lo + hi) >> 1;
+      if (__shfl(incl, mid, WAVE) > k) hi = mid; else lo = mid + 1;
+    }
+    const int j = lo < WAVE ? lo : WAVE - 1;
+    uint64_t bits = shfl_u64(word, j);
+    const uint32_t before = __shfl(incl, j, WAVE) - __shfl(mine, j, WAVE);
+    if (k >= total) continue;
+    for (uint32_t r = k - before; r > 0; --r) bits &= bits - 1;
+    const int32_t line = (int32_t)((tile * WAVE + j) * WAVE + (__ffsll((unsigned long long)bits) - 1));
+    const uint32_t at = tile_base + k;
+    const int32_t gone = st.res_id[line];
+    const int32_t key = st.res_next[line];
+    if (dst + at < o.cs_capacity) o.out_ids[dst + at] = gone;
+    st.addr[gone] = -1;
+    if (key == st.S && !st.lru && !scattered) {   // a dead resident leaves the standing bitmap
+      atomicAnd(&st.dead_bits[(uint32_t)gone >> 5], ~(1u << ((uint32_t)gone & 31)));
+      // (its part count was rewritten by k_threshold when the dead rows were selected from)
+      if (!c.use_dead) atomicSub(&st.dead_part[(uint32_t)gone >> PART_SHIFT], 1u);
+    }
+    if (at < st.max_change) {
+      // the reads of this line's old state are complete (their values were used above)
+      // before the word is swapped in: from then on the other side may rewrite the line
+      __asm__ volatile("" ::: "memory");
+      const uint64_t other = atomicExch((unsigned long long*)&st.pair[at],
+                                        tag | PAIR_EVICT | (uint32_t)line);
+      if ((other & ~((1ull << 40) - 1)) == tag) {
+        const int64_t p = (int64_t)(other & 0xFFFFFFFFull);
+        finish_line(st, line, it.ids[p], key_of(it, p));
+      }
+    }
   }
 }
 
+// The inserted positions of one tile of accesses in position order; the block's insertions
+// are first gathered in LDS by rank and then dealt one to a thread, for the same reason as
+// above.
 __device__ void p_in_emit(const State& st, const Ctrl& c, const Iter& it, const Outputs& o,
                           int64_t vb) {
   __shared__ uint32_t smem[TB / WAVE + 1];
+  __shared__ uint32_t red[TB / WAVE];
+  __shared__ int32_t s_pos[TB * IN_ITEMS];
+  if (st.in_tiles[vb] == 0) return;              // uniform over the block
   const int64_t base = (vb * TB + threadIdx.x) * IN_ITEMS;
   uint32_t flags = 0, cnt = 0;
   int32_t v[IN_ITEMS], key[IN_ITEMS], line[IN_ITEMS];
 #pragma unroll
   for (int t = 0; t < IN_ITEMS; ++t) {
     const int64_t p = base + t < it.n ? base + t : 0;
-    v[t] = it.ids[p];
+    line[t] = st.acc_line[p];
     key[t] = key_of(it, p);
+    v[t] = it.ids[p];
   }
 #pragma unroll
-  for (int t = 0; t < IN_ITEMS; ++t) line[t] = st.addr[v[t]];
-#pragma unroll
   for (int t = 0; t < IN_ITEMS; ++t)
-    if (base + t < it.n && inserts(c, key[t], v[t]) && line[t] < 0) {
+    if (base + t < it.n && line[t] < 0 && inserts(c, key[t], v[t])) {
       flags |= 1u << t;
       ++cnt;
     }
   uint32_t total;
-  uint32_t at = st.in_tiles[vb] + block_exclusive_scan<uint32_t, TB>(cnt, smem, total);
-  if (!cnt) return;
-  const int64_t dst = o.cs_offsets[it.i];
+  uint32_t rank = block_exclusive_scan<uint32_t, TB>(cnt, smem, total);
+  const uint32_t tile_base = block_prefix_of(st.in_tiles, vb, red);
+#pragma unroll
   for (int t = 0; t < IN_ITEMS; ++t)
-    if (flags >> t & 1) {
-      const int64_t p = base + t;
-      if (at < st.max_change) {
-        st.in_id[at] = it.ids[p];
-        st.in_next[at] = key_of(it, p);
-      }
-      if (dst + at < o.cs_capacity) {
-        o.in_ids[dst + at] = it.ids[p];
-        o.in_positions[dst + at] = (int32_t)p;
-      }
-      ++at;
+    if (flags >> t & 1) s_pos[rank++] = threadIdx.x * IN_ITEMS + t;   // position inside the tile
+  __syncthreads();
+  const int64_t dst = o.cs_offsets[it.i];
+  const uint64_t tag = pair_tag(it.i);
+  const int64_t tile_first = vb * (int64_t)(TB * IN_ITEMS);
+  for (uint32_t k = threadIdx.x; k < total; k += TB) {
+    const int64_t p = tile_first + s_pos[k];
+    const uint32_t at = tile_base + k;
+    const int32_t id = it.ids[p];
+    const int32_t nk = key_of(it, p);
+    if (dst + at < o.cs_capacity) {
+      o.in_ids[dst + at] = id;
+      o.in_positions[dst + at] = (int32_t)p;
     }
-}
-
-// The t-th inserted row takes the line of the t-th evicted one.
-__device__ void p_apply(const State& st, int32_t n_change, int64_t vb) {
-  const int64_t t = vb * TB + threadIdx.x;
-  if (t >= n_change || t >= st.max_change) return;
-  const int32_t line = st.out_slot[t];
-  const int32_t gone = st.res_id[line];
-  const int32_t v = st.in_id[t];
-  if (st.res_next[line] == st.S && !st.lru)   // a dead resident leaves the standing bitmap
-    atomicAnd(&st.dead_bits[(uint32_t)gone >> 5], ~(1u << ((uint32_t)gone & 31)));
-  st.res_id[line] = v;
-  st.res_next[line] = st.in_next[t];
-  st.addr[gone] = -1;
-  st.addr[v] = line;
-}
-
-// ---- the launches of one iteration -----------------------------------------------------
-
-__global__ __launch_bounds__(TB) void k_touch(State st, Iter it, unsigned long long* miss_out) {
-  extern __shared__ uint32_t lds[];
-  p_touch(st, it, miss_out, lds, blockIdx.x);
-}
-
-__global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i, int32_t lo_bin, Outputs o) {
-  p_threshold<BIG>(st, i, lo_bin, o.miss_count, o.cs_offsets);
-}
-
-// blocks [0, res_blocks) mark residents, the rest incoming rows; only one class is selected
-__global__ __launch_bounds__(TB) void k_mark(State st, Iter it, int64_t res_blocks) {
-  const Ctrl c = *st.ctrl;
-  if ((int64_t)blockIdx.x < res_blocks) {
-    if (c.mode_res == MODE_SELECT && !c.use_dead) p_mark_residents(st, c, blockIdx.x);
-  } else if (c.mode_in == MODE_SELECT) {
-    p_mark_incoming(st, c, it, blockIdx.x - res_blocks);
+    if (at < st.max_change) {
+      const uint64_t other = atomicExch((unsigned long long*)&st.pair[at], tag | (uint32_t)p);
+      if ((other & ~((1ull << 40) - 1)) == tag)
+        finish_line(st, (int32_t)(other & 0xFFFFFFFFull), id, nk);
+    }
   }
 }
 
-__global__ __launch_bounds__(TB) void k_bits_count(State st, int64_t words) {
-  const Ctrl c = *st.ctrl;
-  if (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT) return;
-  p_bits_count(st, c.use_dead ? st.dead_bits : st.bitmap, words, blockIdx.x);
-}
-
-__global__ __launch_bounds__(BIG) void k_bits_find(State st, int64_t words, int64_t parts) {
-  const Ctrl c = *st.ctrl;
-  if (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT) return;
-  p_bits_find<BIG>(st, c.use_dead ? st.dead_bits : st.bitmap, words, parts);
-}
-
-__global__ __launch_bounds__(TB) void k_dead_scatter(State st, int64_t words) {
-  const Ctrl c = *st.ctrl;
-  if (c.n_change > 0 && c.use_dead) p_dead_scatter(st, c, words, blockIdx.x, gridDim.x);
-}
-
-// blocks [0, evict_tiles): evictions per tile; next in_tiles blocks: insertions per tile;
-// the remaining blocks clear the select bitmap
-__global__ __launch_bounds__(TB) void k_tile_count(State st, Iter it, int64_t evict_tiles,
-                                              int64_t in_tiles, int64_t words) {
-  const Ctrl c = *st.ctrl;
-  const int64_t vb = blockIdx.x;
-  if (vb < evict_tiles) {
-    if (c.n_change > 0) {
-      if (st.dead_scatter && c.use_dead) p_evict_count(st, vb);
-      else p_evict_flags(st, c, vb);
-    }
-  } else if (vb < evict_tiles + in_tiles) {
-    if (c.n_change > 0) p_in_count(st, c, it, vb - evict_tiles);
-  } else if ((c.mode_res == MODE_SELECT || c.mode_in == MODE_SELECT) && !c.use_dead) {
-    p_bits_clear(st, words, vb - evict_tiles - in_tiles);
-  }
-}
-
-__global__ __launch_bounds__(BIG) void k_scan_two(State st, int64_t evict_tiles, int64_t in_tiles) {
-  if (st.ctrl->n_change <= 0) return;
-  if (blockIdx.x == 0) p_scan_counts<BIG>(st.evict_tiles, evict_tiles);
-  else p_scan_counts<BIG>(st.in_tiles, in_tiles);
-}
-
-__global__ __launch_bounds__(TB) void k_tile_emit(State st, Iter it, Outputs o, int64_t evict_tiles) {
+__global__ __launch_bounds__(TB) void k_emit(State st, Iter it, Outputs o, int64_t evict_tiles) {
   const Ctrl c = *st.ctrl;
   if (c.n_change <= 0) return;
   const int64_t evict_blocks = (evict_tiles + TB / WAVE - 1) / (TB / WAVE);
-  if ((int64_t)blockIdx.x < evict_blocks) p_evict_emit(st, it.i, o, blockIdx.x, evict_tiles);
+  if ((int64_t)blockIdx.x < evict_blocks) p_evict_emit(st, c, it, o, blockIdx.x, evict_tiles);
   else p_in_emit(st, c, it, o, blockIdx.x - evict_blocks);
 }
 
-__global__ __launch_bounds__(TB) void k_apply(State st) {
-  p_apply(st, st.ctrl->n_change, blockIdx.x);
+// popcount of one part of a bitmap (the part counts of the dead-row bitmap after a resumed
+// superbatch's start state has been marked)
+__global__ __launch_bounds__(TB) void k_part_count(const uint32_t* __restrict__ bits, int64_t words,
+                                                   uint32_t* __restrict__ part) {
+  __shared__ uint32_t red[TB / WAVE];
+  const int64_t base = (int64_t)blockIdx.x * PART_WORDS;
+  uint32_t cnt = 0;
+  for (int t = threadIdx.x; t < PART_WORDS; t += TB)
+    if (base + t < words) cnt += __popc(bits[base + t]);
+  const uint32_t total = block_sum_u32(cnt, red);
+  if (threadIdx.x == 0) part[blockIdx.x] = total;
 }
 
 struct Workspace {
@@ -890,7 +966,7 @@ struct Workspace {
   int64_t* d_cs_offsets;
   unsigned long long* d_counts;
   State st;
-  int64_t look_tiles, evict_tiles, in_tiles, bit_words, bit_parts, max_heads, max_change;
+  int64_t look_tiles, evict_tiles, in_tiles, max_heads, max_change;
   size_t bytes;
 };
 
@@ -929,11 +1005,12 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   st.addr = a.take<int32_t>(num_nodes);
   st.rhist = a.take<uint32_t>(S + 2);
   st.ihist = a.take<uint32_t>(S + 2);
-  w.bit_words = ceil_div(num_nodes, 32);
-  w.bit_parts = ceil_div(w.bit_words, TB * BITS_WORDS);
-  st.bitmap = a.take<uint32_t>(w.bit_words);
-  st.dead_bits = a.take<uint32_t>(w.bit_words);
-  st.bit_part = a.take<uint32_t>(w.bit_parts);
+  st.words = ceil_div(num_nodes, 32);
+  st.parts = ceil_div(st.words, PART_WORDS);
+  st.bitmap = a.take<uint32_t>(st.words);
+  st.dead_bits = a.take<uint32_t>(st.words);
+  st.sel_part = a.take<uint32_t>(st.parts);
+  st.dead_part = a.take<uint32_t>(st.parts);
   st.ctrl = a.take<Ctrl>(1);
   w.evict_tiles = ceil_div(c, (int64_t)EVICT_TILE);
   st.evict_words = a.take<uint64_t>(w.evict_tiles * WAVE);
@@ -942,9 +1019,8 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   st.in_tiles = a.take<uint32_t>(w.in_tiles);
   w.max_change = max_n < c ? max_n : c;
   if (w.max_change < 1) w.max_change = 1;
-  st.out_slot = a.take<int32_t>(w.max_change);
-  st.in_id = a.take<int32_t>(w.max_change);
-  st.in_next = a.take<int32_t>(w.max_change);
+  st.acc_line = a.take<int32_t>(max_n > 0 ? max_n : 1);
+  st.pair = a.take<uint64_t>(w.max_change);
   st.max_change = w.max_change;
   w.bytes = (a.used + 255) & ~size_t(255);
   return w;
@@ -1128,8 +1204,11 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   GINEX_HIP(fill_async<int32_t>(state.addr, num_nodes, -1, st));
   GINEX_HIP(fill_async<uint32_t>(state.rhist, S + 2, 0u, st));
   GINEX_HIP(fill_async<uint32_t>(state.ihist, S + 2, 0u, st));
-  GINEX_HIP(fill_async<uint32_t>(state.bitmap, w.bit_words, 0u, st));
-  GINEX_HIP(fill_async<uint32_t>(state.dead_bits, w.bit_words, 0u, st));
+  GINEX_HIP(fill_async<uint32_t>(state.bitmap, state.words, 0u, st));
+  GINEX_HIP(fill_async<uint32_t>(state.dead_bits, state.words, 0u, st));
+  GINEX_HIP(fill_async<uint32_t>(state.sel_part, state.parts, 0u, st));
+  GINEX_HIP(fill_async<uint32_t>(state.dead_part, state.parts, 0u, st));
+  GINEX_HIP(fill_async<uint64_t>(state.pair, w.max_change, 0ull, st));
   if (state.dead_scatter)
     GINEX_HIP(fill_async<uint64_t>(state.evict_words, w.evict_tiles * WAVE, 0ull, st));
   {
@@ -1143,6 +1222,10 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                          heads, distinct, w.first_of);
       hipLaunchKernelGGL(k_init_state_resume, dim3((unsigned)blocks), dim3(TB),
                          sizeof(uint32_t) * (S + 1), st, start_ids, w.first_of, state, w.d_counts);
+      GINEX_LAUNCH_CHECK();
+      // the part counts of the dead rows the start state brought along
+      hipLaunchKernelGGL(k_part_count, dim3((unsigned)state.parts), dim3(TB), 0, st,
+                         state.dead_bits, state.words, state.dead_part);
       GINEX_LAUNCH_CHECK();
       GINEX_HIP(hipMemcpyAsync(&bad, w.d_counts, sizeof(bad), hipMemcpyDeviceToHost, st));
       GINEX_HIP(hipStreamSynchronize(st));
@@ -1161,7 +1244,7 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   Outputs outs{in_ids, out_ids, in_positions, cs_capacity, cs_offsets, miss_count};
   {
     const int64_t res_blocks = ceil_div(cap, TB * MARK_ITEMS);
-    const int64_t clear_blocks = ceil_div(w.bit_words, TB * BITS_WORDS);
+    const int64_t evict_blocks = ceil_div(w.evict_tiles, TB / WAVE);
     for (int32_t i = 0; i < S; ++i) {
       Iter it;
       const int64_t lo = ids_offsets[i];
@@ -1177,27 +1260,19 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                            touch_lds, st, state, it, (unsigned long long*)(miss_count + i));
         GINEX_LAUNCH_CHECK();
       }
-      hipLaunchKernelGGL(k_threshold, dim3(1), dim3(BIG), 0, st, state, i, it.lo_bin, outs);
+      hipLaunchKernelGGL(k_threshold, dim3(1), dim3(BIG), 0, st, state, i, it.lo_bin, outs,
+                         w.evict_tiles);
       GINEX_LAUNCH_CHECK();
       if (it.n == 0) continue;  // nothing missed, nothing changes
       const int64_t in_tiles = ceil_div(it.n, (int64_t)TB * IN_ITEMS);
       hipLaunchKernelGGL(k_mark, dim3((unsigned)(res_blocks + ceil_div(it.n, TB * MARK_ITEMS))),
                          dim3(TB), 0, st, state, it, res_blocks);
-      hipLaunchKernelGGL(k_bits_count, dim3((unsigned)w.bit_parts), dim3(TB), 0, st, state,
-                         w.bit_words);
-      hipLaunchKernelGGL(k_bits_find, dim3(1), dim3(BIG), 0, st, state, w.bit_words, w.bit_parts);
-      if (state.dead_scatter)
-        hipLaunchKernelGGL(k_dead_scatter, dim3((unsigned)(w.bit_parts < 64 ? w.bit_parts : 64)),
-                           dim3(TB), 0, st, state, w.bit_words);
+      hipLaunchKernelGGL(k_find, dim3(1), dim3(BIG), 0, st, state);
       GINEX_LAUNCH_CHECK();
-      hipLaunchKernelGGL(k_tile_count, dim3((unsigned)(w.evict_tiles + in_tiles + clear_blocks)),
-                         dim3(TB), 0, st, state, it, w.evict_tiles, in_tiles, w.bit_words);
-      hipLaunchKernelGGL(k_scan_two, dim3(2), dim3(BIG), 0, st, state, w.evict_tiles, in_tiles);
-      hipLaunchKernelGGL(k_tile_emit,
-                         dim3((unsigned)(ceil_div(w.evict_tiles, TB / WAVE) + in_tiles)), dim3(TB), 0,
-                         st, state, it, outs, w.evict_tiles);
-      const int64_t most = it.n < cap ? it.n : cap;
-      hipLaunchKernelGGL(k_apply, dim3((unsigned)ceil_div(most, TB)), dim3(TB), 0, st, state);
+      hipLaunchKernelGGL(k_flags, dim3((unsigned)(w.evict_tiles + in_tiles + 1)), dim3(TB), 0, st,
+                         state, it, w.evict_tiles, in_tiles);
+      hipLaunchKernelGGL(k_emit, dim3((unsigned)(evict_blocks + in_tiles)), dim3(TB), 0, st, state,
+                         it, outs, w.evict_tiles);
       GINEX_LAUNCH_CHECK();
     }
   }
