@@ -12,18 +12,23 @@
 //   pick    a group of G lanes (G = 16/32/64 >= fanout) serves one frontier node: the
 //           lanes draw their Philox words in parallel, resolve Floyd's subset rule with
 //           group ballots, rank the picks, read the neighbours and insert them into the
-//           batch's open-addressing hash table with atomicMin(candidate rank).  The rank
-//           (frontier slot * fanout + pick slot) is exactly the order in which a
+//           batch's open-addressing hash table, keeping the smaller candidate rank per id.
+//           The rank (frontier slot * fanout + pick slot) is exactly the order in which a
 //           sequential scan would meet the candidate, so after the kernel every new id
-//           holds the rank of its first occurrence.
-//   count   per frontier slot: which picks are first occurrences (bit mask); per 256
-//           slots: number of picks and number of first occurrences.
+//           holds the rank of its first occurrence.  A lane knows at once whether its
+//           candidate lost (the id is in the list already, or in the table with a smaller
+//           rank); a candidate that holds its slot may still be displaced by a smaller rank
+//           arriving later, and the displacing lane records that.  The group's ballot of
+//           holders is the first-occurrence mask.
+//   count   per 256 frontier slots: number of picks and of first occurrences (mask minus
+//           displaced), from sequential arrays: no table access.
 //   scan    one block per batch scans its tile counts; one block turns the per-batch
 //           totals into output offsets.
 //   emit    appends the first occurrences to the batch's list at their scanned positions,
 //           writes the hop's rowptr and the adj_col entries of the first occurrences.
-//   col     the remaining picks (ids seen before, or seen earlier in this hop) look their
-//           position up for adj_col.
+//   col     the remaining picks get their position for adj_col: an id of an earlier stage
+//           saw it in the table when it lost, an id seen earlier in this hop looks it up
+//           through its slot.
 //
 // The seeds go through the same count/scan/emit path as a stage with one candidate per
 // slot, which also removes repeated seeds.
@@ -61,9 +66,11 @@ struct Tables {
   uint64_t* tab;         // packed per-batch tables, one 64-bit (key, value) word per slot
   int64_t* tab_off;      // [S] first slot of batch b's table
   uint32_t* tab_slots;   // [S] its number of slots
-  uint64_t* first;       // [S][fr_slots] bit s set: pick s of the slot is a first occurrence
+  uint64_t* first;       // [S][fr_slots] bit s set: pick s of the slot holds its id's table slot
+  uint64_t* displaced;   // [S][fr_slots] bit s set: ... but a smaller rank took it over later
   int32_t* cand;         // [S][cand_slots] candidate node ids of the running stage
-  uint32_t* hslot;       // [S][cand_slots] hash slot of each candidate
+  uint32_t* ref;         // [S][cand_slots] where a pick finds its list position: OLD_ID |
+                         // position (an id of an earlier stage), else its table slot
   uint8_t* cnt;          // [S][fr_slots] picks per frontier slot
   int64_t cand_slots, fr_slots;
   int32_t* wlist;        // [S][stride_ids] the growing list of every batch
@@ -71,28 +78,58 @@ struct Tables {
 };
 
 // A slot is one 64-bit word: key in the high half, value in the low half, all ones = free.
-// Inserting costs one 64-bit compare-and-swap when the key is new (the usual case); a key
-// that is present already keeps the smaller value, which needs a second atomic only when
-// this candidate's value is smaller than the stored one.
-__device__ __forceinline__ uint32_t table_insert(uint64_t* t, uint32_t slots, uint32_t id,
-                                                 uint32_t value) {
+// The value of an id of an earlier stage is its list position, that of an id new in this
+// stage PEND + the smallest candidate rank it was seen with.
+constexpr uint64_t FREE_SLOT = ~0ull;
+constexpr uint32_t OLD_ID = 0x80000000u;
+
+__device__ __forceinline__ uint32_t hash_slot(uint32_t id, uint32_t slots) {
+  return __umulhi(id * 2654435761u, slots);
+}
+
+// Puts the list a batch has so far back into its freshly sized table.
+__device__ __forceinline__ void table_put(uint64_t* t, uint32_t slots, uint32_t id, uint32_t value) {
   const unsigned long long mine = ((unsigned long long)id << 32) | value;
   unsigned long long* tab = reinterpret_cast<unsigned long long*>(t);
-  uint32_t h = __umulhi(id * 2654435761u, slots);
+  uint32_t h = hash_slot(id, slots);
+  while (atomicCAS(&tab[h], FREE_SLOT, mine) != FREE_SLOT) h = h + 1 == slots ? 0 : h + 1;
+}
+
+// Inserts candidate (id, rank) of the running stage, keeping the smaller rank per id, and
+// leaves the pick's reference for k_col.  One 64-bit compare-and-swap when the id is new
+// (the usual case); an id that is present needs a second atomic only if this rank is smaller
+// than the stored one, and the rank it replaces is recorded as displaced.  Returns whether
+// the candidate holds its id's slot now (a smaller rank may still take it over later).
+__device__ __forceinline__ bool place_candidate(const Tables& T, int b, int k, uint32_t id,
+                                                uint32_t rank) {
+  const uint32_t slots = T.tab_slots[b];
+  unsigned long long* tab = reinterpret_cast<unsigned long long*>(T.tab + T.tab_off[b]);
+  const unsigned long long mine = ((unsigned long long)id << 32) | (PEND + rank);
+  uint32_t* ref = T.ref + (int64_t)b * T.cand_slots + rank;
+  uint32_t h = hash_slot(id, slots);
   while (true) {
-    const unsigned long long old = atomicCAS(&tab[h], ~0ull, mine);
-    if (old == ~0ull) break;
+    const unsigned long long old = atomicCAS(&tab[h], FREE_SLOT, mine);
+    if (old == FREE_SLOT) {
+      *ref = h;
+      return true;
+    }
     if ((uint32_t)(old >> 32) == id) {
-      if ((uint32_t)old > value) atomicMin(&tab[h], mine);
-      break;
+      const uint32_t there = (uint32_t)old;
+      if (there < PEND) {             // in the list since an earlier stage: `there` is its position
+        *ref = OLD_ID | there;
+        return false;
+      }
+      *ref = h;
+      if (there < (uint32_t)mine) return false;
+      const uint32_t before = (uint32_t)atomicMin(&tab[h], mine);
+      if (before < (uint32_t)mine) return false;   // an even smaller rank got in between
+      const uint32_t gone = before - PEND;
+      atomicOr((unsigned long long*)&T.displaced[(int64_t)b * T.fr_slots + gone / k],
+               1ull << (gone % k));
+      return true;
     }
     h = h + 1 == slots ? 0 : h + 1;
   }
-  return h;
-}
-
-__device__ __forceinline__ uint32_t table_value(const uint64_t* t, uint32_t h) {
-  return (uint32_t)t[h];
 }
 
 // Which (batch, tile) a block works on.  Grids are one-dimensional and the hardware deals
@@ -123,6 +160,15 @@ inline unsigned grid_blocks(int S, int64_t tiles_per_batch) {
   return (unsigned)(XCDS * ceil_div(S, XCDS) * tiles_per_batch);
 }
 
+// Launches are sized on the host for the worst case a hop allows (every node so far with a
+// full fanout of new neighbours), which is several times what a frontier really holds, and
+// a block that finds nothing to do still costs its dispatch.  So a grid holds at most this
+// many tiles per batch and a block strides over the tiles its batch really has.
+constexpr int64_t SLOT_TILES = 128;   // tiles of TB frontier slots
+constexpr int64_t PICK_TILES = 512;   // tiles of TB/G frontier nodes
+
+inline int64_t capped(int64_t tiles, int64_t most) { return tiles < most ? tiles : most; }
+
 // Single block: table sizes and offsets for the stage that is about to run.
 __global__ __launch_bounds__(TB) void k_table_plan(Tables T, int S, int64_t num_nodes, int k,
                                                    const int32_t* __restrict__ nfront,
@@ -149,11 +195,18 @@ __global__ __launch_bounds__(TB) void k_table_plan(Tables T, int S, int64_t num_
   if (threadIdx.x == 0) *total_slots = run;
 }
 
-__global__ __launch_bounds__(TB) void k_table_clear(uint64_t* __restrict__ tab,
-                                                    const int64_t* __restrict__ total_slots) {
+__global__ __launch_bounds__(TB) void k_table_clear(Tables T, const int64_t* __restrict__ total_slots,
+                                                    const int32_t* __restrict__ nfront, int S,
+                                                    int64_t front) {
   const int64_t n = *total_slots;
   const int64_t span = (int64_t)gridDim.x * TB;
-  for (int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x; i < n; i += span) tab[i] = ~0ull;
+  const int64_t me = (int64_t)blockIdx.x * TB + threadIdx.x;
+  for (int64_t i = me; i < n; i += span) T.tab[i] = FREE_SLOT;
+  // and the displacements of the stage before: displaced[b][0 .. nfront[b]) <- 0
+  for (int64_t i = me; i < (int64_t)S * front; i += span) {
+    const int64_t b = i / front, j = i - b * front;
+    if (j < nfront[b]) T.displaced[b * T.fr_slots + j] = 0;
+  }
 }
 
 // Put the list a batch has so far back into its freshly sized table.
@@ -162,10 +215,10 @@ __global__ __launch_bounds__(TB) void k_reinsert(Tables T, const int32_t* __rest
   const Where at = where_am_i(S, tpb);
   if (at.b < 0) return;
   const int b = at.b;
-  const int64_t j = at.tile * TB + threadIdx.x;
-  if (j >= nlist[b]) return;
   uint64_t* t = T.tab + T.tab_off[b];
-  table_insert(t, T.tab_slots[b], (uint32_t)T.wlist[b * T.stride_ids + j], (uint32_t)j);
+  const uint32_t slots = T.tab_slots[b];
+  for (int64_t j = at.tile * TB + threadIdx.x; j < nlist[b]; j += tpb * TB)
+    table_put(t, slots, (uint32_t)T.wlist[b * T.stride_ids + j], (uint32_t)j);
 }
 
 // Stage "seeds": slot j of batch b holds seed j.
@@ -176,13 +229,12 @@ __global__ __launch_bounds__(TB) void k_seed_stage(Tables T, const int32_t* __re
   const Where at = where_am_i(S, tpb);
   if (at.b < 0) return;
   const int b = at.b;
-  const int64_t j = at.tile * TB + threadIdx.x;
-  if (j >= nfront[b]) return;
-  const uint32_t id = (uint32_t)seeds[seed_off[b] + j];
-  uint64_t* t = T.tab + T.tab_off[b];
-  T.cand[b * T.cand_slots + j] = (int32_t)id;
-  T.hslot[b * T.cand_slots + j] = table_insert(t, T.tab_slots[b], id, PEND + (uint32_t)j);
-  T.cnt[b * T.fr_slots + j] = 1;
+  for (int64_t j = at.tile * TB + threadIdx.x; j < nfront[b]; j += tpb * TB) {
+    const uint32_t id = (uint32_t)seeds[seed_off[b] + j];
+    T.cand[b * T.cand_slots + j] = (int32_t)id;
+    T.first[b * T.fr_slots + j] = place_candidate(T, b, 1, id, (uint32_t)j) ? 1ull : 0ull;
+    T.cnt[b * T.fr_slots + j] = 1;
+  }
 }
 
 // NC: neighbour lists are looked up in the neighbour cache first (Section 3.2: address
@@ -201,86 +253,102 @@ __global__ __launch_bounds__(TB) void k_pick(Tables T, const OffT* __restrict__ 
   const int b = here.b;
   const int lane = lane_id();
   const int sub = threadIdx.x & (G - 1);
-  const int64_t idx = here.tile * (TB / G) + threadIdx.x / G;
-  const bool active = idx < nfront[b];
-  const uint32_t v = active ? (uint32_t)T.wlist[b * T.stride_ids + idx] : 0u;
-  int64_t lo = 0, deg = 0;
-  const int32_t* row = indices;
-  if (active) {
-    int64_t at = -1;
-    if (NC) at = nc_address_table[v];
-    if (at >= 0) {
-      deg = nc_cache_array[at];
-      row = nc_cache_array;
-      lo = at + 1;
-    } else {
-      lo = (int64_t)offsets[v];
-      deg = (int64_t)offsets[v + 1] - lo;
+  const int64_t tiles_needed = ((int64_t)nfront[b] + TB / G - 1) / (TB / G);
+  for (int64_t tile = here.tile; tile < tiles_needed; tile += tpb) {
+    const int64_t idx = tile * (TB / G) + threadIdx.x / G;
+    const bool active = idx < nfront[b];
+    const uint32_t v = active ? (uint32_t)T.wlist[b * T.stride_ids + idx] : 0u;
+    int64_t lo = 0, deg = 0;
+    const int32_t* row = indices;
+    if (active) {
+      int64_t at = -1;
+      if (NC) at = nc_address_table[v];
+      if (at >= 0) {
+        deg = nc_cache_array[at];
+        row = nc_cache_array;
+        lo = at + 1;
+      } else {
+        lo = (int64_t)offsets[v];
+        deg = (int64_t)offsets[v + 1] - lo;
+      }
+    }
+    const int c = deg < k ? (int)deg : k;
+    int64_t pick = sub;   // row position taken by this lane
+    int slot = sub;       // its place among the node's picks (ascending position)
+    if (__any(deg > k)) {
+      // Floyd's subset rule, every lane of the wave takes part so that the group
+      // shuffles and ballots stay convergent; groups with deg <= k discard the result.
+      const int64_t d = deg > k ? deg : (int64_t)k + 1;
+      const int64_t j = d - k + sub;
+      const uint64_t r = philox_draw(seed, v, first_batch + (uint32_t)b, (uint32_t)hop, (uint32_t)sub);
+      const int64_t t = (int64_t)__umul64hi(r, (uint64_t)(j + 1));
+      int64_t mine = t;
+      const int group_shift = lane & ~(G - 1);
+      const uint64_t group_mask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1);
+      for (int i = 1; i < k; ++i) {
+        const int64_t ti = __shfl(t, i, G);
+        const uint64_t hit = (__ballot(sub < i && mine == ti) >> group_shift) & group_mask;
+        if (sub == i && hit) mine = j;
+      }
+      int rank = 0;
+      for (int m = 0; m < k; ++m) rank += __shfl(mine, m, G) < mine;
+      if (deg > k) {
+        pick = mine;
+        slot = rank;
+      }
+    }
+    bool holds = false;
+    if (active && sub < c) {
+      const uint32_t u = (uint32_t)row[lo + pick];
+      const uint32_t rank = (uint32_t)(idx * k + slot);
+      T.cand[b * T.cand_slots + rank] = (int32_t)u;
+      holds = place_candidate(T, b, k, u, rank);
+    }
+    // The group's first-occurrence mask, bit = pick slot.  The slots of a group's active lanes
+    // are distinct (a permutation of 0..c-1), so every holder contributes the bit of its slot.
+    uint64_t mask = 0;
+    {
+      const int group_shift = lane & ~(G - 1);
+      const uint64_t group_mask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1);
+      for (int m = 0; m < k; ++m)
+        if ((__ballot(holds && slot == m) >> group_shift) & group_mask) mask |= 1ull << m;
+    }
+    if (active && sub == 0) {
+      T.cnt[b * T.fr_slots + idx] = (uint8_t)c;
+      T.first[b * T.fr_slots + idx] = mask;
     }
   }
-  const int c = deg < k ? (int)deg : k;
-  int64_t pick = sub;   // row position taken by this lane
-  int slot = sub;       // its place among the node's picks (ascending position)
-  if (__any(deg > k)) {
-    // Floyd's subset rule, every lane of the wave takes part so that the group
-    // shuffles and ballots stay convergent; groups with deg <= k discard the result.
-    const int64_t d = deg > k ? deg : (int64_t)k + 1;
-    const int64_t j = d - k + sub;
-    const uint64_t r = philox_draw(seed, v, first_batch + (uint32_t)b, (uint32_t)hop, (uint32_t)sub);
-    const int64_t t = (int64_t)__umul64hi(r, (uint64_t)(j + 1));
-    int64_t mine = t;
-    const int group_shift = lane & ~(G - 1);
-    const uint64_t group_mask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1);
-    for (int i = 1; i < k; ++i) {
-      const int64_t ti = __shfl(t, i, G);
-      const uint64_t hit = (__ballot(sub < i && mine == ti) >> group_shift) & group_mask;
-      if (sub == i && hit) mine = j;
-    }
-    int rank = 0;
-    for (int m = 0; m < k; ++m) rank += __shfl(mine, m, G) < mine;
-    if (deg > k) {
-      pick = mine;
-      slot = rank;
-    }
-  }
-  if (active && sub < c) {
-    const uint32_t u = (uint32_t)row[lo + pick];
-    const int64_t at = b * T.cand_slots + idx * k + slot;
-    uint64_t* t = T.tab + T.tab_off[b];
-    T.cand[at] = (int32_t)u;
-    T.hslot[at] = table_insert(t, T.tab_slots[b], u, PEND + (uint32_t)(idx * k + slot));
-  }
-  if (active && sub == 0) T.cnt[b * T.fr_slots + idx] = (uint8_t)c;
 }
 
-// tile_sums[b][tile] = (picks << 32 | first occurrences) of 256 frontier slots, and the
-// first-occurrence mask of every slot
-__global__ __launch_bounds__(TB) void k_count(Tables T, const int32_t* __restrict__ nfront, int k,
+// tile_sums[b][tile] = (picks << 32 | first occurrences) of 256 frontier slots; the final
+// first-occurrence mask of a slot is what its lanes held minus what was displaced later
+__global__ __launch_bounds__(TB) void k_count(Tables T, const int32_t* __restrict__ nfront,
                                               uint64_t* __restrict__ tile_sums, int64_t tiles,
                                               int S, int64_t tpb) {
   __shared__ uint64_t red[TB / WAVE];
   const Where here = where_am_i(S, tpb);
   if (here.b < 0) return;
   const int b = here.b;
-  const int64_t idx = here.tile * TB + threadIdx.x;
-  uint64_t first = 0;
-  int c = 0;
-  if (idx < nfront[b]) {
-    c = T.cnt[b * T.fr_slots + idx];
-    const uint64_t* t = T.tab + T.tab_off[b];
-    const int64_t at = b * T.cand_slots + idx * k;
-    for (int s = 0; s < c; ++s)
-      if (table_value(t, T.hslot[at + s]) == PEND + (uint32_t)(idx * k + s)) first |= 1ull << s;
-    T.first[b * T.fr_slots + idx] = first;
-  }
-  uint64_t packed = ((uint64_t)c << 32) | (uint64_t)__popcll(first);
-  packed = wave_reduce_sum(packed);
-  if (lane_id() == 0) red[threadIdx.x / WAVE] = packed;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint64_t s = 0;
-    for (int w = 0; w < TB / WAVE; ++w) s += red[w];
-    tile_sums[b * tiles + here.tile] = s;
+  const int nf = nfront[b];
+  for (int64_t tile = here.tile; tile * TB < nf; tile += tpb) {
+    const int64_t idx = tile * TB + threadIdx.x;
+    uint64_t first = 0;
+    int c = 0;
+    if (idx < nf) {
+      c = T.cnt[b * T.fr_slots + idx];
+      first = T.first[b * T.fr_slots + idx] & ~T.displaced[b * T.fr_slots + idx];
+      T.first[b * T.fr_slots + idx] = first;
+    }
+    uint64_t packed = ((uint64_t)c << 32) | (uint64_t)__popcll(first);
+    packed = wave_reduce_sum(packed);
+    __syncthreads();   // red may still be read from the tile before
+    if (lane_id() == 0) red[threadIdx.x / WAVE] = packed;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint64_t s = 0;
+      for (int w = 0; w < TB / WAVE; ++w) s += red[w];
+      tile_sums[b * tiles + tile] = s;
+    }
   }
 }
 
@@ -374,42 +442,47 @@ __global__ __launch_bounds__(TB) void k_emit(Tables T, const int32_t* __restrict
   if (here.b < 0) return;
   const int b = here.b;
   const int nf = nfront[b];
-  if (here.tile * TB >= nf && here.tile != 0) return;
-  const int64_t idx = here.tile * TB + threadIdx.x;
-  const bool active = idx < nf;
-  const uint64_t first = active ? T.first[b * T.fr_slots + idx] : 0;
-  const int c = active ? T.cnt[b * T.fr_slots + idx] : 0;
-  const uint64_t packed = ((uint64_t)c << 32) | (uint64_t)__popcll(first);
-  uint64_t total;
-  const uint64_t ex = block_exclusive_scan<uint64_t, TB>(packed, smem, total) +
-                      tile_sums[b * tiles + here.tile];
-  const int64_t edges_before = (int64_t)(ex >> 32);
-  if (rowptr) {
-    const int64_t rb = row_base[b];
-    if (active && rb + idx < rowptr_capacity) rowptr[rb + idx] = edges_before;
-    if ((active && idx == nf - 1) || (nf == 0 && idx == 0)) {
-      const int64_t last = nf == 0 ? 0 : idx + 1;
-      if (rb + last < rowptr_capacity) rowptr[rb + last] = edges_before + c;
-    }
-  }
-  if (first) {
-    uint32_t at_list = (uint32_t)nlist[b] + (uint32_t)(ex & 0xFFFFFFFFu);
-    // A first occurrence's slot in `cand` is overwritten with its list position: the table
-    // keeps PEND + its rank, so later duplicates find the position through the rank without
-    // a scattered write into the table here (the next stage rebuilds the tables anyway).
-    const int64_t at = b * T.cand_slots + idx * k;
-    const int64_t dst = col ? col_base[b] + edges_before : 0;
-    for (int s = 0; s < c; ++s)
-      if (first >> s & 1) {
-        T.wlist[b * T.stride_ids + at_list] = T.cand[at + s];
-        T.cand[at + s] = (int32_t)at_list;
-        if (col && dst + s < col_capacity) col[dst + s] = (int32_t)at_list;
-        ++at_list;
+  // tile 0 always runs: an empty frontier still has a rowptr entry
+  for (int64_t tile = here.tile; tile * TB < nf || tile == 0; tile += tpb) {
+    const int64_t idx = tile * TB + threadIdx.x;
+    const bool active = idx < nf;
+    const uint64_t first = active ? T.first[b * T.fr_slots + idx] : 0;
+    const int c = active ? T.cnt[b * T.fr_slots + idx] : 0;
+    const uint64_t packed = ((uint64_t)c << 32) | (uint64_t)__popcll(first);
+    uint64_t total;
+    const uint64_t ex = block_exclusive_scan<uint64_t, TB>(packed, smem, total) +
+                        (nf > 0 ? tile_sums[b * tiles + tile] : 0);
+    const int64_t edges_before = (int64_t)(ex >> 32);
+    if (rowptr) {
+      const int64_t rb = row_base[b];
+      if (active && rb + idx < rowptr_capacity) rowptr[rb + idx] = edges_before;
+      if ((active && idx == nf - 1) || (nf == 0 && idx == 0)) {
+        const int64_t last = nf == 0 ? 0 : idx + 1;
+        if (rb + last < rowptr_capacity) rowptr[rb + last] = edges_before + c;
       }
+    }
+    if (first) {
+      uint32_t at_list = (uint32_t)nlist[b] + (uint32_t)(ex & 0xFFFFFFFFu);
+      // A first occurrence's slot in `cand` is overwritten with its list position: the table
+      // keeps PEND + its rank, so later duplicates find the position through the rank without
+      // a scattered write into the table here (the next stage rebuilds the tables anyway).
+      const int64_t at = b * T.cand_slots + idx * k;
+      const int64_t dst = col ? col_base[b] + edges_before : 0;
+      for (int s = 0; s < c; ++s)
+        if (first >> s & 1) {
+          T.wlist[b * T.stride_ids + at_list] = T.cand[at + s];
+          T.cand[at + s] = (int32_t)at_list;
+          if (col && dst + s < col_capacity) col[dst + s] = (int32_t)at_list;
+          ++at_list;
+        }
+    }
   }
 }
 
-// adj_col of the picks that are not first occurrences: their id is in the table already.
+// adj_col of the picks that are not first occurrences.  An id of an earlier stage carries
+// its list position in its reference; an id that is new in this stage is looked up through
+// its slot, whose final value is PEND + the rank of the id's first occurrence, whose entry in
+// `cand` now holds the position.
 __global__ __launch_bounds__(TB) void k_col(Tables T, const int32_t* __restrict__ nfront, int k,
                                             const int64_t* __restrict__ rowptr,
                                             int64_t rowptr_capacity,
@@ -420,22 +493,21 @@ __global__ __launch_bounds__(TB) void k_col(Tables T, const int32_t* __restrict_
   const Where here = where_am_i(S, tpb);
   if (here.b < 0) return;
   const int b = here.b;
-  const int64_t idx = here.tile * TB + threadIdx.x;
-  if (idx >= nfront[b] || row_base[b] + idx >= rowptr_capacity) return;
-  const int c = T.cnt[b * T.fr_slots + idx];
-  const uint64_t first = T.first[b * T.fr_slots + idx];
-  if (__popcll(first) == c) return;
   const uint64_t* t = T.tab + T.tab_off[b];
-  const int64_t at = b * T.cand_slots + idx * k;
-  const int64_t dst = col_base[b] + rowptr[row_base[b] + idx];
-  for (int s = 0; s < c; ++s)
-    if (!(first >> s & 1) && dst + s < col_capacity) {
-      // an id of an earlier stage carries its list position; an id that is new in this
-      // stage carries PEND + rank of its first occurrence, whose slot in `cand` now holds
-      // the position
-      const uint32_t v = table_value(t, T.hslot[at + s]);
-      col[dst + s] = v < PEND ? (int32_t)v : T.cand[b * T.cand_slots + (v - PEND)];
-    }
+  for (int64_t idx = here.tile * TB + threadIdx.x; idx < nfront[b]; idx += tpb * TB) {
+    if (row_base[b] + idx >= rowptr_capacity) return;
+    const int c = T.cnt[b * T.fr_slots + idx];
+    const uint64_t first = T.first[b * T.fr_slots + idx];
+    if (__popcll(first) == c) continue;
+    const int64_t at = b * T.cand_slots + idx * k;
+    const int64_t dst = col_base[b] + rowptr[row_base[b] + idx];
+    for (int s = 0; s < c; ++s)
+      if (!(first >> s & 1) && dst + s < col_capacity) {
+        const uint32_t r = T.ref[at + s];
+        col[dst + s] = r & OLD_ID ? (int32_t)(r & ~OLD_ID)
+                                  : T.cand[b * T.cand_slots + ((uint32_t)t[r] - PEND)];
+      }
+  }
 }
 
 __global__ __launch_bounds__(TB) void k_ids_offsets(Meta M, int S, const int32_t* __restrict__ nlist) {
@@ -536,11 +608,12 @@ struct Workspace {
   uint64_t* tab;
   int32_t* wlist;
   int32_t* cand;
-  uint32_t* hslot;
+  uint32_t* ref;
   uint8_t* cnt;
   uint64_t* tile_sums;
   uint64_t* batch_total;
   uint64_t* first;
+  uint64_t* displaced;
   int64_t* tab_off;
   uint32_t* tab_slots;
   int64_t* tab_total;
@@ -560,11 +633,12 @@ Workspace carve(void* base, const Plan& p, int32_t S, int32_t H) {
   w.tab = a.take<uint64_t>((size_t)S * p.table_slots);
   w.wlist = a.take<int32_t>((size_t)S * p.stride_ids);
   w.cand = a.take<int32_t>((size_t)S * p.cand_slots);
-  w.hslot = a.take<uint32_t>((size_t)S * p.cand_slots);
+  w.ref = a.take<uint32_t>((size_t)S * p.cand_slots);
   w.cnt = a.take<uint8_t>((size_t)S * p.fr_slots);
   w.tile_sums = a.take<uint64_t>((size_t)S * p.tiles);
   w.batch_total = a.take<uint64_t>(S);
   w.first = a.take<uint64_t>((size_t)S * p.fr_slots);
+  w.displaced = a.take<uint64_t>((size_t)S * p.fr_slots);
   w.tab_off = a.take<int64_t>(S);
   w.tab_slots = a.take<uint32_t>(S);
   w.tab_total = a.take<int64_t>(1);
@@ -594,23 +668,27 @@ int32_t check_shape(int64_t num_nodes, int32_t S, int64_t max_batch, const int32
   return GINEX_OK;
 }
 
+inline int64_t pick_tiles(int64_t front, int group) {
+  return capped(ceil_div(front, TB / group), PICK_TILES);
+}
+
 template <typename OffT, bool NC>
 void launch_pick(const Tables& T, const Plan& p, const ginex_csr_t* g, const int32_t* nfront, int k,
                  int hop, int32_t S, uint64_t seed, uint32_t first_batch, hipStream_t st) {
   const OffT* off = static_cast<const OffT*>(g->offsets);
   const int64_t front = p.stride_front[hop];
   if (k <= 16) {
-    const int64_t tpb = ceil_div(front, TB / 16);
+    const int64_t tpb = pick_tiles(front, 16);
     hipLaunchKernelGGL((k_pick<16, OffT, NC>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
                        g->indices, g->nc_address_table, g->nc_cache_array, nfront, k, hop, seed,
                        first_batch, S, tpb);
   } else if (k <= 32) {
-    const int64_t tpb = ceil_div(front, TB / 32);
+    const int64_t tpb = pick_tiles(front, 32);
     hipLaunchKernelGGL((k_pick<32, OffT, NC>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
                        g->indices, g->nc_address_table, g->nc_cache_array, nfront, k, hop, seed,
                        first_batch, S, tpb);
   } else {
-    const int64_t tpb = ceil_div(front, TB / 64);
+    const int64_t tpb = pick_tiles(front, 64);
     hipLaunchKernelGGL((k_pick<64, OffT, NC>), dim3(grid_blocks(S, tpb)), dim3(TB), 0, st, T, off,
                        g->indices, g->nc_address_table, g->nc_cache_array, nfront, k, hop, seed,
                        first_batch, S, tpb);
@@ -675,7 +753,7 @@ extern "C" int32_t ginex_sample_superbatch(
   hipStream_t st = (hipStream_t)stream;
   Tables T;
   T.tab = w.tab; T.tab_off = w.tab_off; T.tab_slots = w.tab_slots; T.first = w.first;
-  T.cand = w.cand; T.hslot = w.hslot; T.cnt = w.cnt;
+  T.displaced = w.displaced; T.cand = w.cand; T.ref = w.ref; T.cnt = w.cnt;
   T.cand_slots = p.cand_slots; T.fr_slots = p.fr_slots; T.wlist = w.wlist;
   T.stride_ids = p.stride_ids;
   Meta M;
@@ -727,11 +805,11 @@ extern "C" int32_t ginex_sample_superbatch(
     const int64_t front = stage < 0 ? (max_batch > 0 ? max_batch : 1) : p.stride_front[stage];
     // in a hop the frontier is the whole list as it stands when the hop starts
     const int32_t* nfront = stage < 0 ? w.nfront : nlist;
-    const int64_t tpb = ceil_div(front, TB);
+    const int64_t tpb = capped(ceil_div(front, TB), SLOT_TILES);
     const dim3 grid_slots(grid_blocks(S, tpb));
     hipLaunchKernelGGL(k_table_plan, dim3(1), dim3(TB), 0, st, T, S, g->num_nodes, k, nfront,
                        nlist, w.tab_total);
-    hipLaunchKernelGGL(k_table_clear, dim3(4096), dim3(TB), 0, st, w.tab, w.tab_total);
+    hipLaunchKernelGGL(k_table_clear, dim3(4096), dim3(TB), 0, st, T, w.tab_total, nfront, S, front);
     GINEX_LAUNCH_CHECK();
     if (stage >= 0) {
       hipLaunchKernelGGL(k_reinsert, grid_slots, dim3(TB), 0, st, T, nlist, S, tpb);
@@ -751,7 +829,7 @@ extern "C" int32_t ginex_sample_superbatch(
       launch_pick<int32_t, false>(T, p, g, nfront, k, stage, S, rng_seed, first_batch_index, st);
     }
     GINEX_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_count, grid_slots, dim3(TB), 0, st, T, nfront, k, w.tile_sums, p.tiles, S,
+    hipLaunchKernelGGL(k_count, grid_slots, dim3(TB), 0, st, T, nfront, w.tile_sums, p.tiles, S,
                        tpb);
     GINEX_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_scan_batch, dim3(S), dim3(TB), 0, st, w.tile_sums, p.tiles, nfront,
