@@ -167,6 +167,15 @@ inline unsigned grid_blocks(int S, int64_t tiles_per_batch) {
 constexpr int64_t SLOT_TILES = 128;   // tiles of TB frontier slots
 constexpr int64_t PICK_TILES = 512;   // tiles of TB/G frontier nodes
 
+// GINEX_SAMPLER_TILES=n in the environment replaces both caps (any n >= 1 gives the same
+// result: only the assignment of tiles to blocks, and with it the order in which candidates
+// reach the hash tables, changes; the determinism tests use it).
+inline int64_t tile_cap(int64_t standard) {
+  const char* env = getenv("GINEX_SAMPLER_TILES");
+  const long n = env ? atol(env) : 0;
+  return n >= 1 ? n : standard;
+}
+
 inline int64_t capped(int64_t tiles, int64_t most) { return tiles < most ? tiles : most; }
 
 // Single block: table sizes and offsets for the stage that is about to run.
@@ -669,7 +678,7 @@ int32_t check_shape(int64_t num_nodes, int32_t S, int64_t max_batch, const int32
 }
 
 inline int64_t pick_tiles(int64_t front, int group) {
-  return capped(ceil_div(front, TB / group), PICK_TILES);
+  return capped(ceil_div(front, TB / group), tile_cap(PICK_TILES));
 }
 
 template <typename OffT, bool NC>
@@ -805,7 +814,7 @@ extern "C" int32_t ginex_sample_superbatch(
     const int64_t front = stage < 0 ? (max_batch > 0 ? max_batch : 1) : p.stride_front[stage];
     // in a hop the frontier is the whole list as it stands when the hop starts
     const int32_t* nfront = stage < 0 ? w.nfront : nlist;
-    const int64_t tpb = capped(ceil_div(front, TB), SLOT_TILES);
+    const int64_t tpb = capped(ceil_div(front, TB), tile_cap(SLOT_TILES));
     const dim3 grid_slots(grid_blocks(S, tpb));
     hipLaunchKernelGGL(k_table_plan, dim3(1), dim3(TB), 0, st, T, S, g->num_nodes, k, nfront,
                        nlist, w.tab_total);

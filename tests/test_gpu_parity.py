@@ -1043,3 +1043,48 @@ def test_gather_lines_row_sizes(ginex, row_bytes):
         out = cache.gather(ids_d, src_line=lines)
         assert np.array_equal(out.cpu().numpy().view(np.uint8).reshape(count, row_bytes),
                               oracle.gather(slow.numpy(), ids))
+
+
+# ---- determinism across launch shapes ------------------------------------------------------
+
+@pytest.mark.parametrize("tiles", ["1", "3", "100000"])
+def test_sampler_is_independent_of_the_launch_shape(ginex, case1, case2, tiles, monkeypatch):
+    """Another assignment of tiles to blocks (fewer, longer-running blocks, or one block per
+    tile) changes the order in which candidates reach the hash tables, not the result."""
+    for c in (case1, case2):
+        base = run_sample(ginex, c)
+        monkeypatch.setenv("GINEX_SAMPLER_TILES", tiles)
+        other = run_sample(ginex, c)
+        monkeypatch.delenv("GINEX_SAMPLER_TILES")
+        for name in ("ids", "adj_rowptr", "adj_col"):
+            assert torch.equal(getattr(base, name), getattr(other, name)), (tiles, name)
+        assert np.array_equal(base.ids_offsets, other.ids_offsets)
+        assert np.array_equal(base.hop_sizes, other.hop_sizes)
+        check_sample(other, c.samp, c.cfg.S, len(c.cfg.fanout))
+
+
+def test_changeset_is_independent_of_the_eviction_path_and_repeatable(ginex, case2, monkeypatch):
+    """The two ways of finding evictions among dead rows use different grids and atomics; both,
+    and a second run of each, give byte-identical lists, lines and final states."""
+    c = case2
+    n = c.cfg.num_nodes
+    ids_d = dev(c.samp["ids"])
+    io = c.samp["ids_offsets"]
+    # a carried cache with room for every row of the superbatch: the short launch sequence
+    big = len(np.unique(c.samp["ids"])) + 1000
+    start = dev(np.arange(big, dtype=np.int32)[::-1].copy())
+    results = []
+    for scatter, live in (("0", "0"), ("1", "0"), ("0", "1"), ("1", "1")):
+        monkeypatch.setenv("GINEX_DEAD_SCATTER", scatter)
+        monkeypatch.setenv("GINEX_LIVE_SELECT", live)   # keeps the live-select launches in the loop
+        a = ginex.changeset(n, ids_d, io, 20000)
+        b = ginex.changeset_resume(n, ids_d, io, start)
+        results.append((a, b))
+    first = results[0]
+    for a, b in results[1:]:
+        for x, y in ((a, first[0]), (b, first[1])):
+            for name in ("in_ids", "out_ids", "in_positions", "src_line"):
+                assert torch.equal(getattr(x, name), getattr(y, name)), name
+            assert np.array_equal(x.cs_offsets, y.cs_offsets)
+            assert np.array_equal(x.miss_count, y.miss_count)
+        assert torch.equal(b.final_ids, first[1].final_ids)
