@@ -45,6 +45,9 @@ struct Ctrl {        // decisions of the running iteration (device memory)
   int32_t use_dead;  // the select runs on the standing bitmap of dead residents
   int32_t pad;
 };
+// State::fault (device, one word): set when a launch sequence that leaves the live select out
+// meets an iteration that needs it (cannot happen when every row of the superbatch fits the
+// cache beside the rows it already holds; checked by the host after the loop).
 
 struct State {
   int32_t* res_id;      // [cap] node held by each cache line
@@ -57,6 +60,7 @@ struct State {
   uint32_t* dead_bits;  // [words] residents that are never accessed again, kept up to date
   uint32_t* dead_part;  // [parts] its set bits per part, kept up to date
   Ctrl* ctrl;
+  int32_t* fault;
   uint64_t* evict_words;  // bit l%64 of word l/64: line l is evicted in this iteration
   uint32_t* evict_tiles;  // evictions per tile of EVICT_TILE lines
   uint32_t* in_tiles;     // insertions per tile of positions in ids_i
@@ -69,6 +73,7 @@ struct State {
   int32_t lru;            // 0: Belady keys (next accessed iteration), 1: LRU keys
   int32_t dead_scatter;   // evictions among the dead residents are found from the id bitmap
                           // (large caches) instead of by a pass over all cache lines
+  int32_t dead_only;      // every eviction falls among the dead residents: no live select
 };
 
 // Iteration that holds flat position p: the largest i with off[i] <= p.  `off` is the
@@ -316,15 +321,18 @@ __global__ __launch_bounds__(TB) void k_copy_init(const uint64_t* __restrict__ h
 //                it also finds the id threshold T, from part counts of the standing dead-row
 //                bitmap that are kept up to date wherever a bit changes
 //   k_mark       otherwise: the members of the selected class of bucket j* set their bit in a
-//                scratch bitmap over node ids and count themselves per part; or, dead
-//                residents of a large cache: the bits above T are turned into line flags
+//                scratch bitmap over node ids and count themselves per part
 //   k_find       one block: T = the keep-th set bit, from the part counts
-//   k_flags      eviction flags per cache line and insertion counts per tile of accesses;
-//                the scratch bitmap is cleared by the members that set it
+//   k_flags      eviction flags per cache line (dead residents of a large cache: the bits above
+//                T of their bitmap are turned into line flags through the address table
+//                instead) and insertion counts per tile of accesses; the scratch bitmap is
+//                cleared by the members that set it
 //   k_emit       both lists in their order (every block sums the tile counts in front of it:
 //                no scan launch), and the cache state of C_{i+1}: the t-th insertion takes
 //                the line of the t-th eviction, the two sides meeting in one 64-bit word per
 //                t that the second to arrive completes
+// A carried cache that has room for every row of the superbatch never needs k_mark and k_find
+// (all evictions fall among the dead rows): its iterations are four launches.
 // No phase makes a pass over a whole bitmap or scans all tiles in one block: the cost of an
 // iteration follows its accesses and, unless the dead-row path applies, the cache lines.
 // Measured and dropped earlier: a single cooperative kernel with grid.sync() between the
@@ -605,6 +613,9 @@ __global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i, int32_t 
                                                    int64_t evict_tiles) {
   p_threshold<BIG>(st, i, lo_bin, o.miss_count, o.cs_offsets);
   const Ctrl c = *st.ctrl;   // written by this block, in front of the barrier that ends p_threshold
+  if (st.dead_only && !c.use_dead && threadIdx.x == 0 &&
+      (c.mode_res == MODE_SELECT || c.mode_in == MODE_SELECT))
+    *st.fault = 1;
   if (c.use_dead) {
     p_bits_find<BIG>(st, st.dead_bits, st.dead_part, true);
     if (st.dead_scatter)     // the scatter counts evictions per tile with atomics
@@ -674,12 +685,11 @@ __device__ void p_dead_scatter(const State& st, const Ctrl& c, int64_t vb, int64
 }
 
 // blocks [0, res_blocks): residents, the next in_blocks blocks: incoming rows; only one
-// class is selected.  The dead-row scatter uses the whole grid.
+// class is selected, and none when the select runs on the dead rows.
 __global__ __launch_bounds__(TB) void k_mark(State st, Iter it, int64_t res_blocks) {
   const Ctrl c = *st.ctrl;
-  if (c.use_dead) {
-    if (st.dead_scatter && c.n_change > 0) p_dead_scatter(st, c, blockIdx.x, gridDim.x);
-  } else if ((int64_t)blockIdx.x < res_blocks) {
+  if (c.use_dead) return;
+  if ((int64_t)blockIdx.x < res_blocks) {
     if (c.mode_res == MODE_SELECT) p_mark_residents(st, c, blockIdx.x);
   } else if (c.mode_in == MODE_SELECT) {
     p_mark_incoming(st, c, it, blockIdx.x - res_blocks);
@@ -761,16 +771,21 @@ __device__ void p_in_count(const State& st, const Ctrl& c, const Iter& it, int64
   if (threadIdx.x == 0) st.in_tiles[vb] = total;
 }
 
-// blocks [0, evict_tiles): eviction flags and counts per tile (not when the dead-row scatter
-// has produced them); the next in_tiles blocks: insertions per tile; one more block takes the
-// part counts of the scratch bitmap back to zero.
+// blocks [0, evict_tiles): eviction flags and counts per tile, by a pass over the tile's lines
+// or, dead rows of a large cache, by the scatter from the bitmap (the blocks then stride over
+// the stretch above T); the next in_tiles blocks: insertions per tile; one more block takes
+// the part counts of the scratch bitmap back to zero.
 __global__ __launch_bounds__(TB) void k_flags(State st, Iter it, int64_t evict_tiles,
                                               int64_t in_tiles) {
   const Ctrl c = *st.ctrl;
   const int64_t vb = blockIdx.x;
   const bool selected = !c.use_dead && (c.mode_res == MODE_SELECT || c.mode_in == MODE_SELECT);
   if (vb < evict_tiles) {
-    if ((c.n_change > 0 || selected) && !(st.dead_scatter && c.use_dead)) p_evict_flags(st, c, vb);
+    if (st.dead_scatter && c.use_dead) {
+      if (c.n_change > 0) p_dead_scatter(st, c, vb, evict_tiles);
+    } else if (c.n_change > 0 || selected) {
+      p_evict_flags(st, c, vb);
+    }
   } else if (vb < evict_tiles + in_tiles) {
     if (c.n_change > 0 || selected) p_in_count(st, c, it, vb - evict_tiles);
   } else if (selected) {
@@ -1012,6 +1027,7 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   st.sel_part = a.take<uint32_t>(st.parts);
   st.dead_part = a.take<uint32_t>(st.parts);
   st.ctrl = a.take<Ctrl>(1);
+  st.fault = a.take<int32_t>(1);
   w.evict_tiles = ceil_div(c, (int64_t)EVICT_TILE);
   st.evict_words = a.take<uint64_t>(w.evict_tiles * WAVE);
   w.in_tiles = ceil_div(max_n > 0 ? max_n : 1, (int64_t)TB * IN_ITEMS);
@@ -1098,6 +1114,7 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   // GINEX_DEAD_SCATTER=0/1 overrides the choice (both ways give the same lists).
   const char* scatter_env = getenv("GINEX_DEAD_SCATTER");
   state.dead_scatter = !lru && (scatter_env ? scatter_env[0] == '1' : cap >= (int64_t(1) << 20));
+  state.dead_only = 0;
 
   GINEX_HIP(hipMemcpyAsync(w.d_offsets, ids_offsets, sizeof(int64_t) * (S + 1),
                            hipMemcpyHostToDevice, st));
@@ -1201,6 +1218,13 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                        total, w.d_offsets, S, w.next_iter);
     GINEX_LAUNCH_CHECK();
   }
+  // A carried cache with room for every row of the superbatch never evicts a row that is
+  // still needed: each iteration keeps all live candidates, so the threshold bucket is
+  // "never" and the select runs on the dead rows.  The two launches of the live select are
+  // then left out of the loop.  GINEX_LIVE_SELECT=1 keeps them in (same result).
+  const char* live_env = getenv("GINEX_LIVE_SELECT");
+  state.dead_only = start_ids && distinct <= cap && !(live_env && live_env[0] == '1');
+  GINEX_HIP(fill_async<int32_t>(state.fault, 1, 0, st));
   GINEX_HIP(fill_async<int32_t>(state.addr, num_nodes, -1, st));
   GINEX_HIP(fill_async<uint32_t>(state.rhist, S + 2, 0u, st));
   GINEX_HIP(fill_async<uint32_t>(state.ihist, S + 2, 0u, st));
@@ -1265,10 +1289,12 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       GINEX_LAUNCH_CHECK();
       if (it.n == 0) continue;  // nothing missed, nothing changes
       const int64_t in_tiles = ceil_div(it.n, (int64_t)TB * IN_ITEMS);
-      hipLaunchKernelGGL(k_mark, dim3((unsigned)(res_blocks + ceil_div(it.n, TB * MARK_ITEMS))),
-                         dim3(TB), 0, st, state, it, res_blocks);
-      hipLaunchKernelGGL(k_find, dim3(1), dim3(BIG), 0, st, state);
-      GINEX_LAUNCH_CHECK();
+      if (!state.dead_only) {
+        hipLaunchKernelGGL(k_mark, dim3((unsigned)(res_blocks + ceil_div(it.n, TB * MARK_ITEMS))),
+                           dim3(TB), 0, st, state, it, res_blocks);
+        hipLaunchKernelGGL(k_find, dim3(1), dim3(BIG), 0, st, state);
+        GINEX_LAUNCH_CHECK();
+      }
       hipLaunchKernelGGL(k_flags, dim3((unsigned)(w.evict_tiles + in_tiles + 1)), dim3(TB), 0, st,
                          state, it, w.evict_tiles, in_tiles);
       hipLaunchKernelGGL(k_emit, dim3((unsigned)(evict_blocks + in_tiles)), dim3(TB), 0, st, state,
@@ -1281,7 +1307,13 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                              hipMemcpyDeviceToDevice, st));
   GINEX_HIP(hipMemcpyAsync(total_changes, cs_offsets + S, sizeof(int64_t), hipMemcpyDeviceToHost,
                            st));
+  int32_t fault = 0;
+  GINEX_HIP(hipMemcpyAsync(&fault, state.fault, sizeof(fault), hipMemcpyDeviceToHost, st));
   GINEX_HIP(hipStreamSynchronize(st));
+  if (fault)
+    return fail(GINEX_ERR_INPUT, "%s: an iteration needed a select among live rows although all "
+                "%lld rows of the superbatch fit the cache of %lld lines: ids repeated inside an "
+                "iteration?", who, (long long)distinct, (long long)cap);
   if (*total_changes > cs_capacity)
     return fail(GINEX_ERR_CAPACITY, "%s: %lld changeset records, capacity %lld", who,
                 (long long)*total_changes, (long long)cs_capacity);
