@@ -632,9 +632,11 @@ __global__ __launch_bounds__(BIG) void k_find(State st) {
 constexpr int MARK_ITEMS = 8;   // lines / accesses per thread in the mark phases
 constexpr int EVICT_TILE = WAVE * WAVE;   // cache lines per tile: 64 flag words of 64 lines
 
+// The members of a class are distinct ids and the bitmap is all zero before the marking, so
+// every call sets a new bit: neither atomic needs its result.
 __device__ __forceinline__ void select_bit_set(const State& st, uint32_t v) {
-  const uint32_t bit = 1u << (v & 31);
-  if (!(atomicOr(&st.bitmap[v >> 5], bit) & bit)) atomicAdd(&st.sel_part[v >> PART_SHIFT], 1u);
+  atomicOr(&st.bitmap[v >> 5], 1u << (v & 31));
+  atomicAdd(&st.sel_part[v >> PART_SHIFT], 1u);
 }
 
 // Set the bit of every member of the selected class in bucket j*.
