@@ -33,6 +33,8 @@
 // The seeds go through the same count/scan/emit path as a stage with one candidate per
 // slot, which also removes repeated seeds.
 #include <cstdlib>
+#include <cstring>
+#include <vector>
 
 #include "common.hpp"
 
@@ -866,16 +868,23 @@ extern "C" int32_t ginex_sample_superbatch(
                        st, T, M, nlist, ids, ids_capacity);
     GINEX_LAUNCH_CHECK();
   }
-  GINEX_HIP(hipMemcpyAsync(ids_offsets, M.ids_offsets, sizeof(int64_t) * (S + 1),
-                           hipMemcpyDeviceToHost, st));
-  GINEX_HIP(hipMemcpyAsync(hop_sizes, M.hop_sizes, sizeof(int64_t) * S * (H + 1),
-                           hipMemcpyDeviceToHost, st));
-  GINEX_HIP(hipMemcpyAsync(adj_row_offsets, M.row_off, sizeof(int64_t) * ((int64_t)S * H + 1),
-                           hipMemcpyDeviceToHost, st));
-  GINEX_HIP(hipMemcpyAsync(adj_col_offsets, M.col_off, sizeof(int64_t) * ((int64_t)S * H + 1),
-                           hipMemcpyDeviceToHost, st));
-  GINEX_HIP(hipMemcpyAsync(totals, M.totals, sizeof(int64_t) * 3, hipMemcpyDeviceToHost, st));
-  GINEX_HIP(hipStreamSynchronize(st));
+  // the small host outputs sit back to back in the workspace: one copy brings them all over
+  {
+    std::vector<int64_t> host(meta_elems(S, H));
+    GINEX_HIP(hipMemcpyAsync(host.data(), w.meta, sizeof(int64_t) * host.size(),
+                             hipMemcpyDeviceToHost, st));
+    GINEX_HIP(hipStreamSynchronize(st));
+    const int64_t* at = host.data();
+    memcpy(ids_offsets, at, sizeof(int64_t) * (S + 1));
+    at += S + 1;
+    memcpy(hop_sizes, at, sizeof(int64_t) * S * (H + 1));
+    at += (int64_t)S * (H + 1);
+    memcpy(adj_row_offsets, at, sizeof(int64_t) * ((int64_t)S * H + 1));
+    at += (int64_t)S * H + 1;
+    memcpy(adj_col_offsets, at, sizeof(int64_t) * ((int64_t)S * H + 1));
+    at += (int64_t)S * H + 1;
+    memcpy(totals, at, sizeof(int64_t) * 3);
+  }
   if (totals[0] > ids_capacity)
     return fail(GINEX_ERR_CAPACITY, "%s: ids needs %lld entries, capacity %lld", who,
                 (long long)totals[0], (long long)ids_capacity);
