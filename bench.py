@@ -338,7 +338,7 @@ def allmiss_leg(ginex, w, run, samp, launches=16):
         a, b = event(), event()
         n = int(io[i + 1] - io[i])
         a.record()
-        cache.gather(samp.ids[io[i]:io[i + 1]], run.batch_input[:n], src_line=lines[:n])
+        cache.gather(samp.ids[io[i]:io[i + 1]], run.batch_input[:n], src_line=lines[:n], n_slow=n)
         b.record()
         if i:                       # the first launch warms up
             ms.append((a, b))

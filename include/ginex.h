@@ -284,9 +284,12 @@ int32_t ginex_gather(const ginex_cache_t* c /*host struct*/, const int32_t* ids,
  * and ids sequentially and never probes the address table; the update is the one of
  * ginex_gather and keeps the address table current, so the two calls may be mixed.  The
  * gathered bytes equal those of ginex_gather provided src_line describes the cache as it
- * stands (checked by the caller's bookkeeping, not by the kernel). */
+ * stands (checked by the caller's bookkeeping, not by the kernel).
+ * n_slow: how many entries of src_line are -1 (miss_count[i] of the changeset call), or -1 if
+ * not known.  Only a hint for the launch shape: an iteration with many slow-tier rows is bound
+ * by the host link, which a smaller grid uses better; the result does not depend on it. */
 int32_t ginex_gather_lines(const ginex_cache_t* c /*host struct*/, const int32_t* ids,
-                           const int32_t* src_line, int64_t n, void* out,
+                           const int32_t* src_line, int64_t n, int64_t n_slow, void* out,
                            const int32_t* in_ids, const int32_t* out_ids,
                            const int32_t* in_positions, int64_t n_change, void* stream);
 

@@ -41,7 +41,7 @@ SIGNATURES = {
     "ginex_cache_init_part": (i32, [C.POINTER(CacheDesc), vp, i64, i64, vp]),
     "ginex_cache_init_warm": (i32, [C.POINTER(CacheDesc), C.POINTER(CacheDesc), vp, i64, i64, vp]),
     "ginex_gather": (i32, [C.POINTER(CacheDesc), vp, i64, vp, vp, vp, vp, i64, vp]),
-    "ginex_gather_lines": (i32, [C.POINTER(CacheDesc), vp, vp, i64, vp, vp, vp, vp, i64, vp]),
+    "ginex_gather_lines": (i32, [C.POINTER(CacheDesc), vp, vp, i64, i64, vp, vp, vp, vp, i64, vp]),
     "ginex_cache_update": (i32, [C.POINTER(CacheDesc), vp, vp, vp, vp, i64, vp]),
     "ginex_static_select_workspace_bytes": (sz, [i64]),
     "ginex_static_select": (i32, [C.POINTER(CsrDesc), i64, vp, vp, vp, sz, vp]),

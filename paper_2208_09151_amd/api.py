@@ -340,10 +340,12 @@ class FeatureCache:
         if rc:
             _check(rc)
 
-    def gather(self, ids, out=None, in_ids=None, out_ids=None, in_positions=None, src_line=None):
+    def gather(self, ids, out=None, in_ids=None, out_ids=None, in_positions=None, src_line=None,
+               n_slow=-1):
         """One executor iteration: gather the rows of ``ids`` then apply the changeset.  With
         ``src_line`` (the slice of ``ChangesetResult.src_line`` for this iteration) the gather
-        is ginex_gather_lines and does not probe the address table."""
+        is ginex_gather_lines and does not probe the address table; ``n_slow`` (the iteration's
+        miss count, if known) lets it pick a launch shape that suits the host link."""
         _dev(ids, torch.int32)
         n = ids.numel()
         if out is None:
@@ -356,8 +358,8 @@ class FeatureCache:
             _dev(src_line, torch.int32)
             if src_line.numel() != n:
                 raise ValueError("src_line must have one entry per id")
-            _check(self._gather_lines(C.byref(self._desc), _ptr(ids), _ptr(src_line), n, _ptr(out),
-                                      *lists))
+            _check(self._gather_lines(C.byref(self._desc), _ptr(ids), _ptr(src_line), n, int(n_slow),
+                                      _ptr(out), *lists))
         else:
             _check(self._gather(C.byref(self._desc), _ptr(ids), n, _ptr(out), *lists))
         return out
@@ -368,10 +370,11 @@ class FeatureCache:
         if rc:
             _check(rc)
 
-    def gather_lines_raw(self, ids_ptr: int, lines_ptr: int, n: int, out_ptr: int, stream_ptr: int):
+    def gather_lines_raw(self, ids_ptr: int, lines_ptr: int, n: int, n_slow: int, out_ptr: int,
+                         stream_ptr: int):
         """ginex_gather_lines with an empty changeset, on raw device addresses."""
-        rc = self._gather_lines(self._desc_ref, ids_ptr, lines_ptr, n, out_ptr, None, None, None, 0,
-                                stream_ptr)
+        rc = self._gather_lines(self._desc_ref, ids_ptr, lines_ptr, n, n_slow, out_ptr, None, None,
+                                None, 0, stream_ptr)
         if rc:
             _check(rc)
 

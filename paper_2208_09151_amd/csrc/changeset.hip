@@ -327,7 +327,7 @@ __global__ __launch_bounds__(TB) void k_copy_init(const uint64_t* __restrict__ h
 //                T of their bitmap are turned into line flags through the address table
 //                instead) and insertion counts per tile of accesses; the scratch bitmap is
 //                cleared by the members that set it
-//   k_emit       both lists in their order (every block sums the tile counts in front of it:
+//   k_emit_pair  both lists in their order (every block sums the tile counts in front of it:
 //                no scan launch), and the cache state of C_{i+1}: the t-th insertion takes
 //                the line of the t-th eviction, the two sides meeting in one 64-bit word per
 //                t that the second to arrive completes
@@ -951,7 +951,7 @@ __device__ void p_in_emit(const State& st, const Ctrl& c, const Iter& it, const 
   }
 }
 
-__global__ __launch_bounds__(TB) void k_emit(State st, Iter it, Outputs o, int64_t evict_tiles) {
+__global__ __launch_bounds__(TB) void k_emit_pair(State st, Iter it, Outputs o, int64_t evict_tiles) {
   const Ctrl c = *st.ctrl;
   if (c.n_change <= 0) return;
   const int64_t evict_blocks = (evict_tiles + TB / WAVE - 1) / (TB / WAVE);
@@ -1299,7 +1299,7 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       }
       hipLaunchKernelGGL(k_flags, dim3((unsigned)(w.evict_tiles + in_tiles + 1)), dim3(TB), 0, st,
                          state, it, w.evict_tiles, in_tiles);
-      hipLaunchKernelGGL(k_emit, dim3((unsigned)(evict_blocks + in_tiles)), dim3(TB), 0, st, state,
+      hipLaunchKernelGGL(k_emit_pair, dim3((unsigned)(evict_blocks + in_tiles)), dim3(TB), 0, st, state,
                          it, outs, w.evict_tiles);
       GINEX_LAUNCH_CHECK();
     }

@@ -349,11 +349,17 @@ extern "C" int32_t ginex_cache_update(const ginex_cache_t* c, const void* out,
 namespace ginex {
 namespace {
 
-// lines == nullptr: the gather probes the address table itself
+// Chunks a gather keeps in flight over the host link when many of its rows come from the slow
+// tier: what the cache fill found best (64 blocks of 256 threads with UNROLL chunks each;
+// more requests in flight lower the link's throughput, see launch_fill).
+constexpr int64_t LINK_CHUNKS_IN_FLIGHT = 64 * THREADS * UNROLL;
+
+// lines == nullptr: the gather probes the address table itself.  n_slow: rows known to come
+// from the slow tier, or -1.
 int32_t gather_run(const char* who, const ginex_cache_t* c, const int32_t* ids,
-                   const int32_t* lines, int64_t n, void* out, const int32_t* in_ids,
-                   const int32_t* out_ids, const int32_t* in_positions, int64_t n_change,
-                   void* stream) {
+                   const int32_t* lines, int64_t n, int64_t n_slow, void* out,
+                   const int32_t* in_ids, const int32_t* out_ids, const int32_t* in_positions,
+                   int64_t n_change, void* stream) {
   if (int32_t rc = check_cache(c, who)) return rc;
   if (n < 0 || n_change > n)
     return fail(GINEX_ERR_ARG, "%s: n=%lld n_change=%lld inconsistent", who, (long long)n,
@@ -366,6 +372,15 @@ int32_t gather_run(const char* who, const ginex_cache_t* c, const int32_t* ids,
     // one pass of the kernel's loop up to 2^24 blocks (8 TB of rows), more passes beyond
     int64_t blocks = ceil_div(n * cpr, (int64_t)GATHER_THREADS * UNROLL);
     if (blocks > (1 << 24)) blocks = 1 << 24;
+    // A launch that reads at least three quarters of its rows from the slow tier runs on a
+    // smaller grid whose blocks stride over the rows, so that about as many link reads are in
+    // flight as the cache fill keeps (51.8 -> 56.2 GB/s with nothing resident).  With fewer
+    // slow rows the smaller grid starves the resident ones of HBM parallelism (at 42 % slow
+    // rows the launch took 3 % longer), so those keep the full grid.
+    if (n_slow > 0 && n_slow * 4 >= n * 3) {
+      const int64_t want = ceil_div(LINK_CHUNKS_IN_FLIGHT * n, n_slow * (int64_t)GATHER_THREADS * UNROLL);
+      if (want < blocks) blocks = want;
+    }
     const dim3 grid((unsigned)blocks);
 #define GINEX_GATHER(S)                                                                       \
   do {                                                                                        \
@@ -402,16 +417,18 @@ int32_t gather_run(const char* who, const ginex_cache_t* c, const int32_t* ids,
 extern "C" int32_t ginex_gather(const ginex_cache_t* c, const int32_t* ids, int64_t n, void* out,
                                 const int32_t* in_ids, const int32_t* out_ids,
                                 const int32_t* in_positions, int64_t n_change, void* stream) {
-  return gather_run("ginex_gather", c, ids, nullptr, n, out, in_ids, out_ids, in_positions,
+  return gather_run("ginex_gather", c, ids, nullptr, n, -1, out, in_ids, out_ids, in_positions,
                     n_change, stream);
 }
 
 extern "C" int32_t ginex_gather_lines(const ginex_cache_t* c, const int32_t* ids,
-                                      const int32_t* src_line, int64_t n, void* out,
-                                      const int32_t* in_ids, const int32_t* out_ids,
+                                      const int32_t* src_line, int64_t n, int64_t n_slow,
+                                      void* out, const int32_t* in_ids, const int32_t* out_ids,
                                       const int32_t* in_positions, int64_t n_change,
                                       void* stream) {
   if (n > 0 && !src_line) return fail(GINEX_ERR_ARG, "ginex_gather_lines: src_line is null");
-  return gather_run("ginex_gather_lines", c, ids, src_line, n, out, in_ids, out_ids, in_positions,
-                    n_change, stream);
+  if (n_slow > n) return fail(GINEX_ERR_ARG, "ginex_gather_lines: n_slow=%lld exceeds n=%lld",
+                              (long long)n_slow, (long long)n);
+  return gather_run("ginex_gather_lines", c, ids, src_line, n, n_slow, out, in_ids, out_ids,
+                    in_positions, n_change, stream);
 }

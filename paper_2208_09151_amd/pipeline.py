@@ -89,6 +89,7 @@ class Executor:
         bases = (cs.in_ids.data_ptr(), cs.out_ids.data_ptr(), cs.in_positions.data_ptr())
         init_ptr = cs.init_ids.data_ptr()
         lines_base = cs.src_line.data_ptr() if use_lines and cs.src_line is not None else 0
+        slow = cs.miss_count.tolist() if lines_base else None
         wait_for = None
         if resumed:
             self._event(0).record(main)
@@ -129,7 +130,8 @@ class Executor:
             if before_gather is not None:
                 before_gather(i)
             if lines_base:
-                cache.gather_lines_raw(ids_base + 4 * io[i], lines_base + 4 * io[i], n, out_ptr, mp)
+                cache.gather_lines_raw(ids_base + 4 * io[i], lines_base + 4 * io[i], n, slow[i],
+                                       out_ptr, mp)
             else:
                 cache.gather_raw(ids_base + 4 * io[i], n, out_ptr, mp)
             if after_gather is not None:
@@ -243,7 +245,10 @@ class InspectorPipeline:
         ``execute(k, samp, cs)`` (on the calling thread), each stage on its own host thread
         and streams, with three sets of sampler outputs.  Worth it when no stage dominates
         (a cache carried over: sampling, the changeset loop and the executor are of the same
-        order).  Returns the wall time in seconds."""
+        order).  ``execute`` must have finished its GPU work when it returns (synchronize the
+        stream it used): right after it returns the sampler may overwrite the ids and adj
+        buffers of that superbatch, and the changeset tensors, which were allocated on the
+        inspector's stream, may be freed and reused.  Returns the wall time in seconds."""
         import queue
         while len(self.bufs) < 3:
             self.bufs.append(tuple(torch.empty_like(t) for t in self.bufs[0]))

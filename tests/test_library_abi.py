@@ -125,11 +125,14 @@ def test_precondition_and_workspace_errors_are_reported_before_any_launch():
                                           16, None) == -3
     assert lib.ginex_neighbor_cache_workspace_bytes(0) == 0
     assert lib.ginex_cache_update(ctypes.byref(c), fake, fake, fake, fake, 9, None) == -1
-    assert lib.ginex_gather_lines(ctypes.byref(c), fake, None, 2, fake, None, None, None, 0,
+    assert lib.ginex_gather_lines(ctypes.byref(c), fake, None, 2, -1, fake, None, None, None, 0,
                                   None) == -1
     assert b"src_line" in lib.ginex_last_error()
-    assert lib.ginex_gather_lines(ctypes.byref(c), fake, fake, 2, fake, fake, fake, fake, 3,
+    assert lib.ginex_gather_lines(ctypes.byref(c), fake, fake, 2, -1, fake, fake, fake, fake, 3,
                                   None) == -1
+    assert lib.ginex_gather_lines(ctypes.byref(c), fake, fake, 2, 3, fake, None, None, None, 0,
+                                  None) == -1
+    assert b"n_slow" in lib.ginex_last_error()
     # the allocation-free changeset checks its shape against the built-in scratch on the host
     big = np.array([0, 1 << 22, 1 << 23], dtype=np.int64)
     assert lib.ginex_changeset_noalloc(1 << 24, fake, P(big), 2, 1000, fake, P(ic), fake, fake, fake,
