@@ -438,8 +438,12 @@ __global__ __launch_bounds__(TB) void k_stage_offsets(
   }
 }
 
-// Appends first occurrences to the lists, fixes their table values, writes rowptr and the
-// adj_col entries of the first occurrences.
+// Appends first occurrences to the lists, writes rowptr and the adj_col entries of the first
+// occurrences.  Two phases per tile of TB frontier slots: one thread per slot scans the
+// counts (picks and first occurrences in front of each slot) into LDS, then one thread per
+// CANDIDATE does the writes, so that `cand`, the list and adj_col are accessed with
+// consecutive lanes on consecutive addresses (a thread per slot walking its fanout picks
+// touches a different cache line in every lane).
 __global__ __launch_bounds__(TB) void k_emit(Tables T, const int32_t* __restrict__ nfront,
                                              const int32_t* __restrict__ nlist, int k,
                                              const uint64_t* __restrict__ tile_sums, int64_t tiles,
@@ -449,10 +453,14 @@ __global__ __launch_bounds__(TB) void k_emit(Tables T, const int32_t* __restrict
                                              const int64_t* __restrict__ col_base, int S,
                                              int64_t tpb) {
   __shared__ uint64_t smem[TB / WAVE + 1];
+  __shared__ uint64_t s_first[TB];
+  __shared__ uint32_t s_edges[TB], s_firsts[TB];
+  __shared__ uint8_t s_cnt[TB];
   const Where here = where_am_i(S, tpb);
   if (here.b < 0) return;
   const int b = here.b;
   const int nf = nfront[b];
+  const uint32_t list_len = (uint32_t)nlist[b];
   // tile 0 always runs: an empty frontier still has a rowptr entry
   for (int64_t tile = here.tile; tile * TB < nf || tile == 0; tile += tpb) {
     const int64_t idx = tile * TB + threadIdx.x;
@@ -472,28 +480,40 @@ __global__ __launch_bounds__(TB) void k_emit(Tables T, const int32_t* __restrict
         if (rb + last < rowptr_capacity) rowptr[rb + last] = edges_before + c;
       }
     }
-    if (first) {
-      uint32_t at_list = (uint32_t)nlist[b] + (uint32_t)(ex & 0xFFFFFFFFu);
+    s_first[threadIdx.x] = first;
+    s_cnt[threadIdx.x] = (uint8_t)c;
+    s_edges[threadIdx.x] = (uint32_t)edges_before;
+    s_firsts[threadIdx.x] = (uint32_t)(ex & 0xFFFFFFFFu);
+    __syncthreads();
+    if ((uint32_t)(total & 0xFFFFFFFFu)) {      // the tile has first occurrences (uniform)
       // A first occurrence's slot in `cand` is overwritten with its list position: the table
       // keeps PEND + its rank, so later duplicates find the position through the rank without
       // a scattered write into the table here (the next stage rebuilds the tables anyway).
-      const int64_t at = b * T.cand_slots + idx * k;
-      const int64_t dst = col ? col_base[b] + edges_before : 0;
-      for (int s = 0; s < c; ++s)
-        if (first >> s & 1) {
-          T.wlist[b * T.stride_ids + at_list] = T.cand[at + s];
-          T.cand[at + s] = (int32_t)at_list;
-          if (col && dst + s < col_capacity) col[dst + s] = (int32_t)at_list;
-          ++at_list;
+      const int64_t slots_here = nf - tile * TB < TB ? nf - tile * TB : TB;
+      const uint32_t ncand = (uint32_t)(slots_here * k);
+      int32_t* cand = T.cand + b * T.cand_slots + tile * TB * k;
+      int32_t* list = T.wlist + b * T.stride_ids;
+      const int64_t cb = col ? col_base[b] : 0;
+      for (uint32_t r = threadIdx.x; r < ncand; r += TB) {
+        const uint32_t sl = r / (uint32_t)k, pick = r - sl * (uint32_t)k;
+        const uint64_t f = s_first[sl];
+        if (pick < s_cnt[sl] && (f >> pick & 1)) {
+          const uint32_t pos = list_len + s_firsts[sl] + (uint32_t)__popcll(f & ((1ull << pick) - 1));
+          list[pos] = cand[r];
+          cand[r] = (int32_t)pos;
+          const int64_t d = cb + s_edges[sl] + pick;
+          if (col && d < col_capacity) col[d] = (int32_t)pos;
         }
+      }
     }
+    __syncthreads();   // the LDS arrays are rewritten for the next tile
   }
 }
 
-// adj_col of the picks that are not first occurrences.  An id of an earlier stage carries
-// its list position in its reference; an id that is new in this stage is looked up through
-// its slot, whose final value is PEND + the rank of the id's first occurrence, whose entry in
-// `cand` now holds the position.
+// adj_col of the picks that are not first occurrences, one thread per candidate (see k_emit).
+// An id of an earlier stage carries its list position in its reference; an id that is new in
+// this stage is looked up through its slot, whose final value is PEND + the rank of the id's
+// first occurrence, whose entry in `cand` now holds the position.
 __global__ __launch_bounds__(TB) void k_col(Tables T, const int32_t* __restrict__ nfront, int k,
                                             const int64_t* __restrict__ rowptr,
                                             int64_t rowptr_capacity,
@@ -501,23 +521,50 @@ __global__ __launch_bounds__(TB) void k_col(Tables T, const int32_t* __restrict_
                                             int32_t* __restrict__ col, int64_t col_capacity,
                                             const int64_t* __restrict__ col_base, int S,
                                             int64_t tpb) {
+  __shared__ uint64_t s_first[TB];
+  __shared__ int64_t s_dst[TB];
+  __shared__ uint8_t s_cnt[TB];
+  __shared__ uint32_t s_any;
   const Where here = where_am_i(S, tpb);
   if (here.b < 0) return;
   const int b = here.b;
+  const int nf = nfront[b];
   const uint64_t* t = T.tab + T.tab_off[b];
-  for (int64_t idx = here.tile * TB + threadIdx.x; idx < nfront[b]; idx += tpb * TB) {
-    if (row_base[b] + idx >= rowptr_capacity) return;
-    const int c = T.cnt[b * T.fr_slots + idx];
-    const uint64_t first = T.first[b * T.fr_slots + idx];
-    if (__popcll(first) == c) continue;
-    const int64_t at = b * T.cand_slots + idx * k;
-    const int64_t dst = col_base[b] + rowptr[row_base[b] + idx];
-    for (int s = 0; s < c; ++s)
-      if (!(first >> s & 1) && dst + s < col_capacity) {
-        const uint32_t r = T.ref[at + s];
-        col[dst + s] = r & OLD_ID ? (int32_t)(r & ~OLD_ID)
-                                  : T.cand[b * T.cand_slots + ((uint32_t)t[r] - PEND)];
+  const int32_t* cand_b = T.cand + b * T.cand_slots;
+  for (int64_t tile = here.tile; tile * TB < nf; tile += tpb) {
+    const int64_t idx = tile * TB + threadIdx.x;
+    if (threadIdx.x == 0) s_any = 0;
+    __syncthreads();
+    uint64_t first = 0;
+    int c = 0;
+    int64_t dst = 0;
+    if (idx < nf && row_base[b] + idx < rowptr_capacity) {
+      c = T.cnt[b * T.fr_slots + idx];
+      first = T.first[b * T.fr_slots + idx];
+      dst = col_base[b] + rowptr[row_base[b] + idx];
+    }
+    s_first[threadIdx.x] = first;
+    s_cnt[threadIdx.x] = (uint8_t)c;
+    s_dst[threadIdx.x] = dst;
+    if (__popcll(first) != c) s_any = 1;
+    __syncthreads();
+    if (s_any) {                                  // uniform over the block
+      const int64_t slots_here = nf - tile * TB < TB ? nf - tile * TB : TB;
+      const uint32_t ncand = (uint32_t)(slots_here * k);
+      const uint32_t* ref = T.ref + b * T.cand_slots + tile * TB * k;
+      for (uint32_t r = threadIdx.x; r < ncand; r += TB) {
+        const uint32_t sl = r / (uint32_t)k, pick = r - sl * (uint32_t)k;
+        if (pick < s_cnt[sl] && !(s_first[sl] >> pick & 1)) {
+          const int64_t d = s_dst[sl] + pick;
+          if (d < col_capacity) {
+            const uint32_t where = ref[r];
+            col[d] = where & OLD_ID ? (int32_t)(where & ~OLD_ID)
+                                    : cand_b[(uint32_t)t[where] - PEND];
+          }
+        }
       }
+    }
+    __syncthreads();
   }
 }
 
