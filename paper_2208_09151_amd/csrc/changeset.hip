@@ -18,6 +18,7 @@
 //   order and paired.
 //   The same loop serves the LRU policy (other keys) and a superbatch that resumes from the
 //   cache state of the previous one (C_0 given instead of computed).
+#include <cstdio>
 #include <cstdlib>
 #include <mutex>
 
@@ -547,17 +548,16 @@ __device__ void p_threshold(const State& st, int32_t i, int32_t lo_bin, const in
   __syncthreads();
 }
 
-// One block of NT threads: T = the id whose bit is the keep-th set bit of `bits`, found
-// through `part` (set bits per PART_WORDS words).  With `trim`, the part counts are rewritten
-// to what remains once every bit above T is cleared (the dead rows above T are evicted).
+// One block of NT threads: the position of the keep-th set bit (1-based, from the bottom) of
+// `bits`, found through `part` (set bits per PART_WORDS words); -1 if there are fewer set bits.
+// Every thread gets the result.  With `trim`, the part counts are rewritten to what remains
+// once every bit above that position is cleared.
 template <int NT>
-__device__ void p_bits_find(const State& st, const uint32_t* __restrict__ bits,
-                            uint32_t* __restrict__ part, bool trim) {
-  Ctrl* c = st.ctrl;
+__device__ int32_t p_kth_set_bit(const uint32_t* __restrict__ bits, uint32_t* __restrict__ part,
+                                 int64_t parts, int64_t words, int64_t keep, bool trim) {
   __shared__ int64_t smem[NT / WAVE + 1];
   __shared__ int64_t s_part, s_before;
-  const int64_t keep = c->keep;
-  const int64_t parts = st.parts, words = st.words;
+  __shared__ int32_t s_found;
   // 1. the part that holds the keep-th set bit
   const int64_t per = (parts + NT - 1) / NT;
   const int64_t q0 = threadIdx.x * per;
@@ -565,7 +565,10 @@ __device__ void p_bits_find(const State& st, const uint32_t* __restrict__ bits,
   for (int64_t q = q0; q < q0 + per && q < parts; ++q) mine += part[q];
   int64_t total;
   int64_t before = block_exclusive_scan<int64_t, NT>(mine, smem, total);
-  if (threadIdx.x == 0) s_part = -1;
+  if (threadIdx.x == 0) {
+    s_part = -1;
+    s_found = -1;
+  }
   __syncthreads();
   for (int64_t q = q0; q < q0 + per && q < parts; ++q) {
     const int64_t cnt = part[q];
@@ -576,7 +579,7 @@ __device__ void p_bits_find(const State& st, const uint32_t* __restrict__ bits,
     before += cnt;
   }
   __syncthreads();
-  if (s_part < 0) return;  // fewer set bits than asked for: cannot happen, T stays -1
+  if (s_part < 0) return -1;  // fewer set bits than asked for (uniform over the block)
   if (trim) {
     for (int64_t q = q0; q < q0 + per && q < parts; ++q)
       if (q > s_part) part[q] = 0;
@@ -602,10 +605,21 @@ __device__ void p_bits_find(const State& st, const uint32_t* __restrict__ bits,
           if (--need == 0) break;
           word &= word - 1;
         }
-        c->T = (int32_t)((w0 + t) * 32 + bit);
+        s_found = (int32_t)((w0 + t) * 32 + bit);
       }
       bw += pc;
     }
+  __syncthreads();
+  return s_found;
+}
+
+// T of the running iteration = the id whose bit is the keep-th set bit of `bits`.
+template <int NT>
+__device__ void p_bits_find(const State& st, const uint32_t* __restrict__ bits,
+                            uint32_t* __restrict__ part, bool trim) {
+  Ctrl* c = st.ctrl;
+  const int32_t T = p_kth_set_bit<NT>(bits, part, st.parts, st.words, c->keep, trim);
+  if (threadIdx.x == 0 && T >= 0) c->T = T;   // fewer set bits than asked for cannot happen: T stays -1
   __syncthreads();
 }
 
@@ -972,6 +986,438 @@ __global__ __launch_bounds__(TB) void k_part_count(const uint32_t* __restrict__ 
   if (threadIdx.x == 0) part[blockIdx.x] = total;
 }
 
+// ---- part 3 without a loop over the state: a carried cache that holds the whole superbatch ----
+//
+// When the carried cache has a line for every distinct row of the superbatch, an iteration
+// never evicts a row that is still needed (the live candidates alone never exceed the
+// capacity), so:
+//   * hits and misses are known up front: an access misses iff it is the first access of a row
+//     the start state does not hold; it is inserted iff the row is accessed again later
+//     (otherwise it ranks behind every resident and bypasses the cache);
+//   * a row keeps one line for the whole superbatch, the start line or the one it is given;
+//   * iteration i evicts the n_i dead residents with the largest ids, n_i = its insertions,
+//     where a resident is dead once its last access has passed (or from the start).
+// The insertion lists are therefore a compaction over all accesses, and only the choice of
+// the evicted rows is sequential.  All of them lie at the upper end of the id space: with M
+// evictions in total, none has an id below lo_id, the M-th largest id among the rows that are
+// dead from the start (they alone would supply M victims, and later arrivals only raise the
+// thresholds).  The rows from lo_id up that are ever dead residents (the M rows dead from the
+// start, and the rows that die during the superbatch: a few thousand, however wide that id
+// range has become) are the candidates; they are numbered in id order, and one workgroup
+// replays the S iterations on a bitmap over these numbers in LDS: it sets the bits of the
+// rows that die in the iteration, takes the top n_i set bits out, orders these rows by cache
+// line and pairs them with the insertions.  A candidate that is itself inserted during this
+// call gets its line written into the candidates' line array by the thread that pairs it and
+// read back, iterations later and a workgroup barrier apart, by the thread that evicts it.
+// What the path cannot take (more than PLAN_CAND_MAX candidates, an iteration with more than
+// PLAN_SORT_MAX insertions, S above PLAN_S_MAX, fewer rows dead from the start than
+// insertions) goes through the loop above.
+constexpr int PLAN_CAND_WORDS = 8192;               // LDS bitmap of the replay ...
+constexpr int PLAN_CAND_MAX = PLAN_CAND_WORDS * 32; // ... over at most 262 144 candidates
+constexpr int PLAN_SORT_MAX = 2048;      // evictions of one iteration the replay can order
+constexpr int PLAN_S_MAX = 2048;         // iterations (LDS histograms of k_plan_heads)
+enum { PLAN_M = 0, PLAN_MAX_N = 1, PLAN_LO_ID = 2, PLAN_DEAD = 3, PLAN_TAIL = 4, PLAN_FAILED = 5,
+       PLAN_WHERE = 6, PLAN_SCALARS = 8 };
+
+struct Plan {
+  uint32_t* ins_bits;    // [ceil(total / 32)] bit p: access p (flat position) is an insertion
+  uint32_t* ins_tiles;   // insertions per tile of TB words, then their exclusive scan
+  uint32_t* ins_base;    // [ceil(total / 32)] insertions in front of each word (tiles that have any)
+  int32_t* ins_cand;     // [distinct rows] candidate number of each inserted row, -1 = not one
+  int64_t* scalars;      // [PLAN_SCALARS]
+  uint32_t* cand_tiles;  // candidates per tile of TB words of the id bitmap, then their scan
+  uint32_t* cand_base;   // [words] candidates in front of each word of the id bitmap (from lo_id's word on)
+  int32_t* cand_id;      // [PLAN_CAND_MAX] candidates in id order
+  int32_t* cand_line;    // [PLAN_CAND_MAX] their cache line, -1 while not resident
+  uint32_t* cand_dead;   // [PLAN_CAND_WORDS] bit c: candidate c is dead from the start
+  uint32_t* arr_off;     // [S + 2] candidates that die in iteration d: count at d + 1, then offsets
+  uint32_t* arr_cur;     // [S + 1] fill cursors
+  int32_t* arr_cand;     // [PLAN_CAND_MAX] their numbers, grouped by iteration
+  int64_t ins_words, ins_tile_count, cand_tile_count;
+};
+
+// Pass over the node-sorted accesses: the head of a run is the row's first access.  If the
+// start state does not hold the row, that access misses, and it is an insertion if the run
+// goes on.  Misses per iteration go to miss_count, insertions per iteration to
+// cs_offsets[i + 1] (scanned afterwards) and to the bitmap over positions.
+__global__ __launch_bounds__(TB) void k_plan_heads(const uint64_t* __restrict__ sorted, int64_t n,
+                                                   const int64_t* __restrict__ off, int32_t S,
+                                                   const int32_t* __restrict__ addr,
+                                                   uint32_t* __restrict__ ins_bits,
+                                                   unsigned long long* __restrict__ miss_count,
+                                                   unsigned long long* __restrict__ cs_offsets) {
+  extern __shared__ int32_t lds_plan[];   // offsets [S+1], misses [S], insertions [S]
+  int32_t* lds_off = lds_plan;
+  uint32_t* h_miss = reinterpret_cast<uint32_t*>(lds_plan + S + 1);
+  uint32_t* h_ins = h_miss + S;
+  for (int j = threadIdx.x; j < 2 * S; j += TB) h_miss[j] = 0;
+  load_offsets(lds_off, off, S);
+  const int64_t tiles = (n + LOOK_TILE - 1) / LOOK_TILE;
+  for (int64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const int64_t base = tile * LOOK_TILE;
+#pragma unroll
+    for (int i = 0; i < LOOK_ITEMS; ++i) {
+      const int64_t j = base + i * TB + threadIdx.x;
+      if (j >= n || !run_head(sorted, j)) continue;
+      const uint64_t cur = sorted[j];
+      const uint32_t v = (uint32_t)(cur >> 32);
+      if (addr[v] >= 0) continue;
+      const int32_t p = (int32_t)(cur & 0xFFFFFFFFu);
+      const int32_t it = iter_of(lds_off, S, p);
+      atomicAdd(&h_miss[it], 1u);
+      if (j + 1 < n && (uint32_t)(sorted[j + 1] >> 32) == v) {
+        atomicAdd(&h_ins[it], 1u);
+        atomicOr(&ins_bits[p >> 5], 1u << (p & 31));
+      }
+    }
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < S; j += TB) {
+    if (h_miss[j]) atomicAdd(&miss_count[j], (unsigned long long)h_miss[j]);
+    if (h_ins[j]) atomicAdd(&cs_offsets[j + 1], (unsigned long long)h_ins[j]);
+  }
+}
+
+// One block: cs_offsets from the insertion counts, their total M and maximum, the number of
+// rows that are dead from the start, lo_id (num_nodes when nothing is evicted, -1 when the
+// rows dead from the start are fewer than M) and the first sorted access of a row >= lo_id.
+__global__ __launch_bounds__(BIG) void k_plan_scan(State st, const uint64_t* __restrict__ sorted,
+                                                   int64_t n, int64_t* __restrict__ cs_offsets,
+                                                   int64_t* __restrict__ scalars) {
+  __shared__ int64_t smem[BIG / WAVE + 1];
+  const int32_t S = st.S;
+  const int32_t per = (S + BIG - 1) / BIG;
+  const int32_t j0 = threadIdx.x * per;
+  int64_t mine = 0, largest = 0;
+  for (int32_t j = j0; j < j0 + per && j < S; ++j) {
+    const int64_t c = cs_offsets[j + 1];
+    mine += c;
+    largest = c > largest ? c : largest;
+  }
+  int64_t M;
+  int64_t run = block_exclusive_scan<int64_t, BIG>(mine, smem, M);
+  for (int32_t j = j0; j < j0 + per && j < S; ++j) {
+    run += cs_offsets[j + 1];
+    cs_offsets[j + 1] = run;
+  }
+  // the largest count: waves first, then thread 0 over the waves
+#pragma unroll
+  for (int d = WAVE / 2; d > 0; d >>= 1) {
+    const int64_t o = __shfl_xor(largest, d, WAVE);
+    largest = o > largest ? o : largest;
+  }
+  if (lane_id() == 0) smem[threadIdx.x / WAVE] = largest;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int64_t m = 0;
+    for (int w = 0; w < BIG / WAVE; ++w) m = smem[w] > m ? smem[w] : m;
+    scalars[PLAN_MAX_N] = m;
+    scalars[PLAN_M] = M;
+    scalars[PLAN_FAILED] = 0;
+    scalars[PLAN_WHERE] = 0;
+  }
+  __syncthreads();
+  const int64_t pper = (st.parts + BIG - 1) / BIG;
+  int64_t dead_mine = 0;
+  for (int64_t q = threadIdx.x * pper; q < (threadIdx.x + 1) * pper && q < st.parts; ++q)
+    dead_mine += st.dead_part[q];
+  int64_t dead;
+  block_exclusive_scan<int64_t, BIG>(dead_mine, smem, dead);
+  int32_t lo_id = (int32_t)st.num_nodes;
+  if (M >= 1)   // uniform
+    lo_id = dead >= M ? p_kth_set_bit<BIG>(st.dead_bits, st.dead_part, st.parts, st.words,
+                                            dead - M + 1, false)
+                      : -1;
+  if (threadIdx.x == 0) {
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      if ((int64_t)(sorted[mid] >> 32) < (int64_t)lo_id) lo = mid + 1; else hi = mid;
+    }
+    scalars[PLAN_TAIL] = lo;
+    scalars[PLAN_LO_ID] = lo_id;
+    scalars[PLAN_DEAD] = dead;
+  }
+}
+
+// set bits per tile of TB words
+__global__ __launch_bounds__(TB) void k_bit_tiles(const uint32_t* __restrict__ bits, int64_t words,
+                                                  uint32_t* __restrict__ tiles) {
+  __shared__ uint32_t red[TB / WAVE];
+  const int64_t w = (int64_t)blockIdx.x * TB + threadIdx.x;
+  const uint32_t total = block_sum_u32(w < words ? (uint32_t)__popc(bits[w]) : 0u, red);
+  if (threadIdx.x == 0) tiles[blockIdx.x] = total;
+}
+
+// in_ids / in_positions of the whole superbatch: the set bits of ins_bits in position order
+// (iterations are consecutive stretches of positions, so this is iteration by iteration and
+// inside an iteration by position, as the lists are defined).
+__global__ __launch_bounds__(TB) void k_ins_emit(const uint32_t* __restrict__ bits, int64_t words,
+                                                 const uint32_t* __restrict__ tile_base,
+                                                 const int32_t* __restrict__ ids,
+                                                 const int64_t* __restrict__ off, int32_t S,
+                                                 int32_t* __restrict__ in_ids,
+                                                 int32_t* __restrict__ in_positions,
+                                                 uint32_t* __restrict__ ins_base,
+                                                 int32_t* __restrict__ ins_cand) {
+  extern __shared__ int32_t lds_off[];
+  __shared__ uint32_t smem[TB / WAVE + 1];
+  const uint32_t first = tile_base[blockIdx.x];
+  if (tile_base[blockIdx.x + 1] == first) return;   // nothing in this tile (uniform)
+  load_offsets(lds_off, off, S);
+  const int64_t w = (int64_t)blockIdx.x * TB + threadIdx.x;
+  uint32_t word = w < words ? bits[w] : 0u;
+  uint32_t total;
+  uint32_t rank = first + block_exclusive_scan<uint32_t, TB>((uint32_t)__popc(word), smem, total);
+  if (w < words) ins_base[w] = rank;
+  while (word) {
+    const int32_t p = (int32_t)(w * 32 + (__ffs(word) - 1));
+    word &= word - 1;
+    in_ids[rank] = ids[p];
+    in_positions[rank] = p - lds_off[iter_of(lds_off, S, p)];
+    ins_cand[rank] = -1;
+    ++rank;
+  }
+}
+
+// src_line of the insertions: their row arrives with this access
+__global__ __launch_bounds__(TB) void k_ins_lines(const uint32_t* __restrict__ bits, int64_t words,
+                                                  int32_t* __restrict__ src_line) {
+  const int64_t w = (int64_t)blockIdx.x * TB + threadIdx.x;
+  uint32_t word = w < words ? bits[w] : 0u;
+  while (word) {
+    src_line[w * 32 + (__ffs(word) - 1)] = -1;
+    word &= word - 1;
+  }
+}
+
+// The id bitmap of the candidates, from lo_id's word on: first the rows dead from the start ...
+__global__ __launch_bounds__(TB) void k_cand_start(const uint32_t* __restrict__ dead_bits,
+                                                   int64_t lo_word, int64_t nwords, int32_t lo_id,
+                                                   uint32_t* __restrict__ cand_bits) {
+  const int64_t w = (int64_t)blockIdx.x * TB + threadIdx.x;
+  if (w >= nwords) return;
+  uint32_t word = dead_bits[lo_word + w];
+  if (w == 0) word &= ~((1u << (lo_id & 31)) - 1u);
+  cand_bits[lo_word + w] = word;
+}
+
+// Is sorted[j] the last access of a row that is resident when it dies?  (A row the start state
+// does not hold is resident only if it was inserted, that is, if it has an earlier access.)
+__device__ __forceinline__ bool plan_arrival(const uint64_t* __restrict__ sorted, int64_t n,
+                                             int64_t j, const int32_t* __restrict__ addr,
+                                             const int64_t* __restrict__ off, int32_t S,
+                                             int32_t& v, int32_t& d, bool& inserted) {
+  const uint64_t cur = sorted[j];
+  v = (int32_t)(cur >> 32);
+  if (j + 1 < n && (int32_t)(sorted[j + 1] >> 32) == v) return false;
+  const bool earlier = j > 0 && (int32_t)(sorted[j - 1] >> 32) == v;
+  inserted = addr[v] < 0;
+  if (!earlier && inserted) return false;
+  const int64_t p = (int64_t)(cur & 0xFFFFFFFFu);
+  int32_t lo = 0, hi = S;
+  while (hi - lo > 1) {
+    const int32_t mid = (lo + hi) >> 1;
+    if (off[mid] <= p) lo = mid; else hi = mid;
+  }
+  d = lo;
+  return true;
+}
+
+// ... then (PLACE = false) the rows >= lo_id that die during the superbatch, counted per
+// iteration at arr_off[d + 1].  PLACE = true, after the candidates are numbered: their numbers
+// go to arr_cand at the cursors, and a row that is inserted during this call leaves its number
+// with its insertion record.
+template <bool PLACE>
+__global__ __launch_bounds__(TB) void k_plan_arrivals(const uint64_t* __restrict__ sorted, int64_t n,
+                                                      const int64_t* __restrict__ scalars,
+                                                      const int32_t* __restrict__ addr,
+                                                      const int64_t* __restrict__ off, int32_t S,
+                                                      uint32_t* __restrict__ cand_bits,
+                                                      const uint32_t* __restrict__ cand_base,
+                                                      int64_t lo_word, Plan pl) {
+  const int64_t span = (int64_t)gridDim.x * TB;
+  for (int64_t j = scalars[PLAN_TAIL] + (int64_t)blockIdx.x * TB + threadIdx.x; j < n; j += span) {
+    int32_t v, d;
+    bool inserted;
+    if (!plan_arrival(sorted, n, j, addr, off, S, v, d, inserted)) continue;
+    const uint32_t below = (1u << (v & 31)) - 1u;
+    if (!PLACE) {
+      atomicOr(&cand_bits[(uint32_t)v >> 5], 1u << (v & 31));
+      atomicAdd(&pl.arr_off[d + 1], 1u);
+      continue;
+    }
+    const uint32_t c = cand_base[((uint32_t)v >> 5) - lo_word] + __popc(cand_bits[(uint32_t)v >> 5] & below);
+    if (c >= (uint32_t)PLAN_CAND_MAX) continue;     // too many candidates: the replay will not run
+    pl.arr_cand[atomicAdd(&pl.arr_cur[d], 1u)] = (int32_t)c;
+    if (inserted) {
+      int64_t h = j;                                 // the row's first access is its insertion
+      while (h > 0 && (int32_t)(sorted[h - 1] >> 32) == v) --h;
+      const uint32_t p = (uint32_t)(sorted[h] & 0xFFFFFFFFu);
+      pl.ins_cand[pl.ins_base[p >> 5] + __popc(pl.ins_bits[p >> 5] & ((1u << (p & 31)) - 1u))] = (int32_t)c;
+    }
+  }
+}
+
+// Numbers the candidates in id order: cand_base per bitmap word, id, start line (-1 for a row
+// that is inserted during this call) and the dead-from-the-start flag per candidate.
+__global__ __launch_bounds__(TB) void k_cand_emit(const uint32_t* __restrict__ cand_bits,
+                                                  const uint32_t* __restrict__ dead_bits,
+                                                  int64_t lo_word, int64_t nwords,
+                                                  const uint32_t* __restrict__ tile_base,
+                                                  const int32_t* __restrict__ addr, Plan pl) {
+  __shared__ uint32_t smem[TB / WAVE + 1];
+  const int64_t w = (int64_t)blockIdx.x * TB + threadIdx.x;
+  uint32_t word = w < nwords ? cand_bits[lo_word + w] : 0u;
+  const uint32_t dead = w < nwords ? dead_bits[lo_word + w] : 0u;
+  uint32_t total;
+  uint32_t c = tile_base[blockIdx.x] + block_exclusive_scan<uint32_t, TB>((uint32_t)__popc(word), smem, total);
+  if (w < nwords) pl.cand_base[w] = c;
+  while (word) {
+    const int b = __ffs(word) - 1;
+    word &= word - 1;
+    if (c < (uint32_t)PLAN_CAND_MAX) {
+      const int32_t v = (int32_t)((lo_word + w) * 32 + b);
+      pl.cand_id[c] = v;
+      pl.cand_line[c] = addr[v];
+      if (dead >> b & 1) atomicOr(&pl.cand_dead[c >> 5], 1u << (c & 31));
+    }
+    ++c;
+  }
+}
+
+// One block: arr_off <- offsets (arr_off[i] .. arr_off[i + 1] are the candidates that die in
+// iteration i), arr_cur <- the same, as cursors.
+__global__ __launch_bounds__(BIG) void k_plan_arrival_offsets(uint32_t* __restrict__ arr_off,
+                                                              uint32_t* __restrict__ arr_cur,
+                                                              int32_t S) {
+  __shared__ uint32_t smem[BIG / WAVE + 1];
+  const int32_t per = (S + BIG - 1) / BIG;
+  const int32_t j0 = threadIdx.x * per;
+  uint32_t mine = 0;
+  for (int32_t j = j0; j < j0 + per && j < S; ++j) mine += arr_off[j + 1];
+  uint32_t total;
+  uint32_t run = block_exclusive_scan<uint32_t, BIG>(mine, smem, total);
+  for (int32_t j = j0; j < j0 + per && j < S; ++j) {
+    arr_cur[j] = run;
+    run += arr_off[j + 1];
+    arr_off[j + 1] = run;
+  }
+}
+
+// The replay (see the head of this part).  One block.  scalars[PLAN_FAILED] is set, before the
+// state is touched, when there are more candidates than the bitmap holds, and later if an
+// invariant does not hold; the host then runs the loop instead.
+__global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t n_cand_tiles,
+                                                     const int64_t* __restrict__ cs_offsets,
+                                                     const int32_t* __restrict__ in_ids,
+                                                     int32_t* __restrict__ out_ids) {
+  __shared__ uint32_t bits[PLAN_CAND_WORDS];
+  __shared__ int32_t s_a[PLAN_SORT_MAX];
+  __shared__ int32_t s_b[PLAN_SORT_MAX];
+  __shared__ uint32_t smem[BIG / WAVE + 1];
+  __shared__ int32_t s_failed;
+  constexpr int WPT = PLAN_CAND_WORDS / BIG;       // consecutive bitmap words of a thread
+  constexpr int EPT = PLAN_SORT_MAX / BIG;         // evictions of a thread
+  const int32_t S = st.S;
+  if (pl.cand_tiles[n_cand_tiles] > (uint32_t)PLAN_CAND_MAX) {   // uniform
+    if (threadIdx.x == 0) pl.scalars[PLAN_FAILED] = 4;
+    return;
+  }
+  for (int w = threadIdx.x; w < PLAN_CAND_WORDS; w += BIG) bits[w] = pl.cand_dead[w];
+  if (threadIdx.x == 0) s_failed = 0;
+  __syncthreads();
+  for (int32_t i = 0; i < S; ++i) {
+    const uint32_t a0 = pl.arr_off[i], a1 = pl.arr_off[i + 1];
+    const int64_t c0 = cs_offsets[i];
+    const int32_t n = (int32_t)(cs_offsets[i + 1] - c0);
+    // the rows whose last access is in this iteration are dead from here on
+    for (uint32_t a = a0 + threadIdx.x; a < a1; a += BIG) {
+      const uint32_t c = (uint32_t)pl.arr_cand[a];
+      atomicOr(&bits[c >> 5], 1u << (c & 31));
+    }
+    if (n == 0) continue;   // uniform; the next barrier orders the bits set above
+    __syncthreads();
+    // the top n set bits: set bits of the chunks above a thread's own, from a block scan
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int t = 0; t < WPT; ++t) cnt += __popc(bits[threadIdx.x * WPT + t]);
+    uint32_t total;
+    const uint32_t below = block_exclusive_scan<uint32_t, BIG>(cnt, smem, total);
+    const uint32_t above = total - below - cnt;
+    if (total < (uint32_t)n) {                      // cannot happen (see the head of this part)
+      s_failed = 1;
+      pl.scalars[PLAN_WHERE] = i;
+    } else if (above < (uint32_t)n) {
+      uint32_t take = cnt < (uint32_t)n - above ? cnt : (uint32_t)n - above;
+      uint32_t k = above;
+      for (int t = WPT - 1; t >= 0 && take; --t) {
+        uint32_t word = bits[threadIdx.x * WPT + t];
+        while (word && take) {
+          const int b = 31 - __clz(word);
+          word &= ~(1u << b);
+          s_a[k++] = (int32_t)((threadIdx.x * WPT + t) * 32 + b);
+          --take;
+        }
+        bits[threadIdx.x * WPT + t] = word;
+      }
+    }
+    __syncthreads();
+    if (s_failed) break;                            // uniform
+    // the evicted rows and their lines; the insertion a thread will hand on
+    int32_t my_v[EPT], my_line[EPT], my_in[EPT], my_ic[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const int32_t k = threadIdx.x + e * BIG;
+      my_v[e] = my_line[e] = my_in[e] = my_ic[e] = -1;
+      if (k >= n) continue;
+      const int32_t c = s_a[k];
+      my_v[e] = pl.cand_id[c];
+      my_line[e] = pl.cand_line[c];
+      my_in[e] = in_ids[c0 + k];
+      my_ic[e] = pl.ins_cand[c0 + k];
+      s_b[k] = my_line[e];
+      if (my_line[e] < 0) {                         // a dead resident has a line: cannot happen
+        s_failed = 2;
+        pl.scalars[PLAN_WHERE] = i;
+      }
+    }
+    __syncthreads();
+    if (s_failed) break;                            // uniform; no line may be used as an index then
+    // out_ids in line order: the rank of a line is the number of smaller ones
+    int32_t my_rank[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      my_rank[e] = 0;
+      if (my_v[e] < 0) continue;
+      int32_t r = 0;
+      for (int32_t q = 0; q < n; ++q) r += s_b[q] < my_line[e];
+      my_rank[e] = r;
+      out_ids[c0 + r] = my_v[e];
+    }
+    __syncthreads();   // both arrays are free now: they carry the insertions to the threads that hold their lines
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+      if (my_v[e] >= 0) {
+        s_a[threadIdx.x + e * BIG] = my_in[e];
+        s_b[threadIdx.x + e * BIG] = my_ic[e];
+      }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (my_v[e] < 0) continue;
+      const int32_t w = s_a[my_rank[e]];
+      const int32_t wc = s_b[my_rank[e]];
+      const int32_t line = my_line[e];
+      st.addr[w] = line;
+      st.res_id[line] = w;
+      if (wc >= 0) pl.cand_line[wc] = line;        // read when the row is evicted again
+    }
+    __syncthreads();   // also makes these writes visible to the block's later reads
+  }
+  if (threadIdx.x == 0 && s_failed) pl.scalars[PLAN_FAILED] = s_failed;
+}
+
 struct Workspace {
   uint64_t *pairs_a, *pairs_b, *heads_a, *heads_b;
   uint32_t* hist;
@@ -983,6 +1429,7 @@ struct Workspace {
   int64_t* d_cs_offsets;
   unsigned long long* d_counts;
   State st;
+  Plan plan;
   int64_t look_tiles, evict_tiles, in_tiles, max_heads, max_change;
   size_t bytes;
 };
@@ -1040,6 +1487,23 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   st.acc_line = a.take<int32_t>(max_n > 0 ? max_n : 1);
   st.pair = a.take<uint64_t>(w.max_change);
   st.max_change = w.max_change;
+  Plan& pl = w.plan;
+  pl.ins_words = ceil_div(t, 32);
+  pl.ins_tile_count = ceil_div(pl.ins_words, TB);
+  pl.cand_tile_count = ceil_div(st.words, TB);
+  pl.ins_bits = a.take<uint32_t>(pl.ins_words);
+  pl.ins_tiles = a.take<uint32_t>(pl.ins_tile_count + 1 + scan_scratch_elems(pl.ins_tile_count + 1));
+  pl.ins_base = a.take<uint32_t>(pl.ins_words);
+  pl.ins_cand = a.take<int32_t>(w.max_heads);
+  pl.scalars = a.take<int64_t>(PLAN_SCALARS);
+  pl.cand_tiles = a.take<uint32_t>(pl.cand_tile_count + 1 + scan_scratch_elems(pl.cand_tile_count + 1));
+  pl.cand_base = a.take<uint32_t>(st.words);
+  pl.cand_id = a.take<int32_t>(PLAN_CAND_MAX);
+  pl.cand_line = a.take<int32_t>(PLAN_CAND_MAX);
+  pl.cand_dead = a.take<uint32_t>(PLAN_CAND_WORDS);
+  pl.arr_off = a.take<uint32_t>(S + 2);
+  pl.arr_cur = a.take<uint32_t>(S + 1);
+  pl.arr_cand = a.take<int32_t>(PLAN_CAND_MAX);
   w.bytes = (a.used + 255) & ~size_t(255);
   return w;
 }
@@ -1081,7 +1545,7 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                       int32_t* in_positions, int64_t cs_capacity, int64_t* cs_offsets,
                       int64_t* miss_count, int32_t* src_line, int64_t* total_changes,
                       int64_t* init_ready, const int32_t* start_ids, int32_t* final_ids, void* ws,
-                      size_t ws_bytes, void* stream) {
+                      size_t ws_bytes, void* stream, bool allow_planned = true) {
   if (!ids_offsets || !init_count || !cs_offsets || !miss_count || !total_changes || !ws)
     return fail(GINEX_ERR_ARG, "%s: a required pointer is null", who);
   if (S >= 1 && ids_offsets[0] != 0)
@@ -1214,18 +1678,24 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
     GINEX_HIP(hipStreamSynchronize(st));
     return GINEX_OK;
   }
+  // A carried cache with room for every row of the superbatch never evicts a row that is
+  // still needed: each iteration keeps all live candidates, so the threshold bucket is
+  // "never" and the select runs on the dead rows.  The changesets then follow without a loop
+  // over the state (the planned path; GINEX_PLANNED=0 switches it off); where that path does
+  // not apply, the loop runs without the two launches of the live select.
+  // GINEX_LIVE_SELECT=1 keeps them in, and the planned path out.  All ways give the same lists.
+  const char* live_env = getenv("GINEX_LIVE_SELECT");
+  const char* plan_env = getenv("GINEX_PLANNED");
+  state.dead_only = start_ids && distinct <= cap && !(live_env && live_env[0] == '1');
+  const bool planned = state.dead_only && allow_planned && S <= PLAN_S_MAX &&
+                       !(plan_env && plan_env[0] == '0');
   // the cache cannot hold every row: Belady needs the next accessed iteration of every access
-  if (!lru) {
+  // (the planned path reads what it needs from the sorted pairs)
+  if (!lru && !planned) {
     hipLaunchKernelGGL(k_look_right, dim3((unsigned)w.look_tiles), dim3(TB), off_lds, st, sorted,
                        total, w.d_offsets, S, w.next_iter);
     GINEX_LAUNCH_CHECK();
   }
-  // A carried cache with room for every row of the superbatch never evicts a row that is
-  // still needed: each iteration keeps all live candidates, so the threshold bucket is
-  // "never" and the select runs on the dead rows.  The two launches of the live select are
-  // then left out of the loop.  GINEX_LIVE_SELECT=1 keeps them in (same result).
-  const char* live_env = getenv("GINEX_LIVE_SELECT");
-  state.dead_only = start_ids && distinct <= cap && !(live_env && live_env[0] == '1');
   GINEX_HIP(fill_async<int32_t>(state.fault, 1, 0, st));
   GINEX_HIP(fill_async<int32_t>(state.addr, num_nodes, -1, st));
   GINEX_HIP(fill_async<uint32_t>(state.rhist, S + 2, 0u, st));
@@ -1263,6 +1733,114 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                          sizeof(uint32_t) * (S + 1), st, heads, cap, init_ids, state);
       GINEX_LAUNCH_CHECK();
     }
+  }
+
+  if (planned) {
+    const Plan& pl = w.plan;
+    GINEX_HIP(fill_async<uint32_t>(pl.ins_bits, pl.ins_words, 0u, st));
+    GINEX_HIP(fill_async<uint32_t>(pl.arr_off, S + 2, 0u, st));
+    GINEX_HIP(fill_async<uint32_t>(pl.cand_dead, PLAN_CAND_WORDS, 0u, st));
+    {
+      int64_t blocks = w.look_tiles < 512 ? w.look_tiles : 512;
+      hipLaunchKernelGGL(k_plan_heads, dim3((unsigned)blocks), dim3(TB),
+                         sizeof(int32_t) * (3 * (size_t)S + 1), st, sorted, total, w.d_offsets, S,
+                         state.addr, pl.ins_bits, (unsigned long long*)miss_count,
+                         (unsigned long long*)cs_offsets);
+      hipLaunchKernelGGL(k_plan_scan, dim3(1), dim3(BIG), 0, st, state, sorted, total, cs_offsets,
+                         pl.scalars);
+      GINEX_LAUNCH_CHECK();
+    }
+    int64_t sc[PLAN_SCALARS] = {};
+    GINEX_HIP(hipMemcpyAsync(sc, pl.scalars, sizeof(sc), hipMemcpyDeviceToHost, st));
+    GINEX_HIP(hipStreamSynchronize(st));
+    const int64_t M = sc[PLAN_M], lo_id = sc[PLAN_LO_ID];
+    const bool fits = M == 0 || (lo_id >= 0 && sc[PLAN_MAX_N] <= PLAN_SORT_MAX);
+    // GINEX_TRACE=1: one line on stderr that says which way the call went
+    const char* trace_env = getenv("GINEX_TRACE");
+    const bool trace = trace_env && trace_env[0] == '1';
+    if (trace)
+      fprintf(stderr, "[ginex] %s: %lld insertions, at most %lld per iteration, %lld rows dead from "
+              "the start, lowest possible victim %lld of %lld ids: %s\n", who, (long long)M,
+              (long long)sc[PLAN_MAX_N], (long long)sc[PLAN_DEAD], (long long)lo_id,
+              (long long)num_nodes, fits ? "planned path" : "loop");
+    if (fits) {
+      *total_changes = M;
+      if (M > cs_capacity)
+        return fail(GINEX_ERR_CAPACITY, "%s: %lld changeset records, capacity %lld", who,
+                    (long long)M, (long long)cs_capacity);
+      if (M > 0) {
+        // the insertion lists
+        hipLaunchKernelGGL(k_bit_tiles, dim3((unsigned)pl.ins_tile_count), dim3(TB), 0, st,
+                           pl.ins_bits, pl.ins_words, pl.ins_tiles);
+        GINEX_LAUNCH_CHECK();
+        GINEX_HIP(fill_async<uint32_t>(pl.ins_tiles + pl.ins_tile_count, 1, 0u, st));
+        GINEX_HIP(exclusive_scan_inplace<uint32_t>(pl.ins_tiles, pl.ins_tile_count + 1,
+                                                   pl.ins_tiles + pl.ins_tile_count + 1, st));
+        hipLaunchKernelGGL(k_ins_emit, dim3((unsigned)pl.ins_tile_count), dim3(TB), off_lds, st,
+                           pl.ins_bits, pl.ins_words, pl.ins_tiles, ids, w.d_offsets, S, in_ids,
+                           in_positions, pl.ins_base, pl.ins_cand);
+        GINEX_LAUNCH_CHECK();
+        // the candidates: id bitmap from lo_id's word on (in the select's scratch bitmap, which
+        // is all zero here), numbered in id order
+        const int64_t lo_word = lo_id >> 5;
+        const int64_t nwords = state.words - lo_word;
+        const int64_t ctiles = ceil_div(nwords, TB);
+        int64_t tail_blocks = ceil_div(total - sc[PLAN_TAIL], TB);
+        tail_blocks = tail_blocks < 1 ? 1 : (tail_blocks > 1024 ? 1024 : tail_blocks);
+        hipLaunchKernelGGL(k_cand_start, dim3((unsigned)ctiles), dim3(TB), 0, st, state.dead_bits,
+                           lo_word, nwords, (int32_t)lo_id, state.bitmap);
+        hipLaunchKernelGGL(k_plan_arrivals<false>, dim3((unsigned)tail_blocks), dim3(TB), 0, st,
+                           sorted, total, pl.scalars, state.addr, w.d_offsets, S, state.bitmap,
+                           pl.cand_base, lo_word, pl);
+        hipLaunchKernelGGL(k_bit_tiles, dim3((unsigned)ctiles), dim3(TB), 0, st,
+                           state.bitmap + lo_word, nwords, pl.cand_tiles);
+        GINEX_LAUNCH_CHECK();
+        GINEX_HIP(fill_async<uint32_t>(pl.cand_tiles + ctiles, 1, 0u, st));
+        GINEX_HIP(exclusive_scan_inplace<uint32_t>(pl.cand_tiles, ctiles + 1,
+                                                   pl.cand_tiles + ctiles + 1, st));
+        hipLaunchKernelGGL(k_cand_emit, dim3((unsigned)ctiles), dim3(TB), 0, st, state.bitmap,
+                           state.dead_bits, lo_word, nwords, pl.cand_tiles, state.addr, pl);
+        hipLaunchKernelGGL(k_plan_arrival_offsets, dim3(1), dim3(BIG), 0, st, pl.arr_off,
+                           pl.arr_cur, S);
+        hipLaunchKernelGGL(k_plan_arrivals<true>, dim3((unsigned)tail_blocks), dim3(TB), 0, st,
+                           sorted, total, pl.scalars, state.addr, w.d_offsets, S, state.bitmap,
+                           pl.cand_base, lo_word, pl);
+        hipLaunchKernelGGL(k_plan_replay, dim3(1), dim3(BIG), 0, st, state, pl, ctiles, cs_offsets,
+                           in_ids, out_ids);
+        GINEX_LAUNCH_CHECK();
+      }
+      if (src_line) {
+        // every row has one line for the whole superbatch: the start state's or the one it was given
+        hipLaunchKernelGGL(k_lookup_lines, dim3((unsigned)ceil_div(total, TB * 4)), dim3(TB), 0, st,
+                           ids, total, state.addr, src_line);
+        if (M > 0)
+          hipLaunchKernelGGL(k_ins_lines, dim3((unsigned)pl.ins_tile_count), dim3(TB), 0, st,
+                             pl.ins_bits, pl.ins_words, src_line);
+        GINEX_LAUNCH_CHECK();
+      }
+      if (final_ids)
+        GINEX_HIP(hipMemcpyAsync(final_ids, state.res_id, sizeof(int32_t) * cap,
+                                 hipMemcpyDeviceToDevice, st));
+      int64_t failed[2] = {0, 0};
+      GINEX_HIP(hipMemcpyAsync(failed, pl.scalars + PLAN_FAILED, sizeof(failed),
+                               hipMemcpyDeviceToHost, st));
+      GINEX_HIP(hipStreamSynchronize(st));
+      if (!failed[0]) return GINEX_OK;
+      if (trace)
+        fprintf(stderr, "[ginex] %s: the replay gave up (reason %lld, iteration %lld), loop\n", who,
+                (long long)failed[0], (long long)failed[1]);
+      // the replay gave up, possibly after it had changed the state: start over, through the loop
+      return changeset_run(who, lru, num_nodes, ids, ids_offsets, S, cap, init_ids, init_count,
+                           in_ids, out_ids, in_positions, cs_capacity, cs_offsets, miss_count,
+                           src_line, total_changes, init_ready, start_ids, final_ids, ws, ws_bytes,
+                           stream, false);
+    }
+    // not for this path: the loop, from the untouched start state
+    GINEX_HIP(fill_async<int64_t>(miss_count, S, 0, st));
+    GINEX_HIP(fill_async<int64_t>(cs_offsets, S + 1, 0, st));
+    hipLaunchKernelGGL(k_look_right, dim3((unsigned)w.look_tiles), dim3(TB), off_lds, st, sorted,
+                       total, w.d_offsets, S, w.next_iter);
+    GINEX_LAUNCH_CHECK();
   }
 
   // part 3: the recurrence, with no host round trip between iterations

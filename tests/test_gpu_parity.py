@@ -694,6 +694,98 @@ def test_resumed_changeset_random_small_traces(ginex):
             ginex.changeset_resume(50, dev(ids), off, dev(np.array(bad, dtype=np.int32)))
 
 
+def planned_cases(rng):
+    """Traces over a carried cache that holds every distinct row of the trace (the regime in
+    which the changesets follow without a loop over the state), shaped to reach every branch
+    of that path and every reason to leave it."""
+    def revisit(n, S, rows, per_row):          # each of `rows` accessed in per_row iterations
+        tr = [[] for _ in range(S)]
+        for v in rows:
+            for i in rng.choice(S, size=min(per_row, S), replace=False):
+                tr[i].append(v)
+        tr = [rng.permutation(np.array(t, dtype=np.int32)) for t in tr]
+        off = np.cumsum([0] + [len(t) for t in tr]).astype(np.int64)
+        return np.concatenate(tr).astype(np.int32), off
+    # 1. small id spaces: the replayed id range is the whole space, most insertions may be
+    #    evicted again in the same call
+    for _ in range(25):
+        n = int(rng.integers(20, 600))
+        S = int(rng.integers(2, 40))
+        ids, off = random_trace(rng, n, S, int(rng.integers(1, 80)))
+        distinct = len(np.unique(ids))
+        cap = int(rng.integers(max(distinct, 1), n + 1))
+        yield "small", n, ids, off, rng.permutation(n)[:cap].astype(np.int32)
+    # 2. a larger id space, few start rows are ever accessed, rows come and go
+    for _ in range(6):
+        n = int(rng.integers(3000, 40000))
+        S = int(rng.integers(5, 60))
+        rows = rng.choice(n, size=int(rng.integers(50, 1500)), replace=False)
+        ids, off = revisit(n, S, rows, int(rng.integers(1, 5)))
+        cap = int(rng.integers(len(np.unique(ids)) + 1, n))
+        yield "larger", n, ids, off, rng.permutation(n)[:cap].astype(np.int32)
+    # 3. thousands of inserted rows that leave again in the same call: their lines are handed
+    #    from the pairing thread to the evicting thread iterations later
+    n = 8000
+    ids, off = revisit(n, 12, np.arange(6000, 8000), 2)
+    yield "reinserted", n, ids, off, np.arange(6000, dtype=np.int32)
+    # 4. one iteration with more than 2048 insertions: not taken at all
+    n = 9000
+    rows = np.arange(5000, 8000)
+    tr = [rows, rows[::-1].copy(), rng.permutation(n)[:100]]
+    off = np.cumsum([0] + [len(t) for t in tr]).astype(np.int64)
+    yield "wide", n, np.concatenate(tr).astype(np.int32), off, np.arange(5000, dtype=np.int32)
+    # 5. the rows that are dead from the start are spread thinly over a large id space: the
+    #    candidates are few although the id range from the lowest possible victim up is wide
+    n = 900000
+    start = (np.arange(300, dtype=np.int32) * 3000 + 7).astype(np.int32)
+    rows = np.setdiff1d(rng.choice(n, size=260, replace=False), start)[:200]
+    ids, off = revisit(n, 10, rows, 2)
+    yield "sparse", n, ids, off, start
+    # 5b. more candidates than the replay's bitmap holds (300 000 resident rows die above the
+    #     lowest possible victim): the replay declines, the loop runs
+    n = 410000
+    start = np.concatenate([np.arange(1000), np.arange(100000, 400000)]).astype(np.int32)
+    tr = [rng.permutation(np.arange(100000 + 60000 * i, 160000 + 60000 * i)) for i in range(5)]
+    newcomers = np.arange(400000, 400500)
+    tr[0] = np.concatenate([tr[0], newcomers])
+    tr[3] = np.concatenate([tr[3], newcomers[::-1]])
+    off = np.cumsum([0] + [len(t) for t in tr]).astype(np.int64)
+    yield "crowded", n, np.concatenate(tr).astype(np.int32), off, start
+    # 6. nothing is ever inserted (single accesses only), and an empty trace
+    n = 500
+    ids, off = revisit(n, 8, rng.choice(n, size=100, replace=False), 1)
+    yield "bypass", n, ids, off, rng.permutation(n)[:300].astype(np.int32)
+    yield "empty", n, np.zeros(0, dtype=np.int32), np.zeros(5, dtype=np.int64), \
+        rng.permutation(n)[:300].astype(np.int32)
+
+
+def test_carried_cache_that_holds_the_superbatch_needs_no_loop(ginex, monkeypatch, capfd):
+    """A carried cache with a line for every distinct row of the superbatch: hits, misses and
+    insertions are known up front and only the choice of the evicted rows is replayed.  The
+    result equals the oracle's and the loop's (GINEX_PLANNED=0), lists, lines and final state."""
+    rng = np.random.default_rng(77)
+    for kind, n, ids, off, start in planned_cases(rng):
+        cap = len(start)
+        assert len(np.unique(ids)) <= cap
+        ref = oracle.changeset_resume(n, ids, off, cap, start)
+        ids_d = dev(ids) if len(ids) else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
+        print("planned case", kind, n, len(ids), cap, flush=True)
+        monkeypatch.delenv("GINEX_PLANNED", raising=False)
+        monkeypatch.setenv("GINEX_TRACE", "1")
+        capfd.readouterr()
+        res = ginex.changeset_resume(n, ids_d, off, dev(start))
+        said = capfd.readouterr().err
+        monkeypatch.delenv("GINEX_TRACE")
+        check_resumed(res, ref, (n, ids, off))
+        if len(ids):      # the way the call went is the one the case was built for
+            assert ("planned path" in said) == (kind != "wide"), said
+            assert ("gave up" in said) == (kind == "crowded"), said
+        monkeypatch.setenv("GINEX_PLANNED", "0")
+        loop = ginex.changeset_resume(n, ids_d, off, dev(start))
+        check_resumed(loop, ref, (n, ids, off))
+    monkeypatch.delenv("GINEX_PLANNED", raising=False)
+
+
 def test_carried_cache_over_consecutive_superbatches(ginex, case2):
     from workload.configs import seed_batches, train_nodes
     c = case2
@@ -1074,9 +1166,11 @@ def test_changeset_is_independent_of_the_eviction_path_and_repeatable(ginex, cas
     big = len(np.unique(c.samp["ids"])) + 1000
     start = dev(np.arange(big, dtype=np.int32)[::-1].copy())
     results = []
-    for scatter, live in (("0", "0"), ("1", "0"), ("0", "1"), ("1", "1")):
+    for scatter, live, planned in (("0", "0", "1"), ("1", "0", "1"), ("0", "1", "1"), ("1", "1", "1"),
+                                   ("0", "0", "0"), ("1", "0", "0")):
         monkeypatch.setenv("GINEX_DEAD_SCATTER", scatter)
         monkeypatch.setenv("GINEX_LIVE_SELECT", live)   # keeps the live-select launches in the loop
+        monkeypatch.setenv("GINEX_PLANNED", planned)    # 0: the loop also where no loop is needed
         a = ginex.changeset(n, ids_d, io, 20000)
         b = ginex.changeset_resume(n, ids_d, io, start)
         results.append((a, b))
