@@ -1012,8 +1012,8 @@ __global__ __launch_bounds__(TB) void k_part_count(const uint32_t* __restrict__ 
 // What the path cannot take (more than PLAN_CAND_MAX candidates, an iteration with more than
 // PLAN_SORT_MAX insertions, S above PLAN_S_MAX, fewer rows dead from the start than
 // insertions) goes through the loop above.
-constexpr int PLAN_CAND_WORDS = 8192;               // LDS bitmap of the replay ...
-constexpr int PLAN_CAND_MAX = PLAN_CAND_WORDS * 32; // ... over at most 262 144 candidates
+constexpr int PLAN_CAND_WORDS = 4096;               // LDS bitmap of the replay ...
+constexpr int PLAN_CAND_MAX = PLAN_CAND_WORDS * 32; // ... over at most 131 072 candidates
 constexpr int PLAN_SORT_MAX = 2048;      // evictions of one iteration the replay can order
 constexpr int PLAN_S_MAX = 2048;         // iterations (LDS histograms of k_plan_heads)
 enum { PLAN_M = 0, PLAN_MAX_N = 1, PLAN_LO_ID = 2, PLAN_DEAD = 3, PLAN_TAIL = 4, PLAN_FAILED = 5,
@@ -1308,6 +1308,10 @@ __global__ __launch_bounds__(BIG) void k_plan_arrival_offsets(uint32_t* __restri
 // The replay (see the head of this part).  One block.  scalars[PLAN_FAILED] is set, before the
 // state is touched, when there are more candidates than the bitmap holds, and later if an
 // invariant does not hold; the host then runs the loop instead.
+// The iteration's offsets sit in LDS, and what an iteration reads from global memory at
+// addresses that do not depend on the selection (the candidates that die in it, its
+// insertions) is requested an iteration ahead, so that the chain of dependent memory accesses
+// per iteration is: selection in LDS -> id and line of the selected candidates -> stores.
 __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t n_cand_tiles,
                                                      const int64_t* __restrict__ cs_offsets,
                                                      const int32_t* __restrict__ in_ids,
@@ -1315,6 +1319,8 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
   __shared__ uint32_t bits[PLAN_CAND_WORDS];
   __shared__ int32_t s_a[PLAN_SORT_MAX];
   __shared__ int32_t s_b[PLAN_SORT_MAX];
+  __shared__ uint32_t s_arr[PLAN_S_MAX + 1];       // arr_off
+  __shared__ int32_t s_cs[PLAN_S_MAX + 1];         // cs_offsets (below 2^31: they index int32 lists)
   __shared__ uint32_t smem[BIG / WAVE + 1];
   __shared__ int32_t s_failed;
   constexpr int WPT = PLAN_CAND_WORDS / BIG;       // consecutive bitmap words of a thread
@@ -1325,16 +1331,47 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
     return;
   }
   for (int w = threadIdx.x; w < PLAN_CAND_WORDS; w += BIG) bits[w] = pl.cand_dead[w];
+  for (int j = threadIdx.x; j <= S; j += BIG) {
+    s_arr[j] = pl.arr_off[j];
+    s_cs[j] = (int32_t)cs_offsets[j];
+  }
   if (threadIdx.x == 0) s_failed = 0;
   __syncthreads();
+  // requested ahead for iteration 0
+  int32_t next_arr = threadIdx.x < s_arr[1] ? pl.arr_cand[threadIdx.x] : -1;
+  int32_t next_in[EPT], next_ic[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int32_t k = threadIdx.x + e * BIG;
+    const bool have = k < s_cs[1];
+    next_in[e] = have ? in_ids[k] : -1;
+    next_ic[e] = have ? pl.ins_cand[k] : -1;
+  }
   for (int32_t i = 0; i < S; ++i) {
-    const uint32_t a0 = pl.arr_off[i], a1 = pl.arr_off[i + 1];
-    const int64_t c0 = cs_offsets[i];
-    const int32_t n = (int32_t)(cs_offsets[i + 1] - c0);
+    const uint32_t a0 = s_arr[i], a1 = s_arr[i + 1];
+    const int32_t c0 = s_cs[i];
+    const int32_t n = s_cs[i + 1] - c0;
     // the rows whose last access is in this iteration are dead from here on
-    for (uint32_t a = a0 + threadIdx.x; a < a1; a += BIG) {
+    if (next_arr >= 0) atomicOr(&bits[(uint32_t)next_arr >> 5], 1u << (next_arr & 31));
+    for (uint32_t a = a0 + BIG + threadIdx.x; a < a1; a += BIG) {
       const uint32_t c = (uint32_t)pl.arr_cand[a];
       atomicOr(&bits[c >> 5], 1u << (c & 31));
+    }
+    int32_t my_in[EPT], my_ic[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      my_in[e] = next_in[e];
+      my_ic[e] = next_ic[e];
+    }
+    if (i + 1 < S) {        // the requests for the next iteration
+      next_arr = a1 + threadIdx.x < s_arr[i + 2] ? pl.arr_cand[a1 + threadIdx.x] : -1;
+      const int32_t c1 = s_cs[i + 1], n1 = s_cs[i + 2] - c1;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        const int32_t k = threadIdx.x + e * BIG;
+        next_in[e] = k < n1 ? in_ids[c1 + k] : -1;
+        next_ic[e] = k < n1 ? pl.ins_cand[c1 + k] : -1;
+      }
     }
     if (n == 0) continue;   // uniform; the next barrier orders the bits set above
     __syncthreads();
@@ -1364,18 +1401,16 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
     }
     __syncthreads();
     if (s_failed) break;                            // uniform
-    // the evicted rows and their lines; the insertion a thread will hand on
-    int32_t my_v[EPT], my_line[EPT], my_in[EPT], my_ic[EPT];
+    // the evicted rows and their lines
+    int32_t my_v[EPT], my_line[EPT];
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
       const int32_t k = threadIdx.x + e * BIG;
-      my_v[e] = my_line[e] = my_in[e] = my_ic[e] = -1;
+      my_v[e] = my_line[e] = -1;
       if (k >= n) continue;
       const int32_t c = s_a[k];
       my_v[e] = pl.cand_id[c];
       my_line[e] = pl.cand_line[c];
-      my_in[e] = in_ids[c0 + k];
-      my_ic[e] = pl.ins_cand[c0 + k];
       s_b[k] = my_line[e];
       if (my_line[e] < 0) {                         // a dead resident has a line: cannot happen
         s_failed = 2;

@@ -101,32 +101,26 @@ __global__ __launch_bounds__(GATHER_THREADS) void k_gather_lines(
   }
 }
 
-// line = addr[out_ids[j]]; rows[line,:] = out[in_positions[j],:].  The address table is
-// patched by a second kernel so that every line is resolved before any entry changes
-// (in_ids and out_ids are disjoint, but keeping the phases apart costs nothing).
-__global__ __launch_bounds__(THREADS) void k_update_rows(
-    chunk_t* __restrict__ rows, const int32_t* __restrict__ addr,
-    const chunk_t* __restrict__ out, const int32_t* __restrict__ out_ids,
+// Cache update (Section 3.3 "Feature Cache Update"), one wave per changeset record j:
+// line = addr[out_ids[j]]; rows[line,:] = out[in_positions[j],:]; addr[out_ids[j]] = -1;
+// addr[in_ids[j]] = line.  Every lane of the wave reads the evicted row's entry before lane 0
+// overwrites it (one wave, program order), and no other record touches these two entries
+// (in_ids and out_ids of an iteration are disjoint sets of distinct ids), so rows and address
+// table change in one launch.
+__global__ __launch_bounds__(THREADS) void k_update(
+    chunk_t* __restrict__ rows, int32_t* __restrict__ addr, const chunk_t* __restrict__ out,
+    const int32_t* __restrict__ in_ids, const int32_t* __restrict__ out_ids,
     const int32_t* __restrict__ in_positions, int64_t n_change, int32_t cpr) {
-  const int64_t total = n_change * cpr;
-  const int64_t span = (int64_t)gridDim.x * THREADS;
-  for (int64_t c = (int64_t)blockIdx.x * THREADS + threadIdx.x; c < total; c += span) {
-    const int64_t j = c / cpr;
-    const int32_t col = (int32_t)(c - j * cpr);
-    const int32_t line = addr[out_ids[j]];
-    rows[(int64_t)line * cpr + col] = out[(int64_t)in_positions[j] * cpr + col];
-  }
-}
-
-__global__ __launch_bounds__(THREADS) void k_update_addr(
-    int32_t* __restrict__ addr, const int32_t* __restrict__ in_ids,
-    const int32_t* __restrict__ out_ids, int64_t n_change) {
-  const int64_t j = (int64_t)blockIdx.x * THREADS + threadIdx.x;
-  if (j < n_change) {
-    const int32_t o = out_ids[j];
-    const int32_t line = addr[o];
-    addr[o] = -1;
-    addr[in_ids[j]] = line;
+  const int64_t waves = (int64_t)gridDim.x * (THREADS / WAVE);
+  for (int64_t j = ((int64_t)blockIdx.x * THREADS + threadIdx.x) / WAVE; j < n_change; j += waves) {
+    const int32_t gone = out_ids[j];
+    const int32_t line = addr[gone];
+    const int64_t src = (int64_t)in_positions[j] * cpr, dst = (int64_t)line * cpr;
+    for (int32_t col = lane_id(); col < cpr; col += WAVE) rows[dst + col] = out[src + col];
+    if (lane_id() == 0) {
+      addr[gone] = -1;
+      addr[in_ids[j]] = line;
+    }
   }
 }
 
@@ -322,12 +316,9 @@ int32_t launch_update(const ginex_cache_t* c, const void* out, const int32_t* in
                       hipStream_t st) {
   if (n_change == 0) return GINEX_OK;
   const int32_t cpr = (int32_t)(c->row_bytes / 16);
-  hipLaunchKernelGGL(k_update_rows, dim3(grid_for(n_change * cpr, 1)), dim3(THREADS), 0, st,
-                     (chunk_t*)c->rows, c->addr, (const chunk_t*)out, out_ids, in_positions,
+  hipLaunchKernelGGL(k_update, dim3(grid_for(n_change * WAVE, 1)), dim3(THREADS), 0, st,
+                     (chunk_t*)c->rows, c->addr, (const chunk_t*)out, in_ids, out_ids, in_positions,
                      n_change, cpr);
-  GINEX_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_update_addr, dim3(grid_for(n_change, 1)), dim3(THREADS), 0, st, c->addr,
-                     in_ids, out_ids, n_change);
   GINEX_LAUNCH_CHECK();
   return GINEX_OK;
 }
