@@ -14,7 +14,9 @@ path that configuration 4's own cache size never exercises do run (--legs):
              evicts every iteration, the executor updates the cache and reads misses from
              the slow tier (gather "G3": real hit/miss mix against the two-term bound)
   carried    the cache carried from superbatch to superbatch (ginex_changeset_resume), steady
-             state: no initialization, the loop runs over the full-size cache
+             state: no initialization; where the cache holds every row of a superbatch
+             (configurations 3 and 4) the changesets follow without the loop over the state,
+             elsewhere the loop runs from the carried state
   allmiss    the gather kernel with nothing resident (gather "G2": pure host link)
 The gathers of the timed steps are "G1" whenever the configuration never misses (3 and 4).
 
@@ -319,7 +321,8 @@ def carried_leg(ginex, w, run, first_sb, warm=3, timed=3):
            "changeset_accesses_per_s": acc / t, "executor_ms": med(rows["executor_ms"]),
            "ms_per_superbatch": med(rows["total_ms"]),
            "edges_per_s": med(rows["edges"]) / (med(rows["total_ms"]) / 1e3)}
-    roof = changeset_roofline("ginex_changeset_resume (build + Belady loop over the full-size cache)",
+    roof = changeset_roofline("ginex_changeset_resume (next-use sort + changesets of a carried cache "
+                              "that holds the superbatch: no loop over the state)",
                               acc, run.S, 0, med(rows["changes"]), t, 0,
                               measured_traffic(cfg.name, "changeset_carried"))
     del cache, ex
@@ -645,7 +648,7 @@ def main():
         "changeset_accesses_per_s": accesses / mid["changeset_s"],
         "changeset_ms": mid["changeset_s"] * 1e3,
         "changeset_note": ("every row of the superbatch fits the cache: next-use sort and C_0 only, "
-                           "the Belady loop does not run (it does in legs.pressure and legs.carried)"
+                           "the Belady loop does not run (it does in legs.pressure)"
                            if int(np.sum(timers["changes"])) == 0 and all_hit else
                            "the Belady loop runs in the timed steps"),
         "cache_init_ms": mid["cache_init_s"] * 1e3,
