@@ -148,10 +148,6 @@ int32_t ginex_neighbor_cache_build(const ginex_csr_t* g /*host struct*/, int64_t
  *   that the executor's gather (ginex_gather_lines) reads it sequentially instead of probing
  *   the table; it holds for an executor that loads C_0 line by line and applies every
  *   changeset in order.
- *   miss_positions (device, [ids_offsets[S]], may be NULL; needs src_line): the misses as a
- *   list, so that the executor can start their slow-tier reads before everything else: for
- *   iteration i the positions p - ids_offsets[i] with src_line[p] = -1, ascending, stored
- *   from miss_count[0] + ... + miss_count[i-1] on.
  * init_count and total_changes are host outputs.  cs_capacity >= total_changes is
  * required (ids_offsets[S] always suffices).
  * init_ready (host, [S], may be NULL): init_ready[i] = number of rows of C_0 first accessed
@@ -173,7 +169,7 @@ int32_t ginex_changeset(
     int32_t* init_ids /*[cap]*/, int64_t* init_count /*host*/,
     int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
     int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
-    int32_t* src_line /*[total ids] or NULL*/, int32_t* miss_positions /*[total ids] or NULL*/,
+    int32_t* src_line /*[total ids] or NULL*/,
     int64_t* total_changes /*host*/, int64_t* init_ready /*host [S] or NULL*/,
     void* ws, size_t ws_bytes, void* stream);
 
@@ -189,7 +185,7 @@ int32_t ginex_changeset_lru(
     int32_t* init_ids /*[cap]*/, int64_t* init_count /*host*/,
     int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
     int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
-    int32_t* src_line /*[total ids] or NULL*/, int32_t* miss_positions /*[total ids] or NULL*/,
+    int32_t* src_line /*[total ids] or NULL*/,
     int64_t* total_changes /*host*/, int64_t* init_ready /*host [S] or NULL*/,
     void* ws, size_t ws_bytes, void* stream);
 
@@ -210,7 +206,7 @@ int32_t ginex_changeset_noalloc(
     int32_t* init_ids /*[cap]*/, int64_t* init_count /*host*/,
     int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
     int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
-    int32_t* src_line /*[total ids] or NULL*/, int32_t* miss_positions /*[total ids] or NULL*/,
+    int32_t* src_line /*[total ids] or NULL*/,
     int64_t* total_changes /*host*/, int64_t* init_ready /*host [S] or NULL*/,
     void* stream);
 
@@ -223,17 +219,13 @@ int32_t ginex_changeset_noalloc(
  * next accessed iteration "never" and is evicted first (larger id first).  The recurrence,
  * the lists and their order are those of ginex_changeset.  final_ids (device, [cap], may be
  * NULL) receives the row of every line after the last iteration: the start_ids of the next
- * superbatch.  No cache initialization is needed between the two superbatches.
- * When the cache also has a line for every distinct row of the superbatch, no iteration
- * evicts a row that is still needed and the lists follow without a loop over the iterations
- * (same result; GINEX_PLANNED=0 in the environment keeps the loop, GINEX_TRACE=1 reports on
- * stderr which way a call went). */
+ * superbatch.  No cache initialization is needed between the two superbatches. */
 int32_t ginex_changeset_resume(
     int64_t num_nodes, const int32_t* ids, const int64_t* ids_offsets /*host [S+1]*/,
     int32_t S, int64_t cap, const int32_t* start_ids /*[cap]*/, int32_t* final_ids /*[cap]*/,
     int32_t* in_ids, int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
     int64_t* cs_offsets /*[S+1]*/, int64_t* miss_count /*[S]*/,
-    int32_t* src_line /*[total ids] or NULL*/, int32_t* miss_positions /*[total ids] or NULL*/,
+    int32_t* src_line /*[total ids] or NULL*/,
     int64_t* total_changes /*host*/,
     void* ws, size_t ws_bytes, void* stream);
 
@@ -294,17 +286,10 @@ int32_t ginex_gather(const ginex_cache_t* c /*host struct*/, const int32_t* ids,
  * gathered bytes equal those of ginex_gather provided src_line describes the cache as it
  * stands (checked by the caller's bookkeeping, not by the kernel).
  * n_slow: how many entries of src_line are -1 (miss_count[i] of the changeset call), or -1 if
- * not known.  Without miss_positions it is only a hint for the launch shape: an iteration with
- * many slow-tier rows is bound by the host link, which a smaller grid uses better; the result
- * does not depend on it.
- * miss_positions (device, [n_slow], may be NULL): the positions p with src_line[p] = -1 (the
- * iteration's stretch of the miss_positions output of ginex_changeset*; n_slow must then be
- * their exact number).  The first workgroups of the launch copy these rows, so that the slow
- * tier's long reads run from the start of the launch beside the copies from the cache, and
- * the other workgroups skip them.  Same bytes either way. */
+ * not known.  Only a hint for the launch shape: an iteration with many slow-tier rows is bound
+ * by the host link, which a smaller grid uses better; the result does not depend on it. */
 int32_t ginex_gather_lines(const ginex_cache_t* c /*host struct*/, const int32_t* ids,
-                           const int32_t* src_line, int64_t n, int64_t n_slow,
-                           const int32_t* miss_positions, void* out,
+                           const int32_t* src_line, int64_t n, int64_t n_slow, void* out,
                            const int32_t* in_ids, const int32_t* out_ids,
                            const int32_t* in_positions, int64_t n_change, void* stream);
 

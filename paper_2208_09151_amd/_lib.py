@@ -29,20 +29,19 @@ SIGNATURES = {
     "ginex_neighbor_cache_workspace_bytes": (sz, [i64]),
     "ginex_neighbor_cache_build": (i32, [C.POINTER(CsrDesc), i64, vp, vp, vp, vp, vp, sz, vp]),
     "ginex_changeset_workspace_bytes": (sz, [i64, i64, i32, i64]),
-    "ginex_changeset": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp,
+    "ginex_changeset": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp,
                               vp, sz, vp]),
     "ginex_changeset_noalloc": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp,
-                                      vp, vp, vp]),
+                                      vp, vp]),
     "ginex_changeset_lru": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp,
-                                  vp, vp, vp, sz, vp]),
+                                  vp, vp, sz, vp]),
     "ginex_changeset_resume": (i32, [i64, vp, vp, i32, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp,
-                                     vp, vp, vp, sz, vp]),
+                                     vp, vp, sz, vp]),
     "ginex_cache_init": (i32, [C.POINTER(CacheDesc), vp, i64, vp]),
     "ginex_cache_init_part": (i32, [C.POINTER(CacheDesc), vp, i64, i64, vp]),
     "ginex_cache_init_warm": (i32, [C.POINTER(CacheDesc), C.POINTER(CacheDesc), vp, i64, i64, vp]),
     "ginex_gather": (i32, [C.POINTER(CacheDesc), vp, i64, vp, vp, vp, vp, i64, vp]),
-    "ginex_gather_lines": (i32, [C.POINTER(CacheDesc), vp, vp, i64, i64, vp, vp, vp, vp, vp, i64,
-                                 vp]),
+    "ginex_gather_lines": (i32, [C.POINTER(CacheDesc), vp, vp, i64, i64, vp, vp, vp, vp, i64, vp]),
     "ginex_cache_update": (i32, [C.POINTER(CacheDesc), vp, vp, vp, vp, i64, vp]),
     "ginex_static_select_workspace_bytes": (sz, [i64]),
     "ginex_static_select": (i32, [C.POINTER(CsrDesc), i64, vp, vp, vp, sz, vp]),

@@ -210,9 +210,6 @@ class ChangesetResult:
     init_ready: np.ndarray = None   # [S] host: rows of C_0 first accessed in iterations 0..i
     final_ids: torch.Tensor = None  # resumed superbatches: row of every line after the last iteration
     src_line: torch.Tensor = None   # int32 device [total ids]: cache line of every access, -1 = miss
-    miss_positions: torch.Tensor = None  # int32 device [sum(miss_count)]: per iteration the positions
-                                         # inside ids_i that miss, ascending
-    miss_offsets: np.ndarray = None      # [S+1] host: where each iteration's stretch of them starts
 
 
 def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady",
@@ -249,31 +246,21 @@ def changeset(num_nodes, ids, ids_offsets, cap, workspace=None, policy="belady",
     total_changes = np.zeros(1, dtype=np.int64)
     init_ready = np.zeros(max(S, 1), dtype=np.int64)
     lines = torch.empty(cs_cap, dtype=torch.int32, device=dev) if with_lines else None
-    misses = torch.empty(cs_cap, dtype=torch.int32, device=dev) if with_lines else None
     if builtin_scratch:
         rc = lib.ginex_changeset_noalloc(
             num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(init_ids), _np_ptr(init_count),
             _ptr(in_ids), _ptr(out_ids), _ptr(in_pos), cs_cap, _ptr(cs_off), _ptr(miss),
-            _ptr(lines), _ptr(misses), _np_ptr(total_changes), _np_ptr(init_ready), _stream())
+            _ptr(lines), _np_ptr(total_changes), _np_ptr(init_ready), _stream())
     else:
         rc = entry(num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(init_ids),
                    _np_ptr(init_count), _ptr(in_ids), _ptr(out_ids), _ptr(in_pos), cs_cap,
-                   _ptr(cs_off), _ptr(miss), _ptr(lines), _ptr(misses), _np_ptr(total_changes),
+                   _ptr(cs_off), _ptr(miss), _ptr(lines), _np_ptr(total_changes),
                    _np_ptr(init_ready), _ptr(ws), ws.numel(), _stream())
     _check(rc)
     n = int(total_changes[0])
-    miss_count = miss[:S].cpu().numpy()
     return ChangesetResult(init_ids[:int(init_count[0])], in_ids[:n], out_ids[:n], in_pos[:n],
-                           cs_off.cpu().numpy(), miss_count, init_ready[:S],
-                           **_line_outputs(lines, misses, total, miss_count))
-
-
-def _line_outputs(lines, misses, total, miss_count):
-    if lines is None:
-        return {}
-    off = np.zeros(len(miss_count) + 1, dtype=np.int64)
-    np.cumsum(miss_count, out=off[1:])
-    return {"src_line": lines[:total], "miss_positions": misses[:int(off[-1])], "miss_offsets": off}
+                           cs_off.cpu().numpy(), miss[:S].cpu().numpy(), init_ready[:S],
+                           src_line=lines[:total] if with_lines else None)
 
 
 def changeset_resume(num_nodes, ids, ids_offsets, start_ids, workspace=None, with_lines=True):
@@ -301,17 +288,15 @@ def changeset_resume(num_nodes, ids, ids_offsets, start_ids, workspace=None, wit
     miss = torch.empty(max(S, 1), dtype=torch.int64, device=dev)
     total_changes = np.zeros(1, dtype=np.int64)
     lines = torch.empty(cs_cap, dtype=torch.int32, device=dev) if with_lines else None
-    misses = torch.empty(cs_cap, dtype=torch.int32, device=dev) if with_lines else None
     rc = lib.ginex_changeset_resume(num_nodes, _ptr(ids), _np_ptr(io), S, cap, _ptr(start_ids),
                                     _ptr(final_ids), _ptr(in_ids), _ptr(out_ids), _ptr(in_pos),
-                                    cs_cap, _ptr(cs_off), _ptr(miss), _ptr(lines), _ptr(misses),
+                                    cs_cap, _ptr(cs_off), _ptr(miss), _ptr(lines),
                                     _np_ptr(total_changes), _ptr(ws), ws.numel(), _stream())
     _check(rc)
     n = int(total_changes[0])
-    miss_count = miss[:S].cpu().numpy()
     return ChangesetResult(start_ids, in_ids[:n], out_ids[:n], in_pos[:n], cs_off.cpu().numpy(),
-                           miss_count, np.full(S, cap, dtype=np.int64), final_ids,
-                           **_line_outputs(lines, misses, total, miss_count))
+                           miss[:S].cpu().numpy(), np.full(S, cap, dtype=np.int64), final_ids,
+                           src_line=lines[:total] if with_lines else None)
 
 
 class FeatureCache:
@@ -356,13 +341,11 @@ class FeatureCache:
             _check(rc)
 
     def gather(self, ids, out=None, in_ids=None, out_ids=None, in_positions=None, src_line=None,
-               n_slow=-1, miss_positions=None):
+               n_slow=-1):
         """One executor iteration: gather the rows of ``ids`` then apply the changeset.  With
         ``src_line`` (the slice of ``ChangesetResult.src_line`` for this iteration) the gather
         is ginex_gather_lines and does not probe the address table; ``n_slow`` (the iteration's
-        miss count, if known) lets it pick a launch shape that suits the host link; with
-        ``miss_positions`` (the iteration's stretch of ``ChangesetResult.miss_positions``) the
-        slow-tier rows are started first."""
+        miss count, if known) lets it pick a launch shape that suits the host link."""
         _dev(ids, torch.int32)
         n = ids.numel()
         if out is None:
@@ -375,11 +358,7 @@ class FeatureCache:
             _dev(src_line, torch.int32)
             if src_line.numel() != n:
                 raise ValueError("src_line must have one entry per id")
-            if miss_positions is not None:
-                _dev(miss_positions, torch.int32)
-                n_slow = miss_positions.numel()
             _check(self._gather_lines(C.byref(self._desc), _ptr(ids), _ptr(src_line), n, int(n_slow),
-                                      _ptr(miss_positions) if miss_positions is not None else None,
                                       _ptr(out), *lists))
         else:
             _check(self._gather(C.byref(self._desc), _ptr(ids), n, _ptr(out), *lists))
@@ -392,11 +371,10 @@ class FeatureCache:
             _check(rc)
 
     def gather_lines_raw(self, ids_ptr: int, lines_ptr: int, n: int, n_slow: int, out_ptr: int,
-                         stream_ptr: int, miss_ptr: int = 0):
-        """ginex_gather_lines with an empty changeset, on raw device addresses (``miss_ptr``:
-        the iteration's n_slow miss positions, or 0)."""
-        rc = self._gather_lines(self._desc_ref, ids_ptr, lines_ptr, n, n_slow, miss_ptr or None,
-                                out_ptr, None, None, None, 0, stream_ptr)
+                         stream_ptr: int):
+        """ginex_gather_lines with an empty changeset, on raw device addresses."""
+        rc = self._gather_lines(self._desc_ref, ids_ptr, lines_ptr, n, n_slow, out_ptr, None, None,
+                                None, 0, stream_ptr)
         if rc:
             _check(rc)
 

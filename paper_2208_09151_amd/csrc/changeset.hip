@@ -1453,52 +1453,6 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
   if (threadIdx.x == 0 && s_failed) pl.scalars[PLAN_FAILED] = s_failed;
 }
 
-// ---- the misses of every iteration as a list, for the executor ------------------------------
-//
-// miss_positions: for iteration i, the positions inside ids_i whose src_line is -1, ascending,
-// stored from sum(miss_count[0 .. i)) on.  One order-preserving compaction over src_line.
-constexpr int MISS_ITEMS = 8;
-static_assert(TB * MISS_ITEMS == LOOK_TILE, "the tile counters of the next-use build are reused");
-
-__global__ __launch_bounds__(TB) void k_miss_tiles(const int32_t* __restrict__ src_line, int64_t n,
-                                                   uint32_t* __restrict__ tiles) {
-  __shared__ uint32_t red[TB / WAVE];
-  const int64_t base = ((int64_t)blockIdx.x * TB + threadIdx.x) * MISS_ITEMS;
-  uint32_t cnt = 0;
-#pragma unroll
-  for (int t = 0; t < MISS_ITEMS; ++t)
-    if (base + t < n) cnt += src_line[base + t] < 0;
-  const uint32_t total = block_sum_u32(cnt, red);
-  if (threadIdx.x == 0) tiles[blockIdx.x] = total;
-}
-
-__global__ __launch_bounds__(TB) void k_miss_emit(const int32_t* __restrict__ src_line, int64_t n,
-                                                  const uint32_t* __restrict__ tile_base,
-                                                  const int64_t* __restrict__ off, int32_t S,
-                                                  int32_t* __restrict__ miss_positions) {
-  extern __shared__ int32_t lds_off[];
-  __shared__ uint32_t smem[TB / WAVE + 1];
-  const uint32_t first = tile_base[blockIdx.x];
-  if (tile_base[blockIdx.x + 1] == first) return;   // no miss in this tile (uniform)
-  load_offsets(lds_off, off, S);
-  const int64_t base = ((int64_t)blockIdx.x * TB + threadIdx.x) * MISS_ITEMS;
-  uint32_t flags = 0, cnt = 0;
-#pragma unroll
-  for (int t = 0; t < MISS_ITEMS; ++t)
-    if (base + t < n && src_line[base + t] < 0) {
-      flags |= 1u << t;
-      ++cnt;
-    }
-  uint32_t total;
-  uint32_t rank = first + block_exclusive_scan<uint32_t, TB>(cnt, smem, total);
-#pragma unroll
-  for (int t = 0; t < MISS_ITEMS; ++t)
-    if (flags >> t & 1) {
-      const int32_t p = (int32_t)(base + t);
-      miss_positions[rank++] = p - lds_off[iter_of(lds_off, S, p)];
-    }
-}
-
 struct Workspace {
   uint64_t *pairs_a, *pairs_b, *heads_a, *heads_b;
   uint32_t* hist;
@@ -1600,21 +1554,6 @@ int32_t check_shape(int64_t num_nodes, int64_t total, int32_t S, int64_t cap, co
   return GINEX_OK;
 }
 
-int32_t emit_miss_positions(const Workspace& w, const int32_t* src_line, int64_t total, int32_t S,
-                            int32_t* miss_positions, hipStream_t st) {
-  if (!miss_positions || total == 0) return GINEX_OK;
-  const int64_t tiles = w.look_tiles;
-  hipLaunchKernelGGL(k_miss_tiles, dim3((unsigned)tiles), dim3(TB), 0, st, src_line, total,
-                     w.head_tiles);
-  GINEX_LAUNCH_CHECK();
-  GINEX_HIP(fill_async<uint32_t>(w.head_tiles + tiles, 1, 0u, st));
-  GINEX_HIP(exclusive_scan_inplace<uint32_t>(w.head_tiles, tiles + 1, w.head_tiles + tiles + 1, st));
-  hipLaunchKernelGGL(k_miss_emit, dim3((unsigned)tiles), dim3(TB), sizeof(int32_t) * (S + 1), st,
-                     src_line, total, w.head_tiles, w.d_offsets, S, miss_positions);
-  GINEX_LAUNCH_CHECK();
-  return GINEX_OK;
-}
-
 }  // namespace
 }  // namespace ginex
 
@@ -1639,10 +1578,9 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                       const int64_t* ids_offsets, int32_t S, int64_t cap, int32_t* init_ids,
                       int64_t* init_count, int32_t* in_ids, int32_t* out_ids,
                       int32_t* in_positions, int64_t cs_capacity, int64_t* cs_offsets,
-                      int64_t* miss_count, int32_t* src_line, int32_t* miss_positions,
-                      int64_t* total_changes, int64_t* init_ready, const int32_t* start_ids,
-                      int32_t* final_ids, void* ws, size_t ws_bytes, void* stream,
-                      bool allow_planned = true) {
+                      int64_t* miss_count, int32_t* src_line, int64_t* total_changes,
+                      int64_t* init_ready, const int32_t* start_ids, int32_t* final_ids, void* ws,
+                      size_t ws_bytes, void* stream, bool allow_planned = true) {
   if (!ids_offsets || !init_count || !cs_offsets || !miss_count || !total_changes || !ws)
     return fail(GINEX_ERR_ARG, "%s: a required pointer is null", who);
   if (S >= 1 && ids_offsets[0] != 0)
@@ -1664,8 +1602,6 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
     return fail(GINEX_ERR_ARG, "%s: a carried cache needs cap >= 1", who);
   if (cs_capacity < 0 || (cs_capacity > 0 && (!in_ids || !out_ids || !in_positions)))
     return fail(GINEX_ERR_ARG, "%s: bad changeset output arrays", who);
-  if (miss_positions && !src_line)
-    return fail(GINEX_ERR_ARG, "%s: miss_positions needs src_line", who);
   const int64_t bound = total < num_nodes ? total : num_nodes;
   Workspace w = carve(ws, num_nodes, total, S, cap, bound);
   if (ws_bytes < w.bytes)
@@ -1774,8 +1710,6 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                          ids, total, state.addr, src_line);
       GINEX_LAUNCH_CHECK();
     }
-    if (cap == 0)
-      if (int32_t rc = emit_miss_positions(w, src_line, total, S, miss_positions, st)) return rc;
     GINEX_HIP(hipStreamSynchronize(st));
     return GINEX_OK;
   }
@@ -1918,7 +1852,6 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
           hipLaunchKernelGGL(k_ins_lines, dim3((unsigned)pl.ins_tile_count), dim3(TB), 0, st,
                              pl.ins_bits, pl.ins_words, src_line);
         GINEX_LAUNCH_CHECK();
-        if (int32_t rc = emit_miss_positions(w, src_line, total, S, miss_positions, st)) return rc;
       }
       if (final_ids)
         GINEX_HIP(hipMemcpyAsync(final_ids, state.res_id, sizeof(int32_t) * cap,
@@ -1934,8 +1867,8 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       // the replay gave up, possibly after it had changed the state: start over, through the loop
       return changeset_run(who, lru, num_nodes, ids, ids_offsets, S, cap, init_ids, init_count,
                            in_ids, out_ids, in_positions, cs_capacity, cs_offsets, miss_count,
-                           src_line, miss_positions, total_changes, init_ready, start_ids, final_ids,
-                           ws, ws_bytes, stream, false);
+                           src_line, total_changes, init_ready, start_ids, final_ids, ws, ws_bytes,
+                           stream, false);
     }
     // not for this path: the loop, from the untouched start state
     GINEX_HIP(fill_async<int64_t>(miss_count, S, 0, st));
@@ -1987,7 +1920,6 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   if (start_ids && final_ids)
     GINEX_HIP(hipMemcpyAsync(final_ids, state.res_id, sizeof(int32_t) * cap,
                              hipMemcpyDeviceToDevice, st));
-  if (int32_t rc = emit_miss_positions(w, src_line, total, S, miss_positions, st)) return rc;
   GINEX_HIP(hipMemcpyAsync(total_changes, cs_offsets + S, sizeof(int64_t), hipMemcpyDeviceToHost,
                            st));
   int32_t fault = 0;
@@ -2011,11 +1943,11 @@ extern "C" int32_t ginex_changeset(int64_t num_nodes, const int32_t* ids,
                                    int32_t* init_ids, int64_t* init_count, int32_t* in_ids,
                                    int32_t* out_ids, int32_t* in_positions, int64_t cs_capacity,
                                    int64_t* cs_offsets, int64_t* miss_count, int32_t* src_line,
-                                   int32_t* miss_positions, int64_t* total_changes, int64_t* init_ready, void* ws,
+                                   int64_t* total_changes, int64_t* init_ready, void* ws,
                                    size_t ws_bytes, void* stream) {
   return changeset_run("ginex_changeset", false, num_nodes, ids, ids_offsets, S, cap, init_ids,
                        init_count, in_ids, out_ids, in_positions, cs_capacity, cs_offsets,
-                       miss_count, src_line, miss_positions, total_changes, init_ready, nullptr, nullptr, ws,
+                       miss_count, src_line, total_changes, init_ready, nullptr, nullptr, ws,
                        ws_bytes, stream);
 }
 
@@ -2025,14 +1957,14 @@ extern "C" int32_t ginex_changeset_resume(int64_t num_nodes, const int32_t* ids,
                                           int32_t* in_ids, int32_t* out_ids,
                                           int32_t* in_positions, int64_t cs_capacity,
                                           int64_t* cs_offsets, int64_t* miss_count,
-                                          int32_t* src_line, int32_t* miss_positions, int64_t* total_changes, void* ws,
+                                          int32_t* src_line, int64_t* total_changes, void* ws,
                                           size_t ws_bytes, void* stream) {
   if (!start_ids)
     return fail(GINEX_ERR_ARG, "ginex_changeset_resume: start_ids is null");
   int64_t init_count = 0;
   return changeset_run("ginex_changeset_resume", false, num_nodes, ids, ids_offsets, S, cap,
                        nullptr, &init_count, in_ids, out_ids, in_positions, cs_capacity,
-                       cs_offsets, miss_count, src_line, miss_positions, total_changes, nullptr, start_ids,
+                       cs_offsets, miss_count, src_line, total_changes, nullptr, start_ids,
                        final_ids, ws, ws_bytes, stream);
 }
 
@@ -2042,11 +1974,11 @@ extern "C" int32_t ginex_changeset_lru(int64_t num_nodes, const int32_t* ids,
                                        int32_t* out_ids, int32_t* in_positions,
                                        int64_t cs_capacity, int64_t* cs_offsets,
                                        int64_t* miss_count, int32_t* src_line,
-                                       int32_t* miss_positions, int64_t* total_changes, int64_t* init_ready, void* ws,
+                                       int64_t* total_changes, int64_t* init_ready, void* ws,
                                        size_t ws_bytes, void* stream) {
   return changeset_run("ginex_changeset_lru", true, num_nodes, ids, ids_offsets, S, cap, init_ids,
                        init_count, in_ids, out_ids, in_positions, cs_capacity, cs_offsets,
-                       miss_count, src_line, miss_positions, total_changes, init_ready, nullptr, nullptr, ws,
+                       miss_count, src_line, total_changes, init_ready, nullptr, nullptr, ws,
                        ws_bytes, stream);
 }
 
@@ -2090,7 +2022,7 @@ extern "C" int32_t ginex_changeset_noalloc(int64_t num_nodes, const int32_t* ids
                                            int32_t* in_ids, int32_t* out_ids,
                                            int32_t* in_positions, int64_t cs_capacity,
                                            int64_t* cs_offsets, int64_t* miss_count,
-                                           int32_t* src_line, int32_t* miss_positions, int64_t* total_changes,
+                                           int32_t* src_line, int64_t* total_changes,
                                            int64_t* init_ready, void* stream) {
   const char* who = "ginex_changeset_noalloc";
   if (!ids_offsets) return fail(GINEX_ERR_ARG, "%s: ids_offsets is null", who);
@@ -2108,6 +2040,6 @@ extern "C" int32_t ginex_changeset_noalloc(int64_t num_nodes, const int32_t* ids
   if (int32_t rc = scratch_for_current_device(who, &ws)) return rc;
   return changeset_run(who, false, num_nodes, ids, ids_offsets, S, cap, init_ids, init_count,
                        in_ids, out_ids, in_positions, cs_capacity, cs_offsets, miss_count,
-                       src_line, miss_positions, total_changes, init_ready, nullptr, nullptr, ws,
+                       src_line, total_changes, init_ready, nullptr, nullptr, ws,
                        (size_t)GINEX_NOALLOC_SCRATCH_BYTES, stream);
 }

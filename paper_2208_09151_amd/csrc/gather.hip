@@ -68,47 +68,14 @@ __global__ __launch_bounds__(GATHER_THREADS) void k_gather(
 // 4-byte probe of the address table (a 128-byte line fetched per row) and one level of the
 // dependent load chain are gone: what is left per row is R bytes in, R bytes out and 8 bytes
 // of sequential index data.
-// With MISS_FIRST the rows that come from the slow tier are given as a list of positions and
-// copied by the first `miss_blocks` workgroups of the launch (which the hardware dispatches
-// first), a strided grid the size the host link needs; the other workgroups skip these rows.
-// A slow-tier read takes several times as long as a read from HBM, so started at the front of
-// the launch these reads run beside the copies from the cache instead of behind them.
-template <int SHIFT, bool MISS_FIRST>
+template <int SHIFT>
 __global__ __launch_bounds__(GATHER_THREADS) void k_gather_lines(
     const chunk_t* __restrict__ rows, const chunk_t* __restrict__ slow,
     const int32_t* __restrict__ ids, const int32_t* __restrict__ lines, int64_t n,
-    int32_t cpr /*chunks per row*/, chunk_t* __restrict__ out,
-    const int32_t* __restrict__ miss_pos, int64_t n_miss, int64_t miss_blocks) {
-  if (MISS_FIRST && (int64_t)blockIdx.x < miss_blocks) {
-    const int64_t total = n_miss * cpr;
-    const int64_t span = miss_blocks * GATHER_THREADS;
-    int64_t c0 = (int64_t)blockIdx.x * GATHER_THREADS + threadIdx.x;
-    for (; c0 < total; c0 += span * UNROLL) {
-      int64_t p[UNROLL];
-      int32_t id[UNROLL], col[UNROLL];
-      chunk_t v[UNROLL];
-#pragma unroll
-      for (int u = 0; u < UNROLL; ++u) {
-        int64_t c = c0 + u * span;
-        c = c < total ? c : c0;
-        const int64_t m = SHIFT >= 0 ? c >> (SHIFT & 31) : c / cpr;
-        col[u] = SHIFT >= 0 ? (int32_t)(c & ((1 << (SHIFT & 31)) - 1)) : (int32_t)(c - m * cpr);
-        p[u] = miss_pos[m];
-      }
-#pragma unroll
-      for (int u = 0; u < UNROLL; ++u) id[u] = ids[p[u]];
-#pragma unroll
-      for (int u = 0; u < UNROLL; ++u) v[u] = slow[(int64_t)id[u] * cpr + col[u]];
-#pragma unroll
-      for (int u = 0; u < UNROLL; ++u)
-        if (c0 + u * span < total) __builtin_nontemporal_store(v[u], out + p[u] * cpr + col[u]);
-    }
-    return;
-  }
-  const int64_t first = MISS_FIRST ? miss_blocks : 0;
+    int32_t cpr /*chunks per row*/, chunk_t* __restrict__ out) {
   const int64_t total = n * cpr;
-  const int64_t span = ((int64_t)gridDim.x - first) * GATHER_THREADS;
-  int64_t c0 = ((int64_t)blockIdx.x - first) * GATHER_THREADS + threadIdx.x;
+  const int64_t span = (int64_t)gridDim.x * GATHER_THREADS;
+  int64_t c0 = (int64_t)blockIdx.x * GATHER_THREADS + threadIdx.x;
   for (; c0 < total; c0 += span * UNROLL) {
     int32_t id[UNROLL], line[UNROLL], col[UNROLL];
     chunk_t v[UNROLL];
@@ -123,23 +90,13 @@ __global__ __launch_bounds__(GATHER_THREADS) void k_gather_lines(
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-      if (MISS_FIRST) {
-        // a row of the list is not this workgroup's: nothing is stored for it, and its load (kept
-        // unconditional, so that the four loads of a thread stay in flight together) reads its
-        // own place in `out`, which is valid memory whatever the cache holds
-        int64_t c = c0 + u * span;
-        c = c < total ? c : c0;
-        const chunk_t* src = line[u] >= 0 ? rows + (int64_t)line[u] * cpr + col[u] : out + c;
-        v[u] = *src;
-      } else {
-        const chunk_t* src = line[u] >= 0 ? rows + (int64_t)line[u] * cpr : slow + (int64_t)id[u] * cpr;
-        v[u] = src[col[u]];
-      }
+      const chunk_t* src = line[u] >= 0 ? rows + (int64_t)line[u] * cpr : slow + (int64_t)id[u] * cpr;
+      v[u] = src[col[u]];
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       const int64_t c = c0 + u * span;
-      if (c < total && (!MISS_FIRST || line[u] >= 0)) __builtin_nontemporal_store(v[u], out + c);
+      if (c < total) __builtin_nontemporal_store(v[u], out + c);
     }
   }
 }
@@ -391,8 +348,7 @@ constexpr int64_t LINK_CHUNKS_IN_FLIGHT = 64 * THREADS * UNROLL;
 // lines == nullptr: the gather probes the address table itself.  n_slow: rows known to come
 // from the slow tier, or -1.
 int32_t gather_run(const char* who, const ginex_cache_t* c, const int32_t* ids,
-                   const int32_t* lines, int64_t n, int64_t n_slow, const int32_t* miss_pos,
-                   void* out,
+                   const int32_t* lines, int64_t n, int64_t n_slow, void* out,
                    const int32_t* in_ids, const int32_t* out_ids, const int32_t* in_positions,
                    int64_t n_change, void* stream) {
   if (int32_t rc = check_cache(c, who)) return rc;
@@ -412,30 +368,17 @@ int32_t gather_run(const char* who, const ginex_cache_t* c, const int32_t* ids,
     // flight as the cache fill keeps (51.8 -> 56.2 GB/s with nothing resident).  With fewer
     // slow rows the smaller grid starves the resident ones of HBM parallelism (at 42 % slow
     // rows the launch took 3 % longer), so those keep the full grid.
-    // With the list of slow-tier rows: these rows go to the first workgroups of the launch,
-    // as many as keep the link busy (the grid of the cache fill), the rest of the grid copies
-    // the resident rows.
-    int64_t miss_blocks = 0;
-    if (miss_pos && n_slow > 0) {
-      miss_blocks = ceil_div(n_slow * cpr, (int64_t)GATHER_THREADS * UNROLL);
-      const int64_t most = LINK_CHUNKS_IN_FLIGHT / ((int64_t)GATHER_THREADS * UNROLL);
-      if (miss_blocks > most) miss_blocks = most;
-      if (n_slow == n) blocks = 0;     // nothing is resident: the list's workgroups are the launch
-    } else if (n_slow > 0 && n_slow * 4 >= n * 3) {
+    if (n_slow > 0 && n_slow * 4 >= n * 3) {
       const int64_t want = ceil_div(LINK_CHUNKS_IN_FLIGHT * n, n_slow * (int64_t)GATHER_THREADS * UNROLL);
       if (want < blocks) blocks = want;
     }
-    const dim3 grid((unsigned)(blocks + miss_blocks));
+    const dim3 grid((unsigned)blocks);
 #define GINEX_GATHER(S)                                                                       \
   do {                                                                                        \
-    if (lines && miss_blocks)                                                                 \
-      hipLaunchKernelGGL((k_gather_lines<S, true>), grid, dim3(GATHER_THREADS), 0, st,         \
+    if (lines)                                                                                \
+      hipLaunchKernelGGL((k_gather_lines<S>), grid, dim3(GATHER_THREADS), 0, st,               \
                          (const chunk_t*)c->rows, (const chunk_t*)c->slow, ids, lines, n, cpr, \
-                         (chunk_t*)out, miss_pos, n_slow, miss_blocks);                       \
-    else if (lines)                                                                           \
-      hipLaunchKernelGGL((k_gather_lines<S, false>), grid, dim3(GATHER_THREADS), 0, st,        \
-                         (const chunk_t*)c->rows, (const chunk_t*)c->slow, ids, lines, n, cpr, \
-                         (chunk_t*)out, (const int32_t*)nullptr, (int64_t)0, (int64_t)0);     \
+                         (chunk_t*)out);                                                      \
     else                                                                                      \
       hipLaunchKernelGGL((k_gather<S>), grid, dim3(GATHER_THREADS), 0, st,                     \
                          (const chunk_t*)c->rows, c->addr, (const chunk_t*)c->slow, ids, n,    \
@@ -465,23 +408,18 @@ int32_t gather_run(const char* who, const ginex_cache_t* c, const int32_t* ids,
 extern "C" int32_t ginex_gather(const ginex_cache_t* c, const int32_t* ids, int64_t n, void* out,
                                 const int32_t* in_ids, const int32_t* out_ids,
                                 const int32_t* in_positions, int64_t n_change, void* stream) {
-  return gather_run("ginex_gather", c, ids, nullptr, n, -1, nullptr, out, in_ids, out_ids, in_positions,
+  return gather_run("ginex_gather", c, ids, nullptr, n, -1, out, in_ids, out_ids, in_positions,
                     n_change, stream);
 }
 
 extern "C" int32_t ginex_gather_lines(const ginex_cache_t* c, const int32_t* ids,
                                       const int32_t* src_line, int64_t n, int64_t n_slow,
-                                      const int32_t* miss_positions, void* out,
-                                      const int32_t* in_ids, const int32_t* out_ids,
+                                      void* out, const int32_t* in_ids, const int32_t* out_ids,
                                       const int32_t* in_positions, int64_t n_change,
                                       void* stream) {
-  const char* who = "ginex_gather_lines";
-  if (n > 0 && !src_line) return fail(GINEX_ERR_ARG, "%s: src_line is null", who);
-  if (n_slow > n)
-    return fail(GINEX_ERR_ARG, "%s: n_slow=%lld exceeds n=%lld", who, (long long)n_slow, (long long)n);
-  if (miss_positions && n_slow < 0)
-    return fail(GINEX_ERR_ARG, "%s: miss_positions needs the exact number of its entries in n_slow",
-                who);
-  return gather_run(who, c, ids, src_line, n, n_slow, miss_positions, out, in_ids, out_ids,
+  if (n > 0 && !src_line) return fail(GINEX_ERR_ARG, "ginex_gather_lines: src_line is null");
+  if (n_slow > n) return fail(GINEX_ERR_ARG, "ginex_gather_lines: n_slow=%lld exceeds n=%lld",
+                              (long long)n_slow, (long long)n);
+  return gather_run("ginex_gather_lines", c, ids, src_line, n, n_slow, out, in_ids, out_ids,
                     in_positions, n_change, stream);
 }

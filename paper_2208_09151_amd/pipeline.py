@@ -69,8 +69,7 @@ class Executor:
         the cache already holds ``cs.init_ids`` line by line (the changesets come from
         ``changeset_resume`` on the state the last superbatch left) and nothing is loaded.
         With ``use_lines`` (and ``cs.src_line`` present) the gathers take their cache lines from
-        the changeset stage instead of probing the address table, and start the slow-tier reads
-        of the rows listed in ``cs.miss_positions`` first.
+        the changeset stage instead of probing the address table.
         Returns the event that marks the end of the initialization."""
         cache = self.caches[self.turn]
         prev = self.caches[self.turn - 1] if self.warm and len(self.caches) > 1 else None
@@ -91,10 +90,6 @@ class Executor:
         init_ptr = cs.init_ids.data_ptr()
         lines_base = cs.src_line.data_ptr() if use_lines and cs.src_line is not None else 0
         slow = cs.miss_count.tolist() if lines_base else None
-        # the misses as a list: their slow-tier reads are started first in every gather
-        miss_base = cs.miss_positions.data_ptr() \
-            if lines_base and cs.miss_positions is not None and cs.miss_positions.numel() else 0
-        mo = cs.miss_offsets.tolist() if miss_base else None
         wait_for = None
         if resumed:
             self._event(0).record(main)
@@ -136,7 +131,7 @@ class Executor:
                 before_gather(i)
             if lines_base:
                 cache.gather_lines_raw(ids_base + 4 * io[i], lines_base + 4 * io[i], n, slow[i],
-                                       out_ptr, mp, miss_base + 4 * mo[i] if miss_base else 0)
+                                       out_ptr, mp)
             else:
                 cache.gather_raw(ids_base + 4 * io[i], n, out_ptr, mp)
             if after_gather is not None:

@@ -98,13 +98,6 @@ def check_changeset(res, ref, trace=None):
                                     ref["cs_offsets"])
         assert res.src_line is not None and res.src_line.numel() == len(ids)
         assert np.array_equal(res.src_line.cpu().numpy(), want)
-        # the misses as a list: per iteration the positions whose line is -1, ascending
-        assert np.array_equal(res.miss_offsets[1:], np.cumsum(ref["miss_count"]))
-        got = res.miss_positions.cpu().numpy()
-        assert len(got) == res.miss_offsets[-1]
-        for i in range(len(off) - 1):
-            a, b = res.miss_offsets[i], res.miss_offsets[i + 1]
-            assert np.array_equal(got[a:b], np.nonzero(want[off[i]:off[i + 1]] < 0)[0]), i
     assert np.array_equal(res.miss_count, ref["miss_count"])
     assert np.array_equal(res.cs_offsets, ref["cs_offsets"])
     assert np.array_equal(res.init_ids.cpu().numpy(), ref["init_ids"])
@@ -1111,13 +1104,8 @@ def test_gather_through_resolved_lines_matches_oracle(ginex, which, request):
         for i in range(S):
             sl = slice(co[i], co[i + 1])
             a, b = io[i], io[i + 1]
-            # the three forms of the gather by turns: own probes, resolved lines, resolved
-            # lines with the slow-tier rows listed
-            lists = {} if i % 3 == 0 else {"src_line": cs.src_line[a:b]}
-            if i % 3 == 2:
-                lists["miss_positions"] = cs.miss_positions[cs.miss_offsets[i]:cs.miss_offsets[i + 1]]
             out = cache.gather(ids_d[a:b], None, cs.in_ids[sl], cs.out_ids[sl], cs.in_positions[sl],
-                               **lists)
+                               src_line=cs.src_line[a:b])
             want, _ = ref.gather_update(ids[a:b], ref_cs["in_ids"][sl], ref_cs["out_ids"][sl],
                                         ref_cs["in_positions"][sl])
             got = out.cpu().numpy().view(np.uint8).reshape(out.shape[0], -1)
@@ -1146,24 +1134,6 @@ def test_gather_lines_row_sizes(ginex, row_bytes):
         lines = dev(line_of[ids]) if count else torch.zeros(0, dtype=torch.int32, device="cuda")
         out = cache.gather(ids_d, src_line=lines)
         assert np.array_equal(out.cpu().numpy().view(np.uint8).reshape(count, row_bytes),
-                              oracle.gather(slow.numpy(), ids))
-        # with the slow-tier rows listed (they are copied by the first workgroups of the launch)
-        listed = np.nonzero(line_of[ids] < 0)[0].astype(np.int32)
-        misses = dev(listed) if len(listed) else torch.zeros(0, dtype=torch.int32, device="cuda")
-        out = cache.gather(ids_d, src_line=lines, miss_positions=misses)
-        assert np.array_equal(out.cpu().numpy().view(np.uint8).reshape(count, row_bytes),
-                              oracle.gather(slow.numpy(), ids))
-    # nothing resident, and everything resident, with the list
-    for cap2 in (0, n):
-        cache2 = ginex.FeatureCache(slow, cap2)
-        init2 = np.arange(cap2, dtype=np.int32)
-        cache2.init(dev(init2) if cap2 else torch.zeros(0, dtype=torch.int32, device="cuda"))
-        ids = rng.integers(0, n, size=3000).astype(np.int32)
-        lines = ids.copy() if cap2 else np.full(3000, -1, dtype=np.int32)
-        listed = np.nonzero(lines < 0)[0].astype(np.int32)
-        misses = dev(listed) if len(listed) else torch.zeros(0, dtype=torch.int32, device="cuda")
-        out = cache2.gather(dev(ids), src_line=dev(lines), miss_positions=misses)
-        assert np.array_equal(out.cpu().numpy().view(np.uint8).reshape(3000, row_bytes),
                               oracle.gather(slow.numpy(), ids))
 
 
@@ -1207,7 +1177,7 @@ def test_changeset_is_independent_of_the_eviction_path_and_repeatable(ginex, cas
     first = results[0]
     for a, b in results[1:]:
         for x, y in ((a, first[0]), (b, first[1])):
-            for name in ("in_ids", "out_ids", "in_positions", "src_line", "miss_positions"):
+            for name in ("in_ids", "out_ids", "in_positions", "src_line"):
                 assert torch.equal(getattr(x, name), getattr(y, name)), name
             assert np.array_equal(x.cs_offsets, y.cs_offsets)
             assert np.array_equal(x.miss_count, y.miss_count)

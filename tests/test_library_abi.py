@@ -84,13 +84,9 @@ def test_precondition_and_workspace_errors_are_reported_before_any_launch():
 
     def changeset(ids_offsets=io, S=2, cap=3, ws_bytes=16, n=100):
         return lib.ginex_changeset(n, fake, P(ids_offsets), S, cap, fake, P(ic), fake, fake, fake,
-                                   100, fake, fake, None, None, P(tc), None, fake, ws_bytes, None)
+                                   100, fake, fake, None, P(tc), None, fake, ws_bytes, None)
 
     assert changeset() == -3
-    # the miss lists are cut out of the resolved lines: one without the other is refused
-    assert lib.ginex_changeset(100, fake, P(io), 2, 3, fake, P(ic), fake, fake, fake, 100, fake, fake,
-                               None, fake, P(tc), None, fake, 1 << 40, None) == -1
-    assert b"miss_positions" in lib.ginex_last_error()
     assert changeset(ids_offsets=np.array([0, 9, 4], dtype=np.int64)) == -4
     assert changeset(ids_offsets=np.array([0, 200, 300], dtype=np.int64)) == -4   # > nodes
     assert b"more ids than nodes" in lib.ginex_last_error()
@@ -110,9 +106,9 @@ def test_precondition_and_workspace_errors_are_reported_before_any_launch():
     assert b"share" in lib.ginex_last_error()
     # a carried cache needs a start state, and at least one line
     assert lib.ginex_changeset_resume(100, fake, P(io), 2, 3, None, fake, fake, fake, fake, 100,
-                                      fake, fake, None, None, P(tc), fake, 16, None) == -1
+                                      fake, fake, None, P(tc), fake, 16, None) == -1
     assert lib.ginex_changeset_resume(100, fake, P(io), 2, 0, fake, fake, fake, fake, fake, 100,
-                                      fake, fake, None, None, P(tc), fake, 1 << 40, None) == -1
+                                      fake, fake, None, P(tc), fake, 1 << 40, None) == -1
     assert b"cap >= 1" in lib.ginex_last_error()
     # neighbour cache: half a cache in the graph descriptor, missing outputs, small workspace
     half = _lib.CsrDesc(100, 1000, 0x1000, 0, 0x1000, 0x1000, None)
@@ -129,21 +125,18 @@ def test_precondition_and_workspace_errors_are_reported_before_any_launch():
                                           16, None) == -3
     assert lib.ginex_neighbor_cache_workspace_bytes(0) == 0
     assert lib.ginex_cache_update(ctypes.byref(c), fake, fake, fake, fake, 9, None) == -1
-    assert lib.ginex_gather_lines(ctypes.byref(c), fake, None, 2, -1, None, fake, None, None, None,
-                                  0, None) == -1
+    assert lib.ginex_gather_lines(ctypes.byref(c), fake, None, 2, -1, fake, None, None, None, 0,
+                                  None) == -1
     assert b"src_line" in lib.ginex_last_error()
-    assert lib.ginex_gather_lines(ctypes.byref(c), fake, fake, 2, -1, None, fake, fake, fake, fake,
-                                  3, None) == -1
-    assert lib.ginex_gather_lines(ctypes.byref(c), fake, fake, 2, 3, None, fake, None, None, None,
-                                  0, None) == -1
+    assert lib.ginex_gather_lines(ctypes.byref(c), fake, fake, 2, -1, fake, fake, fake, fake, 3,
+                                  None) == -1
+    assert lib.ginex_gather_lines(ctypes.byref(c), fake, fake, 2, 3, fake, None, None, None, 0,
+                                  None) == -1
     assert b"n_slow" in lib.ginex_last_error()
-    assert lib.ginex_gather_lines(ctypes.byref(c), fake, fake, 2, -1, fake, fake, None, None, None,
-                                  0, None) == -1       # a miss list without its length
-    assert b"miss_positions" in lib.ginex_last_error()
     # the allocation-free changeset checks its shape against the built-in scratch on the host
     big = np.array([0, 1 << 22, 1 << 23], dtype=np.int64)
     assert lib.ginex_changeset_noalloc(1 << 24, fake, P(big), 2, 1000, fake, P(ic), fake, fake, fake,
-                                       1 << 23, fake, fake, None, None, P(tc), None, None) == -3
+                                       1 << 23, fake, fake, None, P(tc), None, None) == -3
     assert b"scratch" in lib.ginex_last_error()
     # static policy: descriptor, outputs and workspace are checked on the host
     assert lib.ginex_static_select_workspace_bytes(0) == 0
