@@ -219,7 +219,11 @@ int32_t ginex_changeset_noalloc(
  * next accessed iteration "never" and is evicted first (larger id first).  The recurrence,
  * the lists and their order are those of ginex_changeset.  final_ids (device, [cap], may be
  * NULL) receives the row of every line after the last iteration: the start_ids of the next
- * superbatch.  No cache initialization is needed between the two superbatches. */
+ * superbatch.  No cache initialization is needed between the two superbatches.
+ * When the cache also has a line for every distinct row of the superbatch, no iteration
+ * evicts a row that is still needed and the lists follow without a loop over the iterations
+ * (same result; GINEX_PLANNED=0 in the environment keeps the loop, GINEX_TRACE=1 reports on
+ * stderr which way a call went). */
 int32_t ginex_changeset_resume(
     int64_t num_nodes, const int32_t* ids, const int64_t* ids_offsets /*host [S+1]*/,
     int32_t S, int64_t cap, const int32_t* start_ids /*[cap]*/, int32_t* final_ids /*[cap]*/,
