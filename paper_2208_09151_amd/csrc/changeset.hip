@@ -1012,12 +1012,14 @@ __global__ __launch_bounds__(TB) void k_part_count(const uint32_t* __restrict__ 
 // What the path cannot take (more than PLAN_CAND_MAX candidates, an iteration with more than
 // PLAN_SORT_MAX insertions, S above PLAN_S_MAX, fewer rows dead from the start than
 // insertions) goes through the loop above.
-constexpr int PLAN_CAND_WORDS = 4096;               // LDS bitmap of the replay ...
-constexpr int PLAN_CAND_MAX = PLAN_CAND_WORDS * 32; // ... over at most 131 072 candidates
-constexpr int PLAN_SORT_MAX = 2048;      // evictions of one iteration the replay can order
+constexpr int PLAN_CAND_WORDS = 16384;              // LDS bitmap of the replay ...
+constexpr int PLAN_CAND_MAX = PLAN_CAND_WORDS * 32; // ... over at most 524 288 candidates
+constexpr int PLAN_SORT_MAX = 4096;      // evictions of one iteration the replay can order
+// (the replay's LDS: 64 KB of bitmap, 32 KB for the ordering, 16 KB of offsets; a workgroup
+// of this GPU may use up to 160 KB)
 constexpr int PLAN_S_MAX = 2048;         // iterations (LDS histograms of k_plan_heads)
 enum { PLAN_M = 0, PLAN_MAX_N = 1, PLAN_LO_ID = 2, PLAN_DEAD = 3, PLAN_TAIL = 4, PLAN_FAILED = 5,
-       PLAN_WHERE = 6, PLAN_SCALARS = 8 };
+       PLAN_WHERE = 6, PLAN_CANDS = 7, PLAN_SCALARS = 8 };
 
 struct Plan {
   uint32_t* ins_bits;    // [ceil(total / 32)] bit p: access p (flat position) is an insertion
@@ -1192,14 +1194,20 @@ __global__ __launch_bounds__(TB) void k_ins_lines(const uint32_t* __restrict__ b
 }
 
 // The id bitmap of the candidates, from lo_id's word on: first the rows dead from the start ...
+// (lo_id comes from the device-side scalars: this and the next two kernels run before the host
+// has read them, so that the host learns the exact number of candidates with the same copy)
 __global__ __launch_bounds__(TB) void k_cand_start(const uint32_t* __restrict__ dead_bits,
-                                                   int64_t lo_word, int64_t nwords, int32_t lo_id,
+                                                   int64_t words, int64_t num_nodes,
+                                                   const int64_t* __restrict__ scalars,
                                                    uint32_t* __restrict__ cand_bits) {
-  const int64_t w = (int64_t)blockIdx.x * TB + threadIdx.x;
-  if (w >= nwords) return;
-  uint32_t word = dead_bits[lo_word + w];
-  if (w == 0) word &= ~((1u << (lo_id & 31)) - 1u);
-  cand_bits[lo_word + w] = word;
+  const int64_t lo_id = scalars[PLAN_LO_ID];
+  if (lo_id < 0 || lo_id >= num_nodes) return;      // nothing is evicted, or this path is not taken
+  const int64_t span = (int64_t)gridDim.x * TB;
+  for (int64_t w = (lo_id >> 5) + (int64_t)blockIdx.x * TB + threadIdx.x; w < words; w += span) {
+    uint32_t word = dead_bits[w];
+    if (w == (lo_id >> 5)) word &= ~((1u << (lo_id & 31)) - 1u);
+    cand_bits[w] = word;
+  }
 }
 
 // Is sorted[j] the last access of a row that is resident when it dies?  (A row the start state
@@ -1235,7 +1243,10 @@ __global__ __launch_bounds__(TB) void k_plan_arrivals(const uint64_t* __restrict
                                                       const int64_t* __restrict__ off, int32_t S,
                                                       uint32_t* __restrict__ cand_bits,
                                                       const uint32_t* __restrict__ cand_base,
-                                                      int64_t lo_word, Plan pl) {
+                                                      int64_t num_nodes, Plan pl) {
+  const int64_t lo_id = scalars[PLAN_LO_ID];
+  if (lo_id < 0 || lo_id >= num_nodes) return;
+  const int64_t lo_word = lo_id >> 5;
   const int64_t span = (int64_t)gridDim.x * TB;
   for (int64_t j = scalars[PLAN_TAIL] + (int64_t)blockIdx.x * TB + threadIdx.x; j < n; j += span) {
     int32_t v, d;
@@ -1290,7 +1301,8 @@ __global__ __launch_bounds__(TB) void k_cand_emit(const uint32_t* __restrict__ c
 // iteration i), arr_cur <- the same, as cursors.
 __global__ __launch_bounds__(BIG) void k_plan_arrival_offsets(uint32_t* __restrict__ arr_off,
                                                               uint32_t* __restrict__ arr_cur,
-                                                              int32_t S) {
+                                                              int32_t S,
+                                                              int64_t* __restrict__ scalars) {
   __shared__ uint32_t smem[BIG / WAVE + 1];
   const int32_t per = (S + BIG - 1) / BIG;
   const int32_t j0 = threadIdx.x * per;
@@ -1303,6 +1315,8 @@ __global__ __launch_bounds__(BIG) void k_plan_arrival_offsets(uint32_t* __restri
     run += arr_off[j + 1];
     arr_off[j + 1] = run;
   }
+  // the candidates: the M rows dead from the start and the rows that die during the superbatch
+  if (threadIdx.x == 0) scalars[PLAN_CANDS] = scalars[PLAN_M] + (int64_t)total;
 }
 
 // The replay (see the head of this part).  One block.  scalars[PLAN_FAILED] is set, before the
@@ -1323,14 +1337,16 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
   __shared__ int32_t s_cs[PLAN_S_MAX + 1];         // cs_offsets (below 2^31: they index int32 lists)
   __shared__ uint32_t smem[BIG / WAVE + 1];
   __shared__ int32_t s_failed;
-  constexpr int WPT = PLAN_CAND_WORDS / BIG;       // consecutive bitmap words of a thread
   constexpr int EPT = PLAN_SORT_MAX / BIG;         // evictions of a thread
   const int32_t S = st.S;
-  if (pl.cand_tiles[n_cand_tiles] > (uint32_t)PLAN_CAND_MAX) {   // uniform
+  const uint32_t n_cand = pl.cand_tiles[n_cand_tiles];
+  if (n_cand > (uint32_t)PLAN_CAND_MAX) {          // uniform
     if (threadIdx.x == 0) pl.scalars[PLAN_FAILED] = 4;
     return;
   }
-  for (int w = threadIdx.x; w < PLAN_CAND_WORDS; w += BIG) bits[w] = pl.cand_dead[w];
+  // consecutive bitmap words of a thread: as many as the candidates there are need
+  const int WPT = (int)(((n_cand + 31) / 32 + BIG - 1) / BIG);
+  for (int w = threadIdx.x; w < WPT * BIG; w += BIG) bits[w] = pl.cand_dead[w];
   for (int j = threadIdx.x; j <= S; j += BIG) {
     s_arr[j] = pl.arr_off[j];
     s_cs[j] = (int32_t)cs_offsets[j];
@@ -1377,7 +1393,6 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
     __syncthreads();
     // the top n set bits: set bits of the chunks above a thread's own, from a block scan
     uint32_t cnt = 0;
-#pragma unroll
     for (int t = 0; t < WPT; ++t) cnt += __popc(bits[threadIdx.x * WPT + t]);
     uint32_t total;
     const uint32_t below = block_exclusive_scan<uint32_t, BIG>(cnt, smem, total);
@@ -1783,21 +1798,33 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                          (unsigned long long*)cs_offsets);
       hipLaunchKernelGGL(k_plan_scan, dim3(1), dim3(BIG), 0, st, state, sorted, total, cs_offsets,
                          pl.scalars);
+      // the id bitmap of the candidates (in the select's scratch bitmap, which is all zero
+      // here) and their number, still without the host
+      int64_t tail_blocks = ceil_div(total, (int64_t)TB * 16);
+      tail_blocks = tail_blocks < 1 ? 1 : (tail_blocks > 1024 ? 1024 : tail_blocks);
+      hipLaunchKernelGGL(k_cand_start, dim3((unsigned)tail_blocks), dim3(TB), 0, st,
+                         state.dead_bits, state.words, num_nodes, pl.scalars, state.bitmap);
+      hipLaunchKernelGGL(k_plan_arrivals<false>, dim3((unsigned)tail_blocks), dim3(TB), 0, st,
+                         sorted, total, pl.scalars, state.addr, w.d_offsets, S, state.bitmap,
+                         pl.cand_base, num_nodes, pl);
+      hipLaunchKernelGGL(k_plan_arrival_offsets, dim3(1), dim3(BIG), 0, st, pl.arr_off,
+                         pl.arr_cur, S, pl.scalars);
       GINEX_LAUNCH_CHECK();
     }
     int64_t sc[PLAN_SCALARS] = {};
     GINEX_HIP(hipMemcpyAsync(sc, pl.scalars, sizeof(sc), hipMemcpyDeviceToHost, st));
     GINEX_HIP(hipStreamSynchronize(st));
     const int64_t M = sc[PLAN_M], lo_id = sc[PLAN_LO_ID];
-    const bool fits = M == 0 || (lo_id >= 0 && sc[PLAN_MAX_N] <= PLAN_SORT_MAX);
+    const bool fits = M == 0 || (lo_id >= 0 && sc[PLAN_MAX_N] <= PLAN_SORT_MAX &&
+                                 sc[PLAN_CANDS] <= PLAN_CAND_MAX);
     // GINEX_TRACE=1: one line on stderr that says which way the call went
     const char* trace_env = getenv("GINEX_TRACE");
     const bool trace = trace_env && trace_env[0] == '1';
     if (trace)
       fprintf(stderr, "[ginex] %s: %lld insertions, at most %lld per iteration, %lld rows dead from "
-              "the start, lowest possible victim %lld of %lld ids: %s\n", who, (long long)M,
-              (long long)sc[PLAN_MAX_N], (long long)sc[PLAN_DEAD], (long long)lo_id,
-              (long long)num_nodes, fits ? "planned path" : "loop");
+              "the start, lowest possible victim %lld of %lld ids, %lld candidates: %s\n", who,
+              (long long)M, (long long)sc[PLAN_MAX_N], (long long)sc[PLAN_DEAD], (long long)lo_id,
+              (long long)num_nodes, (long long)sc[PLAN_CANDS], fits ? "planned path" : "loop");
     if (fits) {
       *total_changes = M;
       if (M > cs_capacity)
@@ -1815,18 +1842,12 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                            pl.ins_bits, pl.ins_words, pl.ins_tiles, ids, w.d_offsets, S, in_ids,
                            in_positions, pl.ins_base, pl.ins_cand);
         GINEX_LAUNCH_CHECK();
-        // the candidates: id bitmap from lo_id's word on (in the select's scratch bitmap, which
-        // is all zero here), numbered in id order
+        // the candidates numbered in id order
         const int64_t lo_word = lo_id >> 5;
         const int64_t nwords = state.words - lo_word;
         const int64_t ctiles = ceil_div(nwords, TB);
         int64_t tail_blocks = ceil_div(total - sc[PLAN_TAIL], TB);
         tail_blocks = tail_blocks < 1 ? 1 : (tail_blocks > 1024 ? 1024 : tail_blocks);
-        hipLaunchKernelGGL(k_cand_start, dim3((unsigned)ctiles), dim3(TB), 0, st, state.dead_bits,
-                           lo_word, nwords, (int32_t)lo_id, state.bitmap);
-        hipLaunchKernelGGL(k_plan_arrivals<false>, dim3((unsigned)tail_blocks), dim3(TB), 0, st,
-                           sorted, total, pl.scalars, state.addr, w.d_offsets, S, state.bitmap,
-                           pl.cand_base, lo_word, pl);
         hipLaunchKernelGGL(k_bit_tiles, dim3((unsigned)ctiles), dim3(TB), 0, st,
                            state.bitmap + lo_word, nwords, pl.cand_tiles);
         GINEX_LAUNCH_CHECK();
@@ -1835,11 +1856,9 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                                                    pl.cand_tiles + ctiles + 1, st));
         hipLaunchKernelGGL(k_cand_emit, dim3((unsigned)ctiles), dim3(TB), 0, st, state.bitmap,
                            state.dead_bits, lo_word, nwords, pl.cand_tiles, state.addr, pl);
-        hipLaunchKernelGGL(k_plan_arrival_offsets, dim3(1), dim3(BIG), 0, st, pl.arr_off,
-                           pl.arr_cur, S);
         hipLaunchKernelGGL(k_plan_arrivals<true>, dim3((unsigned)tail_blocks), dim3(TB), 0, st,
                            sorted, total, pl.scalars, state.addr, w.d_offsets, S, state.bitmap,
-                           pl.cand_base, lo_word, pl);
+                           pl.cand_base, num_nodes, pl);
         hipLaunchKernelGGL(k_plan_replay, dim3(1), dim3(BIG), 0, st, state, pl, ctiles, cs_offsets,
                            in_ids, out_ids);
         GINEX_LAUNCH_CHECK();
@@ -1871,6 +1890,7 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                            stream, false);
     }
     // not for this path: the loop, from the untouched start state
+    GINEX_HIP(fill_async<uint32_t>(state.bitmap, state.words, 0u, st));
     GINEX_HIP(fill_async<int64_t>(miss_count, S, 0, st));
     GINEX_HIP(fill_async<int64_t>(cs_offsets, S + 1, 0, st));
     hipLaunchKernelGGL(k_look_right, dim3((unsigned)w.look_tiles), dim3(TB), off_lds, st, sorted,
