@@ -248,9 +248,64 @@ __global__ __launch_bounds__(TB) void k_seed_stage(Tables T, const int32_t* __re
   }
 }
 
-// NC: neighbour lists are looked up in the neighbour cache first (Section 3.2: address
-// table, then the count in front of the record, then the neighbours); a miss falls back to
-// the CSR, which then may sit in host memory.
+// Where the neighbour list of node v starts and how long it is.  NC: neighbour lists are
+// looked up in the neighbour cache first (Section 3.2: address table, then the count in front
+// of the record, then the neighbours); a miss falls back to the CSR, which then may sit in
+// host memory.  `cached` tells which array `lo` indexes.
+template <typename OffT, bool NC>
+__device__ __forceinline__ void row_of(uint32_t v, const OffT* __restrict__ offsets,
+                                       const int64_t* __restrict__ nc_address_table,
+                                       const int32_t* __restrict__ nc_cache_array, int64_t& lo,
+                                       int64_t& deg, bool& cached) {
+  int64_t at = -1;
+  if (NC) at = nc_address_table[v];
+  cached = at >= 0;
+  if (cached) {
+    deg = nc_cache_array[at];
+    lo = at + 1;
+  } else {
+    lo = (int64_t)offsets[v];
+    deg = (int64_t)offsets[v + 1] - lo;
+  }
+}
+
+// What one lane of a G-lane group contributes to the picks of frontier node v, whose list has
+// `deg` entries: c = number of picks of the node (min(deg, k)), and, for a lane with sub < c,
+// `slot` = its place among the node's picks (ascending row position) and `pick` = the row
+// position it takes.  Every lane of the wave calls it (the group shuffles and ballots inside
+// need them all).
+template <int G>
+__device__ __forceinline__ void group_choose(uint32_t v, int64_t deg, int k, int hop, uint64_t seed,
+                                             uint32_t batch, int& c, int& slot, int64_t& pick) {
+  const int lane = lane_id();
+  const int sub = threadIdx.x & (G - 1);
+  c = deg < k ? (int)deg : k;
+  pick = sub;
+  slot = sub;
+  if (__any(deg > k)) {
+    // Floyd's subset rule, every lane of the wave takes part so that the group
+    // shuffles and ballots stay convergent; groups with deg <= k discard the result.
+    const int64_t d = deg > k ? deg : (int64_t)k + 1;
+    const int64_t j = d - k + sub;
+    const uint64_t r = philox_draw(seed, v, batch, (uint32_t)hop, (uint32_t)sub);
+    const int64_t t = (int64_t)__umul64hi(r, (uint64_t)(j + 1));
+    int64_t mine = t;
+    const int group_shift = lane & ~(G - 1);
+    const uint64_t group_mask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1);
+    for (int i = 1; i < k; ++i) {
+      const int64_t ti = __shfl(t, i, G);
+      const uint64_t hit = (__ballot(sub < i && mine == ti) >> group_shift) & group_mask;
+      if (sub == i && hit) mine = j;
+    }
+    int rank = 0;
+    for (int m = 0; m < k; ++m) rank += __shfl(mine, m, G) < mine;
+    if (deg > k) {
+      pick = mine;
+      slot = rank;
+    }
+  }
+}
+
 template <int G, typename OffT, bool NC>
 __global__ __launch_bounds__(TB) void k_pick(Tables T, const OffT* __restrict__ offsets,
                                              const int32_t* __restrict__ indices,
@@ -269,48 +324,14 @@ __global__ __launch_bounds__(TB) void k_pick(Tables T, const OffT* __restrict__ 
     const int64_t idx = tile * (TB / G) + threadIdx.x / G;
     const bool active = idx < nfront[b];
     const uint32_t v = active ? (uint32_t)T.wlist[b * T.stride_ids + idx] : 0u;
-    int64_t lo = 0, deg = 0;
-    const int32_t* row = indices;
-    if (active) {
-      int64_t at = -1;
-      if (NC) at = nc_address_table[v];
-      if (at >= 0) {
-        deg = nc_cache_array[at];
-        row = nc_cache_array;
-        lo = at + 1;
-      } else {
-        lo = (int64_t)offsets[v];
-        deg = (int64_t)offsets[v + 1] - lo;
-      }
-    }
-    const int c = deg < k ? (int)deg : k;
-    int64_t pick = sub;   // row position taken by this lane
-    int slot = sub;       // its place among the node's picks (ascending position)
-    if (__any(deg > k)) {
-      // Floyd's subset rule, every lane of the wave takes part so that the group
-      // shuffles and ballots stay convergent; groups with deg <= k discard the result.
-      const int64_t d = deg > k ? deg : (int64_t)k + 1;
-      const int64_t j = d - k + sub;
-      const uint64_t r = philox_draw(seed, v, first_batch + (uint32_t)b, (uint32_t)hop, (uint32_t)sub);
-      const int64_t t = (int64_t)__umul64hi(r, (uint64_t)(j + 1));
-      int64_t mine = t;
-      const int group_shift = lane & ~(G - 1);
-      const uint64_t group_mask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1);
-      for (int i = 1; i < k; ++i) {
-        const int64_t ti = __shfl(t, i, G);
-        const uint64_t hit = (__ballot(sub < i && mine == ti) >> group_shift) & group_mask;
-        if (sub == i && hit) mine = j;
-      }
-      int rank = 0;
-      for (int m = 0; m < k; ++m) rank += __shfl(mine, m, G) < mine;
-      if (deg > k) {
-        pick = mine;
-        slot = rank;
-      }
-    }
+    int64_t lo = 0, deg = 0, pick;
+    bool cached = false;
+    if (active) row_of<OffT, NC>(v, offsets, nc_address_table, nc_cache_array, lo, deg, cached);
+    int c, slot;
+    group_choose<G>(v, deg, k, hop, seed, first_batch + (uint32_t)b, c, slot, pick);
     bool holds = false;
     if (active && sub < c) {
-      const uint32_t u = (uint32_t)row[lo + pick];
+      const uint32_t u = (uint32_t)(cached ? nc_cache_array : indices)[lo + pick];
       const uint32_t rank = (uint32_t)(idx * k + slot);
       T.cand[b * T.cand_slots + rank] = (int32_t)u;
       holds = place_candidate(T, b, k, u, rank);
@@ -730,6 +751,212 @@ inline int64_t pick_tiles(int64_t front, int group) {
   return capped(ceil_div(front, TB / group), tile_cap(PICK_TILES));
 }
 
+// ---- seeds and hop 0 in LDS ------------------------------------------------------------------
+//
+// A batch's seeds and the candidates of its first hop are few enough (at most LDS_MAX_IDS)
+// for their hash set to live in LDS: one workgroup per batch clears a table of LDS_SLOTS
+// 64-bit slots in its own LDS, deduplicates the seeds, draws the picks of hop 0, inserts them
+// (same slot word and the same rule as the tables in HBM: the smallest candidate rank per id
+// wins), appends the first occurrences to the batch's list and resolves every pick's list
+// position, all without a table access outside the CU.  What crosses batches (where a
+// batch's adj segment starts) is left to k_stage_offsets; the picks' positions and the rows'
+// edge counts wait in the batch's scratch arrays until k_adj_copy moves them there.
+// The later hops do not fit (a batch's set reaches 10^5 ids) and keep the tables in HBM.
+constexpr int LDS_SLOTS = 16384;       // 128 KB
+constexpr int LDS_BLOCK = 1024;        // threads, and the most seeds a batch may have here
+constexpr int LDS_MAX_IDS = 12288;     // seeds + candidates of hop 0: load factor 0.75 at most
+
+__device__ __forceinline__ uint32_t lds_place(unsigned long long* tab, uint32_t id, uint32_t value,
+                                              uint32_t& old_value) {
+  // Inserts (id, value) unless the id is there; returns the slot; old_value = what the slot
+  // held for this id before (all ones if the id was new).  A present id keeps the smaller value.
+  const unsigned long long mine = ((unsigned long long)id << 32) | value;
+  uint32_t h = hash_slot(id, LDS_SLOTS);
+  while (true) {
+    const unsigned long long old = atomicCAS(&tab[h], FREE_SLOT, mine);
+    if (old == FREE_SLOT) {
+      old_value = 0xFFFFFFFFu;
+      return h;
+    }
+    if ((uint32_t)(old >> 32) == id) {
+      old_value = (uint32_t)old;
+      if (old_value >= PEND && old_value > value) atomicMin(&tab[h], mine);
+      return h;
+    }
+    h = h + 1 == LDS_SLOTS ? 0 : h + 1;
+  }
+}
+
+template <int G, typename OffT, bool NC>
+__global__ __launch_bounds__(LDS_BLOCK) void k_front_lds(
+    Tables T, const OffT* __restrict__ offsets, const int32_t* __restrict__ indices,
+    const int64_t* __restrict__ nc_address_table, const int32_t* __restrict__ nc_cache_array,
+    const int32_t* __restrict__ seeds, const int64_t* __restrict__ seed_off, int k, uint64_t seed,
+    uint32_t first_batch, int H, Meta M, int32_t* __restrict__ nlist_seeds,
+    uint64_t* __restrict__ batch_total) {
+  __shared__ unsigned long long tab[LDS_SLOTS];
+  __shared__ uint64_t s_first[LDS_BLOCK];
+  __shared__ uint32_t s_edges[LDS_BLOCK], s_firsts[LDS_BLOCK];
+  __shared__ uint8_t s_cnt[LDS_BLOCK];
+  __shared__ int64_t s_lo[LDS_BLOCK];     // start of a frontier node's neighbour list; ~start if it is a cached one
+  __shared__ int32_t s_deg[LDS_BLOCK];
+  __shared__ uint64_t smem[LDS_BLOCK / WAVE + 1];
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int ns = (int)(seed_off[b + 1] - seed_off[b]);
+  int32_t* list = T.wlist + (int64_t)b * T.stride_ids;
+  int32_t* cand = T.cand + (int64_t)b * T.cand_slots;
+  uint32_t* ref = T.ref + (int64_t)b * T.cand_slots;
+  for (int i = tid; i < LDS_SLOTS; i += LDS_BLOCK) tab[i] = FREE_SLOT;
+  if (b == 0 && tid == 0) {
+    M.totals[1] = 0;
+    M.totals[2] = 0;
+  }
+  __syncthreads();
+  // the seeds: a seed repeated inside the batch is kept once, at its first position
+  uint32_t id = 0, slot_of_mine = 0, before;
+  if (tid < ns) {
+    id = (uint32_t)seeds[seed_off[b] + tid];
+    slot_of_mine = lds_place(tab, id, PEND + (uint32_t)tid, before);
+  }
+  __syncthreads();
+  const bool kept = tid < ns && (uint32_t)tab[slot_of_mine] == PEND + (uint32_t)tid;
+  uint64_t total64;
+  const uint32_t at = (uint32_t)block_exclusive_scan<uint64_t, LDS_BLOCK>(kept ? 1ull : 0ull, smem, total64);
+  const int n0 = (int)total64;
+  if (kept) {
+    list[at] = (int32_t)id;
+    tab[slot_of_mine] = ((unsigned long long)id << 32) | at;   // from now on: an id of the list, with its position
+  }
+  if (tid == 0) {
+    M.hop_sizes[(int64_t)b * (H + 1)] = n0;
+    nlist_seeds[b] = n0;
+  }
+  __syncthreads();
+  // hop 0: the frontier is the list.  First every node's neighbour list is located, one
+  // thread per node, so that the rounds below wait for memory once and not once each.
+  if (tid < n0) {
+    int64_t lo, deg;
+    bool cached;
+    row_of<OffT, NC>((uint32_t)list[tid], offsets, nc_address_table, nc_cache_array, lo, deg,
+                     cached);
+    s_lo[tid] = cached ? ~lo : lo;
+    s_deg[tid] = (int32_t)(deg < 0x7FFFFFFF ? deg : 0x7FFFFFFF);
+  }
+  __syncthreads();
+  // One G-lane group per node and round; the reads of the picked neighbours of ROUNDS rounds
+  // are issued before any is inserted, so that they are in flight together.
+  constexpr int ROUNDS = 8;
+  const int sub = tid & (G - 1);
+  const int per_round = LDS_BLOCK / G;
+  for (int base = 0; base < n0; base += per_round * ROUNDS) {
+    uint32_t u[ROUNDS], rank[ROUNDS];
+#pragma unroll
+    for (int q = 0; q < ROUNDS; ++q) {
+      const int idx = base + q * per_round + tid / G;
+      const bool active = idx < n0;
+      const uint32_t v = active ? (uint32_t)list[idx] : 0u;
+      int64_t deg = active ? (int64_t)s_deg[idx] : 0;
+      if (deg == 0x7FFFFFFF) {   // saturated in LDS (a list of 2^31 entries or more): look again
+        int64_t lo;
+        bool cached;
+        row_of<OffT, NC>(v, offsets, nc_address_table, nc_cache_array, lo, deg, cached);
+      }
+      int c, slot;
+      int64_t pick;
+      group_choose<G>(v, deg, k, 0, seed, first_batch + (uint32_t)b, c, slot, pick);
+      rank[q] = 0xFFFFFFFFu;
+      u[q] = 0;
+      if (active && sub < c) {
+        const int64_t lo = s_lo[idx];
+        u[q] = (uint32_t)(lo < 0 ? nc_cache_array[~lo + pick] : indices[lo + pick]);
+        rank[q] = (uint32_t)(idx * k + slot);
+      }
+      if (active && sub == 0) s_cnt[idx] = (uint8_t)c;
+    }
+#pragma unroll
+    for (int q = 0; q < ROUNDS; ++q)
+      if (rank[q] != 0xFFFFFFFFu) {
+        cand[rank[q]] = (int32_t)u[q];
+        const uint32_t h = lds_place(tab, u[q], PEND + rank[q], before);
+        ref[rank[q]] = before < PEND ? OLD_ID | before : h;
+      }
+  }
+  __syncthreads();
+  // per node: which of its picks are first occurrences (they hold their id's slot), and the
+  // picks / first occurrences in front of the node
+  uint64_t first = 0;
+  int c = 0;
+  if (tid < n0) {
+    c = s_cnt[tid];
+    for (int s = 0; s < c; ++s) {
+      const uint32_t rank = (uint32_t)(tid * k + s);
+      const uint32_t r = ref[rank];
+      if (!(r & OLD_ID) && (uint32_t)tab[r] == PEND + rank) first |= 1ull << s;
+    }
+  }
+  const uint64_t ex = block_exclusive_scan<uint64_t, LDS_BLOCK>(((uint64_t)c << 32) | (uint64_t)__popcll(first),
+                                                                smem, total64);
+  s_first[tid] = first;
+  s_edges[tid] = (uint32_t)(ex >> 32);
+  s_firsts[tid] = (uint32_t)(ex & 0xFFFFFFFFu);
+  __syncthreads();
+  // one thread per candidate: first occurrences go to the list, their slot gets the position
+  const uint32_t ncand = (uint32_t)n0 * (uint32_t)k;
+  for (uint32_t r = tid; r < ncand; r += LDS_BLOCK) {
+    const uint32_t node = r / (uint32_t)k, pick = r - node * (uint32_t)k;
+    const uint64_t f = s_first[node];
+    if (pick < s_cnt[node] && (f >> pick & 1)) {
+      const uint32_t pos = (uint32_t)n0 + s_firsts[node] + (uint32_t)__popcll(f & ((1ull << pick) - 1));
+      const uint32_t u = (uint32_t)cand[r];
+      list[pos] = (int32_t)u;
+      tab[ref[r]] = ((unsigned long long)u << 32) | pos;
+    }
+  }
+  __syncthreads();
+  // every pick's position in the list (adj_col), parked in `cand` (same thread per entry as above)
+  for (uint32_t r = tid; r < ncand; r += LDS_BLOCK) {
+    const uint32_t node = r / (uint32_t)k, pick = r - node * (uint32_t)k;
+    if (pick < s_cnt[node]) {
+      const uint32_t where = ref[r];
+      cand[r] = (int32_t)(where & OLD_ID ? where & ~OLD_ID : (uint32_t)tab[where]);
+    }
+  }
+  __syncthreads();   // `ref` is free now: it parks the rows' edge offsets
+  if (tid < n0) {
+    ref[tid] = s_edges[tid];
+    T.cnt[(int64_t)b * T.fr_slots + tid] = s_cnt[tid];
+  }
+  if (tid == 0) batch_total[b] = total64;
+}
+
+// adj of hop 0 from the scratch arrays k_front_lds left: rowptr of every frontier node, and
+// the list position of every pick at its place in the batch's segment.
+__global__ __launch_bounds__(TB) void k_adj_copy(Tables T, const int32_t* __restrict__ nfront, int k,
+                                                 const uint64_t* __restrict__ batch_total,
+                                                 int64_t* __restrict__ rowptr, int64_t rowptr_capacity,
+                                                 const int64_t* __restrict__ row_base,
+                                                 int32_t* __restrict__ col, int64_t col_capacity,
+                                                 const int64_t* __restrict__ col_base) {
+  const int b = blockIdx.y;
+  const int n0 = nfront[b];
+  const int32_t* cand = T.cand + (int64_t)b * T.cand_slots;
+  const uint32_t* edges = T.ref + (int64_t)b * T.cand_slots;
+  const int64_t rb = row_base[b], cb = col_base[b];
+  const int64_t span = (int64_t)gridDim.x * TB;
+  for (int64_t r = (int64_t)blockIdx.x * TB + threadIdx.x; r <= n0; r += span)
+    if (rb + r < rowptr_capacity)
+      rowptr[rb + r] = r < n0 ? (int64_t)edges[r] : (int64_t)(batch_total[b] >> 32);
+  const int64_t ncand = (int64_t)n0 * k;
+  for (int64_t r = (int64_t)blockIdx.x * TB + threadIdx.x; r < ncand; r += span) {
+    const int64_t node = r / k, pick = r - node * k;
+    if (pick < T.cnt[(int64_t)b * T.fr_slots + node]) {
+      const int64_t d = cb + edges[node] + pick;
+      if (d < col_capacity) col[d] = cand[r];
+    }
+  }
+}
+
 template <typename OffT, bool NC>
 void launch_pick(const Tables& T, const Plan& p, const ginex_csr_t* g, const int32_t* nfront, int k,
                  int hop, int32_t S, uint64_t seed, uint32_t first_batch, hipStream_t st) {
@@ -751,6 +978,22 @@ void launch_pick(const Tables& T, const Plan& p, const ginex_csr_t* g, const int
                        g->indices, g->nc_address_table, g->nc_cache_array, nfront, k, hop, seed,
                        first_batch, S, tpb);
   }
+}
+
+template <typename OffT, bool NC>
+void launch_front(const Tables& T, const ginex_csr_t* g, const int32_t* seeds,
+                  const int64_t* seed_off, int k, int32_t S, int32_t H, uint64_t seed,
+                  uint32_t first_batch, const Meta& M, int32_t* nlist_seeds, uint64_t* batch_total,
+                  hipStream_t st) {
+  const OffT* off = static_cast<const OffT*>(g->offsets);
+#define GINEX_FRONT(G)                                                                          \
+  hipLaunchKernelGGL((k_front_lds<G, OffT, NC>), dim3((unsigned)S), dim3(LDS_BLOCK), 0, st, T, off, \
+                     g->indices, g->nc_address_table, g->nc_cache_array, seeds, seed_off, k, seed, \
+                     first_batch, H, M, nlist_seeds, batch_total)
+  if (k <= 16) GINEX_FRONT(16);
+  else if (k <= 32) GINEX_FRONT(32);
+  else GINEX_FRONT(64);
+#undef GINEX_FRONT
 }
 
 }  // namespace
@@ -852,13 +1095,50 @@ extern "C" int32_t ginex_sample_superbatch(
                   "num_edges without a decrease, indices inside [0, %lld))", who, bad,
                   (long long)g->num_nodes);
   }
-  hipLaunchKernelGGL(k_seed_counts, dim3((unsigned)ceil_div(S, TB)), dim3(TB), 0, st, w.seed_off, S,
-                     w.nfront, w.nlist_a);
-  GINEX_LAUNCH_CHECK();
-
   int32_t* nlist = w.nlist_a;
   int32_t* nlist_next = w.nlist_b;
-  for (int stage = -1; stage < H; ++stage) {
+  int first_stage = -1;
+  // Seeds and hop 0 of a batch in the LDS of one workgroup, when their hash set fits there
+  // (GINEX_SAMPLER_LDS=0 keeps them on the tables in HBM; same result).
+  const char* lds_env = getenv("GINEX_SAMPLER_LDS");
+  const bool front_lds = max_batch <= LDS_BLOCK &&
+                         max_batch * (1 + (int64_t)fanout[0]) <= LDS_MAX_IDS &&
+                         !(lds_env && lds_env[0] == '0');
+  if (front_lds) {
+    const int k0 = fanout[0];
+    if (g->nc_address_table) {
+      if (g->offsets_64)
+        launch_front<int64_t, true>(T, g, seeds, w.seed_off, k0, S, H, rng_seed, first_batch_index, M,
+                                    w.nlist_b, w.batch_total, st);
+      else
+        launch_front<int32_t, true>(T, g, seeds, w.seed_off, k0, S, H, rng_seed, first_batch_index, M,
+                                    w.nlist_b, w.batch_total, st);
+    } else if (g->offsets_64) {
+      launch_front<int64_t, false>(T, g, seeds, w.seed_off, k0, S, H, rng_seed, first_batch_index, M,
+                                   w.nlist_b, w.batch_total, st);
+    } else {
+      launch_front<int32_t, false>(T, g, seeds, w.seed_off, k0, S, H, rng_seed, first_batch_index, M,
+                                   w.nlist_b, w.batch_total, st);
+    }
+    GINEX_LAUNCH_CHECK();
+    // the list after the seeds (nlist_b) is the frontier of hop 0; nlist_a receives the list after hop 0
+    hipLaunchKernelGGL(k_stage_offsets, dim3(1), dim3(TB), 0, st, M, S, H, 0, w.batch_total,
+                       w.nlist_b, w.nlist_b, w.nlist_a, w.row_base, w.col_base);
+    GINEX_LAUNCH_CHECK();
+    if (adj_rowptr) {
+      const int64_t per_batch = ceil_div(max_batch * (int64_t)k0 + 1, TB);
+      hipLaunchKernelGGL(k_adj_copy, dim3((unsigned)(per_batch < 16 ? per_batch : 16), (unsigned)S),
+                         dim3(TB), 0, st, T, w.nlist_b, k0, w.batch_total, adj_rowptr,
+                         rowptr_capacity, w.row_base, adj_col, col_capacity, w.col_base);
+      GINEX_LAUNCH_CHECK();
+    }
+    first_stage = 1;
+  } else {
+    hipLaunchKernelGGL(k_seed_counts, dim3((unsigned)ceil_div(S, TB)), dim3(TB), 0, st, w.seed_off,
+                       S, w.nfront, w.nlist_a);
+    GINEX_LAUNCH_CHECK();
+  }
+  for (int stage = first_stage; stage < H; ++stage) {
     const int k = stage < 0 ? 1 : fanout[stage];
     const int64_t front = stage < 0 ? (max_batch > 0 ? max_batch : 1) : p.stride_front[stage];
     // in a hop the frontier is the whole list as it stands when the hop starts

@@ -1156,6 +1156,50 @@ def test_sampler_is_independent_of_the_launch_shape(ginex, case1, case2, tiles, 
         check_sample(other, c.samp, c.cfg.S, len(c.cfg.fanout))
 
 
+def test_seeds_and_first_hop_in_lds_equal_the_tables_in_hbm(ginex, case1, case2, monkeypatch):
+    """Seeds and hop 0 of a batch are deduplicated in the LDS of one workgroup when their hash
+    set fits there; GINEX_SAMPLER_LDS=0 sends them through the tables in HBM like the later
+    hops.  Both ways against the oracle and against each other, with and without adj, on
+    the fixtures and on shapes at the edges of what the LDS path takes (1024 seeds, a
+    repeated seed, an empty batch, a fanout that selects 32- and 64-lane groups)."""
+    from workload import make_workload
+    for c in (case1, case2):
+        ref = run_sample(ginex, c)
+        check_sample(ref, c.samp, c.cfg.S, len(c.cfg.fanout))
+        monkeypatch.setenv("GINEX_SAMPLER_LDS", "0")
+        other = run_sample(ginex, c)
+        no_adj = run_sample(ginex, c, with_adj=False)
+        monkeypatch.delenv("GINEX_SAMPLER_LDS")
+        check_sample(other, c.samp, c.cfg.S, len(c.cfg.fanout))
+        for name in ("ids", "adj_rowptr", "adj_col"):
+            assert torch.equal(getattr(ref, name), getattr(other, name)), name
+        assert np.array_equal(ref.hop_sizes, other.hop_sizes)
+        assert torch.equal(no_adj.ids, ref.ids)
+    w = make_workload(1)
+    off, ind = w.offsets.numpy(), w.indices.numpy()
+    n = w.cfg.num_nodes
+    rng = np.random.default_rng(9)
+    shapes = [([1024, 0, 1, 700], (10, 3)), ([300, 299], (20, 2)), ([150, 1], (40, 2)),
+              ([1025, 10], (5, 2))]          # the last one does not fit: 1025 seeds
+    for sizes, fanout in shapes:
+        seeds = [rng.integers(0, n, size=m).astype(np.int32) for m in sizes]
+        if len(seeds[0]) > 4:
+            seeds[0][3] = seeds[0][1]            # a repeated seed
+        so = np.cumsum([0] + sizes).astype(np.int64)
+        flat = np.concatenate(seeds).astype(np.int32)
+        want = oracle.sample_superbatch(off, ind, flat, so, list(fanout), rng_seed=5,
+                                        first_batch_index=7)
+        results = []
+        for lds in ("1", "0"):
+            monkeypatch.setenv("GINEX_SAMPLER_LDS", lds)
+            got = ginex.sample_superbatch(w.offsets.cuda(), w.indices.cuda(), dev(flat), so,
+                                          list(fanout), rng_seed=5, first_batch_index=7)
+            check_sample(got, want, len(sizes), len(fanout))
+            results.append(got)
+        monkeypatch.delenv("GINEX_SAMPLER_LDS")
+        assert torch.equal(results[0].adj_col, results[1].adj_col)
+
+
 def test_changeset_is_independent_of_the_eviction_path_and_repeatable(ginex, case2, monkeypatch):
     """The two ways of finding evictions among dead rows use different grids and atomics; both,
     and a second run of each, give byte-identical lists, lines and final states."""
