@@ -32,6 +32,10 @@
 //
 // The seeds go through the same count/scan/emit path as a stage with one candidate per
 // slot, which also removes repeated seeds.
+//
+// Where the hash set of a batch's seeds and first hop fits LDS (the usual case), those two
+// stages run in one workgroup per batch with the table in LDS instead (k_front_lds, further
+// down); the later hops, whose sets are far too large for that, run as described above.
 #include <cstdlib>
 #include <cstring>
 #include <vector>
