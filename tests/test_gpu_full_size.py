@@ -137,10 +137,42 @@ def run_full(index, extras=False, every=1):
             del want, got
         say(f"gather parity ok (cap={cap}): all {len(resident)} resident lines hold their rows")
         del cache, cs, rcs, out, rows8
+    if cfg.cap >= distinct + 100000:
+        carried_cache_both_ways(ginex, cfg, res, ids, distinct)
     if extras:
         widened_rows(ginex, w, res, ref, distinct)
     del w, res, ref, feats
     release_memory()
+
+
+def carried_cache_both_ways(ginex, cfg, res, ids, distinct):
+    """A carried cache of the configuration's own size that holds nearly every row of the
+    superbatch (the steady state of the carried mode): the changesets that follow without a
+    loop over the state equal the loop's, lists, lines and final state.  (The loop is compared
+    with the oracle at this size above, the loop-free path at configuration 3's size.)"""
+    t = time.time()
+    rng = np.random.default_rng(6)
+    rows = np.unique(ids)
+    gone = rng.random(len(rows)) < 0.01
+    room = cfg.cap - int((~gone).sum())
+    outside = np.setdiff1d(np.arange(0, cfg.num_nodes, 3, dtype=np.int64), rows)[:room]
+    start = dev(rng.permutation(np.concatenate([rows[~gone], outside])).astype(np.int32))
+    assert start.numel() == cfg.cap
+    del rows, outside
+    both = []
+    for planned in ("1", "0"):
+        os.environ["GINEX_PLANNED"] = planned
+        try:
+            both.append(ginex.changeset_resume(cfg.num_nodes, res.ids, res.ids_offsets, start))
+        finally:
+            del os.environ["GINEX_PLANNED"]
+    a, b = both
+    assert int(a.cs_offsets[-1]) > 0
+    assert np.array_equal(a.cs_offsets, b.cs_offsets) and np.array_equal(a.miss_count, b.miss_count)
+    for name in ("in_ids", "out_ids", "in_positions", "src_line", "final_ids"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    say(f"carried cache of {cfg.cap} lines: loop-free changesets equal the loop's "
+        f"({int(a.cs_offsets[-1])} changes, {int(a.miss_count.sum())} misses, {time.time() - t:.1f}s)")
 
 
 def widened_rows(ginex, w, res, ref, distinct):
