@@ -53,7 +53,7 @@ def release_memory():
         torch._C._host_emptyCache()
 
 
-def run_full(index, extras=False, every=1):
+def run_full(index, extras=False, every=1, capfd=None):
     import paper_2208_09151_amd as ginex
     release_memory()
     t = time.time()
@@ -138,14 +138,14 @@ def run_full(index, extras=False, every=1):
         say(f"gather parity ok (cap={cap}): all {len(resident)} resident lines hold their rows")
         del cache, cs, rcs, out, rows8
     if cfg.cap >= distinct + 100000:
-        carried_cache_both_ways(ginex, cfg, res, ids, distinct)
+        carried_cache_both_ways(ginex, cfg, res, ids, distinct, capfd)
     if extras:
-        widened_rows(ginex, w, res, ref, distinct)
+        widened_rows(ginex, w, res, ref, distinct, capfd)
     del w, res, ref, feats
     release_memory()
 
 
-def carried_cache_both_ways(ginex, cfg, res, ids, distinct):
+def carried_cache_both_ways(ginex, cfg, res, ids, distinct, capfd=None):
     """A carried cache of the configuration's own size that holds nearly every row of the
     superbatch (the steady state of the carried mode): the changesets that follow without a
     loop over the state equal the loop's, lists, lines and final state.  (The loop is compared
@@ -155,17 +155,24 @@ def carried_cache_both_ways(ginex, cfg, res, ids, distinct):
     rows = np.unique(ids)
     gone = rng.random(len(rows)) < 0.01
     room = cfg.cap - int((~gone).sum())
-    outside = np.setdiff1d(np.arange(0, cfg.num_nodes, 3, dtype=np.int64), rows)[:room]
+    outside = np.setdiff1d(np.arange(0, cfg.num_nodes, 3, dtype=np.int64), rows)
+    outside = outside[np.linspace(0, len(outside) - 1, room).astype(np.int64)]   # spread over all ids
     start = dev(rng.permutation(np.concatenate([rows[~gone], outside])).astype(np.int32))
     assert start.numel() == cfg.cap
     del rows, outside
     both = []
     for planned in ("1", "0"):
         os.environ["GINEX_PLANNED"] = planned
+        os.environ["GINEX_TRACE"] = "1"
+        if capfd is not None:
+            capfd.readouterr()
         try:
             both.append(ginex.changeset_resume(cfg.num_nodes, res.ids, res.ids_offsets, start))
         finally:
-            del os.environ["GINEX_PLANNED"]
+            del os.environ["GINEX_PLANNED"], os.environ["GINEX_TRACE"]
+        if capfd is not None:   # the first call really went the loop-free way, the second did not
+            said = capfd.readouterr().err
+            assert ("planned path" in said) == (planned == "1"), said
     a, b = both
     assert int(a.cs_offsets[-1]) > 0
     assert np.array_equal(a.cs_offsets, b.cs_offsets) and np.array_equal(a.miss_count, b.miss_count)
@@ -175,7 +182,7 @@ def carried_cache_both_ways(ginex, cfg, res, ids, distinct):
         f"({int(a.cs_offsets[-1])} changes, {int(a.miss_count.sum())} misses, {time.time() - t:.1f}s)")
 
 
-def widened_rows(ginex, w, res, ref, distinct):
+def widened_rows(ginex, w, res, ref, distinct, capfd=None):
     """The rows built after the main path, at full size: LRU changesets, changesets resumed
     from a carried cache state, the neighbour cache and sampling through it."""
     cfg = w.cfg
@@ -203,11 +210,20 @@ def widened_rows(ginex, w, res, ref, distinct):
     rows = np.unique(ids)
     gone = rng.random(len(rows)) < 0.01
     outside = np.setdiff1d(np.arange(0, cfg.num_nodes, 37, dtype=np.int64), rows)
-    outside = outside[:100000 + int(gone.sum())]
+    outside = outside[np.linspace(0, len(outside) - 1, 100000 + int(gone.sum())).astype(np.int64)]
     start = rng.permutation(np.concatenate([rows[~gone], outside])).astype(np.int32)
     assert len(start) >= len(rows)
     rcs = oracle.changeset_resume(cfg.num_nodes, ids, io, len(start), start)
-    cs = ginex.changeset_resume(cfg.num_nodes, res.ids, res.ids_offsets, dev(start))
+    os.environ["GINEX_TRACE"] = "1"
+    if capfd is not None:
+        capfd.readouterr()
+    try:
+        cs = ginex.changeset_resume(cfg.num_nodes, res.ids, res.ids_offsets, dev(start))
+    finally:
+        del os.environ["GINEX_TRACE"]
+    if capfd is not None:
+        said = capfd.readouterr().err
+        assert "planned path" in said, said
     compare_changeset(cs, rcs)
     assert np.array_equal(cs.final_ids.cpu().numpy(), rcs["final_ids"])
     assert np.array_equal(cs.src_line.cpu().numpy(),
@@ -231,12 +247,12 @@ def widened_rows(ginex, w, res, ref, distinct):
     say(f"neighbour cache parity ok: {cached} nodes cached ({time.time() - t:.1f}s)")
 
 
-def test_full_size_config3():
-    run_full(3, extras=True)
+def test_full_size_config3(capfd):
+    run_full(3, extras=True, capfd=capfd)
 
 
-def test_full_size_config4():
-    run_full(4)
+def test_full_size_config4(capfd):
+    run_full(4, capfd=capfd)
 
 
 @pytest.mark.heavy
