@@ -787,6 +787,49 @@ def test_carried_cache_that_holds_the_superbatch_needs_no_loop(ginex, monkeypatc
     monkeypatch.delenv("GINEX_PLANNED", raising=False)
 
 
+def test_one_workspace_serves_every_kind_of_call_in_any_order(ginex, case1):
+    """Sampling, changesets with and without pressure, LRU, resumed changesets through the loop
+    and without it, all on ONE workspace filled with junk in between: no call relies on what an
+    earlier one left there."""
+    c = case1
+    n, S = c.cfg.num_nodes, c.cfg.S
+    ids, io = c.samp["ids"], c.samp["ids_offsets"]
+    ids_d = dev(ids)
+    distinct = len(np.unique(ids))
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(3)
+    start_small = rng.permutation(n)[:max(1, distinct // 8)].astype(np.int32)
+    rows = np.unique(ids)
+    others = np.setdiff1d(np.arange(n), rows)
+    keep = rows[rng.random(len(rows)) < 0.9]
+    start_big = rng.permutation(np.concatenate([keep, others[:len(rows) - len(keep) + 200]])).astype(np.int32)
+    calls = [
+        ("belady", lambda: ginex.changeset(n, ids_d, io, distinct // 8, workspace=ws),
+         lambda: oracle.changeset(n, ids, io, distinct // 8)),
+        ("resume, no loop", lambda: ginex.changeset_resume(n, ids_d, io, dev(start_big), workspace=ws),
+         lambda: oracle.changeset_resume(n, ids, io, len(start_big), start_big)),
+        ("lru", lambda: ginex.changeset(n, ids_d, io, distinct // 8, workspace=ws, policy="lru"),
+         lambda: oracle.changeset_lru(n, ids, io, distinct // 8)),
+        ("resume, loop", lambda: ginex.changeset_resume(n, ids_d, io, dev(start_small), workspace=ws),
+         lambda: oracle.changeset_resume(n, ids, io, len(start_small), start_small)),
+        ("all fit", lambda: ginex.changeset(n, ids_d, io, distinct + 5, workspace=ws),
+         lambda: oracle.changeset(n, ids, io, distinct + 5)),
+    ]
+    refs = [ref() for _, _, ref in calls]
+    for order in (range(len(calls)), reversed(range(len(calls))), (1, 1, 3, 1, 0, 1)):
+        for k in order:
+            ws.random_(0, 256)                     # junk, different every time
+            name, run, _ = calls[k]
+            res = run()
+            check_changeset(res, refs[k], (n, ids, io))
+            if "resume" in name:
+                assert np.array_equal(res.final_ids.cpu().numpy(), refs[k]["final_ids"]), name
+        ws.random_(0, 256)
+        samp = ginex.sample_superbatch(c.w.offsets, c.w.indices, c.w.seeds.cuda(), c.seed_off,
+                                       c.cfg.fanout, rng_seed=0, workspace=ws)
+        check_sample(samp, c.samp, S, len(c.cfg.fanout))
+
+
 def test_carried_cache_over_consecutive_superbatches(ginex, case2):
     from workload.configs import seed_batches, train_nodes
     c = case2
