@@ -20,6 +20,14 @@
  *    GINEX_ERR_CAPACITY the required element counts are written to the host size
  *    outputs and the contents of the output arrays are unspecified.
  *  - Node ids are int32 in [0, num_nodes); CSR offsets are int32 or int64.
+ *  - Environment switches, read at every call; none changes a result, only the way to it:
+ *      GINEX_VALIDATE=1       check the documented preconditions on the device first
+ *      GINEX_TRACE=1          ginex_changeset_resume reports on stderr which way it went
+ *      GINEX_SAMPLER_LDS=0    seeds and first hop through the tables in HBM like the later hops
+ *      GINEX_SAMPLER_TILES=n  at most n tiles of a batch per workgroup column of the sampler
+ *      GINEX_DEAD_SCATTER=0/1 evictions among dead rows from a pass over the lines / from the id bitmap
+ *      GINEX_LIVE_SELECT=1    no shortcut that relies on the cache holding the whole superbatch
+ *      GINEX_PLANNED=0        a carried cache that holds the whole superbatch still runs the loop
  */
 #ifndef GINEX_H
 #define GINEX_H
