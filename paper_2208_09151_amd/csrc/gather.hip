@@ -14,6 +14,11 @@ namespace {
 typedef unsigned int chunk_t __attribute__((ext_vector_type(4)));  // 16 bytes
 constexpr int THREADS = 256;
 constexpr int UNROLL = 4;
+// chunks per thread in k_gather_lines: with one dependent load less per chunk than k_gather and
+// no id load in all-resident waves, two chunks per thread (twice the waves) beat four
+// (30.3 against 31.8 us per launch on configuration 4; 1: 32.1, 3: 31.3, 6: 32.3, 8: 32.7);
+// a launch that is bound by the host link keeps four, like the cache fill
+constexpr int LINES_UNROLL = 2;
 // The gather runs in blocks of one wave: finer to schedule at the end of a launch (37.7 us
 // per 177 k rows of 512 B against 38.3 with 256 threads and 39.9 with 1024); four chunks per
 // thread (1, 2, 6, 8 are 1-5 % slower).
@@ -68,7 +73,7 @@ __global__ __launch_bounds__(GATHER_THREADS) void k_gather(
 // 4-byte probe of the address table (a 128-byte line fetched per row) and one level of the
 // dependent load chain are gone: what is left per row is R bytes in, R bytes out and 8 bytes
 // of sequential index data.
-template <int SHIFT>
+template <int SHIFT, int U>
 __global__ __launch_bounds__(GATHER_THREADS) void k_gather_lines(
     const chunk_t* __restrict__ rows, const chunk_t* __restrict__ slow,
     const int32_t* __restrict__ ids, const int32_t* __restrict__ lines, int64_t n,
@@ -76,25 +81,40 @@ __global__ __launch_bounds__(GATHER_THREADS) void k_gather_lines(
   const int64_t total = n * cpr;
   const int64_t span = (int64_t)gridDim.x * GATHER_THREADS;
   int64_t c0 = (int64_t)blockIdx.x * GATHER_THREADS + threadIdx.x;
-  for (; c0 < total; c0 += span * UNROLL) {
-    int32_t id[UNROLL], line[UNROLL], col[UNROLL];
-    chunk_t v[UNROLL];
+  for (; c0 < total; c0 += span * U) {
+    int64_t p[U];
+    int32_t line[U], col[U];
+    chunk_t v[U];
+    bool slow_row = false;
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
+    for (int u = 0; u < U; ++u) {
       int64_t c = c0 + u * span;
       c = c < total ? c : c0;
-      const int64_t p = SHIFT >= 0 ? c >> (SHIFT & 31) : c / cpr;
-      col[u] = SHIFT >= 0 ? (int32_t)(c & ((1 << (SHIFT & 31)) - 1)) : (int32_t)(c - p * cpr);
-      id[u] = ids[p];
-      line[u] = lines[p];
+      p[u] = SHIFT >= 0 ? c >> (SHIFT & 31) : c / cpr;
+      col[u] = SHIFT >= 0 ? (int32_t)(c & ((1 << (SHIFT & 31)) - 1)) : (int32_t)(c - p[u] * cpr);
+      line[u] = lines[p[u]];
     }
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-      const chunk_t* src = line[u] >= 0 ? rows + (int64_t)line[u] * cpr : slow + (int64_t)id[u] * cpr;
-      v[u] = src[col[u]];
+    for (int u = 0; u < U; ++u) slow_row |= line[u] < 0;
+    // The node id of a row is needed only where the row comes from the slow tier: a wave
+    // whose rows are all resident (every wave of an iteration without misses) never loads
+    // one.  The test is per wave, so both ways stay straight-line code with the loads of a
+    // level in flight together.
+    if (!__any(slow_row)) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) v[u] = rows[(int64_t)line[u] * cpr + col[u]];
+    } else {
+      int32_t id[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) id[u] = ids[p[u]];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const chunk_t* src = line[u] >= 0 ? rows + (int64_t)line[u] * cpr : slow + (int64_t)id[u] * cpr;
+        v[u] = src[col[u]];
+      }
     }
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int64_t c = c0 + u * span;
       if (c < total) __builtin_nontemporal_store(v[u], out + c);
     }
@@ -361,22 +381,28 @@ int32_t gather_run(const char* who, const ginex_cache_t* c, const int32_t* ids,
   if (n > 0) {
     const int32_t cpr = (int32_t)(c->row_bytes / 16);
     // one pass of the kernel's loop up to 2^24 blocks (8 TB of rows), more passes beyond
-    int64_t blocks = ceil_div(n * cpr, (int64_t)GATHER_THREADS * UNROLL);
+    const bool link_bound = n_slow > 0 && n_slow * 4 >= n * 3;
+    const int per_thread = lines && !link_bound ? LINES_UNROLL : UNROLL;
+    int64_t blocks = ceil_div(n * cpr, (int64_t)GATHER_THREADS * per_thread);
     if (blocks > (1 << 24)) blocks = 1 << 24;
     // A launch that reads at least three quarters of its rows from the slow tier runs on a
     // smaller grid whose blocks stride over the rows, so that about as many link reads are in
     // flight as the cache fill keeps (51.8 -> 56.2 GB/s with nothing resident).  With fewer
     // slow rows the smaller grid starves the resident ones of HBM parallelism (at 42 % slow
     // rows the launch took 3 % longer), so those keep the full grid.
-    if (n_slow > 0 && n_slow * 4 >= n * 3) {
+    if (link_bound) {
       const int64_t want = ceil_div(LINK_CHUNKS_IN_FLIGHT * n, n_slow * (int64_t)GATHER_THREADS * UNROLL);
       if (want < blocks) blocks = want;
     }
     const dim3 grid((unsigned)blocks);
 #define GINEX_GATHER(S)                                                                       \
   do {                                                                                        \
-    if (lines)                                                                                \
-      hipLaunchKernelGGL((k_gather_lines<S>), grid, dim3(GATHER_THREADS), 0, st,               \
+    if (lines && link_bound)                                                                  \
+      hipLaunchKernelGGL((k_gather_lines<S, UNROLL>), grid, dim3(GATHER_THREADS), 0, st,       \
+                         (const chunk_t*)c->rows, (const chunk_t*)c->slow, ids, lines, n, cpr, \
+                         (chunk_t*)out);                                                      \
+    else if (lines)                                                                           \
+      hipLaunchKernelGGL((k_gather_lines<S, LINES_UNROLL>), grid, dim3(GATHER_THREADS), 0, st, \
                          (const chunk_t*)c->rows, (const chunk_t*)c->slow, ids, lines, n, cpr, \
                          (chunk_t*)out);                                                      \
     else                                                                                      \
