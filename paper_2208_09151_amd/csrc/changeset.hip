@@ -1015,6 +1015,7 @@ __global__ __launch_bounds__(TB) void k_part_count(const uint32_t* __restrict__ 
 constexpr int PLAN_CAND_WORDS = 16384;              // LDS bitmap of the replay ...
 constexpr int PLAN_CAND_MAX = PLAN_CAND_WORDS * 32; // ... over at most 524 288 candidates
 constexpr int PLAN_SORT_MAX = 4096;      // evictions of one iteration the replay can order
+constexpr int PLAN_RANK_DIRECT = 256;    // up to here every eviction is compared with every other
 // (the replay's LDS: 64 KB of bitmap, 32 KB for the ordering, 16 KB of offsets; a workgroup
 // of this GPU may use up to 160 KB)
 constexpr int PLAN_S_MAX = 2048;         // iterations (LDS histograms of k_plan_heads)
@@ -1214,7 +1215,7 @@ __global__ __launch_bounds__(TB) void k_cand_start(const uint32_t* __restrict__ 
 // does not hold is resident only if it was inserted, that is, if it has an earlier access.)
 __device__ __forceinline__ bool plan_arrival(const uint64_t* __restrict__ sorted, int64_t n,
                                              int64_t j, const int32_t* __restrict__ addr,
-                                             const int64_t* __restrict__ off, int32_t S,
+                                             const int32_t* off, int32_t S,
                                              int32_t& v, int32_t& d, bool& inserted) {
   const uint64_t cur = sorted[j];
   v = (int32_t)(cur >> 32);
@@ -1222,20 +1223,17 @@ __device__ __forceinline__ bool plan_arrival(const uint64_t* __restrict__ sorted
   const bool earlier = j > 0 && (int32_t)(sorted[j - 1] >> 32) == v;
   inserted = addr[v] < 0;
   if (!earlier && inserted) return false;
-  const int64_t p = (int64_t)(cur & 0xFFFFFFFFu);
-  int32_t lo = 0, hi = S;
-  while (hi - lo > 1) {
-    const int32_t mid = (lo + hi) >> 1;
-    if (off[mid] <= p) lo = mid; else hi = mid;
-  }
-  d = lo;
+  d = iter_of(off, S, (int32_t)(cur & 0xFFFFFFFFu));
   return true;
 }
 
 // ... then (PLACE = false) the rows >= lo_id that die during the superbatch, counted per
 // iteration at arr_off[d + 1].  PLACE = true, after the candidates are numbered: their numbers
 // go to arr_cand at the cursors, and a row that is inserted during this call leaves its number
-// with its insertion record.
+// with its insertion record.  A block works on one stretch of the sorted pairs and counts
+// per iteration in LDS first, so that the counters and cursors in global memory, a few
+// addresses that every arrival would otherwise meet at, see one atomic per block and iteration.
+// lds: S + 1 offsets, S counters.
 template <bool PLACE>
 __global__ __launch_bounds__(TB) void k_plan_arrivals(const uint64_t* __restrict__ sorted, int64_t n,
                                                       const int64_t* __restrict__ scalars,
@@ -1244,24 +1242,44 @@ __global__ __launch_bounds__(TB) void k_plan_arrivals(const uint64_t* __restrict
                                                       uint32_t* __restrict__ cand_bits,
                                                       const uint32_t* __restrict__ cand_base,
                                                       int64_t num_nodes, Plan pl) {
+  extern __shared__ int32_t lds_off[];
+  uint32_t* s_cnt = reinterpret_cast<uint32_t*>(lds_off + S + 1);
   const int64_t lo_id = scalars[PLAN_LO_ID];
   if (lo_id < 0 || lo_id >= num_nodes) return;
+  for (int d = threadIdx.x; d < S; d += TB) s_cnt[d] = 0;
+  load_offsets(lds_off, off, S);
   const int64_t lo_word = lo_id >> 5;
-  const int64_t span = (int64_t)gridDim.x * TB;
-  for (int64_t j = scalars[PLAN_TAIL] + (int64_t)blockIdx.x * TB + threadIdx.x; j < n; j += span) {
+  const int64_t tail = scalars[PLAN_TAIL];
+  const int64_t per = (((n - tail + gridDim.x - 1) / gridDim.x + TB - 1) / TB) * TB;
+  const int64_t first = tail + (int64_t)blockIdx.x * per;
+  const int64_t last = first + per < n ? first + per : n;
+  for (int64_t j = first + threadIdx.x; j < last; j += TB) {
     int32_t v, d;
     bool inserted;
-    if (!plan_arrival(sorted, n, j, addr, off, S, v, d, inserted)) continue;
-    const uint32_t below = (1u << (v & 31)) - 1u;
+    if (!plan_arrival(sorted, n, j, addr, lds_off, S, v, d, inserted)) continue;
+    if (!PLACE) atomicOr(&cand_bits[(uint32_t)v >> 5], 1u << (v & 31));
+    atomicAdd(&s_cnt[d], 1u);
+  }
+  __syncthreads();
+  for (int d = threadIdx.x; d < S; d += TB) {
+    const uint32_t c = s_cnt[d];
     if (!PLACE) {
-      atomicOr(&cand_bits[(uint32_t)v >> 5], 1u << (v & 31));
-      atomicAdd(&pl.arr_off[d + 1], 1u);
-      continue;
+      if (c) atomicAdd(&pl.arr_off[d + 1], c);
+    } else {
+      s_cnt[d] = c ? atomicAdd(&pl.arr_cur[d], c) : 0u;   // the block's places in the iteration's list
     }
+  }
+  if (!PLACE) return;
+  __syncthreads();
+  for (int64_t j = first + threadIdx.x; j < last; j += TB) {
+    int32_t v, d;
+    bool inserted;
+    if (!plan_arrival(sorted, n, j, addr, lds_off, S, v, d, inserted)) continue;
+    const uint32_t below = (1u << (v & 31)) - 1u;
     const uint32_t c = cand_base[((uint32_t)v >> 5) - lo_word] + __popc(cand_bits[(uint32_t)v >> 5] & below);
-    if (c >= (uint32_t)PLAN_CAND_MAX) continue;     // too many candidates: the replay will not run
-    pl.arr_cand[atomicAdd(&pl.arr_cur[d], 1u)] = (int32_t)c;
-    if (inserted) {
+    // (the host takes this path only with at most PLAN_CAND_MAX candidates: c is below that)
+    pl.arr_cand[atomicAdd(&s_cnt[d], 1u)] = (int32_t)c;
+    if (inserted && c < (uint32_t)PLAN_CAND_MAX) {
       int64_t h = j;                                 // the row's first access is its insertion
       while (h > 0 && (int32_t)(sorted[h - 1] >> 32) == v) --h;
       const uint32_t p = (uint32_t)(sorted[h] & 0xFFFFFFFFu);
@@ -1319,6 +1337,26 @@ __global__ __launch_bounds__(BIG) void k_plan_arrival_offsets(uint32_t* __restri
   if (threadIdx.x == 0) scalars[PLAN_CANDS] = scalars[PLAN_M] + (int64_t)total;
 }
 
+// Exclusive prefix of v over the BIG threads of the block, and the block total, with a single
+// barrier: every thread adds up the totals of the waves in front of its own.  `slots` (one
+// per wave) must not be rewritten before a later barrier.
+__device__ __forceinline__ uint32_t block_prefix_one_barrier(uint32_t v, uint32_t* slots,
+                                                             uint32_t& total) {
+  const uint32_t inc = wave_inclusive_scan(v);
+  const int w = threadIdx.x / WAVE;
+  if (lane_id() == WAVE - 1) slots[w] = inc;
+  __syncthreads();
+  uint32_t before = 0, all = 0;
+#pragma unroll
+  for (int q = 0; q < BIG / WAVE; ++q) {
+    const uint32_t t = slots[q];
+    all += t;
+    if (q < w) before += t;
+  }
+  total = all;
+  return before + inc - v;
+}
+
 // The replay (see the head of this part).  One block.  scalars[PLAN_FAILED] is set, before the
 // state is touched, when there are more candidates than the bitmap holds, and later if an
 // invariant does not hold; the host then runs the loop instead.
@@ -1330,13 +1368,17 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
                                                      const int64_t* __restrict__ cs_offsets,
                                                      const int32_t* __restrict__ in_ids,
                                                      int32_t* __restrict__ out_ids) {
-  __shared__ uint32_t bits[PLAN_CAND_WORDS];
+  __shared__ uint32_t bits[PLAN_CAND_WORDS + BIG];   // room for one more word per thread, see WPT
   __shared__ int32_t s_a[PLAN_SORT_MAX];
   __shared__ int32_t s_b[PLAN_SORT_MAX];
   __shared__ uint32_t s_arr[PLAN_S_MAX + 1];       // arr_off
   __shared__ int32_t s_cs[PLAN_S_MAX + 1];         // cs_offsets (below 2^31: they index int32 lists)
-  __shared__ uint32_t smem[BIG / WAVE + 1];
+  __shared__ uint32_t slots_select[BIG / WAVE], slots_rank[BIG / WAVE];
+  __shared__ int32_t slots_lo[BIG / WAVE], slots_hi[BIG / WAVE];
   __shared__ int32_t s_failed;
+  static_assert(PLAN_CAND_WORDS + BIG <= (1 << 26), "a noted word packs its index and a count up to 32");
+  static_assert(BIG + PLAN_SORT_MAX / 2 <= PLAN_SORT_MAX && 2 * BIG <= PLAN_SORT_MAX,
+                "the fine buckets of the ranking and the coarse buckets' records fit the two arrays");
   constexpr int EPT = PLAN_SORT_MAX / BIG;         // evictions of a thread
   const int32_t S = st.S;
   const uint32_t n_cand = pl.cand_tiles[n_cand_tiles];
@@ -1344,9 +1386,11 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
     if (threadIdx.x == 0) pl.scalars[PLAN_FAILED] = 4;
     return;
   }
-  // consecutive bitmap words of a thread: as many as the candidates there are need
-  const int WPT = (int)(((n_cand + 31) / 32 + BIG - 1) / BIG);
-  for (int w = threadIdx.x; w < WPT * BIG; w += BIG) bits[w] = pl.cand_dead[w];
+  // consecutive bitmap words of a thread: as many as the candidates there are need, and an
+  // odd number, so that the threads of a wave that read their t-th word hit different banks
+  int WPT = (int)(((n_cand + 31) / 32 + BIG - 1) / BIG);
+  if (WPT > 1) WPT |= 1;
+  for (int w = threadIdx.x; w < WPT * BIG; w += BIG) bits[w] = w < PLAN_CAND_WORDS ? pl.cand_dead[w] : 0u;
   for (int j = threadIdx.x; j <= S; j += BIG) {
     s_arr[j] = pl.arr_off[j];
     s_cs[j] = (int32_t)cs_offsets[j];
@@ -1354,11 +1398,11 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
   if (threadIdx.x == 0) s_failed = 0;
   __syncthreads();
   // requested ahead for iteration 0
-  int32_t next_arr = threadIdx.x < s_arr[1] ? pl.arr_cand[threadIdx.x] : -1;
-  int32_t next_in[EPT], next_ic[EPT];
+  int32_t next_arr[EPT], next_in[EPT], next_ic[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
     const int32_t k = threadIdx.x + e * BIG;
+    next_arr[e] = (uint32_t)k < s_arr[1] ? pl.arr_cand[k] : -1;
     const bool have = k < s_cs[1];
     next_in[e] = have ? in_ids[k] : -1;
     next_ic[e] = have ? pl.ins_cand[k] : -1;
@@ -1368,8 +1412,10 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
     const int32_t c0 = s_cs[i];
     const int32_t n = s_cs[i + 1] - c0;
     // the rows whose last access is in this iteration are dead from here on
-    if (next_arr >= 0) atomicOr(&bits[(uint32_t)next_arr >> 5], 1u << (next_arr & 31));
-    for (uint32_t a = a0 + BIG + threadIdx.x; a < a1; a += BIG) {
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+      if (next_arr[e] >= 0) atomicOr(&bits[(uint32_t)next_arr[e] >> 5], 1u << (next_arr[e] & 31));
+    for (uint32_t a = a0 + EPT * BIG + threadIdx.x; a < a1; a += BIG) {
       const uint32_t c = (uint32_t)pl.arr_cand[a];
       atomicOr(&bits[c >> 5], 1u << (c & 31));
     }
@@ -1380,22 +1426,24 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
       my_ic[e] = next_ic[e];
     }
     if (i + 1 < S) {        // the requests for the next iteration
-      next_arr = a1 + threadIdx.x < s_arr[i + 2] ? pl.arr_cand[a1 + threadIdx.x] : -1;
       const int32_t c1 = s_cs[i + 1], n1 = s_cs[i + 2] - c1;
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
         const int32_t k = threadIdx.x + e * BIG;
+        next_arr[e] = a1 + (uint32_t)k < s_arr[i + 2] ? pl.arr_cand[a1 + k] : -1;
         next_in[e] = k < n1 ? in_ids[c1 + k] : -1;
         next_ic[e] = k < n1 ? pl.ins_cand[c1 + k] : -1;
       }
     }
     if (n == 0) continue;   // uniform; the next barrier orders the bits set above
+    if (WPT > 1)            // (s_b is free: the barrier that ended the iteration before)
+      for (int32_t q = threadIdx.x; q < n; q += BIG) s_b[q] = -1;
     __syncthreads();
     // the top n set bits: set bits of the chunks above a thread's own, from a block scan
     uint32_t cnt = 0;
     for (int t = 0; t < WPT; ++t) cnt += __popc(bits[threadIdx.x * WPT + t]);
     uint32_t total;
-    const uint32_t below = block_exclusive_scan<uint32_t, BIG>(cnt, smem, total);
+    const uint32_t below = block_prefix_one_barrier(cnt, slots_select, total);
     const uint32_t above = total - below - cnt;
     if (total < (uint32_t)n) {                      // cannot happen (see the head of this part)
       s_failed = 1;
@@ -1403,19 +1451,48 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
     } else if (above < (uint32_t)n) {
       uint32_t take = cnt < (uint32_t)n - above ? cnt : (uint32_t)n - above;
       uint32_t k = above;
-      for (int t = WPT - 1; t >= 0 && take; --t) {
-        uint32_t word = bits[threadIdx.x * WPT + t];
-        while (word && take) {
+      if (WPT == 1) {
+        uint32_t word = bits[threadIdx.x];
+        while (take) {
           const int b = 31 - __clz(word);
           word &= ~(1u << b);
-          s_a[k++] = (int32_t)((threadIdx.x * WPT + t) * 32 + b);
+          s_a[k++] = (int32_t)(threadIdx.x * 32 + b);
           --take;
         }
-        bits[threadIdx.x * WPT + t] = word;
+        bits[threadIdx.x] = word;
+      } else {
+        // Several words per thread: the selection falls on the few threads at the upper end,
+        // hundreds of bits each.  They only note their words (word and bits to take from its
+        // top, in s_b at the word's first place in s_a; the other entries of s_b are -1), and
+        // the whole block then takes the words apart, one a thread.
+        for (int t = WPT - 1; t >= 0 && take; --t) {
+          const uint32_t wi = threadIdx.x * WPT + t;
+          const uint32_t pc = (uint32_t)__popc(bits[wi]);
+          if (!pc) continue;
+          const uint32_t tw = pc < take ? pc : take;
+          s_b[k] = (int32_t)((wi << 5) | (tw - 1));
+          k += tw;
+          take -= tw;
+        }
       }
     }
     __syncthreads();
     if (s_failed) break;                            // uniform
+    if (WPT > 1) {
+      for (uint32_t q = threadIdx.x; q < (uint32_t)n; q += BIG) {
+        const int32_t d = s_b[q];
+        if (d < 0) continue;
+        const uint32_t wi = (uint32_t)d >> 5, tw = ((uint32_t)d & 31u) + 1u;
+        uint32_t word = bits[wi];
+        for (uint32_t r = 0; r < tw; ++r) {
+          const int b = 31 - __clz(word);
+          word &= ~(1u << b);
+          s_a[q + r] = (int32_t)(wi * 32 + b);
+        }
+        bits[wi] = word;
+      }
+      __syncthreads();
+    }
     // the evicted rows and their lines
     int32_t my_v[EPT], my_line[EPT];
 #pragma unroll
@@ -1432,19 +1509,123 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
         pl.scalars[PLAN_WHERE] = i;
       }
     }
+    if (n > PLAN_RANK_DIRECT) {                     // uniform: the range of the evicted lines
+      int32_t lo = INT32_MAX, hi = 0;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e)
+        if (my_v[e] >= 0) {
+          lo = my_line[e] < lo ? my_line[e] : lo;
+          hi = my_line[e] > hi ? my_line[e] : hi;
+        }
+#pragma unroll
+      for (int d = WAVE / 2; d > 0; d >>= 1) {
+        const int32_t olo = __shfl_xor(lo, d, WAVE), ohi = __shfl_xor(hi, d, WAVE);
+        lo = olo < lo ? olo : lo;
+        hi = ohi > hi ? ohi : hi;
+      }
+      if (lane_id() == 0) {
+        slots_lo[threadIdx.x / WAVE] = lo;
+        slots_hi[threadIdx.x / WAVE] = hi;
+      }
+    }
     __syncthreads();
     if (s_failed) break;                            // uniform; no line may be used as an index then
     // out_ids in line order: the rank of a line is the number of smaller ones
     int32_t my_rank[EPT];
+    if (n <= PLAN_RANK_DIRECT) {                    // uniform: every thread counts over all lines
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      my_rank[e] = 0;
-      if (my_v[e] < 0) continue;
-      int32_t r = 0;
-      for (int32_t q = 0; q < n; ++q) r += s_b[q] < my_line[e];
-      my_rank[e] = r;
-      out_ids[c0 + r] = my_v[e];
+      for (int e = 0; e < EPT; ++e) {
+        my_rank[e] = 0;
+        if (my_v[e] < 0) continue;
+        int32_t r = 0;
+        for (int32_t q = 0; q < n; ++q) r += s_b[q] < my_line[e];
+        my_rank[e] = r;
+      }
+    } else {
+      // Many evictions: the lines are dealt to buckets that grow with the line, a scan of the
+      // bucket sizes gives the number of lines in the buckets below, and a line is compared
+      // with the members of its own bucket only.  The evicted lines crowd where rows come and
+      // go, so buckets of equal width over their range would leave most of them in a few:
+      // BIG coarse buckets of equal width are counted first, and a coarse bucket with m
+      // members is cut into about m/4 fine ones (a power of two, at most one per line), fewer
+      // than BIG + n/2 in all.
+      // s_a is free (every thread has read its candidates): the fine counters; s_b holds the
+      // coarse counts, then first fine bucket and cut of every coarse bucket, then the lines
+      // by fine bucket.
+      int32_t range_lo = INT32_MAX, range_hi = 0;
+#pragma unroll
+      for (int q = 0; q < BIG / WAVE; ++q) {
+        range_lo = slots_lo[q] < range_lo ? slots_lo[q] : range_lo;
+        range_hi = slots_hi[q] > range_hi ? slots_hi[q] : range_hi;
+      }
+      int coarse_shift = 0;                         // (line - range_lo) >> coarse_shift < BIG
+      while (((range_hi - range_lo) >> coarse_shift) >= BIG) ++coarse_shift;
+      s_b[threadIdx.x] = 0;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) s_a[threadIdx.x + e * BIG] = 0;
+      __syncthreads();
+      int32_t coarse[EPT], bucket[EPT], slot[EPT];
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        coarse[e] = bucket[e] = slot[e] = 0;
+        if (my_v[e] < 0) continue;
+        coarse[e] = (my_line[e] - range_lo) >> coarse_shift;
+        atomicAdd(&s_b[coarse[e]], 1);
+      }
+      __syncthreads();
+      {
+        const uint32_t members = (uint32_t)s_b[threadIdx.x];
+        int cut = 0;                                // the coarse bucket becomes 1 << cut fine ones
+        while ((4u << cut) < members && cut < coarse_shift) ++cut;
+        uint32_t fine_total;
+        const uint32_t fine_first = block_prefix_one_barrier(1u << cut, slots_rank, fine_total);
+        s_b[threadIdx.x] = (int32_t)fine_first;     // (only this thread read the entry)
+        s_b[BIG + threadIdx.x] = cut;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        if (my_v[e] < 0) continue;
+        const int cut = s_b[BIG + coarse[e]];
+        const int32_t within = (my_line[e] - range_lo) & ((1 << coarse_shift) - 1);
+        bucket[e] = s_b[coarse[e]] + (within >> (coarse_shift - cut));
+        slot[e] = atomicAdd(&s_a[bucket[e]], 1);
+      }
+      __syncthreads();
+      {
+        uint32_t cnt_b[EPT], sum = 0;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+          cnt_b[e] = (uint32_t)s_a[threadIdx.x * EPT + e];
+          sum += cnt_b[e];
+        }
+        uint32_t all;
+        uint32_t run = block_prefix_one_barrier(sum, slots_select, all);
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+          s_a[threadIdx.x * EPT + e] = (int32_t)run;
+          run += cnt_b[e];
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < EPT; ++e)
+        if (my_v[e] >= 0) s_b[s_a[bucket[e]] + slot[e]] = my_line[e];
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        my_rank[e] = 0;
+        if (my_v[e] < 0) continue;
+        const int32_t first = s_a[bucket[e]];
+        const int32_t end = bucket[e] + 1 < PLAN_SORT_MAX ? s_a[bucket[e] + 1] : n;
+        int32_t r = first;
+        for (int32_t q = first; q < end; ++q) r += s_b[q] < my_line[e];
+        my_rank[e] = r;
+      }
     }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+      if (my_v[e] >= 0) out_ids[c0 + my_rank[e]] = my_v[e];
     __syncthreads();   // both arrays are free now: they carry the insertions to the threads that hold their lines
 #pragma unroll
     for (int e = 0; e < EPT; ++e)
@@ -1804,7 +1985,7 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       tail_blocks = tail_blocks < 1 ? 1 : (tail_blocks > 1024 ? 1024 : tail_blocks);
       hipLaunchKernelGGL(k_cand_start, dim3((unsigned)tail_blocks), dim3(TB), 0, st,
                          state.dead_bits, state.words, num_nodes, pl.scalars, state.bitmap);
-      hipLaunchKernelGGL(k_plan_arrivals<false>, dim3((unsigned)tail_blocks), dim3(TB), 0, st,
+      hipLaunchKernelGGL(k_plan_arrivals<false>, dim3((unsigned)tail_blocks), dim3(TB), 2 * off_lds, st,
                          sorted, total, pl.scalars, state.addr, w.d_offsets, S, state.bitmap,
                          pl.cand_base, num_nodes, pl);
       hipLaunchKernelGGL(k_plan_arrival_offsets, dim3(1), dim3(BIG), 0, st, pl.arr_off,
@@ -1856,7 +2037,7 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                                                    pl.cand_tiles + ctiles + 1, st));
         hipLaunchKernelGGL(k_cand_emit, dim3((unsigned)ctiles), dim3(TB), 0, st, state.bitmap,
                            state.dead_bits, lo_word, nwords, pl.cand_tiles, state.addr, pl);
-        hipLaunchKernelGGL(k_plan_arrivals<true>, dim3((unsigned)tail_blocks), dim3(TB), 0, st,
+        hipLaunchKernelGGL(k_plan_arrivals<true>, dim3((unsigned)tail_blocks), dim3(TB), 2 * off_lds, st,
                            sorted, total, pl.scalars, state.addr, w.d_offsets, S, state.bitmap,
                            pl.cand_base, num_nodes, pl);
         hipLaunchKernelGGL(k_plan_replay, dim3(1), dim3(BIG), 0, st, state, pl, ctiles, cs_offsets,

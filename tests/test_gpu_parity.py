@@ -735,6 +735,29 @@ def planned_cases(rng):
         tr = [rows, rows[::-1].copy(), rng.permutation(n)[:100]]
         off = np.cumsum([0] + [len(t) for t in tr]).astype(np.int64)
         yield kind, n, np.concatenate(tr).astype(np.int32), off, np.arange(6000, dtype=np.int32)
+    # 4b. thousands of evictions in one iteration whose lines all lie at the upper end of a
+    #     large cache (the ranking by line then finds them in a few of its buckets)
+    n = 1000000
+    rows = np.arange(700000, 703000)
+    tr = [rng.permutation(rows), rows[::-1].copy(), rng.permutation(rows)[:1200]]
+    off = np.cumsum([0] + [len(t) for t in tr]).astype(np.int64)
+    yield "clustered", n, np.concatenate(tr).astype(np.int32), off, np.arange(700000, dtype=np.int32)
+    # 4c. tens of thousands of candidates (several bitmap words per thread of the replay): most
+    #     rows of the upper half of the start state are accessed once and die on the way, one
+    #     in twenty is dead from the start, and two waves of new rows push rows out
+    n = 300000
+    upper = np.arange(100000, 200000)
+    once = upper[upper % 20 != 7]
+    tr = [[] for _ in range(6)]
+    for i, part in enumerate(np.array_split(rng.permutation(once), 6)):
+        tr[i] = list(part)
+    first, second = np.arange(200000, 203000), np.arange(203000, 204500)
+    tr[0] += list(first); tr[3] += list(first[::-1])
+    tr[4] += list(second); tr[5] += list(second)
+    tr = [rng.permutation(np.array(t, dtype=np.int32)) for t in tr]
+    off = np.cumsum([0] + [len(t) for t in tr]).astype(np.int64)
+    yield "many_candidates", n, np.concatenate(tr).astype(np.int32), off, \
+        rng.permutation(200000).astype(np.int32)
     # 5. the rows that are dead from the start are spread thinly over a large id space: the
     #    candidates are few although the id range from the lowest possible victim up is wide
     n = 900000
