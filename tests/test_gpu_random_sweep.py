@@ -1,0 +1,110 @@
+"""Randomised parity sweeps: many small random cases per entry point, shapes and switches drawn
+at random from a fixed seed, every result compared with the oracle element by element."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from test_gpu_parity import check_changeset, check_resumed, check_sample, dev, ginex  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+
+def _trace(rng, n, S, max_len, skew):
+    tr = []
+    for _ in range(S):
+        m = int(rng.integers(0, min(max_len, n) + 1))
+        if skew and m:                       # a few hot rows that come back in most iterations
+            w = 1.0 / (1.0 + np.arange(n)) ** skew
+            tr.append(rng.choice(n, size=m, replace=False, p=w / w.sum()))
+        else:
+            tr.append(rng.choice(n, size=m, replace=False))
+    off = np.cumsum([0] + [len(x) for x in tr]).astype(np.int64)
+    ids = np.concatenate(tr).astype(np.int32) if off[-1] else np.zeros(0, dtype=np.int32)
+    return ids, off
+
+
+def _ids(ids):
+    return dev(ids) if len(ids) else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
+
+
+def test_changeset_entry_points_on_random_traces(ginex):
+    """Belady, LRU, resumed (a cache that holds the trace and one that does not) and chains of
+    resumed calls that hand final_ids on, 1 600 cases."""
+    rng = np.random.default_rng(20261127)
+    for trial in range(1600):
+        big = rng.random() < 0.25
+        n = int(rng.integers(2, 60000 if big else 600))
+        S = int(rng.integers(1, 300 if rng.random() < 0.2 else 20))
+        max_len = int(rng.integers(1, 4000 if big else 200))
+        skew = 0.0 if n > 5000 else float(rng.choice([0.0, 0.0, 0.7, 1.2]))
+        ids, off = _trace(rng, n, S, max_len, skew)
+        distinct = max(len(np.unique(ids)), 1)
+        kind = rng.choice(["belady", "lru", "resume", "chain"])
+        try:
+            if kind in ("belady", "lru"):
+                cap = int(rng.integers(0, n + 2)) if rng.random() < 0.5 else int(rng.integers(0, distinct + 1))
+                ref = (oracle.changeset if kind == "belady" else oracle.changeset_lru)(n, ids, off, cap)
+                res = ginex.changeset(n, _ids(ids), off, cap,
+                                      **({"policy": "lru"} if kind == "lru" else {}))
+                check_changeset(res, ref, (n, ids, off))
+                continue
+            holds = rng.random() < 0.6      # a line for every distinct row: no loop over the state
+            cap = int(rng.integers(min(distinct, n), n + 1)) if holds else int(rng.integers(1, n + 1))
+            start = rng.permutation(n)[:cap].astype(np.int32)
+            for _ in range(1 if kind == "resume" else int(rng.integers(2, 5))):
+                ref = oracle.changeset_resume(n, ids, off, cap, start)
+                res = ginex.changeset_resume(n, _ids(ids), off, dev(start))
+                check_resumed(res, ref, (n, ids, off))
+                start = ref["final_ids"].astype(np.int32)
+                ids, off = _trace(rng, n, S, max_len, skew)
+        except AssertionError:
+            print("failing trial", trial, kind, n, S, max_len, skew, flush=True)
+            raise
+
+
+def test_sampler_on_random_graphs_batches_and_switches(ginex, monkeypatch):
+    """Random R-MAT graphs (both offset widths), 1-3 hops with fanouts up to 64, batches from
+    empty to 1 100 seeds with and without repeats, the hash sets in LDS or in HBM, several
+    launch shapes; every fourth case feeds the sampled ids into ginex_changeset.  1 500 cases."""
+    from workload import rmat_csr
+    rng = np.random.default_rng(4242)
+    graphs = []
+    for g in range(10):
+        n = int(rng.integers(10, 20000))
+        off, ind = rmat_csr(n, int(n * rng.integers(1, 30)),
+                            (0.5, 0.2, 0.2) if g % 2 else (0.45, 0.22, 0.22),
+                            int(rng.integers(1, 1000)), "cpu", offsets_64=bool(g & 2))
+        graphs.append((n, off.numpy(), ind.numpy(), off.cuda(), ind.cuda()))
+    for trial in range(1500):
+        n, off, ind, off_d, ind_d = graphs[int(rng.integers(0, len(graphs)))]
+        H = int(rng.integers(1, 4))
+        fanout = tuple(int(rng.integers(1, 26)) if rng.random() < 0.9 else int(rng.integers(26, 65))
+                       for _ in range(H))
+        S = int(rng.integers(1, 12))
+        most = min(n, 1100 if rng.random() < 0.3 else 80)
+        sizes = [int(rng.integers(0, most + 1)) for _ in range(S)]
+        batches = [rng.choice(n, size=s, replace=bool(rng.random() < 0.1)) for s in sizes]
+        seeds = np.concatenate(batches).astype(np.int32)
+        so = np.cumsum([0] + sizes)
+        rs, fb = int(rng.integers(0, 2**31)), int(rng.integers(0, 1000))
+        monkeypatch.setenv("GINEX_SAMPLER_LDS", "1" if rng.random() < 0.7 else "0")
+        tiles = str(rng.choice(["", "1", "3", "64"]))
+        if tiles:
+            monkeypatch.setenv("GINEX_SAMPLER_TILES", tiles)
+        else:
+            monkeypatch.delenv("GINEX_SAMPLER_TILES", raising=False)
+        try:
+            ref = oracle.sample_superbatch(off, ind, seeds, so, fanout, rng_seed=rs,
+                                           first_batch_index=fb)
+            res = ginex.sample_superbatch(off_d, ind_d, _ids(seeds), so, fanout, rng_seed=rs,
+                                          first_batch_index=fb)
+            check_sample(res, ref, S, H)
+            if trial % 4 == 0 and len(ref["ids"]):
+                cap = int(rng.integers(0, n + 1))
+                cref = oracle.changeset(n, ref["ids"], ref["ids_offsets"], cap)
+                cres = ginex.changeset(n, res.ids[:res.totals[0]], res.ids_offsets, cap)
+                check_changeset(cres, cref, (n, ref["ids"], ref["ids_offsets"]))
+        except AssertionError:
+            print("failing trial", trial, n, fanout, sizes, rs, fb, flush=True)
+            raise
