@@ -161,3 +161,44 @@ def test_executor_on_random_traces_and_row_sizes(ginex):
         except AssertionError:
             print("failing trial", trial, kind, n, S, row_words, flush=True)
             raise
+
+
+def test_static_selection_and_neighbour_cache_on_random_graphs(ginex):
+    """The highest-out-degree selection and the neighbour cache (build, then sampling through
+    it with `indices` in HBM or in pinned host memory) on random R-MAT graphs of both offset
+    widths, random capacities and budgets.  300 cases."""
+    from test_gpu_parity import check_neighbor_cache
+    from workload import rmat_csr
+    rng = np.random.default_rng(777)
+    for trial in range(300):
+        n = int(rng.integers(1, 8000))
+        e = int(rng.integers(0, 25 * n + 1))
+        off, ind = rmat_csr(n, e, (0.5, 0.2, 0.2) if trial % 2 else (0.57, 0.19, 0.19),
+                            int(rng.integers(1, 10**6)), "cpu", offsets_64=bool(trial & 2))
+        e = int(off[-1])
+        off_np, ind_np = off.numpy(), ind.numpy()
+        ind_d = ind.cuda() if e else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
+        try:
+            cap = int(rng.integers(0, n + 3))
+            assert np.array_equal(ginex.static_select(n, ind_d, cap).cpu().numpy(),
+                                  oracle.static_select(n, ind_np, cap)), "static"
+            budget = int(rng.integers(0, e + n + 2))
+            nc = ginex.neighbor_cache_build(off.cuda(), ind_d, budget)
+            check_neighbor_cache(nc, oracle.neighbor_cache_build(off_np, ind_np, budget))
+            if e == 0:
+                continue
+            H = int(rng.integers(1, 4))
+            fanout = tuple(int(rng.integers(1, 20)) for _ in range(H))
+            S = int(rng.integers(1, 6))
+            sizes = [int(rng.integers(0, min(n, 200) + 1)) for _ in range(S)]
+            seeds = np.concatenate([rng.choice(n, size=s, replace=False) for s in sizes]).astype(np.int32)
+            so = np.cumsum([0] + sizes)
+            rs = int(rng.integers(0, 2**31))
+            ref = oracle.sample_superbatch(off_np, ind_np, seeds, so, fanout, rng_seed=rs)
+            where = ind.pin_memory() if trial % 3 == 0 else ind_d
+            res = ginex.sample_superbatch(off.cuda(), where, _ids(seeds), so, fanout, rng_seed=rs,
+                                          neighbor_cache=nc)
+            check_sample(res, ref, S, H)
+        except AssertionError:
+            print("failing trial", trial, n, e, flush=True)
+            raise
