@@ -48,9 +48,9 @@ SAMPLER_LINES_PER_EDGE = 2.0
 # 1.6 offsets (two 8-byte offsets per frontier node, fanout 10) + 4 x (share of new ids)
 SAMPLER_BYTES_PER_EDGE = 20.0
 # changeset, per access: four radix passes of the (node, position) pairs (8-byte histogram
-# read, 8 read, 8 written each) and the look-right pass (12); then the loop's id, key,
-# address-table probe and key refresh (16)
-CHANGESET_BUILD_BYTES_PER_ACCESS = 108
+# read, 8 read, 8 written each; the first pass reads the 4-byte ids instead, twice) and the
+# look-right pass (12); then the loop's id, key, address-table probe and key refresh (16)
+CHANGESET_BUILD_BYTES_PER_ACCESS = 100
 CHANGESET_LOOP_BYTES_PER_ACCESS = 16
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 

@@ -96,12 +96,6 @@ __device__ __forceinline__ void load_offsets(int32_t* lds_off, const int64_t* __
 
 // ---- part 1 -----------------------------------------------------------------------
 
-__global__ __launch_bounds__(TB) void k_make_pairs(const int32_t* __restrict__ ids, int64_t n,
-                                                   uint64_t* __restrict__ pairs) {
-  const int64_t p = (int64_t)blockIdx.x * TB + threadIdx.x;
-  if (p < n) pairs[p] = ((uint64_t)(uint32_t)ids[p] << 32) | (uint64_t)p;
-}
-
 constexpr int LOOK_ITEMS = 8;
 constexpr int LOOK_TILE = TB * LOOK_ITEMS;
 
@@ -1830,15 +1824,14 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   }
 
   // part 1: sort (node, position) by node, then look right
-  hipLaunchKernelGGL(k_make_pairs, dim3((unsigned)ceil_div(total, TB)), dim3(TB), 0, st, ids, total,
-                     w.pairs_a);
-  GINEX_LAUNCH_CHECK();
+  // (the first pass reads the ids themselves and forms the pairs on the way)
   uint64_t* sorted = nullptr;
   const char* validate_env = getenv("GINEX_VALIDATE");
   const bool validate = validate_env && validate_env[0] == '1';
   // when validating, sort on all 32 id bits so that ids beyond num_nodes are ordered too
-  GINEX_HIP(radix_sort_u64(w.pairs_a, w.pairs_b, total, 32,
-                           validate ? 64 : 32 + bits_for(num_nodes), w.hist, st, &sorted));
+  GINEX_HIP(radix_sort_values_with_positions(ids, w.pairs_a, w.pairs_b, total,
+                                             validate ? 64 : 32 + bits_for(num_nodes), w.hist, st,
+                                             &sorted));
   if (validate) {
     unsigned long long bad[2] = {0, 0};
     GINEX_HIP(fill_async<unsigned long long>(w.d_counts, 2, 0ull, st));

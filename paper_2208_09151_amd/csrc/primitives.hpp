@@ -116,9 +116,24 @@ constexpr int RS_ITEMS = 16;                    // keys per thread
 constexpr int RS_TILE = RS_THREADS * RS_ITEMS;  // 4096 keys, 32 KB of LDS staging
 constexpr int RS_BINS = 256;
 
-static __global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t* __restrict__ in,
-                                                           int64_t n, int shift, int64_t tiles,
-                                                           uint32_t* __restrict__ hist) {
+// Where a pass reads its words: an array of words, or (the first pass of a sort of
+// (value, position) pairs) an array of 32-bit values, word j = value j << 32 | j, so that the
+// pairs need not be written out and read back first.
+struct RadixWords {
+  const uint64_t* in;
+  __device__ __forceinline__ uint64_t operator()(int64_t j) const { return in[j]; }
+};
+struct RadixValuesWithPositions {
+  const int32_t* values;
+  __device__ __forceinline__ uint64_t operator()(int64_t j) const {
+    return ((uint64_t)(uint32_t)values[j] << 32) | (uint64_t)j;
+  }
+};
+
+template <typename Source>
+static __global__ __launch_bounds__(RS_THREADS) void k_radix_hist(Source in, int64_t n, int shift,
+                                                                  int64_t tiles,
+                                                                  uint32_t* __restrict__ hist) {
   __shared__ uint32_t bins[RS_BINS];
   bins[threadIdx.x] = 0;
   __syncthreads();
@@ -126,15 +141,16 @@ static __global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t
 #pragma unroll
   for (int i = 0; i < RS_ITEMS; ++i) {
     const int64_t j = base + i * RS_THREADS + threadIdx.x;
-    if (j < n) atomicAdd(&bins[(in[j] >> shift) & (RS_BINS - 1)], 1u);
+    if (j < n) atomicAdd(&bins[(in(j) >> shift) & (RS_BINS - 1)], 1u);
   }
   __syncthreads();
   hist[(int64_t)threadIdx.x * tiles + blockIdx.x] = bins[threadIdx.x];
 }
 
+template <typename Source>
 static __global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
-    const uint64_t* __restrict__ in, uint64_t* __restrict__ out, int64_t n, int shift,
-    int64_t tiles, const uint32_t* __restrict__ hist_scanned) {
+    Source in, uint64_t* __restrict__ out, int64_t n, int shift, int64_t tiles,
+    const uint32_t* __restrict__ hist_scanned) {
   __shared__ uint64_t staged[RS_TILE];
   __shared__ uint32_t wave_count[RS_WAVES][RS_BINS];
   __shared__ uint32_t digit_start[RS_BINS];   // start of each digit inside the tile
@@ -154,7 +170,7 @@ static __global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
   for (int i = 0; i < RS_ITEMS; ++i) {
     const int64_t j = wave_base + i * WAVE + lane;
     const bool valid = j < n;
-    key[i] = valid ? in[j] : 0;
+    key[i] = valid ? in(j) : 0;
     const uint32_t d = (uint32_t)(key[i] >> shift) & (RS_BINS - 1);
     uint64_t peers = __ballot(valid);
 #pragma unroll
@@ -227,22 +243,48 @@ inline RadixPlan radix_plan(int64_t n) {
 // Sorts `n` words by bits [bit_lo, bit_hi).  `a` holds the input, `b` is a buffer of the
 // same size; returns (through *sorted) which of the two holds the result.  The total
 // number of keys must stay below 2^32 (uint32 histogram).
+template <typename Source>
+inline hipError_t radix_pass(Source in, uint64_t* out, int64_t n, int shift, const RadixPlan& p,
+                             uint32_t* hist, hipStream_t st) {
+  const int64_t h = p.tiles * RS_BINS;
+  hipLaunchKernelGGL(k_radix_hist<Source>, dim3((unsigned)p.tiles), dim3(RS_THREADS), 0, st, in, n,
+                     shift, p.tiles, hist);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  e = exclusive_scan_inplace<uint32_t>(hist, h, hist + h, st);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_radix_scatter<Source>, dim3((unsigned)p.tiles), dim3(RS_THREADS), 0, st, in,
+                     out, n, shift, p.tiles, hist);
+  return hipGetLastError();
+}
+
 inline hipError_t radix_sort_u64(uint64_t* a, uint64_t* b, int64_t n, int bit_lo, int bit_hi,
                                  uint32_t* hist, hipStream_t st, uint64_t** sorted) {
   *sorted = a;
   if (n <= 1) return hipSuccess;
   const RadixPlan p = radix_plan(n);
-  const int64_t h = p.tiles * RS_BINS;
   for (int shift = bit_lo; shift < bit_hi; shift += 8) {
-    hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)p.tiles), dim3(RS_THREADS), 0, st, a, n, shift,
-                       p.tiles, hist);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = radix_pass(RadixWords{a}, b, n, shift, p, hist, st);
     if (e != hipSuccess) return e;
-    e = exclusive_scan_inplace<uint32_t>(hist, h, hist + h, st);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)p.tiles), dim3(RS_THREADS), 0, st, a, b, n,
-                       shift, p.tiles, hist);
-    e = hipGetLastError();
+    uint64_t* t = a; a = b; b = t;
+  }
+  *sorted = a;
+  return hipSuccess;
+}
+
+// The words (values[j] << 32 | j), j in [0, n), sorted by bits [32, bit_hi) of the word, that
+// is by the low bits of the value; equal values keep the order of their positions.  `a` and
+// `b` are two buffers of n words; *sorted tells which of them holds the result.
+inline hipError_t radix_sort_values_with_positions(const int32_t* values, uint64_t* a, uint64_t* b,
+                                                   int64_t n, int bit_hi, uint32_t* hist,
+                                                   hipStream_t st, uint64_t** sorted) {
+  *sorted = a;
+  if (n <= 0) return hipSuccess;
+  const RadixPlan p = radix_plan(n);
+  hipError_t e = radix_pass(RadixValuesWithPositions{values}, a, n, 32, p, hist, st);
+  if (e != hipSuccess) return e;
+  for (int shift = 40; shift < bit_hi; shift += 8) {
+    e = radix_pass(RadixWords{a}, b, n, shift, p, hist, st);
     if (e != hipSuccess) return e;
     uint64_t* t = a; a = b; b = t;
   }
