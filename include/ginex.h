@@ -27,7 +27,8 @@
  *      GINEX_SAMPLER_TILES=n  at most n tiles of a batch per workgroup column of the sampler
  *      GINEX_DEAD_SCATTER=0/1 evictions among dead rows from a pass over the lines / from the id bitmap
  *      GINEX_LIVE_SELECT=1    no shortcut that relies on the cache holding the whole superbatch
- *      GINEX_PLANNED=0        a carried cache that holds the whole superbatch still runs the loop
+ *      GINEX_PLANNED=0/2      a carried cache that holds the whole superbatch: still the general
+ *                             loop / the three-launch steps also where the replay would do
  */
 #ifndef GINEX_H
 #define GINEX_H
@@ -229,9 +230,12 @@ int32_t ginex_changeset_noalloc(
  * NULL) receives the row of every line after the last iteration: the start_ids of the next
  * superbatch.  No cache initialization is needed between the two superbatches.
  * When the cache also has a line for every distinct row of the superbatch, no iteration
- * evicts a row that is still needed and the lists follow without a loop over the iterations
- * (same result; GINEX_PLANNED=0 in the environment keeps the loop, GINEX_TRACE=1 reports on
- * stderr which way a call went). */
+ * evicts a row that is still needed: hits, misses and insertions are known up front and only
+ * the choice of the evicted rows follows the iterations, replayed by one workgroup or, for
+ * more candidates or evictions than that holds, in three small launches per iteration
+ * (same result; GINEX_PLANNED=0 in the environment keeps the general loop, 2 takes the
+ * three-launch way also where the replay would do, GINEX_TRACE=1 reports on stderr which way
+ * a call went). */
 int32_t ginex_changeset_resume(
     int64_t num_nodes, const int32_t* ids, const int64_t* ids_offsets /*host [S+1]*/,
     int32_t S, int64_t cap, const int32_t* start_ids /*[cap]*/, int32_t* final_ids /*[cap]*/,

@@ -675,11 +675,11 @@ __device__ void p_mark_incoming(const State& st, const Ctrl& c, const Iter& it, 
 // tile counts were zeroed by k_threshold; the bits above T leave the bitmap here.
 __device__ void p_dead_scatter(const State& st, const Ctrl& c, int64_t vb, int64_t vblocks) {
   // the stretch above T is short as a rule, so a small grid strides over it from T's word on
-  const int64_t t_word = c.T >> 5;
+  const int64_t t_word = c.T < 0 ? 0 : c.T >> 5;   // T = -1: every dead row goes
   for (int64_t w = t_word + vb * TB + threadIdx.x; w < st.words; w += vblocks * TB) {
     const uint32_t all = st.dead_bits[w];
     uint32_t bits = all;
-    if (w == t_word) bits &= (c.T & 31) == 31 ? 0u : ~((2u << (c.T & 31)) - 1u);
+    if (c.T >= 0 && w == t_word) bits &= (c.T & 31) == 31 ? 0u : ~((2u << (c.T & 31)) - 1u);
     if (!bits) continue;
     st.dead_bits[w] = all & ~bits;
     while (bits) {
@@ -1224,7 +1224,8 @@ __device__ __forceinline__ bool plan_arrival(const uint64_t* __restrict__ sorted
 // ... then (PLACE = false) the rows >= lo_id that die during the superbatch, counted per
 // iteration at arr_off[d + 1].  PLACE = true, after the candidates are numbered: their numbers
 // go to arr_cand at the cursors, and a row that is inserted during this call leaves its number
-// with its insertion record.  A block works on one stretch of the sorted pairs and counts
+// with its insertion record (with arr_ids, the rows themselves go there instead, and nothing
+// else is written).  A block works on one stretch of the sorted pairs and counts
 // per iteration in LDS first, so that the counters and cursors in global memory, a few
 // addresses that every arrival would otherwise meet at, see one atomic per block and iteration.
 // lds: S + 1 offsets, S counters.
@@ -1235,7 +1236,8 @@ __global__ __launch_bounds__(TB) void k_plan_arrivals(const uint64_t* __restrict
                                                       const int64_t* __restrict__ off, int32_t S,
                                                       uint32_t* __restrict__ cand_bits,
                                                       const uint32_t* __restrict__ cand_base,
-                                                      int64_t num_nodes, Plan pl) {
+                                                      int64_t num_nodes, Plan pl,
+                                                      int32_t* __restrict__ arr_ids) {
   extern __shared__ int32_t lds_off[];
   uint32_t* s_cnt = reinterpret_cast<uint32_t*>(lds_off + S + 1);
   const int64_t lo_id = scalars[PLAN_LO_ID];
@@ -1269,6 +1271,10 @@ __global__ __launch_bounds__(TB) void k_plan_arrivals(const uint64_t* __restrict
     int32_t v, d;
     bool inserted;
     if (!plan_arrival(sorted, n, j, addr, lds_off, S, v, d, inserted)) continue;
+    if (arr_ids) {                                   // the stepped path wants the rows themselves
+      arr_ids[atomicAdd(&s_cnt[d], 1u)] = v;
+      continue;
+    }
     const uint32_t below = (1u << (v & 31)) - 1u;
     const uint32_t c = cand_base[((uint32_t)v >> 5) - lo_word] + __popc(cand_bits[(uint32_t)v >> 5] & below);
     // (the host takes this path only with at most PLAN_CAND_MAX candidates: c is below that)
@@ -1643,6 +1649,129 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
   if (threadIdx.x == 0 && s_failed) pl.scalars[PLAN_FAILED] = s_failed;
 }
 
+// ---- the same regime with more candidates or evictions than the replay holds ------------------
+//
+// Hits, misses and insertions are known up front as above; the choice of the evicted rows runs
+// on the standing bitmap of dead rows in global memory instead, three launches per iteration
+// that evicts: k_step_find (one block: the id T above which the iteration's n dead rows lie),
+// k_step_scatter (their bits leave the bitmap, their lines are flagged), k_step_emit (the
+// flagged lines in line order take the iteration's insertions; other blocks set the bits of the
+// rows that die in the next iteration).  No pass touches the accesses.
+
+// The rows of arr_ids[a0, a1) are dead residents from now on.
+__device__ __forceinline__ void step_arrivals(const State& st, const int32_t* __restrict__ arr_ids,
+                                              uint32_t a0, uint32_t a1, int64_t vb, int64_t vblocks) {
+  for (int64_t a = a0 + vb * TB + threadIdx.x; a < a1; a += vblocks * TB)
+    dead_bit_set(st, (uint32_t)arr_ids[a]);
+}
+
+__global__ __launch_bounds__(TB) void k_step_arrive(State st, const int32_t* __restrict__ arr_ids,
+                                                    uint32_t a0, uint32_t a1) {
+  step_arrivals(st, arr_ids, a0, a1, blockIdx.x, gridDim.x);
+}
+
+// One block.  n rows are evicted: the n dead rows with the largest ids.
+__global__ __launch_bounds__(BIG) void k_step_find(State st, int64_t n, int64_t evict_tiles) {
+  __shared__ int64_t smem[BIG / WAVE + 1];
+  int64_t mine = 0;
+  for (int64_t q = threadIdx.x; q < st.parts; q += BIG) mine += st.dead_part[q];
+  int64_t total;
+  block_exclusive_scan<int64_t, BIG>(mine, smem, total);
+  const int64_t keep = total - n;
+  int32_t T = -1;
+  if (keep > 0) {
+    T = p_kth_set_bit<BIG>(st.dead_bits, st.dead_part, st.parts, st.words, keep, true);
+  } else {
+    for (int64_t q = threadIdx.x; q < st.parts; q += BIG) st.dead_part[q] = 0;
+  }
+  if (threadIdx.x == 0) {
+    if (keep < 0) *st.fault = 1;   // fewer dead rows than insertions: cannot happen in this regime
+    Ctrl c{};
+    c.jstar = st.S;
+    c.mode_in = MODE_ALL;
+    c.mode_res = MODE_SELECT;
+    c.keep = (int32_t)keep;
+    c.T = T;
+    c.n_change = (int32_t)n;
+    c.use_dead = 1;
+    *st.ctrl = c;
+  }
+  for (int64_t q = threadIdx.x; q < evict_tiles; q += BIG) st.evict_tiles[q] = 0;
+}
+
+__global__ void k_step_verdict(const int32_t* __restrict__ fault, int64_t* __restrict__ scalars) {
+  if (*fault) {
+    scalars[PLAN_FAILED] = 8;
+    scalars[PLAN_WHERE] = -1;
+  }
+}
+
+__global__ __launch_bounds__(TB) void k_step_scatter(State st) {
+  const Ctrl c = *st.ctrl;
+  p_dead_scatter(st, c, blockIdx.x, gridDim.x);
+}
+
+// blocks [0, evict_blocks): one wave per tile of 64 flag words, the evicted lines in line order
+// (see p_evict_emit); the t-th of them takes the t-th insertion of the iteration, whose list
+// starts at in_ids[dst].  The other blocks: the rows that die in the next iteration.
+__global__ __launch_bounds__(TB) void k_step_emit(State st, int64_t evict_tiles, int64_t evict_blocks,
+                                                  int64_t dst, const int32_t* __restrict__ in_ids,
+                                                  int32_t* __restrict__ out_ids,
+                                                  const int32_t* __restrict__ arr_ids, uint32_t a0,
+                                                  uint32_t a1) {
+  __shared__ uint32_t red[TB / WAVE];
+  if ((int64_t)blockIdx.x >= evict_blocks) {
+    step_arrivals(st, arr_ids, a0, a1, blockIdx.x - evict_blocks, gridDim.x - evict_blocks);
+    return;
+  }
+  constexpr int TPB = TB / WAVE;
+  const int64_t first_tile = (int64_t)blockIdx.x * TPB;
+  const int w = threadIdx.x / WAVE;
+  const int64_t tile = first_tile + w;
+  uint32_t own[TPB];
+  uint32_t any = 0;
+#pragma unroll
+  for (int k = 0; k < TPB; ++k) {
+    own[k] = first_tile + k < evict_tiles ? st.evict_tiles[first_tile + k] : 0;
+    any |= own[k];
+  }
+  if (!any) return;                                // uniform over the block
+  const int64_t word_at = tile * WAVE + lane_id();
+  const uint64_t word = tile < evict_tiles && word_at * WAVE < st.cap ? st.evict_words[word_at] : 0;
+  uint32_t tile_base = block_prefix_of(st.evict_tiles, first_tile, red);
+#pragma unroll
+  for (int k = 0; k < TPB; ++k)
+    if (k < w) tile_base += own[k];
+  if (tile >= evict_tiles) return;                 // uniform over the wave
+  if (word) st.evict_words[word_at] = 0;           // consumed: zero for the next scatter
+  const uint32_t mine = (uint32_t)__popcll(word);
+  const uint32_t incl = wave_inclusive_scan(mine);
+  const uint32_t total = __shfl(incl, WAVE - 1, WAVE);
+  for (uint32_t k0 = 0; k0 < total; k0 += WAVE) {  // uniform trip count: shuffles inside
+    const uint32_t k = k0 + lane_id();
+    int lo = 0, hi = WAVE - 1;                     // the first word whose running count exceeds k
+#pragma unroll
+    for (int step = 0; step < 6; ++step) {
+      const int mid = (lo + hi) >> 1;
+      if (__shfl(incl, mid, WAVE) > k) hi = mid; else lo = mid + 1;
+    }
+    const int j = lo < WAVE ? lo : WAVE - 1;
+    uint64_t bits = shfl_u64(word, j);
+    const uint32_t before = __shfl(incl, j, WAVE) - __shfl(mine, j, WAVE);
+    if (k >= total) continue;
+    for (uint32_t r = k - before; r > 0; --r) bits &= bits - 1;
+    const int32_t line = (int32_t)((tile * WAVE + j) * WAVE + (__ffsll((unsigned long long)bits) - 1));
+    const int64_t at = dst + tile_base + k;
+    const int32_t gone = st.res_id[line];
+    const int32_t comes = in_ids[at];
+    out_ids[at] = gone;
+    // (the evicted row keeps its entry of the address table: it is never accessed again, and the
+    // lookup after the last iteration finds the line it had)
+    st.addr[comes] = line;
+    st.res_id[line] = comes;
+  }
+}
+
 struct Workspace {
   uint64_t *pairs_a, *pairs_b, *heads_a, *heads_b;
   uint32_t* hist;
@@ -1980,7 +2109,7 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                          state.dead_bits, state.words, num_nodes, pl.scalars, state.bitmap);
       hipLaunchKernelGGL(k_plan_arrivals<false>, dim3((unsigned)tail_blocks), dim3(TB), 2 * off_lds, st,
                          sorted, total, pl.scalars, state.addr, w.d_offsets, S, state.bitmap,
-                         pl.cand_base, num_nodes, pl);
+                         pl.cand_base, num_nodes, pl, (int32_t*)nullptr);
       hipLaunchKernelGGL(k_plan_arrival_offsets, dim3(1), dim3(BIG), 0, st, pl.arr_off,
                          pl.arr_cur, S, pl.scalars);
       GINEX_LAUNCH_CHECK();
@@ -1989,8 +2118,12 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
     GINEX_HIP(hipMemcpyAsync(sc, pl.scalars, sizeof(sc), hipMemcpyDeviceToHost, st));
     GINEX_HIP(hipStreamSynchronize(st));
     const int64_t M = sc[PLAN_M], lo_id = sc[PLAN_LO_ID];
-    const bool fits = M == 0 || (lo_id >= 0 && sc[PLAN_MAX_N] <= PLAN_SORT_MAX &&
-                                 sc[PLAN_CANDS] <= PLAN_CAND_MAX);
+    // the replay in LDS where its arrays hold the call, else (or with GINEX_PLANNED=2) the
+    // steps on the bitmap in global memory; neither with fewer dead rows than insertions
+    const bool stepped = M > 0 && lo_id >= 0 &&
+                         ((plan_env && plan_env[0] == '2') || sc[PLAN_MAX_N] > PLAN_SORT_MAX ||
+                          sc[PLAN_CANDS] > PLAN_CAND_MAX);
+    const bool fits = M == 0 || lo_id >= 0;
     // GINEX_TRACE=1: one line on stderr that says which way the call went
     const char* trace_env = getenv("GINEX_TRACE");
     const bool trace = trace_env && trace_env[0] == '1';
@@ -1998,7 +2131,8 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       fprintf(stderr, "[ginex] %s: %lld insertions, at most %lld per iteration, %lld rows dead from "
               "the start, lowest possible victim %lld of %lld ids, %lld candidates: %s\n", who,
               (long long)M, (long long)sc[PLAN_MAX_N], (long long)sc[PLAN_DEAD], (long long)lo_id,
-              (long long)num_nodes, (long long)sc[PLAN_CANDS], fits ? "planned path" : "loop");
+              (long long)num_nodes, (long long)sc[PLAN_CANDS],
+              !fits ? "loop" : stepped ? "stepped path" : "planned path");
     if (fits) {
       *total_changes = M;
       if (M > cs_capacity)
@@ -2016,12 +2150,62 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                            pl.ins_bits, pl.ins_words, pl.ins_tiles, ids, w.d_offsets, S, in_ids,
                            in_positions, pl.ins_base, pl.ins_cand);
         GINEX_LAUNCH_CHECK();
+        int64_t tail_blocks = ceil_div(total - sc[PLAN_TAIL], TB);
+        tail_blocks = tail_blocks < 1 ? 1 : (tail_blocks > 1024 ? 1024 : tail_blocks);
+        if (stepped) {
+          // the rows that die, as ids grouped by iteration (in the array that holds the
+          // candidate numbers of the insertions for the replay, which does not run)
+          int32_t* const arr_ids = pl.ins_cand;
+          hipLaunchKernelGGL(k_plan_arrivals<true>, dim3((unsigned)tail_blocks), dim3(TB),
+                             2 * off_lds, st, sorted, total, pl.scalars, state.addr, w.d_offsets, S,
+                             state.bitmap, pl.cand_base, num_nodes, pl, arr_ids);
+          GINEX_LAUNCH_CHECK();
+          std::vector<int64_t> cs(S + 1);
+          std::vector<uint32_t> arr(S + 2);
+          GINEX_HIP(hipMemcpyAsync(cs.data(), cs_offsets, sizeof(int64_t) * (S + 1),
+                                   hipMemcpyDeviceToHost, st));
+          GINEX_HIP(hipMemcpyAsync(arr.data(), pl.arr_off, sizeof(uint32_t) * (S + 1),
+                                   hipMemcpyDeviceToHost, st));
+          GINEX_HIP(hipStreamSynchronize(st));
+          arr[S + 1] = arr[S];
+          if (!state.dead_scatter)
+            GINEX_HIP(fill_async<uint64_t>(state.evict_words, w.evict_tiles * WAVE, 0ull, st));
+          const int64_t evict_blocks = ceil_div(w.evict_tiles, TB / WAVE);
+          int64_t scatter_blocks = ceil_div(state.words, TB);
+          scatter_blocks = scatter_blocks > 256 ? 256 : scatter_blocks;
+          auto arrive_blocks = [](uint32_t count) {
+            const int64_t b = ceil_div((int64_t)count, TB);
+            return (unsigned)(b < 1 ? 1 : (b > 64 ? 64 : b));
+          };
+          if (arr[1] > arr[0])
+            hipLaunchKernelGGL(k_step_arrive, dim3(arrive_blocks(arr[1] - arr[0])), dim3(TB), 0, st,
+                               state, arr_ids, arr[0], arr[1]);
+          for (int32_t i = 0; i < S; ++i) {
+            const int64_t n = cs[i + 1] - cs[i];
+            const uint32_t a0 = arr[i + 1], a1 = i + 1 < S ? arr[i + 2] : arr[i + 1];
+            if (n > 0) {
+              hipLaunchKernelGGL(k_step_find, dim3(1), dim3(BIG), 0, st, state, n, w.evict_tiles);
+              hipLaunchKernelGGL(k_step_scatter, dim3((unsigned)scatter_blocks), dim3(TB), 0, st,
+                                 state);
+              hipLaunchKernelGGL(k_step_emit,
+                                 dim3((unsigned)evict_blocks + (a1 > a0 ? arrive_blocks(a1 - a0) : 0u)),
+                                 dim3(TB), 0, st, state, w.evict_tiles, evict_blocks, cs[i], in_ids,
+                                 out_ids, arr_ids, a0, a1);
+            } else if (a1 > a0) {
+              hipLaunchKernelGGL(k_step_arrive, dim3(arrive_blocks(a1 - a0)), dim3(TB), 0, st, state,
+                                 arr_ids, a0, a1);
+            }
+          }
+          GINEX_LAUNCH_CHECK();
+          // (a step that met fewer dead rows than insertions leaves its mark in the word the
+          // copy below brings over beside the replay's)
+          hipLaunchKernelGGL(k_step_verdict, dim3(1), dim3(1), 0, st, state.fault, pl.scalars);
+          GINEX_LAUNCH_CHECK();
+        } else {
         // the candidates numbered in id order
         const int64_t lo_word = lo_id >> 5;
         const int64_t nwords = state.words - lo_word;
         const int64_t ctiles = ceil_div(nwords, TB);
-        int64_t tail_blocks = ceil_div(total - sc[PLAN_TAIL], TB);
-        tail_blocks = tail_blocks < 1 ? 1 : (tail_blocks > 1024 ? 1024 : tail_blocks);
         hipLaunchKernelGGL(k_bit_tiles, dim3((unsigned)ctiles), dim3(TB), 0, st,
                            state.bitmap + lo_word, nwords, pl.cand_tiles);
         GINEX_LAUNCH_CHECK();
@@ -2032,10 +2216,11 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                            state.dead_bits, lo_word, nwords, pl.cand_tiles, state.addr, pl);
         hipLaunchKernelGGL(k_plan_arrivals<true>, dim3((unsigned)tail_blocks), dim3(TB), 2 * off_lds, st,
                            sorted, total, pl.scalars, state.addr, w.d_offsets, S, state.bitmap,
-                           pl.cand_base, num_nodes, pl);
+                           pl.cand_base, num_nodes, pl, (int32_t*)nullptr);
         hipLaunchKernelGGL(k_plan_replay, dim3(1), dim3(BIG), 0, st, state, pl, ctiles, cs_offsets,
                            in_ids, out_ids);
         GINEX_LAUNCH_CHECK();
+        }
       }
       if (src_line) {
         // every row has one line for the whole superbatch: the start state's or the one it was given

@@ -161,7 +161,7 @@ def carried_cache_both_ways(ginex, cfg, res, ids, distinct, capfd=None):
     assert start.numel() == cfg.cap
     del rows, outside
     both = []
-    for planned in ("1", "0"):
+    for planned in ("1", "2", "0"):     # the replay in LDS, the steps in global memory, the loop
         os.environ["GINEX_PLANNED"] = planned
         os.environ["GINEX_TRACE"] = "1"
         if capfd is not None:
@@ -170,14 +170,16 @@ def carried_cache_both_ways(ginex, cfg, res, ids, distinct, capfd=None):
             both.append(ginex.changeset_resume(cfg.num_nodes, res.ids, res.ids_offsets, start))
         finally:
             del os.environ["GINEX_PLANNED"], os.environ["GINEX_TRACE"]
-        if capfd is not None:   # the first call really went the loop-free way, the second did not
+        if capfd is not None:   # every call really went the way it was asked to
             said = capfd.readouterr().err
             assert ("planned path" in said) == (planned == "1"), said
-    a, b = both
+            assert ("stepped path" in said) == (planned == "2"), said
+    a = both[0]
     assert int(a.cs_offsets[-1]) > 0
-    assert np.array_equal(a.cs_offsets, b.cs_offsets) and np.array_equal(a.miss_count, b.miss_count)
-    for name in ("in_ids", "out_ids", "in_positions", "src_line", "final_ids"):
-        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    for b in both[1:]:
+        assert np.array_equal(a.cs_offsets, b.cs_offsets) and np.array_equal(a.miss_count, b.miss_count)
+        for name in ("in_ids", "out_ids", "in_positions", "src_line", "final_ids"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), name
     say(f"carried cache of {cfg.cap} lines: loop-free changesets equal the loop's "
         f"({int(a.cs_offsets[-1])} changes, {int(a.miss_count.sum())} misses, {time.time() - t:.1f}s)")
 

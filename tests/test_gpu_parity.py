@@ -785,8 +785,10 @@ def planned_cases(rng):
 
 def test_carried_cache_that_holds_the_superbatch_needs_no_loop(ginex, monkeypatch, capfd):
     """A carried cache with a line for every distinct row of the superbatch: hits, misses and
-    insertions are known up front and only the choice of the evicted rows is replayed.  The
-    result equals the oracle's and the loop's (GINEX_PLANNED=0), lists, lines and final state."""
+    insertions are known up front and only the choice of the evicted rows is replayed, by one
+    workgroup in LDS or, for more candidates or evictions than that holds (or GINEX_PLANNED=2),
+    step by step on the bitmap in global memory.  The results equal the oracle's and the
+    loop's (GINEX_PLANNED=0), lists, lines and final state."""
     rng = np.random.default_rng(77)
     for kind, n, ids, off, start in planned_cases(rng):
         cap = len(start)
@@ -802,8 +804,20 @@ def test_carried_cache_that_holds_the_superbatch_needs_no_loop(ginex, monkeypatc
         monkeypatch.delenv("GINEX_TRACE")
         check_resumed(res, ref, (n, ids, off))
         if len(ids):      # the way the call went is the one the case was built for
-            assert ("planned path" in said) == (kind not in ("wide", "crowded")), said
-            assert "gave up" not in said, said
+            big = kind in ("wide", "crowded")   # more than the replay's arrays in LDS hold
+            assert ("stepped path" in said) == big and ("planned path" in said) == (not big), said
+            assert "gave up" not in said and ": loop" not in said, said
+        # the same through the steps on the bitmap in global memory, whatever the sizes ...
+        monkeypatch.setenv("GINEX_PLANNED", "2")
+        monkeypatch.setenv("GINEX_TRACE", "1")
+        capfd.readouterr()
+        stepped = ginex.changeset_resume(n, ids_d, off, dev(start))
+        said = capfd.readouterr().err
+        monkeypatch.delenv("GINEX_TRACE")
+        check_resumed(stepped, ref, (n, ids, off))
+        if len(ids) and int(ref["cs_offsets"][-1]):
+            assert "stepped path" in said and "gave up" not in said, said
+        # ... and through the loop
         monkeypatch.setenv("GINEX_PLANNED", "0")
         loop = ginex.changeset_resume(n, ids_d, off, dev(start))
         check_resumed(loop, ref, (n, ids, off))
@@ -1278,7 +1292,7 @@ def test_changeset_is_independent_of_the_eviction_path_and_repeatable(ginex, cas
     start = dev(np.arange(big, dtype=np.int32)[::-1].copy())
     results = []
     for scatter, live, planned in (("0", "0", "1"), ("1", "0", "1"), ("0", "1", "1"), ("1", "1", "1"),
-                                   ("0", "0", "0"), ("1", "0", "0")):
+                                   ("0", "0", "0"), ("1", "0", "0"), ("0", "0", "2"), ("1", "0", "2")):
         monkeypatch.setenv("GINEX_DEAD_SCATTER", scatter)
         monkeypatch.setenv("GINEX_LIVE_SELECT", live)   # keeps the live-select launches in the loop
         monkeypatch.setenv("GINEX_PLANNED", planned)    # 0: the loop also where no loop is needed

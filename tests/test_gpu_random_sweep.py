@@ -28,7 +28,7 @@ def _ids(ids):
     return dev(ids) if len(ids) else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
 
 
-def test_changeset_entry_points_on_random_traces(ginex):
+def test_changeset_entry_points_on_random_traces(ginex, monkeypatch):
     """Belady, LRU, resumed (a cache that holds the trace and one that does not) and chains of
     resumed calls that hand final_ids on, 1 600 cases."""
     rng = np.random.default_rng(20261127)
@@ -51,6 +51,11 @@ def test_changeset_entry_points_on_random_traces(ginex):
                 continue
             holds = rng.random() < 0.6      # a line for every distinct row: no loop over the state
             cap = int(rng.integers(min(distinct, n), n + 1)) if holds else int(rng.integers(1, n + 1))
+            way = str(rng.choice(["", "", "2", "0"]))   # as the library chooses, stepped, loop
+            if way:
+                monkeypatch.setenv("GINEX_PLANNED", way)
+            else:
+                monkeypatch.delenv("GINEX_PLANNED", raising=False)
             start = rng.permutation(n)[:cap].astype(np.int32)
             for _ in range(1 if kind == "resume" else int(rng.integers(2, 5))):
                 ref = oracle.changeset_resume(n, ids, off, cap, start)
