@@ -1659,10 +1659,28 @@ __global__ __launch_bounds__(BIG) void k_plan_replay(State st, Plan pl, int64_t 
 // rows that die in the next iteration).  No pass touches the accesses.
 
 // The rows of arr_ids[a0, a1) are dead residents from now on.
+// (The list of an iteration comes in ascending stretches, so neighbouring lanes mostly fall
+// into the same part of the bitmap: the first lane of each run adds the run's length to the
+// part's count, instead of one atomic per row on a few hundred addresses.)
 __device__ __forceinline__ void step_arrivals(const State& st, const int32_t* __restrict__ arr_ids,
                                               uint32_t a0, uint32_t a1, int64_t vb, int64_t vblocks) {
-  for (int64_t a = a0 + vb * TB + threadIdx.x; a < a1; a += vblocks * TB)
-    dead_bit_set(st, (uint32_t)arr_ids[a]);
+  const int lane = lane_id();
+  for (int64_t first = a0 + vb * TB + (threadIdx.x - lane); first < a1; first += vblocks * TB) {
+    const int64_t a = first + lane;                // whole waves stay in the loop together
+    const bool valid = a < a1;
+    const uint32_t v = valid ? (uint32_t)arr_ids[a] : 0u;
+    const uint32_t part = valid ? v >> PART_SHIFT : 0xFFFFFFFFu;
+    if (valid) atomicOr(&st.dead_bits[v >> 5], 1u << (v & 31));
+    const uint32_t prev = __shfl_up(part, 1, WAVE);
+    const bool leader = valid && (lane == 0 || prev != part);
+    const uint64_t leaders = __ballot(leader);
+    const int valid_lanes = __popcll(__ballot(valid));   // the valid lanes are the lowest ones
+    if (leader) {
+      const uint64_t higher = lane == WAVE - 1 ? 0ull : leaders & ~((2ull << lane) - 1ull);
+      const int next = higher ? __ffsll((unsigned long long)higher) - 1 : valid_lanes;
+      atomicAdd(&st.dead_part[part], (uint32_t)(next - lane));
+    }
+  }
 }
 
 __global__ __launch_bounds__(TB) void k_step_arrive(State st, const int32_t* __restrict__ arr_ids,
@@ -1711,57 +1729,53 @@ __global__ __launch_bounds__(TB) void k_step_scatter(State st) {
   p_dead_scatter(st, c, blockIdx.x, gridDim.x);
 }
 
-// blocks [0, evict_blocks): one wave per tile of 64 flag words, the evicted lines in line order
-// (see p_evict_emit); the t-th of them takes the t-th insertion of the iteration, whose list
-// starts at in_ids[dst].  The other blocks: the rows that die in the next iteration.
+// blocks [0, evict_blocks): a block per TB flag words (TB / WAVE tiles), the evicted lines in
+// line order; the t-th of them takes the t-th insertion of the iteration, whose list starts
+// at in_ids[dst].  The evicted lines crowd in few tiles (where rows come and go), so the
+// block's evictions are dealt to all its threads by rank: a thread finds the flag word of its
+// rank in the block's running popcounts (LDS), then the bit inside the word.
+// The other blocks: the rows that die in the next iteration.
 __global__ __launch_bounds__(TB) void k_step_emit(State st, int64_t evict_tiles, int64_t evict_blocks,
                                                   int64_t dst, const int32_t* __restrict__ in_ids,
                                                   int32_t* __restrict__ out_ids,
                                                   const int32_t* __restrict__ arr_ids, uint32_t a0,
                                                   uint32_t a1) {
   __shared__ uint32_t red[TB / WAVE];
+  __shared__ uint32_t smem[TB / WAVE + 1];
+  __shared__ uint64_t s_word[TB];
+  __shared__ uint32_t s_incl[TB];
   if ((int64_t)blockIdx.x >= evict_blocks) {
     step_arrivals(st, arr_ids, a0, a1, blockIdx.x - evict_blocks, gridDim.x - evict_blocks);
     return;
   }
   constexpr int TPB = TB / WAVE;
   const int64_t first_tile = (int64_t)blockIdx.x * TPB;
-  const int w = threadIdx.x / WAVE;
-  const int64_t tile = first_tile + w;
-  uint32_t own[TPB];
   uint32_t any = 0;
 #pragma unroll
-  for (int k = 0; k < TPB; ++k) {
-    own[k] = first_tile + k < evict_tiles ? st.evict_tiles[first_tile + k] : 0;
-    any |= own[k];
-  }
-  if (!any) return;                                // uniform over the block
-  const int64_t word_at = tile * WAVE + lane_id();
-  const uint64_t word = tile < evict_tiles && word_at * WAVE < st.cap ? st.evict_words[word_at] : 0;
-  uint32_t tile_base = block_prefix_of(st.evict_tiles, first_tile, red);
-#pragma unroll
   for (int k = 0; k < TPB; ++k)
-    if (k < w) tile_base += own[k];
-  if (tile >= evict_tiles) return;                 // uniform over the wave
+    any |= first_tile + k < evict_tiles ? st.evict_tiles[first_tile + k] : 0;
+  if (!any) return;                                // uniform over the block
+  const int64_t word_at = first_tile * WAVE + threadIdx.x;
+  const uint64_t word = word_at < evict_tiles * WAVE && word_at * WAVE < st.cap
+                            ? st.evict_words[word_at] : 0;
   if (word) st.evict_words[word_at] = 0;           // consumed: zero for the next scatter
   const uint32_t mine = (uint32_t)__popcll(word);
-  const uint32_t incl = wave_inclusive_scan(mine);
-  const uint32_t total = __shfl(incl, WAVE - 1, WAVE);
-  for (uint32_t k0 = 0; k0 < total; k0 += WAVE) {  // uniform trip count: shuffles inside
-    const uint32_t k = k0 + lane_id();
-    int lo = 0, hi = WAVE - 1;                     // the first word whose running count exceeds k
+  uint32_t total;
+  const uint32_t before_me = block_exclusive_scan<uint32_t, TB>(mine, smem, total);
+  s_word[threadIdx.x] = word;
+  s_incl[threadIdx.x] = before_me + mine;
+  const int64_t base = dst + block_prefix_of(st.evict_tiles, first_tile, red);   // (barriers inside)
+  for (uint32_t r = threadIdx.x; r < total; r += TB) {
+    int lo = 0, hi = TB - 1;                       // the first word whose running count exceeds r
 #pragma unroll
-    for (int step = 0; step < 6; ++step) {
+    for (int step = 0; step < 8; ++step) {
       const int mid = (lo + hi) >> 1;
-      if (__shfl(incl, mid, WAVE) > k) hi = mid; else lo = mid + 1;
+      if (s_incl[mid] > r) hi = mid; else lo = mid + 1;
     }
-    const int j = lo < WAVE ? lo : WAVE - 1;
-    uint64_t bits = shfl_u64(word, j);
-    const uint32_t before = __shfl(incl, j, WAVE) - __shfl(mine, j, WAVE);
-    if (k >= total) continue;
-    for (uint32_t r = k - before; r > 0; --r) bits &= bits - 1;
-    const int32_t line = (int32_t)((tile * WAVE + j) * WAVE + (__ffsll((unsigned long long)bits) - 1));
-    const int64_t at = dst + tile_base + k;
+    uint64_t bits = s_word[lo];
+    for (uint32_t skip = r - (s_incl[lo] - (uint32_t)__popcll(bits)); skip > 0; --skip) bits &= bits - 1;
+    const int32_t line = (int32_t)((first_tile * WAVE + lo) * WAVE + (__ffsll((unsigned long long)bits) - 1));
+    const int64_t at = base + r;
     const int32_t gone = st.res_id[line];
     const int32_t comes = in_ids[at];
     out_ids[at] = gone;
