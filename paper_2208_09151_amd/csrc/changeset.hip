@@ -44,8 +44,10 @@ struct Ctrl {        // decisions of the running iteration (device memory)
   int32_t T;         // id threshold of the select
   int32_t n_change;  // evictions (= insertions) of the iteration
   int32_t use_dead;  // the select runs on the standing bitmap of dead residents
-  int32_t pad;
+  int32_t marked;    // bit 0: residents of bucket j* have their bits in the scratch bitmap,
+                     // bit 1: incoming rows of bucket j* in theirs (both are cleared in k_flags)
 };
+enum { MARKED_RES = 1, MARKED_IN = 2 };
 // State::fault (device, one word): set when a launch sequence that leaves the live select out
 // meets an iteration that needs it (cannot happen when every row of the superbatch fits the
 // cache beside the rows it already holds; checked by the host after the loop).
@@ -56,8 +58,10 @@ struct State {
   int32_t* addr;        // [N] line of a node or -1
   uint32_t* rhist;      // [S+1] residents per next iteration
   uint32_t* ihist;      // [S+1] incoming rows of the running iteration per next iteration
-  uint32_t* bitmap;     // [words] select scratch, all zero between iterations
+  uint32_t* bitmap;     // [words] select scratch (residents of bucket j*), all zero between iterations
   uint32_t* sel_part;   // [parts] its set bits per part, all zero between iterations
+  uint32_t* bitmap_in;  // [words] the same for the incoming rows of bucket j*
+  uint32_t* sel_part_in;
   uint32_t* dead_bits;  // [words] residents that are never accessed again, kept up to date
   uint32_t* dead_part;  // [parts] its set bits per part, kept up to date
   Ctrl* ctrl;
@@ -620,7 +624,11 @@ __device__ void p_bits_find(const State& st, const uint32_t* __restrict__ bits,
 __global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i, int32_t lo_bin, Outputs o,
                                                    int64_t evict_tiles) {
   p_threshold<BIG>(st, i, lo_bin, o.miss_count, o.cs_offsets);
-  const Ctrl c = *st.ctrl;   // written by this block, in front of the barrier that ends p_threshold
+  Ctrl c = *st.ctrl;   // written by this block, in front of the barrier that ends p_threshold
+  // k_mark will set the bits of the selected class only
+  c.marked = (c.mode_res == MODE_SELECT && !c.use_dead ? MARKED_RES : 0) |
+             (c.mode_in == MODE_SELECT ? MARKED_IN : 0);
+  if (threadIdx.x == 0) st.ctrl->marked = c.marked;
   if (st.dead_only && !c.use_dead && threadIdx.x == 0 &&
       (c.mode_res == MODE_SELECT || c.mode_in == MODE_SELECT))
     *st.fault = 1;
@@ -634,7 +642,8 @@ __global__ __launch_bounds__(BIG) void k_threshold(State st, int32_t i, int32_t 
 __global__ __launch_bounds__(BIG) void k_find(State st) {
   const Ctrl c = *st.ctrl;
   if (c.use_dead || (c.mode_res != MODE_SELECT && c.mode_in != MODE_SELECT)) return;
-  p_bits_find<BIG>(st, st.bitmap, st.sel_part, false);
+  if (c.mode_res == MODE_SELECT) p_bits_find<BIG>(st, st.bitmap, st.sel_part, false);
+  else p_bits_find<BIG>(st, st.bitmap_in, st.sel_part_in, false);
 }
 
 constexpr int MARK_ITEMS = 8;   // lines / accesses per thread in the mark phases
@@ -645,6 +654,10 @@ constexpr int EVICT_TILE = WAVE * WAVE;   // cache lines per tile: 64 flag words
 __device__ __forceinline__ void select_bit_set(const State& st, uint32_t v) {
   atomicOr(&st.bitmap[v >> 5], 1u << (v & 31));
   atomicAdd(&st.sel_part[v >> PART_SHIFT], 1u);
+}
+__device__ __forceinline__ void select_bit_set_in(const State& st, uint32_t v) {
+  atomicOr(&st.bitmap_in[v >> 5], 1u << (v & 31));
+  atomicAdd(&st.sel_part_in[v >> PART_SHIFT], 1u);
 }
 
 // Set the bit of every member of the selected class in bucket j*.
@@ -663,7 +676,7 @@ __device__ void p_mark_incoming(const State& st, const Ctrl& c, const Iter& it, 
   for (int t = 0; t < MARK_ITEMS; ++t) {
     const int64_t p = base + t * TB + threadIdx.x;
     if (p < it.n && st.acc_line[p] < 0 && key_of(it, p) == c.jstar)
-      select_bit_set(st, (uint32_t)it.ids[p]);
+      select_bit_set_in(st, (uint32_t)it.ids[p]);
   }
 }
 
@@ -723,7 +736,7 @@ __device__ void p_evict_flags(const State& st, const Ctrl& c, int64_t vb) {
   __shared__ uint32_t red[TB / WAVE];
   constexpr int PER_WAVE = WAVE / (TB / WAVE);
   const int64_t first_word = vb * WAVE + (threadIdx.x / WAVE) * PER_WAVE;
-  const bool unmark = c.mode_res == MODE_SELECT && !c.use_dead;
+  const bool unmark = c.marked & MARKED_RES;
   // all keys of the wave's 16 x 64 lines first, so that the loads are in flight together;
   // a line beyond the end repeats line 0 and is masked out below
   int32_t next[PER_WAVE];
@@ -759,7 +772,7 @@ constexpr int IN_ITEMS = 8;
 __device__ void p_in_count(const State& st, const Ctrl& c, const Iter& it, int64_t vb) {
   __shared__ uint32_t red[TB / WAVE];
   const int64_t base = (vb * TB + threadIdx.x) * IN_ITEMS;
-  const bool unmark = c.mode_in == MODE_SELECT;
+  const bool unmark = c.marked & MARKED_IN;
   // line, key and id of all items first (an item beyond the end repeats item 0 of the
   // iteration and is not counted)
   int32_t line[IN_ITEMS], key[IN_ITEMS], v[IN_ITEMS];
@@ -775,7 +788,7 @@ __device__ void p_in_count(const State& st, const Ctrl& c, const Iter& it, int64
   for (int t = 0; t < IN_ITEMS; ++t)
     if (base + t < it.n && line[t] < 0 && key[t] <= c.jstar) {
       cnt += inserts(c, key[t], v[t]);
-      if (unmark && key[t] == c.jstar) st.bitmap[(uint32_t)v[t] >> 5] = 0;
+      if (unmark && key[t] == c.jstar) st.bitmap_in[(uint32_t)v[t] >> 5] = 0;
     }
   const uint32_t total = block_sum_u32(cnt, red);
   if (threadIdx.x == 0) st.in_tiles[vb] = total;
@@ -789,17 +802,19 @@ __global__ __launch_bounds__(TB) void k_flags(State st, Iter it, int64_t evict_t
                                               int64_t in_tiles) {
   const Ctrl c = *st.ctrl;
   const int64_t vb = blockIdx.x;
-  const bool selected = !c.use_dead && (c.mode_res == MODE_SELECT || c.mode_in == MODE_SELECT);
   if (vb < evict_tiles) {
     if (st.dead_scatter && c.use_dead) {
       if (c.n_change > 0) p_dead_scatter(st, c, vb, evict_tiles);
-    } else if (c.n_change > 0 || selected) {
+    } else if (c.n_change > 0 || (c.marked & MARKED_RES)) {
       p_evict_flags(st, c, vb);
     }
   } else if (vb < evict_tiles + in_tiles) {
-    if (c.n_change > 0 || selected) p_in_count(st, c, it, vb - evict_tiles);
-  } else if (selected) {
-    for (int64_t q = threadIdx.x; q < st.parts; q += TB) st.sel_part[q] = 0;
+    if (c.n_change > 0 || (c.marked & MARKED_IN)) p_in_count(st, c, it, vb - evict_tiles);
+  } else {
+    if (c.marked & MARKED_RES)
+      for (int64_t q = threadIdx.x; q < st.parts; q += TB) st.sel_part[q] = 0;
+    if (c.marked & MARKED_IN)
+      for (int64_t q = threadIdx.x; q < st.parts; q += TB) st.sel_part_in[q] = 0;
   }
 }
 
@@ -1842,6 +1857,8 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   st.bitmap = a.take<uint32_t>(st.words);
   st.dead_bits = a.take<uint32_t>(st.words);
   st.sel_part = a.take<uint32_t>(st.parts);
+  st.bitmap_in = a.take<uint32_t>(st.words);
+  st.sel_part_in = a.take<uint32_t>(st.parts);
   st.dead_part = a.take<uint32_t>(st.parts);
   st.ctrl = a.take<Ctrl>(1);
   st.fault = a.take<int32_t>(1);
@@ -2070,6 +2087,8 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   GINEX_HIP(fill_async<uint32_t>(state.bitmap, state.words, 0u, st));
   GINEX_HIP(fill_async<uint32_t>(state.dead_bits, state.words, 0u, st));
   GINEX_HIP(fill_async<uint32_t>(state.sel_part, state.parts, 0u, st));
+  GINEX_HIP(fill_async<uint32_t>(state.bitmap_in, state.words, 0u, st));
+  GINEX_HIP(fill_async<uint32_t>(state.sel_part_in, state.parts, 0u, st));
   GINEX_HIP(fill_async<uint32_t>(state.dead_part, state.parts, 0u, st));
   GINEX_HIP(fill_async<uint64_t>(state.pair, w.max_change, 0ull, st));
   if (state.dead_scatter)
