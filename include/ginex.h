@@ -27,6 +27,8 @@
  *      GINEX_SAMPLER_TILES=n  at most n tiles of a batch per workgroup column of the sampler
  *      GINEX_DEAD_SCATTER=0/1 evictions among dead rows from a pass over the lines / from the id bitmap
  *      GINEX_LIVE_SELECT=1    no shortcut that relies on the cache holding the whole superbatch
+ *      GINEX_STATIC_THRESHOLDS=0  Belady thresholds from histograms of the cache state, iteration by
+ *                             iteration, instead of from the trace alone in front of the loop
  *      GINEX_PLANNED=0/2      a carried cache that holds the whole superbatch: still the general
  *                             loop / the three-launch steps also where the replay would do
  */

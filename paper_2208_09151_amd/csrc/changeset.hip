@@ -18,6 +18,7 @@
 //   order and paired.
 //   The same loop serves the LRU policy (other keys) and a superbatch that resumes from the
 //   cache state of the previous one (C_0 given instead of computed).
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <mutex>
@@ -647,6 +648,266 @@ __global__ __launch_bounds__(BIG) void k_find(State st) {
 }
 
 constexpr int MARK_ITEMS = 8;   // lines / accesses per thread in the mark phases
+
+// ---- Belady: what an iteration decides without looking at the cache ---------------------------
+//
+// The candidates of iteration i per next-use bucket are the residents that the iteration does
+// not access (a histogram R_i that rolls forward by the rule of p_threshold) plus the
+// iteration's accesses by their new key (a histogram H_i of next_iter alone), and the number
+// to drop is the iteration's length minus R_i[i], the residents keyed to it.  So the threshold
+// bucket j* of every iteration, the number of rows to drop from it, and R_{i+1} follow from S
+// histograms in front of the loop.  What depends on the cache is which accesses are hits: the
+// split of bucket j* into residents and incoming rows (it decides the class the id select runs
+// on) and the size of the changeset.  The touch phase counts those and marks the members of
+// bucket j* of both classes on the way, so that the loop needs neither the threshold launch
+// over histograms of the state nor a marking launch.
+constexpr int STATIC_S_MAX = 2048;      // iterations up to which the S x (S + 1) histograms are kept
+
+struct StaticIter {      // per iteration, written by k_static_roll
+  int32_t jstar;         // threshold bucket, S + 1: nothing is dropped
+  int32_t rem;           // rows to drop from bucket j*
+  int32_t res_idle;      // residents of bucket j* that the iteration does not access
+  int32_t acc_jstar;     // accesses of the iteration whose new key is j*
+  int32_t res_above;     // residents above j* that the iteration does not access
+  int32_t pad;
+};
+
+// H[i][k] = accesses of iteration i whose next accessed iteration is k.  blockIdx.y = iteration.
+__global__ __launch_bounds__(TB) void k_key_hists(const int32_t* __restrict__ next_iter,
+                                                  const int64_t* __restrict__ off, int32_t S,
+                                                  uint32_t* __restrict__ hists) {
+  extern __shared__ uint32_t lds_h[];   // S + 1 bins
+  const int32_t i = blockIdx.y;
+  const int64_t lo = off[i], n = off[i + 1] - lo;
+  const int64_t base = (int64_t)blockIdx.x * (TB * TOUCH_ITEMS);
+  if (base >= n) return;                // uniform
+  for (int j = threadIdx.x; j <= S; j += TB) lds_h[j] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < TOUCH_ITEMS; ++t) {
+    const int64_t p = base + t * TB + threadIdx.x;
+    if (p < n) atomicAdd(&lds_h[next_iter[lo + p]], 1u);
+  }
+  __syncthreads();
+  for (int j = i + 1 + threadIdx.x; j <= S; j += TB)
+    if (lds_h[j]) atomicAdd(&hists[(int64_t)i * (S + 1) + j], lds_h[j]);
+}
+
+// One block: the thresholds of all iterations, one after the other.  rhist holds R_0 (the
+// residents of the start state by key).  Bins are walked as r = S - j, `per` consecutive r to a
+// thread; a bin's word packs (idle residents << 32 | candidates).
+__global__ __launch_bounds__(BIG) void k_static_roll(State st, const uint32_t* __restrict__ hists,
+                                                     const int64_t* __restrict__ off,
+                                                     StaticIter* __restrict__ plan,
+                                                     int64_t* __restrict__ miss_count) {
+  __shared__ uint32_t s_res[STATIC_S_MAX + 1];
+  __shared__ uint64_t slots[BIG / WAVE];
+  __shared__ int32_t s_jstar, s_rem;
+  const int32_t S = st.S;
+  const int per = (S + 1 + BIG - 1) / BIG;            // at most 3
+  const int r0 = threadIdx.x * per;
+  for (int j = threadIdx.x; j <= S; j += BIG) s_res[j] = st.rhist[j];
+  // the histogram values and the length of an iteration are requested an iteration ahead
+  uint32_t ahead[3] = {0, 0, 0};
+  for (int t = 0; t < per; ++t) {
+    const int j = S - (r0 + t);
+    if (j > 0) ahead[t] = hists[j];
+  }
+  int64_t n_ahead = off[1] - off[0];
+  __syncthreads();
+  for (int32_t i = 0; i < S; ++i) {
+    const int64_t n = n_ahead;
+    const int64_t drop = n - (int64_t)s_res[i];       // the misses: the cache is full
+    uint64_t word[3];
+    uint64_t mine = 0;
+    for (int t = 0; t < per; ++t) {
+      const int j = S - (r0 + t);
+      word[t] = 0;
+      if (j > i) {                                     // (no candidate has a key up to i)
+        const uint64_t idle = s_res[j];
+        word[t] = (idle << 32) | (idle + ahead[t]);
+      }
+      mine += word[t];
+    }
+    if (i + 1 < S) {
+      for (int t = 0; t < per; ++t) {
+        const int j = S - (r0 + t);
+        ahead[t] = j > i + 1 ? hists[(int64_t)(i + 1) * (S + 1) + j] : 0u;
+      }
+      n_ahead = off[i + 2] - off[i + 1];
+    }
+    if (threadIdx.x == 0) {
+      s_jstar = S + 1;
+      s_rem = 0;
+      miss_count[i] = drop;
+    }
+    // exclusive prefix over the threads with one barrier (see block_prefix_one_barrier)
+    const uint64_t inc = wave_inclusive_scan(mine);
+    if (lane_id() == WAVE - 1) slots[threadIdx.x / WAVE] = inc;
+    __syncthreads();
+    uint64_t before = inc - mine;
+    for (int q = 0; q < (int)(threadIdx.x / WAVE); ++q) before += slots[q];
+    StaticIter me{};
+    bool found = false;
+    if (drop > 0)
+      for (int t = 0; t < per; ++t) {
+        const int j = S - (r0 + t);
+        const int64_t cum = (int64_t)(before & 0xFFFFFFFFull), c = (int64_t)(word[t] & 0xFFFFFFFFull);
+        if (j > i && cum <= drop && cum + c > drop) {
+          me.jstar = j;
+          me.rem = (int32_t)(drop - cum);
+          me.res_idle = (int32_t)(word[t] >> 32);
+          me.acc_jstar = (int32_t)(c - (int64_t)(word[t] >> 32));
+          me.res_above = (int32_t)(before >> 32);
+          found = true;
+        }
+        before += word[t];
+      }
+    if (found) {
+      plan[i] = me;
+      s_jstar = me.jstar;
+      s_rem = me.rem;
+    }
+    __syncthreads();
+    const int32_t jstar = s_jstar, rem = s_rem;
+    if (threadIdx.x == 0 && jstar > S) {
+      StaticIter none{};
+      none.jstar = S + 1;
+      plan[i] = none;
+    }
+    // R_{i+1}: everything below j* stays, bucket j* loses rem, everything above goes
+    for (int t = 0; t < per; ++t) {
+      const int j = S - (r0 + t);
+      if (j < 0) continue;
+      const uint32_t c = (uint32_t)(word[t] & 0xFFFFFFFFull);
+      s_res[j] = j <= i ? 0u : j < jstar ? c : j == jstar ? c - (uint32_t)rem : 0u;
+    }
+    __syncthreads();
+  }
+}
+
+// k_touch with the threshold bucket known: no histograms; hits keyed to or above j* are
+// counted (ctr[0], ctr[1]), and the members of bucket j* mark themselves, refreshed residents
+// in the residents' scratch bitmap, misses in the incoming rows'.  The blocks from
+// touch_blocks on walk the cache lines and mark the residents of bucket j* that the iteration
+// does not access (a line that a touch block refreshes to j* meanwhile may be marked by both:
+// the part count goes to whoever sets the bit).
+__device__ __forceinline__ void mark_once(uint32_t* bits, uint32_t* part, uint32_t v) {
+  const uint32_t bit = 1u << (v & 31);
+  if (!(atomicOr(&bits[v >> 5], bit) & bit)) atomicAdd(&part[v >> PART_SHIFT], 1u);
+}
+
+__global__ __launch_bounds__(TB) void k_touch_static(State st, Iter it,
+                                                     const StaticIter* __restrict__ plan,
+                                                     uint32_t* __restrict__ ctr,
+                                                     int64_t touch_blocks) {
+  __shared__ uint32_t red[TB / WAVE];
+  const StaticIter si = plan[it.i];
+  const int32_t jstar = si.jstar;
+  const bool mark_res = jstar < st.S;     // (bucket "never": the standing dead-row bitmap serves)
+  if ((int64_t)blockIdx.x >= touch_blocks) {
+    if (!mark_res || si.res_idle == 0) return;
+    const int64_t base = ((int64_t)blockIdx.x - touch_blocks) * (TB * MARK_ITEMS);
+#pragma unroll
+    for (int t = 0; t < MARK_ITEMS; ++t) {
+      const int64_t l = base + t * TB + threadIdx.x;
+      if (l < st.cap && st.res_next[l] == jstar)
+        mark_once(st.bitmap, st.sel_part, (uint32_t)st.res_id[l]);
+    }
+    return;
+  }
+  const int64_t base = (int64_t)blockIdx.x * (TB * TOUCH_ITEMS);
+  int32_t v[TOUCH_ITEMS], line[TOUCH_ITEMS], nx[TOUCH_ITEMS];
+#pragma unroll
+  for (int t = 0; t < TOUCH_ITEMS; ++t) {
+    int64_t p = base + t * TB + threadIdx.x;
+    p = p < it.n ? p : base;
+    v[t] = it.ids[p];
+    nx[t] = it.next[p];
+  }
+#pragma unroll
+  for (int t = 0; t < TOUCH_ITEMS; ++t) line[t] = st.addr[v[t]];
+  uint32_t at_jstar = 0, above = 0;
+#pragma unroll
+  for (int t = 0; t < TOUCH_ITEMS; ++t) {
+    const int64_t p = base + t * TB + threadIdx.x;
+    if (p >= it.n) continue;
+    st.acc_line[p] = line[t];
+    if (it.src_line) it.src_line[p] = line[t];   // the state is C_i here
+    if (line[t] >= 0) {
+      st.res_next[line[t]] = nx[t];
+      if (nx[t] == st.S) dead_bit_set(st, (uint32_t)v[t]);   // the row's last access
+      if (nx[t] == jstar) {
+        ++at_jstar;
+        if (mark_res) mark_once(st.bitmap, st.sel_part, (uint32_t)v[t]);
+      } else if (nx[t] > jstar) {
+        ++above;
+      }
+    } else if (nx[t] == jstar) {
+      mark_once(st.bitmap_in, st.sel_part_in, (uint32_t)v[t]);
+    }
+  }
+  // (a block has at most TB * TOUCH_ITEMS accesses: the two counts share a word)
+  const uint32_t both = block_sum_u32((at_jstar << 16) | above, red);
+  if (threadIdx.x == 0) {
+    if (both >> 16) atomicAdd(&ctr[0], both >> 16);
+    if (both & 0xFFFFu) atomicAdd(&ctr[1], both & 0xFFFFu);
+  }
+}
+
+// One block: the rest of the iteration's decision (what p_threshold decides inside bucket j*),
+// the size of the changeset, and the id select.
+__global__ __launch_bounds__(BIG) void k_decide(State st, int32_t i,
+                                                const StaticIter* __restrict__ plan,
+                                                uint32_t* __restrict__ ctr, Outputs o,
+                                                int64_t evict_tiles) {
+  const StaticIter si = plan[i];
+  const int64_t hits_at = ctr[0], hits_above = ctr[1];
+  __syncthreads();                       // every thread has read the counters
+  if (threadIdx.x == 0) {
+    ctr[0] = 0;
+    ctr[1] = 0;
+    Ctrl c{};
+    c.jstar = si.jstar;
+    c.mode_in = MODE_ALL;
+    c.mode_res = MODE_ALL;
+    c.T = -1;
+    int64_t from_res = 0;
+    if (si.jstar <= st.S) {
+      const int64_t R = (int64_t)si.res_idle + hits_at, I = (int64_t)si.acc_jstar - hits_at;
+      const int64_t rem = si.rem;
+      if (rem == 0) {
+      } else if (rem < I) {
+        c.mode_in = MODE_SELECT; c.keep = (int32_t)(I - rem);
+      } else if (rem == I) {
+        c.mode_in = MODE_NONE;
+      } else {
+        c.mode_in = MODE_NONE; c.mode_res = MODE_SELECT;
+        from_res = rem - I;
+        c.keep = (int32_t)(R - from_res);
+        c.use_dead = si.jstar == st.S;
+      }
+      c.n_change = (int32_t)((int64_t)si.res_above + hits_above + from_res);
+      c.marked = (si.jstar < st.S && R > 0 ? MARKED_RES : 0) | (I > 0 ? MARKED_IN : 0);
+    }
+    *st.ctrl = c;
+    o.cs_offsets[i + 1] = o.cs_offsets[i] + c.n_change;
+  }
+  __syncthreads();
+  const Ctrl c = *st.ctrl;
+  if (c.mode_res == MODE_SELECT) {
+    if (c.use_dead) {
+      p_bits_find<BIG>(st, st.dead_bits, st.dead_part, true);
+      if (st.dead_scatter)
+        for (int64_t q = threadIdx.x; q < evict_tiles; q += BIG) st.evict_tiles[q] = 0;
+    } else {
+      p_bits_find<BIG>(st, st.bitmap, st.sel_part, false);
+    }
+  } else if (c.mode_in == MODE_SELECT) {
+    p_bits_find<BIG>(st, st.bitmap_in, st.sel_part_in, false);
+  }
+}
+
 constexpr int EVICT_TILE = WAVE * WAVE;   // cache lines per tile: 64 flag words of 64 lines
 
 // The members of a class are distinct ids and the bitmap is all zero before the marking, so
@@ -1803,6 +2064,9 @@ __global__ __launch_bounds__(TB) void k_step_emit(State st, int64_t evict_tiles,
 
 struct Workspace {
   uint64_t *pairs_a, *pairs_b, *heads_a, *heads_b;
+  uint32_t* key_hists;      // [S x (S + 1)] accesses per iteration and next accessed iteration (S <= STATIC_S_MAX)
+  StaticIter* static_plan;  // [S]
+  uint32_t* touch_ctr;      // [2] hits keyed to / above the threshold bucket, of the running iteration
   uint32_t* hist;
   uint32_t* head_tiles;
   int32_t* next_iter;
@@ -1837,6 +2101,9 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   w.look_tiles = ceil_div(t, LOOK_TILE);
   w.head_tiles = a.take<uint32_t>(w.look_tiles + 1 + scan_scratch_elems(w.look_tiles + 1));
   w.next_iter = a.take<int32_t>(t);
+  w.key_hists = a.take<uint32_t>(S <= STATIC_S_MAX ? (size_t)S * (S + 1) : 0);
+  w.static_plan = a.take<StaticIter>(S);
+  w.touch_ctr = a.take<uint32_t>(2);
   w.first_of = a.take<int32_t>(num_nodes);   // resumed superbatches only
   w.d_offsets = a.take<int64_t>(S + 1);
   w.d_ready = a.take<int64_t>(S);
@@ -2293,6 +2560,26 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
   // part 3: the recurrence, with no host round trip between iterations
   const size_t touch_lds = sizeof(uint32_t) * 2 * (S + 1);
   Outputs outs{in_ids, out_ids, in_positions, cs_capacity, cs_offsets, miss_count};
+  // Belady with a cache that does not hold the superbatch: the threshold bucket of every
+  // iteration from histograms of next_iter alone, in front of the loop (GINEX_STATIC_THRESHOLDS=0:
+  // from histograms of the state, iteration by iteration, as LRU needs it)
+  const char* static_env = getenv("GINEX_STATIC_THRESHOLDS");
+  const bool static_thresholds = !lru && !state.dead_only && S <= STATIC_S_MAX &&
+                                 !(static_env && static_env[0] == '0');
+  if (static_thresholds) {
+    int64_t longest = 0;
+    for (int32_t i = 0; i < S; ++i)
+      longest = std::max<int64_t>(longest, ids_offsets[i + 1] - ids_offsets[i]);
+    GINEX_HIP(fill_async<uint32_t>(w.key_hists, (int64_t)S * (S + 1), 0u, st));
+    GINEX_HIP(fill_async<uint32_t>(w.touch_ctr, 2, 0u, st));
+    if (longest > 0)
+      hipLaunchKernelGGL(k_key_hists, dim3((unsigned)ceil_div(longest, TB * TOUCH_ITEMS), (unsigned)S),
+                         dim3(TB), sizeof(uint32_t) * (S + 1), st, w.next_iter, w.d_offsets, S,
+                         w.key_hists);
+    hipLaunchKernelGGL(k_static_roll, dim3(1), dim3(BIG), 0, st, state, w.key_hists, w.d_offsets,
+                       w.static_plan, miss_count);
+    GINEX_LAUNCH_CHECK();
+  }
   {
     const int64_t res_blocks = ceil_div(cap, TB * MARK_ITEMS);
     const int64_t evict_blocks = ceil_div(w.evict_tiles, TB / WAVE);
@@ -2306,6 +2593,24 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       it.key = lru ? S - 1 - i : -1;
       it.lo_bin = lru ? S - 1 - i : i + 1;
       it.src_line = src_line ? src_line + lo : nullptr;
+      if (static_thresholds) {
+        if (it.n > 0) {
+          const int64_t touch_blocks = ceil_div(it.n, TB * TOUCH_ITEMS);
+          hipLaunchKernelGGL(k_touch_static, dim3((unsigned)(touch_blocks + res_blocks)), dim3(TB), 0,
+                             st, state, it, w.static_plan, w.touch_ctr, touch_blocks);
+        }
+        hipLaunchKernelGGL(k_decide, dim3(1), dim3(BIG), 0, st, state, i, w.static_plan, w.touch_ctr,
+                           outs, w.evict_tiles);
+        GINEX_LAUNCH_CHECK();
+        if (it.n == 0) continue;
+        const int64_t in_tiles = ceil_div(it.n, (int64_t)TB * IN_ITEMS);
+        hipLaunchKernelGGL(k_flags, dim3((unsigned)(w.evict_tiles + in_tiles + 1)), dim3(TB), 0, st,
+                           state, it, w.evict_tiles, in_tiles);
+        hipLaunchKernelGGL(k_emit_pair, dim3((unsigned)(evict_blocks + in_tiles)), dim3(TB), 0, st,
+                           state, it, outs, w.evict_tiles);
+        GINEX_LAUNCH_CHECK();
+        continue;
+      }
       if (it.n > 0) {
         hipLaunchKernelGGL(k_touch, dim3((unsigned)ceil_div(it.n, TB * TOUCH_ITEMS)), dim3(TB),
                            touch_lds, st, state, it, (unsigned long long*)(miss_count + i));

@@ -994,6 +994,7 @@ def structured_traces():
 @pytest.mark.parametrize("scatter", ["0", "1"])
 def test_changesets_on_structured_traces(ginex, scatter, monkeypatch):
     monkeypatch.setenv("GINEX_DEAD_SCATTER", scatter)
+    monkeypatch.setenv("GINEX_STATIC_THRESHOLDS", scatter)   # both ways of finding the thresholds
     n, traces = structured_traces()
     rng = np.random.default_rng(82)
     for name, tr in traces:
@@ -1296,6 +1297,8 @@ def test_changeset_is_independent_of_the_eviction_path_and_repeatable(ginex, cas
         monkeypatch.setenv("GINEX_DEAD_SCATTER", scatter)
         monkeypatch.setenv("GINEX_LIVE_SELECT", live)   # keeps the live-select launches in the loop
         monkeypatch.setenv("GINEX_PLANNED", planned)    # 0: the loop also where no loop is needed
+        # the thresholds of the general loop from histograms of the state (0) or in front of it
+        monkeypatch.setenv("GINEX_STATIC_THRESHOLDS", scatter)
         a = ginex.changeset(n, ids_d, io, 20000)
         b = ginex.changeset_resume(n, ids_d, io, start)
         results.append((a, b))

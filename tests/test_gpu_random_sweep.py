@@ -42,6 +42,7 @@ def test_changeset_entry_points_on_random_traces(ginex, monkeypatch):
         distinct = max(len(np.unique(ids)), 1)
         kind = rng.choice(["belady", "lru", "resume", "chain"])
         try:
+            monkeypatch.setenv("GINEX_STATIC_THRESHOLDS", "1" if rng.random() < 0.7 else "0")
             if kind in ("belady", "lru"):
                 cap = int(rng.integers(0, n + 2)) if rng.random() < 0.5 else int(rng.integers(0, distinct + 1))
                 ref = (oracle.changeset if kind == "belady" else oracle.changeset_lru)(n, ids, off, cap)
