@@ -968,6 +968,23 @@ def test_changeset_at_the_largest_superbatch_the_library_accepts(ginex):
         ginex.changeset(n, ids_d, np.concatenate([off, off[-1:]]), cap)     # S = 8192
 
 
+@pytest.mark.parametrize("S", [1, 2, 1024, 1025, 2047, 2048, 2049])
+def test_changeset_around_the_sizes_at_which_the_loop_changes_its_way(ginex, S):
+    """Iteration counts around the limits of the per-iteration bookkeeping (one, two or three
+    histogram bins per thread of the block that rolls the thresholds forward; 2 048 iterations,
+    beyond which the thresholds come from the state's histograms), under eviction pressure, for
+    Belady from a fresh and from a given cache."""
+    rng = np.random.default_rng(S)
+    n, cap = 700, 55
+    ids, off = random_trace(rng, n, S, 9)
+    ids_d = dev(ids) if len(ids) else torch.zeros(1, dtype=torch.int32, device="cuda")[:0]
+    check_changeset(ginex.changeset(n, ids_d, off, cap), oracle.changeset(n, ids, off, cap),
+                    (n, ids, off))
+    start = rng.permutation(n)[:cap].astype(np.int32)
+    check_resumed(ginex.changeset_resume(n, ids_d, off, dev(start)),
+                  oracle.changeset_resume(n, ids, off, cap, start), (n, ids, off))
+
+
 def structured_traces():
     """Traces built to sit on the tie rules and the mode switches of the threshold walk."""
     rng = np.random.default_rng(81)
