@@ -662,6 +662,7 @@ constexpr int MARK_ITEMS = 8;   // lines / accesses per thread in the mark phase
 // bucket j* of both classes on the way, so that the loop needs neither the threshold launch
 // over histograms of the state nor a marking launch.
 constexpr int STATIC_S_MAX = 2048;      // iterations up to which the S x (S + 1) histograms are kept
+constexpr int64_t TOUCH_FEW = 400000;   // accesses of an iteration below which a thread of k_touch_static takes four
 
 struct StaticIter {      // per iteration, written by k_static_roll
   int32_t jstar;         // threshold bucket, S + 1: nothing is dropped
@@ -786,7 +787,8 @@ __global__ __launch_bounds__(BIG) void k_static_roll(State st, const uint32_t* _
   }
 }
 
-// k_touch with the threshold bucket known: no histograms; hits keyed to or above j* are
+// k_touch with the threshold bucket known (ITEMS accesses per thread: four while an iteration is
+// bound by the latency of its chain, eight once it is bound by its scattered accesses): no histograms; hits keyed to or above j* are
 // counted (ctr[0], ctr[1]), and the members of bucket j* mark themselves, refreshed residents
 // in the residents' scratch bitmap, misses in the incoming rows'.  The blocks from
 // touch_blocks on walk the cache lines and mark the residents of bucket j* that the iteration
@@ -797,6 +799,7 @@ __device__ __forceinline__ void mark_once(uint32_t* bits, uint32_t* part, uint32
   if (!(atomicOr(&bits[v >> 5], bit) & bit)) atomicAdd(&part[v >> PART_SHIFT], 1u);
 }
 
+template <int ITEMS>
 __global__ __launch_bounds__(TB) void k_touch_static(State st, Iter it,
                                                      const StaticIter* __restrict__ plan,
                                                      uint32_t* __restrict__ ctr,
@@ -816,20 +819,20 @@ __global__ __launch_bounds__(TB) void k_touch_static(State st, Iter it,
     }
     return;
   }
-  const int64_t base = (int64_t)blockIdx.x * (TB * TOUCH_ITEMS);
-  int32_t v[TOUCH_ITEMS], line[TOUCH_ITEMS], nx[TOUCH_ITEMS];
+  const int64_t base = (int64_t)blockIdx.x * (TB * ITEMS);
+  int32_t v[ITEMS], line[ITEMS], nx[ITEMS];
 #pragma unroll
-  for (int t = 0; t < TOUCH_ITEMS; ++t) {
+  for (int t = 0; t < ITEMS; ++t) {
     int64_t p = base + t * TB + threadIdx.x;
     p = p < it.n ? p : base;
     v[t] = it.ids[p];
     nx[t] = it.next[p];
   }
 #pragma unroll
-  for (int t = 0; t < TOUCH_ITEMS; ++t) line[t] = st.addr[v[t]];
+  for (int t = 0; t < ITEMS; ++t) line[t] = st.addr[v[t]];
   uint32_t at_jstar = 0, above = 0;
 #pragma unroll
-  for (int t = 0; t < TOUCH_ITEMS; ++t) {
+  for (int t = 0; t < ITEMS; ++t) {
     const int64_t p = base + t * TB + threadIdx.x;
     if (p >= it.n) continue;
     st.acc_line[p] = line[t];
@@ -847,7 +850,7 @@ __global__ __launch_bounds__(TB) void k_touch_static(State st, Iter it,
       mark_once(st.bitmap_in, st.sel_part_in, (uint32_t)v[t]);
     }
   }
-  // (a block has at most TB * TOUCH_ITEMS accesses: the two counts share a word)
+  // (a block has at most TB * ITEMS accesses: the two counts share a word)
   const uint32_t both = block_sum_u32((at_jstar << 16) | above, red);
   if (threadIdx.x == 0) {
     if (both >> 16) atomicAdd(&ctr[0], both >> 16);
@@ -2595,9 +2598,15 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
       it.src_line = src_line ? src_line + lo : nullptr;
       if (static_thresholds) {
         if (it.n > 0) {
-          const int64_t touch_blocks = ceil_div(it.n, TB * TOUCH_ITEMS);
-          hipLaunchKernelGGL(k_touch_static, dim3((unsigned)(touch_blocks + res_blocks)), dim3(TB), 0,
-                             st, state, it, w.static_plan, w.touch_ctr, touch_blocks);
+          if (it.n < TOUCH_FEW) {
+            const int64_t touch_blocks = ceil_div(it.n, TB * 4);
+            hipLaunchKernelGGL(k_touch_static<4>, dim3((unsigned)(touch_blocks + res_blocks)), dim3(TB),
+                               0, st, state, it, w.static_plan, w.touch_ctr, touch_blocks);
+          } else {
+            const int64_t touch_blocks = ceil_div(it.n, TB * 8);
+            hipLaunchKernelGGL(k_touch_static<8>, dim3((unsigned)(touch_blocks + res_blocks)), dim3(TB),
+                               0, st, state, it, w.static_plan, w.touch_ctr, touch_blocks);
+          }
         }
         hipLaunchKernelGGL(k_decide, dim3(1), dim3(BIG), 0, st, state, i, w.static_plan, w.touch_ctr,
                            outs, w.evict_tiles);
