@@ -1029,10 +1029,13 @@ __device__ void p_evict_flags(const State& st, const Ctrl& c, int64_t vb) {
   if (threadIdx.x == 0) st.evict_tiles[vb] = total;
 }
 
-constexpr int IN_ITEMS = 8;
+constexpr int IN_ITEMS = 8;        // accesses per thread in the insertion phases ...
+constexpr int IN_ITEMS_MANY = 4;   // ... of an iteration with TOUCH_FEW accesses or more (smaller tiles
+                                   // rank and place faster once the phases are bound by their accesses)
 
 // Insertions per tile of TB*IN_ITEMS accesses; incoming rows that marked themselves for the
 // select take their word of the scratch bitmap back to zero.
+template <int IN_ITEMS>
 __device__ void p_in_count(const State& st, const Ctrl& c, const Iter& it, int64_t vb) {
   __shared__ uint32_t red[TB / WAVE];
   const int64_t base = (vb * TB + threadIdx.x) * IN_ITEMS;
@@ -1062,6 +1065,7 @@ __device__ void p_in_count(const State& st, const Ctrl& c, const Iter& it, int64
 // or, dead rows of a large cache, by the scatter from the bitmap (the blocks then stride over
 // the stretch above T); the next in_tiles blocks: insertions per tile; one more block takes
 // the part counts of the scratch bitmap back to zero.
+template <int IN_ITEMS>
 __global__ __launch_bounds__(TB) void k_flags(State st, Iter it, int64_t evict_tiles,
                                               int64_t in_tiles) {
   const Ctrl c = *st.ctrl;
@@ -1073,7 +1077,7 @@ __global__ __launch_bounds__(TB) void k_flags(State st, Iter it, int64_t evict_t
       p_evict_flags(st, c, vb);
     }
   } else if (vb < evict_tiles + in_tiles) {
-    if (c.n_change > 0 || (c.marked & MARKED_IN)) p_in_count(st, c, it, vb - evict_tiles);
+    if (c.n_change > 0 || (c.marked & MARKED_IN)) p_in_count<IN_ITEMS>(st, c, it, vb - evict_tiles);
   } else {
     if (c.marked & MARKED_RES)
       for (int64_t q = threadIdx.x; q < st.parts; q += TB) st.sel_part[q] = 0;
@@ -1189,6 +1193,7 @@ __device__ void p_evict_emit(const State& st, const Ctrl& c, const Iter& it, con
 // The inserted positions of one tile of accesses in position order; the block's insertions
 // are first gathered in LDS by rank and then dealt one to a thread, for the same reason as
 // above.
+template <int IN_ITEMS>
 __device__ void p_in_emit(const State& st, const Ctrl& c, const Iter& it, const Outputs& o,
                           int64_t vb) {
   __shared__ uint32_t smem[TB / WAVE + 1];
@@ -1238,12 +1243,13 @@ __device__ void p_in_emit(const State& st, const Ctrl& c, const Iter& it, const 
   }
 }
 
+template <int IN_ITEMS>
 __global__ __launch_bounds__(TB) void k_emit_pair(State st, Iter it, Outputs o, int64_t evict_tiles) {
   const Ctrl c = *st.ctrl;
   if (c.n_change <= 0) return;
   const int64_t evict_blocks = (evict_tiles + TB / WAVE - 1) / (TB / WAVE);
   if ((int64_t)blockIdx.x < evict_blocks) p_evict_emit(st, c, it, o, blockIdx.x, evict_tiles);
-  else p_in_emit(st, c, it, o, blockIdx.x - evict_blocks);
+  else p_in_emit<IN_ITEMS>(st, c, it, o, blockIdx.x - evict_blocks);
 }
 
 // popcount of one part of a bitmap (the part counts of the dead-row bitmap after a resumed
@@ -2134,7 +2140,7 @@ Workspace carve(void* base, int64_t num_nodes, int64_t total, int32_t S, int64_t
   st.fault = a.take<int32_t>(1);
   w.evict_tiles = ceil_div(c, (int64_t)EVICT_TILE);
   st.evict_words = a.take<uint64_t>(w.evict_tiles * WAVE);
-  w.in_tiles = ceil_div(max_n > 0 ? max_n : 1, (int64_t)TB * IN_ITEMS);
+  w.in_tiles = ceil_div(max_n > 0 ? max_n : 1, (int64_t)TB * IN_ITEMS_MANY);
   st.evict_tiles = a.take<uint32_t>(w.evict_tiles);
   st.in_tiles = a.take<uint32_t>(w.in_tiles);
   w.max_change = max_n < c ? max_n : c;
@@ -2612,11 +2618,19 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
                            outs, w.evict_tiles);
         GINEX_LAUNCH_CHECK();
         if (it.n == 0) continue;
-        const int64_t in_tiles = ceil_div(it.n, (int64_t)TB * IN_ITEMS);
-        hipLaunchKernelGGL(k_flags, dim3((unsigned)(w.evict_tiles + in_tiles + 1)), dim3(TB), 0, st,
-                           state, it, w.evict_tiles, in_tiles);
-        hipLaunchKernelGGL(k_emit_pair, dim3((unsigned)(evict_blocks + in_tiles)), dim3(TB), 0, st,
-                           state, it, outs, w.evict_tiles);
+        if (it.n < TOUCH_FEW) {
+          const int64_t in_tiles = ceil_div(it.n, (int64_t)TB * IN_ITEMS);
+          hipLaunchKernelGGL(k_flags<IN_ITEMS>, dim3((unsigned)(w.evict_tiles + in_tiles + 1)), dim3(TB),
+                             0, st, state, it, w.evict_tiles, in_tiles);
+          hipLaunchKernelGGL(k_emit_pair<IN_ITEMS>, dim3((unsigned)(evict_blocks + in_tiles)), dim3(TB),
+                             0, st, state, it, outs, w.evict_tiles);
+        } else {
+          const int64_t in_tiles = ceil_div(it.n, (int64_t)TB * IN_ITEMS_MANY);
+          hipLaunchKernelGGL(k_flags<IN_ITEMS_MANY>, dim3((unsigned)(w.evict_tiles + in_tiles + 1)),
+                             dim3(TB), 0, st, state, it, w.evict_tiles, in_tiles);
+          hipLaunchKernelGGL(k_emit_pair<IN_ITEMS_MANY>, dim3((unsigned)(evict_blocks + in_tiles)),
+                             dim3(TB), 0, st, state, it, outs, w.evict_tiles);
+        }
         GINEX_LAUNCH_CHECK();
         continue;
       }
@@ -2636,10 +2650,10 @@ int32_t changeset_run(const char* who, bool lru, int64_t num_nodes, const int32_
         hipLaunchKernelGGL(k_find, dim3(1), dim3(BIG), 0, st, state);
         GINEX_LAUNCH_CHECK();
       }
-      hipLaunchKernelGGL(k_flags, dim3((unsigned)(w.evict_tiles + in_tiles + 1)), dim3(TB), 0, st,
-                         state, it, w.evict_tiles, in_tiles);
-      hipLaunchKernelGGL(k_emit_pair, dim3((unsigned)(evict_blocks + in_tiles)), dim3(TB), 0, st, state,
-                         it, outs, w.evict_tiles);
+      hipLaunchKernelGGL(k_flags<IN_ITEMS>, dim3((unsigned)(w.evict_tiles + in_tiles + 1)), dim3(TB), 0,
+                         st, state, it, w.evict_tiles, in_tiles);
+      hipLaunchKernelGGL(k_emit_pair<IN_ITEMS>, dim3((unsigned)(evict_blocks + in_tiles)), dim3(TB), 0, st,
+                         state, it, outs, w.evict_tiles);
       GINEX_LAUNCH_CHECK();
     }
   }
