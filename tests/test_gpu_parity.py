@@ -968,7 +968,7 @@ def test_changeset_at_the_largest_superbatch_the_library_accepts(ginex):
         ginex.changeset(n, ids_d, np.concatenate([off, off[-1:]]), cap)     # S = 8192
 
 
-@pytest.mark.parametrize("S", [1, 2, 1024, 1025, 2047, 2048, 2049])
+@pytest.mark.parametrize("S", [1, 2, 31, 32, 33, 255, 256, 1024, 1025, 2047, 2048, 2049])
 def test_changeset_around_the_sizes_at_which_the_loop_changes_its_way(ginex, S):
     """Iteration counts around the limits of the per-iteration bookkeeping (one, two or three
     histogram bins per thread of the block that rolls the thresholds forward; 2 048 iterations,
